@@ -1,0 +1,210 @@
+"""Pins for the oracle's ring buffer and staleness-gated sampling (CPU only).
+
+Each test checks the oracle against something other than itself: published
+generator outputs, exact integer arithmetic, a brute-force enumeration written
+here, the Lag-k closed form of the paper (Appendix D.1; Eq. 2), invariants.
+"""
+import os
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+M64 = (1 << 64) - 1
+
+
+def test_rng64_published_vectors(orc):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "splitmix64_vectors.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 8
+    for seed, j, val in rows:
+        assert orc.rng64(int(seed), int(j)) == int(val)
+
+
+def test_rng64_monobit_and_byte_chi2(orc):
+    n = 20000
+    vals = np.array([orc.rng64(20190, j) for j in range(n)], dtype=np.uint64)
+    bits = np.unpackbits(vals.view(np.uint8))
+    assert abs(bits.mean() - 0.5) < 4 * 0.5 / np.sqrt(bits.size)
+    counts = np.bincount(vals.view(np.uint8), minlength=256)
+    exp = vals.size * 8 / 256
+    chi2 = ((counts - exp) ** 2 / exp).sum()
+    assert chi2 < 255 + 6 * np.sqrt(2 * 255)
+
+
+def test_mulhi64_exact_against_python_integers(orc):
+    rng = np.random.default_rng(7)
+    cases = [(0, 5), (M64, 1), (M64, M64), ((1 << 63) + 1, (1 << 63) + 1), (1 << 63, 2),
+             (M64, 3), (12345, 0)]
+    cases += [(int(a) * 2 + 1, int(b) * 2 + 1) for a, b in rng.integers(0, 1 << 63, size=(200, 2), dtype=np.int64)]
+    for a, b in cases:
+        assert orc.mulhi64(a, b) == (a * b) >> 64
+    for K in (1, 2, 3, 1000, (1 << 63) + 1, M64):
+        for j in range(50):
+            assert orc.mulhi64(orc.rng64(99, j), K) < K
+
+
+def _eligible_bruteforce(version, count, cur, max_st):
+    out = []
+    for i in range(count):
+        if version[i] <= cur and cur - version[i] <= max_st:
+            out.append(i)
+    return out
+
+
+@pytest.mark.parametrize("seed", [0, 1, 20190])
+def test_sample_matches_bruteforce_enumeration(orc, seed):
+    rng = np.random.default_rng(seed)
+    for _ in range(40):
+        n = int(rng.integers(1, 65))
+        count = int(rng.integers(1, n + 1))
+        version = rng.integers(0, 12, size=n).astype(np.int32)
+        cur, max_st = int(rng.integers(0, 14)), int(rng.integers(0, 6))
+        E = _eligible_bruteforce(version, count, cur, max_st)
+        st, idx, K = orc.sample(version, count, cur, max_st, seed, 16)
+        assert K == len(E)
+        if not E:
+            assert st == -4 and (idx == 0xFFFFFFFF).all()
+            continue
+        assert st == 0
+        for j in range(16):
+            k = (orc.rng64(seed, j) * len(E)) >> 64
+            assert idx[j] == E[k]
+
+
+def test_sampling_distribution_uniform_on_eligible(orc):
+    version = np.array([5, 9, 3, 9, 8, 7, 1, 9, 6, 9, 2, 9, 10, 4, 8, 0, 9, 9], dtype=np.int32)
+    count, cur, max_st = 16, 9, 1   # last two slots are beyond count; 10 > cur is ineligible
+    E = _eligible_bruteforce(version, count, cur, max_st)
+    assert E == [1, 3, 4, 7, 9, 11, 14]
+    hist = np.zeros(len(version), dtype=np.int64)
+    draws = 0
+    for seed in range(400):
+        st, idx, K = orc.sample(version, count, cur, max_st, seed, 500)
+        assert st == 0 and K == len(E)
+        hist += np.bincount(idx, minlength=len(version))
+        draws += 500
+    assert hist[[i for i in range(len(version)) if i not in E]].sum() == 0
+    exp = draws / len(E)
+    chi2 = ((hist[E] - exp) ** 2 / exp).sum()
+    assert chi2 < 22.46  # chi-square 6 dof, p = 0.001
+
+
+def test_staleness_invariant_and_prefix_property(orc):
+    from paper_2502_20190_amd import synth
+
+    wl = synth.WORKLOADS["c1"]
+    rows = synth.make_chunk(wl, synth.MASTER_SEED, 0, wl.capacity)
+    buf = orc.Buffer(wl.capacity, wl.obs_elems, wl.obs_dtype)
+    assert buf.insert(**rows) == 0
+    ver = buf.versions()
+    st, idx, K = buf.sample(wl.batch, wl.current_version, wl.max_staleness, 42)
+    assert st == 0
+    stale = wl.current_version - ver[idx]
+    assert ((stale >= 0) & (stale <= wl.max_staleness)).all() and (idx < buf.count).all()
+    assert K == int(((ver >= 89) & (ver <= 99)).sum())
+    # same arguments, same result; a shorter batch is a prefix of a longer one
+    st2, idx2, _ = buf.sample(wl.batch, wl.current_version, wl.max_staleness, 42)
+    assert (idx == idx2).all()
+    st3, idx3, _ = buf.sample(7, wl.current_version, wl.max_staleness, 42)
+    assert (idx3 == idx[:7]).all()
+    st4, idx4, _ = buf.sample(wl.batch, wl.current_version, wl.max_staleness, 43)
+    assert (idx4 != idx).any()
+
+
+@pytest.mark.parametrize("k_lag,max_st,extra", [(1, 0, 0), (2, 0, 3), (4, 1, 5), (8, 3, 17), (4, 10, 2)])
+def test_lag_k_closed_form(orc, k_lag, max_st, extra):
+    """A ring of N_s = k*B_s filled serially, B_s rows per policy version, holds
+    exactly the last k versions (Appendix D.1: buffer = k*batch gives 1/k new
+    samples; Eq. 2: P = B_s/N_s).  Then K = min(max_st+1, k)*B_s wherever the
+    head is, and at max_st = 0 the eligible fraction is P."""
+    bs = 6
+    ns = k_lag * bs
+    buf = orc.Buffer(ns, 2, "f32")
+    n_versions = k_lag + extra
+    for v in range(n_versions):
+        z = np.zeros((bs, 2), np.float32)
+        buf.insert(z, z, np.zeros(bs, np.int32), np.zeros(bs, np.float32), np.zeros(bs, np.uint8),
+                   np.full(bs, v, np.int32))
+    cur = n_versions - 1
+    st, idx, K = buf.sample(64, cur, max_st, 5)
+    assert st == 0 and buf.count == ns and buf.head == (n_versions * bs) % ns
+    assert K == min(max_st + 1, k_lag) * bs
+    if max_st == 0:
+        assert K / ns == pytest.approx(bs / ns)
+
+
+def test_edge_cases(orc):
+    ver = np.array([3, 4, 5, 6, 7, 8], dtype=np.int32)
+    # max_st = 0: only the current version
+    st, idx, K = orc.sample(ver, 6, 5, 0, 1, 8)
+    assert st == 0 and K == 1 and (idx == 2).all()
+    # max_st >= cur: every valid slot not ahead of cur
+    st, idx, K = orc.sample(ver, 6, 8, 100, 1, 64)
+    assert K == 6 and set(idx) <= set(range(6))
+    # tags ahead of the current version are ineligible
+    st, idx, K = orc.sample(ver, 6, 4, 100, 1, 8)
+    assert K == 2 and set(idx) <= {0, 1}
+    # partially filled ring: slots >= count are never returned
+    st, idx, K = orc.sample(ver, 2, 8, 100, 1, 64)
+    assert K == 2 and set(idx) <= {0, 1}
+    # nothing eligible
+    st, idx, K = orc.sample(ver, 6, 100, 3, 1, 4)
+    assert st == -4 and K == 0 and (idx == 0xFFFFFFFF).all()
+    st, idx, K = orc.sample(ver, 0, 5, 3, 1, 4)
+    assert st == -4 and K == 0
+    # negative tags and large staleness windows do not overflow
+    ver2 = np.array([-2**31, 2**31 - 1, 0], dtype=np.int32)
+    st, idx, K = orc.sample(ver2, 3, 2**31 - 1, 2**40, 1, 4)
+    assert K == 3
+    st, idx, K = orc.sample(ver2, 3, 0, 2**31, 1, 16)
+    assert K == 2 and set(idx) <= {0, 2}
+
+
+def test_insert_wraparound_and_gather(orc):
+    cap, d = 10, 3
+    buf = orc.Buffer(cap, d, "f32")
+    mirror = {k: None for k in ("obs", "next_obs", "action", "reward", "done", "version")}
+    mirror["obs"] = np.zeros((cap, d), np.float32)
+    mirror["next_obs"] = np.zeros((cap, d), np.float32)
+    mirror["action"] = np.zeros(cap, np.int32)
+    mirror["reward"] = np.zeros(cap, np.float32)
+    mirror["done"] = np.zeros(cap, np.uint8)
+    mirror["version"] = np.zeros(cap, np.int32)
+    rng = np.random.default_rng(3)
+    head = count = 0
+    for n in (4, 3, 7, 10, 1, 9):
+        rows = {"obs": rng.standard_normal((n, d)).astype(np.float32),
+                "next_obs": rng.standard_normal((n, d)).astype(np.float32),
+                "action": rng.integers(0, 5, n).astype(np.int32),
+                "reward": rng.uniform(-1, 1, n).astype(np.float32),
+                "done": rng.integers(0, 2, n).astype(np.uint8),
+                "version": rng.integers(0, 50, n).astype(np.int32)}
+        assert buf.insert(**rows) == 0
+        for i in range(n):           # independent mirror of the ring semantics
+            s = (head + i) % cap
+            for k in rows:
+                mirror[k][s] = rows[k][i]
+        head, count = (head + n) % cap, min(count + n, cap)
+        assert buf.head == head and buf.count == count
+    assert (buf.versions() == mirror["version"]).all()
+    idx = np.array([9, 0, 0, 5, 3], np.uint32)
+    mb = buf.gather(idx)
+    for k in ("obs", "next_obs", "action", "reward", "done"):
+        assert (mb[k] == mirror[k][idx]).all()
+    z = np.zeros((11, d), np.float32)
+    assert buf.insert(z, z, np.zeros(11, np.int32), np.zeros(11, np.float32), np.zeros(11, np.uint8),
+                      np.zeros(11, np.int32)) == -5
+    assert buf.head == head and buf.count == count
+
+
+def test_c5_geometric_eligible_fraction(orc):
+    """Version tags 999 - Geometric0(0.1): eligible fraction 1 - 0.9^(max_st+1)."""
+    from paper_2502_20190_amd import synth
+
+    wl = synth.WORKLOADS["c5"]
+    rng = np.random.Generator(np.random.Philox(key=[1, 2]))
+    ver = synth._versions_np(wl, rng, 200_000)
+    for ms in wl.staleness_sweep:
+        st, idx, K = orc.sample(ver, len(ver), 999, ms, 3, 4)
+        assert K / len(ver) == pytest.approx(1 - 0.9 ** (ms + 1), abs=0.005)
