@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Learner-throughput benchmark on one MI355X.
+
+A step = one pass of the whole hot path on one synthetic minibatch:
+tj_sample (staleness mask, prefix sum, uniform select, row gather from the
+device-resident ring) followed by tj_learner_step (three forward passes,
+double-DQN TD target, Huber loss, backward, Adam, periodic target update).
+The ring is filled on the device before the timed region starts.
+
+Prints ONE JSON line: transitions consumed per second, the roofline figure of
+the dominant kernel (the MFMA GEMM) from HIP events recorded inside the timed
+region, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
+
+
+def gemm_flops_per_step(wl, synth):
+    """Algorithmic flops of the dense contractions of one step: three forward
+    passes (2*B*W each), weight gradients (2*B*W) and input gradients for every
+    layer but the first (2*B*W_l)."""
+    shapes = synth.layer_shapes(wl.layers, wl.in_chw)
+    per_sample = []
+    for kind, ws, fin, fout, out_chw in shapes:
+        w = 1
+        for x in ws:
+            w *= x
+        per_sample.append(2 * w * (out_chw[1] * out_chw[2] if kind == synth.CONV else 1))
+    fwd = sum(per_sample)
+    bwd = sum(per_sample) + sum(per_sample[1:])
+    return wl.batch * (3 * fwd + bwd)
+
+
+def fill_ring(tj, synth, wl, chunk_rows):
+    import torch
+
+    buf = tj.Buffer(wl.capacity, wl.obs_elems, wl.obs_dtype)
+    versions = []
+    c = 0
+    for start in range(0, wl.capacity, chunk_rows):
+        n = min(chunk_rows, wl.capacity - start)
+        rows = synth.make_chunk_device(wl, synth.MASTER_SEED, c, n)
+        buf.insert(rows["obs"], rows["next_obs"], rows["action"], rows["reward"], rows["done"],
+                   rows["version"])
+        versions.append(rows["version"].cpu())
+        c += 1
+    torch.cuda.synchronize()
+    return buf, torch.cat(versions).numpy()
+
+
+def cpu_baseline(wl, synth, buf, versions, theta, target, budget_rows):
+    """The CPU oracle on a bounded sample: sampling over the full tag array with
+    the full batch, then one learner step on `budget_rows` rows (copied from the
+    device ring, copy untimed); the learner time is scaled to the full batch."""
+    import numpy as np
+    import torch
+
+    from oracle import orc
+
+    t0 = time.perf_counter()
+    st, idx, K = orc.sample(versions, wl.capacity, wl.current_version, wl.max_staleness, 1, wl.batch)
+    t_sample = time.perf_counter() - t0
+    sel = torch.from_numpy(idx[:budget_rows].astype(np.int64)).cuda()
+    rows = {f: buf.field(f)[sel].cpu().numpy() for f in ("obs", "next_obs", "action", "reward", "done")}
+    o = orc.Learner(wl.layers, wl.in_chw, obs_dtype=wl.obs_dtype, gamma=wl.gamma, kappa=wl.kappa, lr=wl.lr,
+                    beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, target_interval=wl.target_interval)
+    o.set_state(orc.PARAMS, theta.astype(np.float64))
+    o.set_state(orc.TARGET, target.astype(np.float64))
+    t0 = time.perf_counter()
+    o.step(**rows)
+    t_learn = time.perf_counter() - t0
+    full = t_sample + t_learn * wl.batch / budget_rows
+    return {
+        "value": wl.batch / full, "unit": "transitions/s", "cores": orc.num_threads(), "kind": "oracle",
+        "sample": (f"sampling over all {wl.capacity} tags at batch {wl.batch} ({t_sample * 1e3:.1f} ms) + one "
+                   f"fp64 learner step on {budget_rows} of the {wl.batch} rows ({t_learn:.2f} s), learner "
+                   f"time scaled by {wl.batch}/{budget_rows}"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="c3", help="workload: c1, c2 or c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's learner step (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no collectives are part of it)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2502_20190_amd import binding as tj, synth
+
+    wl = synth.WORKLOADS[args.config]
+    torch.cuda.set_device(0)
+    buf, versions = fill_ring(tj, synth, wl, 65_536)
+    theta = synth.xavier_init(wl.layers, wl.in_chw, 1)
+    target = synth.xavier_init(wl.layers, wl.in_chw, 2)
+    lrn = tj.learner_for_workload(wl, theta, target)
+    mb = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype)
+    L = tj.lib()
+
+    def one_step(i):
+        rc = buf.sample(mb, wl.current_version, wl.max_staleness, i)
+        rc = rc or lrn.step(mb)
+        if rc != tj.TJ_OK:
+            raise tj.TjError(rc, "bench step")
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    bev = [tj.HipEvents(3) for _ in range(K)]
+    lev = [tj.HipEvents(5) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        L.tj_buffer_set_phase_events(buf.h, bev[i].ev, 3)
+        L.tj_learner_set_phase_events(lrn.h, lev[i].ev, 5)
+        one_step(args.warmup + i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    L.tj_buffer_set_phase_events(buf.h, None, 0)
+    L.tj_learner_set_phase_events(lrn.h, None, 0)
+    st, info = buf.status()
+    loss, t = lrn.read_stats()
+    assert st == tj.TJ_OK and t == args.warmup + K and np.isfinite(loss)
+
+    ms = lambda evs, a, b: sum(e.elapsed_ms(a, b) for e in evs) / K
+    ph = {
+        "mask_scan_select_ms": ms(bev, 0, 1), "gather_ms": ms(bev, 1, 2),
+        "forward_gemm_ms": ms(lev, 0, 1), "td_huber_ms": ms(lev, 1, 2), "backward_gemm_ms": ms(lev, 2, 3),
+        "adam_recast_ms": ms(lev, 3, 4),
+    }
+    n_layers = len(wl.layers)
+    n_gemm_launch = 3 * n_layers - 1
+    flops = gemm_flops_per_step(wl, synth)
+    gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
+    achieved = flops / (gemm_ms * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[wl.precision]
+    P = synth.num_params(wl.layers, wl.in_chw)
+    adam_bytes = (30 if wl.precision == "bf16" else 28) * P
+    gather_bytes = 2 * wl.batch * wl.record_bytes
+    out = {
+        "metric": "learner transitions consumed/sec at 1 MI355X",
+        "value": wl.batch * K / wall, "unit": "transitions/s", "n_gpus": 1, "steps": K,
+        "warmup": args.warmup, "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.precision, "data": "synthetic",
+        "config": {"workload": wl.name, "ring_slots": wl.capacity, "obs_elems": wl.obs_elems,
+                   "batch": wl.batch, "max_staleness": wl.max_staleness, "n_eligible": int(info.last_n_eligible),
+                   "layers": [l[1] for l in wl.layers], "params": P},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "kernel": "gemm_pq", "launches_per_step": n_gemm_launch,
+                     "flops_per_launch": flops / n_gemm_launch, "avg_launch_ms": gemm_ms / n_gemm_launch},
+        "phases_ms": ph,
+        "gather": {"bound": "hbm", "achieved": gather_bytes / (ph["gather_ms"] * 1e-3) / 1e9,
+                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": gather_bytes},
+        "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_recast_ms"] * 1e-3) / 1e9,
+                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": adam_bytes},
+        "loss": loss,
+    }
+    out["gather"]["frac"] = out["gather"]["achieved"] / PEAK_HBM_GBS
+    out["adam"]["frac"] = out["adam"]["achieved"] / PEAK_HBM_GBS
+    if not args.no_cpu_baseline:
+        rows = args.cpu_rows or max(8, min(wl.batch, int(3e11 / (flops / wl.batch))))
+        out["cpu_baseline"] = cpu_baseline(wl, synth, buf, versions, theta, target, rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,226 @@
+/*
+ * tianji.h - C ABI of the MI355X (gfx950) learner hot path of the TianJi RL
+ * training system (arXiv 2502.20190).
+ *
+ * The library implements what the paper's Learner does with the Buffer
+ * (Section 3.1: the learner loop loads trajectories, then learns and updates the
+ * model; the buffer loop receives what actors push): a device-resident replay
+ * ring whose transitions carry the policy version that produced them
+ * (Section 2.2: actors hold different policy versions at any time), a
+ * staleness-gated uniform minibatch sample (uniform rather than prioritised,
+ * Section 2.2), and one batched double-DQN update generalising the TD(0) policy
+ * update of Algorithm 1, with the Adam settings of Appendix E, Table 2.
+ *
+ * Conventions
+ *  - Every function returns TJ_OK (0) or a negative tj_status; none throws or
+ *    exits.  tj_strerror() names a status.
+ *  - "device pointer" = HIP device memory on the current device; "host pointer"
+ *    = ordinary host memory.  All bulk device memory (ring arena, minibatch,
+ *    learner arena) is owned by the caller and must outlive the handle; the
+ *    library never allocates or frees device memory.  Handles are small host
+ *    objects owned by the library until the matching destroy call.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *    insert / sample / learner_step only enqueue work on that stream and return
+ *    argument errors at once; data-dependent errors are reported through a
+ *    sticky device status word read by tj_buffer_status().
+ *  - Calls on one handle must be ordered by the caller (same stream, or events).
+ */
+#ifndef TIANJI_H
+#define TIANJI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TJ_OK = 0,
+    TJ_ERR_INVALID_ARG = -1,     /* null pointer, zero size, bad enum            */
+    TJ_ERR_SHAPE = -2,           /* dimensions the kernels do not support        */
+    TJ_ERR_ARENA_TOO_SMALL = -3, /* arena_bytes < tj_*_arena_bytes()             */
+    TJ_ERR_NO_ELIGIBLE = -4,     /* a sample found no slot inside the gate       */
+    TJ_ERR_CAPACITY = -5,        /* insert of more rows than the ring holds      */
+    TJ_ERR_DEVICE = -6           /* a HIP call failed                            */
+} tj_status;
+
+enum { TJ_OBS_F32 = 0, TJ_OBS_U8 = 1 };
+enum { TJ_PRECISION_FP32 = 0, TJ_PRECISION_BF16 = 1 };
+enum { TJ_LAYER_LINEAR = 0, TJ_LAYER_CONV2D = 1 };
+enum { TJ_MAX_LAYERS = 8 };
+
+typedef struct tj_buffer tj_buffer;
+typedef struct tj_learner tj_learner;
+
+/* ---------------------------------------------------------------- buffer */
+
+typedef struct {
+    uint64_t capacity;  /* ring slots N, 1 <= N < 2^32 - 1                      */
+    uint32_t obs_elems; /* elements of one observation (D, or C*H*W)            */
+    uint32_t obs_dtype; /* TJ_OBS_F32 or TJ_OBS_U8                              */
+} tj_buffer_desc;
+
+/* A dense minibatch in caller-owned device memory (structure of arrays):
+ * obs, next_obs [batch][obs_elems] in the ring's dtype; action i32, reward f32,
+ * done u8, idx u32 [batch] (idx = the sampled ring slots). */
+typedef struct {
+    void *obs;
+    void *next_obs;
+    int32_t *action;
+    float *reward;
+    uint8_t *done;
+    uint32_t *idx;
+    uint32_t batch;
+} tj_minibatch;
+
+typedef struct {
+    uint64_t capacity, head, count; /* ring state (host side)                    */
+    uint64_t last_n_eligible;       /* K of the most recent tj_sample            */
+    int32_t sticky_error;           /* TJ_OK or TJ_ERR_NO_ELIGIBLE               */
+} tj_buffer_info;
+
+/* Bytes of device memory tj_buffer_create needs for `desc` (0 if desc is bad). */
+size_t tj_buffer_arena_bytes(const tj_buffer_desc *desc);
+
+/* The Buffer component (Section 3.1).  `dev_arena` (device pointer, 256-byte
+ * aligned, arena_bytes >= tj_buffer_arena_bytes) holds the ring as a structure
+ * of arrays plus the sampler's scratch; the library zeroes its scratch on
+ * `hip_stream` and keeps the arena pointer, it does not own it. */
+int tj_buffer_create(const tj_buffer_desc *desc, void *dev_arena, size_t arena_bytes,
+                     void *hip_stream, tj_buffer **out);
+
+/* Releases the handle; never touches the arena. */
+int tj_buffer_destroy(tj_buffer *buf);
+
+/* Buffer receive (Section 3.1, buffer loop): append n transitions, each tagged
+ * with the version of the policy that produced it (Section 2.2).  Row i goes to
+ * slot (head+i) mod capacity; then head advances and count saturates at
+ * capacity.  All six sources are device pointers: d_obs/d_next_obs
+ * [n][obs_elems] in the ring's dtype, the others [n].  n > capacity returns
+ * TJ_ERR_CAPACITY and writes nothing; n == 0 is a no-op. */
+int tj_buffer_insert(tj_buffer *buf, uint32_t n, const void *d_obs, const void *d_next_obs,
+                     const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
+                     const int32_t *d_version, void *hip_stream);
+
+/* Learner load (Section 3.1, learner loop): a slot i < count is eligible iff
+ * 0 <= current_version - version[i] <= max_staleness.  With E the ascending
+ * list of eligible slots and K = |E|, draw j (0 <= j < batch) takes
+ * E[floor(SplitMix64(seed, j) * K / 2^64)] (uniform, with replacement), and
+ * minibatch row j is a copy of that ring row.  out->batch must equal `batch`
+ * and every pointer in *out is a device pointer of that many rows.  The mask is
+ * recomputed from the version tags on every call.  K == 0: idx is filled with
+ * 0xFFFFFFFF, the other minibatch fields are left untouched and the sticky
+ * status becomes TJ_ERR_NO_ELIGIBLE (see tj_buffer_status). */
+int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+              uint64_t seed, const tj_minibatch *out, void *hip_stream);
+
+/* Synchronises `hip_stream`, then reports ring state, the last K and the sticky
+ * status (which it clears).  Returns the sticky status. */
+int tj_buffer_status(tj_buffer *buf, tj_buffer_info *h_out, void *hip_stream);
+
+/* Device pointers into the arena, for tests: field 0 obs, 1 next_obs, 2 action,
+ * 3 reward, 4 done, 5 version.  NULL on a bad argument. */
+void *tj_buffer_field_ptr(tj_buffer *buf, int field);
+
+/* ---------------------------------------------------------------- learner */
+
+typedef struct {
+    uint32_t kind;   /* TJ_LAYER_LINEAR or TJ_LAYER_CONV2D (valid padding)       */
+    uint32_t out;    /* output features / channels                               */
+    uint32_t kernel; /* conv: square kernel size; linear: 0                      */
+    uint32_t stride; /* conv: stride; linear: 0                                  */
+} tj_layer;
+
+typedef struct {
+    uint32_t n_layers;               /* ReLU after every layer but the last       */
+    tj_layer layers[TJ_MAX_LAYERS];
+    uint32_t in_c, in_h, in_w;       /* one observation; vectors: (D, 1, 1)       */
+    uint32_t obs_dtype;              /* TJ_OBS_F32, or TJ_OBS_U8 (scaled by 1/255) */
+    uint32_t precision;              /* TJ_PRECISION_FP32 / _BF16 (GEMM operands
+                                        bf16, fp32 accumulate, fp32 master)       */
+    uint32_t max_batch;
+    float gamma, huber_delta;        /* discount (Table 2: 0.99), Huber kappa      */
+    float lr, beta1, beta2, eps;     /* Adam (Table 2: eps 1e-8)                   */
+    uint32_t target_interval;        /* hard target update period (Table 2), 0 = never */
+} tj_learner_desc;
+
+/* Written to device memory by tj_learner_step. */
+typedef struct {
+    float loss;        /* mean Huber loss of the minibatch                        */
+    uint32_t step;     /* t after this step (Adam's step count)                   */
+} tj_step_stats;
+
+enum {
+    TJ_STATE_PARAMS = 0,  /* online parameters, fp32 master [P]                   */
+    TJ_STATE_TARGET = 1,  /* target parameters [P]                                */
+    TJ_STATE_GRADS = 2,   /* gradient of the last step [P] (get only)             */
+    TJ_STATE_ADAM_M = 3,  /* first moment [P]                                     */
+    TJ_STATE_ADAM_V = 4,  /* second moment [P]                                    */
+    TJ_STATE_QVALS = 5,   /* last step: Q_online(s), Q_online(s'), Q_target(s'),
+                             each [batch][A], concatenated (get only)             */
+    TJ_STATE_ASTAR = 6    /* last step: greedy next actions as floats [batch]
+                             (get only)                                           */
+};
+
+/* Number of parameters P of the network in `desc` (0 if desc is bad).  Flat
+ * order: layer by layer, weight [out][in] (conv [Cout][Cin][kh][kw]; a linear
+ * layer after a conv sees its input flattened as (C, H, W)), then bias [out]. */
+size_t tj_learner_num_params(const tj_learner_desc *desc);
+
+size_t tj_learner_arena_bytes(const tj_learner_desc *desc);
+
+/* The Learner's model state (Section 3.1).  h_init_online / h_init_target: host
+ * pointers to P floats each.  Adam moments start at zero, t at 0.  Copies are
+ * enqueued on hip_stream and complete before this returns. */
+int tj_learner_create(const tj_learner_desc *desc, void *dev_arena, size_t arena_bytes,
+                      const float *h_init_online, const float *h_init_target, void *hip_stream,
+                      tj_learner **out);
+
+int tj_learner_destroy(tj_learner *lrn);
+
+/* One policy update (Algorithm 1, "Policy update", batched): with Q_on / Q_tg
+ * the online and target networks,
+ *   a*_j = argmax_a Q_on(s'_j, a)            (lowest index on ties)
+ *   y_j  = r_j + gamma (1 - done_j) Q_tg(s'_j, a*_j)
+ *   d_j  = Q_on(s_j, a_j) - y_j
+ *   L    = mean_j Huber_kappa(d_j)
+ * gradients of L flow through Q_on(s) only; then Adam (bias-corrected, eps added
+ * outside the square root) with t = 1, 2, ...; then, if t is a multiple of
+ * target_interval, the target parameters become a copy of the online ones.
+ * `mb` holds device pointers (idx is not read); mb->batch <= max_batch.
+ * d_stats (device pointer, may be NULL) receives loss and t. */
+int tj_learner_step(tj_learner *lrn, const tj_minibatch *mb, tj_step_stats *d_stats,
+                    void *hip_stream);
+
+/* Synchronising host copies of learner state (h_out / h_in: host pointers to n
+ * floats; n must match the size given at the enum).  set_state accepts PARAMS,
+ * TARGET, ADAM_M, ADAM_V and refreshes the derived weight copies. */
+int tj_learner_get_state(tj_learner *lrn, int which, float *h_out, size_t n, void *hip_stream);
+int tj_learner_set_state(tj_learner *lrn, int which, const float *h_in, size_t n,
+                         void *hip_stream);
+
+/* Adam's step count t (set it together with the moments when resuming). */
+int tj_learner_get_step(tj_learner *lrn, uint64_t *h_t);
+int tj_learner_set_step(tj_learner *lrn, uint64_t t);
+
+/* ---------------------------------------------------------------- timing */
+
+/* Optional phase timing for benchmarks.  `hip_events` is a host array of
+ * hipEvent_t (created by the caller with timing enabled, passed as void*), or
+ * NULL / n == 0 to switch timing off.  While set, every tj_sample records
+ *   [0] start, [1] after mask + scan + select, [2] after the row gather
+ * (n must be 3), and every tj_learner_step records
+ *   [0] after the input cast, [1] after the forward GEMMs, [2] after the TD /
+ *   Huber kernel, [3] after the backward GEMMs, [4] after Adam and the weight
+ *   recast (n must be 5),
+ * on the call's stream.  The caller reads them after synchronising. */
+int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n);
+int tj_learner_set_phase_events(tj_learner *lrn, void *const *hip_events, uint32_t n);
+
+const char *tj_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIANJI_H */

@@ -1,0 +1,366 @@
+"""Thin ctypes binding of libtianji_hip.so (see include/tianji.h).
+
+Argument marshalling only: torch supplies device memory and streams, every step
+of the path runs in the library's HIP kernels.  There is no CPU fallback: if the
+library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtianji_hip.so")
+
+TJ_OK = 0
+TJ_ERR_INVALID_ARG, TJ_ERR_SHAPE, TJ_ERR_ARENA_TOO_SMALL = -1, -2, -3
+TJ_ERR_NO_ELIGIBLE, TJ_ERR_CAPACITY, TJ_ERR_DEVICE = -4, -5, -6
+TJ_OBS_F32, TJ_OBS_U8 = 0, 1
+TJ_PRECISION_FP32, TJ_PRECISION_BF16 = 0, 1
+TJ_LAYER_LINEAR, TJ_LAYER_CONV2D = 0, 1
+TJ_MAX_LAYERS = 8
+(TJ_STATE_PARAMS, TJ_STATE_TARGET, TJ_STATE_GRADS, TJ_STATE_ADAM_M, TJ_STATE_ADAM_V, TJ_STATE_QVALS,
+ TJ_STATE_ASTAR) = range(7)
+
+EXPORTS = [
+    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_sample",
+    "tj_buffer_status", "tj_buffer_field_ptr", "tj_learner_num_params", "tj_learner_arena_bytes",
+    "tj_learner_create", "tj_learner_destroy", "tj_learner_step", "tj_learner_get_state",
+    "tj_learner_set_state", "tj_learner_get_step", "tj_learner_set_step", "tj_strerror",
+    "tj_buffer_set_phase_events", "tj_learner_set_phase_events",
+]
+
+
+class tj_buffer_desc(C.Structure):
+    _fields_ = [("capacity", C.c_uint64), ("obs_elems", C.c_uint32), ("obs_dtype", C.c_uint32)]
+
+
+class tj_minibatch(C.Structure):
+    _fields_ = [("obs", C.c_void_p), ("next_obs", C.c_void_p), ("action", C.c_void_p),
+                ("reward", C.c_void_p), ("done", C.c_void_p), ("idx", C.c_void_p), ("batch", C.c_uint32)]
+
+
+class tj_buffer_info(C.Structure):
+    _fields_ = [("capacity", C.c_uint64), ("head", C.c_uint64), ("count", C.c_uint64),
+                ("last_n_eligible", C.c_uint64), ("sticky_error", C.c_int32)]
+
+
+class tj_layer(C.Structure):
+    _fields_ = [("kind", C.c_uint32), ("out", C.c_uint32), ("kernel", C.c_uint32), ("stride", C.c_uint32)]
+
+
+class tj_learner_desc(C.Structure):
+    _fields_ = [("n_layers", C.c_uint32), ("layers", tj_layer * TJ_MAX_LAYERS), ("in_c", C.c_uint32),
+                ("in_h", C.c_uint32), ("in_w", C.c_uint32), ("obs_dtype", C.c_uint32),
+                ("precision", C.c_uint32), ("max_batch", C.c_uint32), ("gamma", C.c_float),
+                ("huber_delta", C.c_float), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("target_interval", C.c_uint32)]
+
+
+class tj_step_stats(C.Structure):
+    _fields_ = [("loss", C.c_float), ("step", C.c_uint32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  torch is imported first so that both share one HIP runtime."""
+    global _lib
+    if _lib is None:
+        import torch  # noqa: F401  (loads libamdhip64 before our library binds to it)
+
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        vp, u32, u64, i64, sz, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int64, C.c_size_t, C.c_int
+        L.tj_buffer_arena_bytes.restype = sz
+        L.tj_buffer_arena_bytes.argtypes = [C.POINTER(tj_buffer_desc)]
+        L.tj_buffer_create.restype = i32
+        L.tj_buffer_create.argtypes = [C.POINTER(tj_buffer_desc), vp, sz, vp, C.POINTER(vp)]
+        L.tj_buffer_destroy.restype = i32
+        L.tj_buffer_destroy.argtypes = [vp]
+        L.tj_buffer_insert.restype = i32
+        L.tj_buffer_insert.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp, vp]
+        L.tj_sample.restype = i32
+        L.tj_sample.argtypes = [vp, u32, i64, i64, u64, C.POINTER(tj_minibatch), vp]
+        L.tj_buffer_status.restype = i32
+        L.tj_buffer_status.argtypes = [vp, C.POINTER(tj_buffer_info), vp]
+        L.tj_buffer_field_ptr.restype = vp
+        L.tj_buffer_field_ptr.argtypes = [vp, i32]
+        L.tj_learner_num_params.restype = sz
+        L.tj_learner_num_params.argtypes = [C.POINTER(tj_learner_desc)]
+        L.tj_learner_arena_bytes.restype = sz
+        L.tj_learner_arena_bytes.argtypes = [C.POINTER(tj_learner_desc)]
+        L.tj_learner_create.restype = i32
+        L.tj_learner_create.argtypes = [C.POINTER(tj_learner_desc), vp, sz, vp, vp, vp, C.POINTER(vp)]
+        L.tj_learner_destroy.restype = i32
+        L.tj_learner_destroy.argtypes = [vp]
+        L.tj_learner_step.restype = i32
+        L.tj_learner_step.argtypes = [vp, C.POINTER(tj_minibatch), vp, vp]
+        L.tj_learner_get_state.restype = i32
+        L.tj_learner_get_state.argtypes = [vp, i32, vp, sz, vp]
+        L.tj_learner_set_state.restype = i32
+        L.tj_learner_set_state.argtypes = [vp, i32, vp, sz, vp]
+        L.tj_learner_get_step.restype = i32
+        L.tj_learner_get_step.argtypes = [vp, C.POINTER(u64)]
+        L.tj_learner_set_step.restype = i32
+        L.tj_learner_set_step.argtypes = [vp, u64]
+        L.tj_buffer_set_phase_events.restype = i32
+        L.tj_buffer_set_phase_events.argtypes = [vp, C.POINTER(vp), u32]
+        L.tj_learner_set_phase_events.restype = i32
+        L.tj_learner_set_phase_events.argtypes = [vp, C.POINTER(vp), u32]
+        L.tj_strerror.restype = C.c_char_p
+        L.tj_strerror.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def tj_strerror(status: int) -> str:
+    return lib().tj_strerror(status).decode()
+
+
+class TjError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {tj_strerror(status)} ({status})")
+        self.status = status
+
+
+def _check(status: int, where: str) -> None:
+    if status != TJ_OK:
+        raise TjError(status, where)
+
+
+def _stream_ptr(stream=None) -> int:
+    import torch
+
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _require_gpu():
+    import torch
+
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU: the HIP path has no CPU fallback")
+
+
+class Minibatch:
+    """Caller-owned device tensors for one dense minibatch."""
+
+    def __init__(self, batch: int, obs_elems: int, obs_dtype: str, device="cuda:0"):
+        import torch
+
+        tdt = torch.float32 if obs_dtype == "f32" else torch.uint8
+        self.batch = batch
+        self.obs = torch.empty((batch, obs_elems), dtype=tdt, device=device)
+        self.next_obs = torch.empty((batch, obs_elems), dtype=tdt, device=device)
+        self.action = torch.empty(batch, dtype=torch.int32, device=device)
+        self.reward = torch.empty(batch, dtype=torch.float32, device=device)
+        self.done = torch.empty(batch, dtype=torch.uint8, device=device)
+        self.idx = torch.empty(batch, dtype=torch.int32, device=device)   # bits are uint32
+        self.c = tj_minibatch(self.obs.data_ptr(), self.next_obs.data_ptr(), self.action.data_ptr(),
+                              self.reward.data_ptr(), self.done.data_ptr(), self.idx.data_ptr(), batch)
+
+    def load(self, obs, next_obs, action, reward, done) -> None:
+        """Fill from host arrays (tests feed the learner without a ring)."""
+        import torch
+
+        self.obs.copy_(torch.from_numpy(np.ascontiguousarray(obs)).reshape(self.obs.shape))
+        self.next_obs.copy_(torch.from_numpy(np.ascontiguousarray(next_obs)).reshape(self.obs.shape))
+        self.action.copy_(torch.from_numpy(np.ascontiguousarray(action, np.int32)))
+        self.reward.copy_(torch.from_numpy(np.ascontiguousarray(reward, np.float32)))
+        self.done.copy_(torch.from_numpy(np.ascontiguousarray(done, np.uint8)))
+
+    def host(self):
+        out = {k: getattr(self, k).cpu().numpy() for k in ("obs", "next_obs", "action", "reward", "done")}
+        out["idx"] = self.idx.cpu().numpy().view(np.uint32)
+        return out
+
+
+class Buffer:
+    """tj_buffer_* over a torch-allocated arena."""
+
+    def __init__(self, capacity: int, obs_elems: int, obs_dtype: str, device="cuda:0", stream=None):
+        import torch
+
+        _require_gpu()
+        self.obs_dtype, self.obs_elems, self.capacity, self.device = obs_dtype, obs_elems, capacity, device
+        self.desc = tj_buffer_desc(capacity, obs_elems, TJ_OBS_F32 if obs_dtype == "f32" else TJ_OBS_U8)
+        nbytes = lib().tj_buffer_arena_bytes(C.byref(self.desc))
+        if nbytes == 0:
+            raise TjError(TJ_ERR_INVALID_ARG, "tj_buffer_arena_bytes")
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        self.arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
+        self.arena_bytes = nbytes
+        h = C.c_void_p()
+        _check(lib().tj_buffer_create(C.byref(self.desc), self.arena_ptr, nbytes, _stream_ptr(stream),
+                                      C.byref(h)), "tj_buffer_create")
+        self.h = h
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().tj_buffer_destroy(self.h)
+            self.h = None
+
+    def insert(self, obs, next_obs, action, reward, done, version, stream=None) -> None:
+        """All arguments are device tensors (torch), n = len(action)."""
+        n = int(action.shape[0])
+        self._keep = (obs, next_obs, action, reward, done, version)   # alive until the next call
+        _check(lib().tj_buffer_insert(self.h, n, obs.data_ptr(), next_obs.data_ptr(), action.data_ptr(),
+                                      reward.data_ptr(), done.data_ptr(), version.data_ptr(),
+                                      _stream_ptr(stream)), "tj_buffer_insert")
+
+    def insert_host(self, rows: dict, stream=None) -> None:
+        import torch
+
+        dev = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.device) for k, v in rows.items()}
+        self.insert(dev["obs"], dev["next_obs"], dev["action"], dev["reward"], dev["done"], dev["version"],
+                    stream)
+        torch.cuda.current_stream().synchronize()
+
+    def sample(self, mb: Minibatch, current_version: int, max_staleness: int, seed: int, stream=None) -> int:
+        return lib().tj_sample(self.h, mb.batch, current_version, max_staleness, seed & (2**64 - 1),
+                               C.byref(mb.c), _stream_ptr(stream))
+
+    def status(self, stream=None):
+        info = tj_buffer_info()
+        st = lib().tj_buffer_status(self.h, C.byref(info), _stream_ptr(stream))
+        return st, info
+
+    def field(self, name: str):
+        """A torch view of one ring field (tests only)."""
+        import torch
+
+        fid = ["obs", "next_obs", "action", "reward", "done", "version"].index(name)
+        ptr = lib().tj_buffer_field_ptr(self.h, fid)
+        off = ptr - self.arena.data_ptr()
+        n = self.capacity
+        if fid < 2:
+            eb = 4 if self.obs_dtype == "f32" else 1
+            raw = self.arena[off:off + n * self.obs_elems * eb]
+            dt = torch.float32 if self.obs_dtype == "f32" else torch.uint8
+            return raw.view(dt).reshape(n, self.obs_elems)
+        dt, eb = {2: (torch.int32, 4), 3: (torch.float32, 4), 4: (torch.uint8, 1), 5: (torch.int32, 4)}[fid]
+        return self.arena[off:off + n * eb].view(dt)
+
+
+def make_learner_desc(layers, in_chw, obs_dtype: str, precision: str, max_batch: int, gamma: float,
+                      kappa: float, lr: float, beta1: float, beta2: float, eps: float,
+                      target_interval: int) -> tj_learner_desc:
+    d = tj_learner_desc()
+    d.n_layers = len(layers)
+    for i, (kind, out, k, s) in enumerate(layers):
+        d.layers[i] = tj_layer(kind, out, k, s)
+    d.in_c, d.in_h, d.in_w = in_chw
+    d.obs_dtype = TJ_OBS_F32 if obs_dtype == "f32" else TJ_OBS_U8
+    d.precision = TJ_PRECISION_FP32 if precision == "fp32" else TJ_PRECISION_BF16
+    d.max_batch = max_batch
+    d.gamma, d.huber_delta, d.lr, d.beta1, d.beta2, d.eps = gamma, kappa, lr, beta1, beta2, eps
+    d.target_interval = target_interval
+    return d
+
+
+class Learner:
+    """tj_learner_* over a torch-allocated arena."""
+
+    def __init__(self, desc: tj_learner_desc, init_online: np.ndarray, init_target: np.ndarray,
+                 device="cuda:0", stream=None):
+        import torch
+
+        _require_gpu()
+        self.desc = desc
+        self.n_params = lib().tj_learner_num_params(C.byref(desc))
+        nbytes = lib().tj_learner_arena_bytes(C.byref(desc))
+        if nbytes == 0 or self.n_params == 0:
+            raise TjError(TJ_ERR_SHAPE, "tj_learner_arena_bytes")
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        self.arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
+        on = np.ascontiguousarray(init_online, np.float32)
+        tg = np.ascontiguousarray(init_target, np.float32)
+        assert on.size == self.n_params and tg.size == self.n_params
+        h = C.c_void_p()
+        _check(lib().tj_learner_create(C.byref(desc), self.arena_ptr, nbytes, on.ctypes.data, tg.ctypes.data,
+                                       _stream_ptr(stream), C.byref(h)), "tj_learner_create")
+        self.h = h
+        self.stats = torch.zeros(2, dtype=torch.int32, device=device)   # tj_step_stats {f32, u32}
+        self.n_actions = desc.layers[desc.n_layers - 1].out
+        self.last_batch = 0
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().tj_learner_destroy(self.h)
+            self.h = None
+
+    def step(self, mb: Minibatch, stream=None) -> int:
+        self.last_batch = mb.batch
+        return lib().tj_learner_step(self.h, C.byref(mb.c), self.stats.data_ptr(), _stream_ptr(stream))
+
+    def read_stats(self):
+        raw = self.stats.cpu().numpy()
+        return float(raw.view(np.float32)[0]), int(raw.view(np.uint32)[1])
+
+    def get_state(self, which: int, stream=None) -> np.ndarray:
+        if which == TJ_STATE_QVALS:
+            n = 3 * self.last_batch * self.n_actions
+        elif which == TJ_STATE_ASTAR:
+            n = self.last_batch
+        else:
+            n = self.n_params
+        out = np.empty(n, np.float32)
+        _check(lib().tj_learner_get_state(self.h, which, out.ctypes.data, n, _stream_ptr(stream)),
+               "tj_learner_get_state")
+        return out
+
+    def set_state(self, which: int, values, stream=None) -> None:
+        v = np.ascontiguousarray(values, np.float32)
+        _check(lib().tj_learner_set_state(self.h, which, v.ctypes.data, v.size, _stream_ptr(stream)),
+               "tj_learner_set_state")
+
+    @property
+    def t(self) -> int:
+        t = C.c_uint64(0)
+        _check(lib().tj_learner_get_step(self.h, C.byref(t)), "tj_learner_get_step")
+        return t.value
+
+    @t.setter
+    def t(self, value: int) -> None:
+        _check(lib().tj_learner_set_step(self.h, value), "tj_learner_set_step")
+
+
+def learner_for_workload(wl, init_online, init_target, device="cuda:0", max_batch: Optional[int] = None):
+    desc = make_learner_desc(wl.layers, wl.in_chw, wl.obs_dtype, wl.precision, max_batch or wl.batch,
+                             wl.gamma, wl.kappa, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.target_interval)
+    return Learner(desc, init_online, init_target, device=device)
+
+
+class HipEvents:
+    """n timing-enabled hipEvent_t created through the HIP runtime that torch loaded."""
+
+    def __init__(self, n: int):
+        import torch  # noqa: F401
+
+        self.rt = C.CDLL("libamdhip64.so.7")
+        self.rt.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.rt.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.rt.hipEventDestroy.argtypes = [C.c_void_p]
+        self.ev = (C.c_void_p * n)()
+        for i in range(n):
+            e = C.c_void_p()
+            if self.rt.hipEventCreate(C.byref(e)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.ev[i] = e
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        ms = C.c_float(0)
+        if self.rt.hipEventElapsedTime(C.byref(ms), self.ev[i], self.ev[j]) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value
+
+    def __del__(self):
+        for e in getattr(self, "ev", []):
+            if e:
+                self.rt.hipEventDestroy(e)

@@ -1,0 +1,499 @@
+// Replay ring buffer with policy-version tags and the staleness-gated uniform
+// sampler (Buffer component and learner load of Section 3.1 of the paper).
+//
+// Device layout (structure of arrays inside the caller's arena):
+//   obs, next_obs  [N][row_bytes]      action i32 [N]   reward f32 [N]
+//   done u8 [N]    version i32 [N]
+//   mask  u64 [ceil(N/64)]  bit b of word w = slot 64w+b is eligible
+//   tile_count / tile_off u32 [ceil(N/1024)]   state u32 [4] {sticky, K, -, -}
+//
+// tj_sample = four kernels on one stream:
+//   1 stale_mask_count : coalesced read of the tags, wave ballot -> mask words,
+//                        popcount -> per-tile counts            (HBM bound, 4N B)
+//   2 tile_scan        : exclusive prefix sum of tile counts, K (one block)
+//   3 select_slots     : per draw: SplitMix64, mul-high range reduction, binary
+//                        search over tile offsets, popcount walk over the tile's
+//                        mask words, k-th set bit; copies the scalar fields
+//   4 copy_rows        : gathers obs / next_obs rows with 16-byte lanes
+//                        (HBM bound, 2*B*row_bytes read + written)
+#include "tj_common.h"
+
+namespace {
+
+constexpr int kTile = 1024;        // slots per tile
+constexpr int kWordsPerTile = kTile / 64;
+constexpr uint32_t kInvalid = 0xFFFFFFFFu;
+
+struct RingPtrs {
+    uint8_t *obs, *next_obs;
+    int32_t *action;
+    float *reward;
+    uint8_t *done;
+    int32_t *version;
+};
+
+// ---------------------------------------------------------------- sampler
+
+// One block per tile of 1024 slots, four waves, each wave 4 x 64 slots.
+__global__ __launch_bounds__(256) void stale_mask_count(const int32_t *__restrict__ version,
+                                                        uint32_t count, int64_t cur, int64_t max_st,
+                                                        unsigned long long *__restrict__ mask,
+                                                        uint32_t *__restrict__ tile_count)
+{
+    __shared__ uint32_t wave_cnt[4];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t base = blockIdx.x * kTile + wave * 256;
+    int32_t v[4];
+    bool ok[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        uint32_t s = base + r * 64 + lane;
+        ok[r] = s < count;
+        v[r] = ok[r] ? version[s] : 0;
+    }
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        int64_t st = cur - (int64_t)v[r];
+        bool e = ok[r] && st >= 0 && st <= max_st;
+        unsigned long long b = __ballot(e);
+        uint32_t w = (base >> 6) + r;
+        if (lane == 0) mask[w] = b;   // the mask array is padded to whole tiles
+        cnt += __popcll(b);
+    }
+    if (lane == 0) wave_cnt[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        tile_count[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+}
+
+// Exclusive scan of the tile counts by one block of 1024 threads; K to state[1];
+// K == 0 raises the sticky status.
+__global__ __launch_bounds__(1024) void tile_scan(const uint32_t *__restrict__ tile_count,
+                                                  uint32_t n_tiles, uint32_t *__restrict__ tile_off,
+                                                  uint32_t *__restrict__ state)
+{
+    __shared__ uint32_t wave_sum[16];
+    __shared__ uint32_t carry;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < n_tiles; base += 1024) {
+        uint32_t t = base + threadIdx.x;
+        uint32_t c = t < n_tiles ? tile_count[t] : 0;
+        uint32_t incl = c;                      // inclusive scan inside the wave
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint32_t up = __shfl_up(incl, d, 64);
+            if (lane >= (uint32_t)d) incl += up;
+        }
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        uint32_t before = carry;
+        for (uint32_t w = 0; w < wave; ++w) before += wave_sum[w];
+        if (t < n_tiles) tile_off[t] = before + incl - c;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = before + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        state[1] = carry;
+        if (carry == 0) state[0] = (uint32_t)TJ_ERR_NO_ELIGIBLE;
+    }
+}
+
+__device__ __forceinline__ uint64_t splitmix64(uint64_t seed, uint64_t j)
+{
+    uint64_t z = seed + (j + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// One thread per draw.
+__global__ __launch_bounds__(256) void select_slots(
+    const unsigned long long *__restrict__ mask, const uint32_t *__restrict__ tile_off,
+    uint32_t n_tiles, const uint32_t *__restrict__ state, uint64_t seed, uint32_t batch,
+    RingPtrs ring, uint32_t *__restrict__ idx, int32_t *__restrict__ action,
+    float *__restrict__ reward, uint8_t *__restrict__ done)
+{
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= batch) return;
+    const uint32_t K = state[1];
+    if (K == 0) {
+        idx[j] = kInvalid;
+        return;
+    }
+    uint32_t k = (uint32_t)__umul64hi(splitmix64(seed, j), (uint64_t)K);
+    // last tile t with tile_off[t] <= k
+    uint32_t lo = 0, hi = n_tiles;
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (tile_off[mid] <= k) lo = mid; else hi = mid;
+    }
+    uint32_t rem = k - tile_off[lo];
+    uint32_t w = lo * kWordsPerTile;
+    unsigned long long m = mask[w];
+    uint32_t c = __popcll(m);
+    // K > 0 guarantees the walk ends inside this tile
+    for (int i = 1; i < kWordsPerTile && rem >= c; ++i) {
+        rem -= c;
+        ++w;
+        m = mask[w];
+        c = __popcll(m);
+    }
+    for (uint32_t i = 0; i < rem; ++i) m &= m - 1;   // drop the rem lowest set bits
+    uint32_t slot = w * 64 + (uint32_t)(__ffsll((long long)m) - 1);
+    idx[j] = slot;
+    action[j] = ring.action[slot];
+    reward[j] = ring.reward[slot];
+    done[j] = ring.done[slot];
+}
+
+// ---------------------------------------------------------------- row copies
+
+// mode 0 (gather): dst row r <- src row idx[r];  mode 1 (insert): dst row
+// (head + r) mod cap <- src row r.  Rows are `vpr` vectors of type V.
+// blockIdx.x = row, blockIdx.y = chunk of 256*U vectors inside the row,
+// blockIdx.z selects the field (obs / next_obs).
+template <typename V, int U>
+__global__ __launch_bounds__(256) void copy_rows_wide(const V *__restrict__ src0, V *__restrict__ dst0,
+                                                      const V *__restrict__ src1, V *__restrict__ dst1,
+                                                      uint32_t vpr, const uint32_t *__restrict__ idx,
+                                                      int mode, uint64_t head, uint64_t cap)
+{
+    const uint32_t r = blockIdx.x;
+    const V *src = blockIdx.z ? src1 : src0;
+    V *dst = blockIdx.z ? dst1 : dst0;
+    uint64_t srow, drow;
+    if (mode == 0) {
+        uint32_t s = idx[r];
+        if (s == kInvalid) return;
+        srow = s; drow = r;
+    } else {
+        srow = r; drow = head + r; if (drow >= cap) drow -= cap;
+    }
+    const V *sp = src + srow * vpr;
+    V *dp = dst + drow * vpr;
+    const uint32_t c0 = blockIdx.y * (256 * U) + threadIdx.x;
+    V tmp[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t c = c0 + u * 256;
+        if (c < vpr) tmp[u] = sp[c];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t c = c0 + u * 256;
+        if (c < vpr) dp[c] = tmp[u];
+    }
+}
+
+// Narrow rows (vpr < 256): flat index over rows*vpr vectors, several rows per block.
+template <typename V, int U>
+__global__ __launch_bounds__(256) void copy_rows_narrow(const V *__restrict__ src0, V *__restrict__ dst0,
+                                                        const V *__restrict__ src1, V *__restrict__ dst1,
+                                                        uint32_t vpr, uint32_t rows,
+                                                        const uint32_t *__restrict__ idx, int mode,
+                                                        uint64_t head, uint64_t cap)
+{
+    const V *src = blockIdx.z ? src1 : src0;
+    V *dst = blockIdx.z ? dst1 : dst0;
+    const uint32_t total = rows * vpr;
+    const uint32_t f0 = blockIdx.x * (256 * U) + threadIdx.x;
+    V tmp[U];
+    uint64_t daddr[U];
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t f = f0 + u * 256;
+        live[u] = f < total;
+        if (!live[u]) continue;
+        uint32_t r = f / vpr, c = f - r * vpr;
+        uint64_t srow, drow;
+        if (mode == 0) {
+            uint32_t s = idx[r];
+            if (s == kInvalid) { live[u] = false; continue; }
+            srow = s; drow = r;
+        } else {
+            srow = r; drow = head + r; if (drow >= cap) drow -= cap;
+        }
+        tmp[u] = src[srow * vpr + c];
+        daddr[u] = drow * vpr + c;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) dst[daddr[u]] = tmp[u];
+}
+
+// The four scalar fields of an insert: slot (head + i) mod cap <- row i.
+__global__ __launch_bounds__(256) void insert_scalars(RingPtrs ring, uint32_t n,
+                                                      const int32_t *__restrict__ action,
+                                                      const float *__restrict__ reward,
+                                                      const uint8_t *__restrict__ done,
+                                                      const int32_t *__restrict__ version,
+                                                      uint64_t head, uint64_t cap)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint64_t s = head + i;
+    if (s >= cap) s -= cap;
+    ring.action[s] = action[i];
+    ring.reward[s] = reward[i];
+    ring.done[s] = done[i];
+    ring.version[s] = version[i];
+}
+
+__global__ void zero_words(uint32_t *p, uint32_t n)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+template <typename V>
+int launch_copy_rows(const void *s0, void *d0, const void *s1, void *d1, uint32_t row_bytes,
+                     uint32_t rows, const uint32_t *idx, int mode, uint64_t head, uint64_t cap,
+                     hipStream_t st)
+{
+    const uint32_t vpr = row_bytes / sizeof(V);
+    if (vpr >= 256) {
+        // U vectors per thread: one block covers up to 256*U vectors of a row
+        if (vpr <= 256 * 2) {
+            dim3 g2(rows, (vpr + 511) / 512, 2);
+            copy_rows_wide<V, 2><<<g2, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
+                                                     idx, mode, head, cap);
+        } else if (vpr <= 256 * 4) {
+            dim3 g4(rows, (vpr + 1023) / 1024, 2);
+            copy_rows_wide<V, 4><<<g4, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
+                                                     idx, mode, head, cap);
+        } else {
+            dim3 g8(rows, (vpr + 2047) / 2048, 2);
+            copy_rows_wide<V, 8><<<g8, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
+                                                     idx, mode, head, cap);
+        }
+    } else {
+        constexpr int U = 4;
+        // rows * vpr must fit 32 bits: callers split larger jobs
+        uint64_t total = (uint64_t)rows * vpr;
+        dim3 grid((uint32_t)((total + 256 * U - 1) / (256 * U)), 1, 2);
+        copy_rows_narrow<V, U><<<grid, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
+                                                     rows, idx, mode, head, cap);
+    }
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+int copy_rows(const void *s0, void *d0, const void *s1, void *d1, uint32_t row_bytes, uint32_t rows,
+              const uint32_t *idx, int mode, uint64_t head, uint64_t cap, hipStream_t st)
+{
+    if (rows == 0) return TJ_OK;
+    auto aligned = [&](size_t a) {
+        return row_bytes % a == 0 && ((uintptr_t)s0 | (uintptr_t)d0 | (uintptr_t)s1 | (uintptr_t)d1) % a == 0;
+    };
+    if (aligned(16)) return launch_copy_rows<uint4>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st);
+    if (aligned(4)) return launch_copy_rows<uint32_t>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st);
+    return launch_copy_rows<uint8_t>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st);
+}
+
+size_t layout(const tj_buffer_desc *d, TjArena &a, RingPtrs *ring, unsigned long long **mask,
+              uint32_t **tile_count, uint32_t **tile_off, uint32_t **state)
+{
+    const uint64_t n = d->capacity;
+    const size_t row = (size_t)d->obs_elems * (d->obs_dtype == TJ_OBS_F32 ? 4 : 1);
+    const uint64_t n_tiles = (n + kTile - 1) / kTile;
+    RingPtrs r;
+    r.obs = (uint8_t *)a.take(n * row);
+    r.next_obs = (uint8_t *)a.take(n * row);
+    r.action = (int32_t *)a.take(n * 4);
+    r.reward = (float *)a.take(n * 4);
+    r.done = (uint8_t *)a.take(n);
+    r.version = (int32_t *)a.take(n * 4);
+    unsigned long long *m = (unsigned long long *)a.take(n_tiles * kWordsPerTile * 8);
+    uint32_t *tc = (uint32_t *)a.take(n_tiles * 4);
+    uint32_t *to = (uint32_t *)a.take(n_tiles * 4);
+    uint32_t *s = (uint32_t *)a.take(16);
+    if (ring) *ring = r;
+    if (mask) *mask = m;
+    if (tile_count) *tile_count = tc;
+    if (tile_off) *tile_off = to;
+    if (state) *state = s;
+    return a.off;
+}
+
+bool desc_ok(const tj_buffer_desc *d)
+{
+    return d && d->capacity >= 1 && d->capacity < 0xFFFFFFFFull && d->obs_elems >= 1 &&
+           (d->obs_dtype == TJ_OBS_F32 || d->obs_dtype == TJ_OBS_U8);
+}
+
+}  // namespace
+
+struct tj_buffer {
+    tj_buffer_desc desc;
+    RingPtrs ring;
+    unsigned long long *mask;
+    uint32_t *tile_count, *tile_off, *state;
+    uint32_t row_bytes, n_tiles;
+    uint64_t head, count;
+    hipEvent_t ev[3];
+    bool timed;
+};
+
+extern "C" {
+
+size_t tj_buffer_arena_bytes(const tj_buffer_desc *desc)
+{
+    if (!desc_ok(desc)) return 0;
+    TjArena a(nullptr);
+    return layout(desc, a, nullptr, nullptr, nullptr, nullptr, nullptr);
+}
+
+int tj_buffer_create(const tj_buffer_desc *desc, void *dev_arena, size_t arena_bytes, void *hip_stream,
+                     tj_buffer **out)
+{
+    if (!out) return TJ_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!desc_ok(desc) || !dev_arena || ((uintptr_t)dev_arena & 255)) return TJ_ERR_INVALID_ARG;
+    if (arena_bytes < tj_buffer_arena_bytes(desc)) return TJ_ERR_ARENA_TOO_SMALL;
+    tj_buffer *b = new tj_buffer();
+    b->desc = *desc;
+    TjArena a(dev_arena);
+    layout(desc, a, &b->ring, &b->mask, &b->tile_count, &b->tile_off, &b->state);
+    b->row_bytes = desc->obs_elems * (desc->obs_dtype == TJ_OBS_F32 ? 4u : 1u);
+    b->n_tiles = (uint32_t)((desc->capacity + kTile - 1) / kTile);
+    b->head = b->count = 0;
+    b->timed = false;
+    zero_words<<<1, 64, 0, (hipStream_t)hip_stream>>>(b->state, 4);
+    if (hipGetLastError() != hipSuccess) {
+        delete b;
+        return TJ_ERR_DEVICE;
+    }
+    *out = b;
+    return TJ_OK;
+}
+
+int tj_buffer_destroy(tj_buffer *buf)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    delete buf;
+    return TJ_OK;
+}
+
+int tj_buffer_insert(tj_buffer *buf, uint32_t n, const void *d_obs, const void *d_next_obs,
+                     const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
+                     const int32_t *d_version, void *hip_stream)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    if (n == 0) return TJ_OK;
+    if (!d_obs || !d_next_obs || !d_action || !d_reward || !d_done || !d_version) return TJ_ERR_INVALID_ARG;
+    const uint64_t cap = buf->desc.capacity;
+    if ((uint64_t)n > cap) return TJ_ERR_CAPACITY;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // narrow rows use a flat 32-bit vector index: split very large inserts
+    const uint32_t max_rows = 1u << 20;
+    for (uint32_t done_rows = 0; done_rows < n; done_rows += max_rows) {
+        uint32_t rows = n - done_rows < max_rows ? n - done_rows : max_rows;
+        uint64_t head = (buf->head + done_rows) % cap;
+        size_t off = (size_t)done_rows * buf->row_bytes;
+        int rc = copy_rows((const uint8_t *)d_obs + off, buf->ring.obs, (const uint8_t *)d_next_obs + off,
+                           buf->ring.next_obs, buf->row_bytes, rows, nullptr, 1, head, cap, st);
+        if (rc != TJ_OK) return rc;
+    }
+    insert_scalars<<<(n + 255) / 256, 256, 0, st>>>(buf->ring, n, d_action, d_reward, d_done, d_version,
+                                                    buf->head, cap);
+    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+    buf->head = (buf->head + n) % cap;
+    buf->count = buf->count + n < cap ? buf->count + n : cap;
+    return TJ_OK;
+}
+
+int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+              uint64_t seed, const tj_minibatch *out, void *hip_stream)
+{
+    if (!buf || !out || batch == 0 || out->batch != batch) return TJ_ERR_INVALID_ARG;
+    if (!out->obs || !out->next_obs || !out->action || !out->reward || !out->done || !out->idx)
+        return TJ_ERR_INVALID_ARG;
+    if (batch > (1u << 20)) return TJ_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint32_t count = (uint32_t)buf->count;
+    // only the tiles that hold valid slots take part (at least one, so K is always written)
+    uint32_t n_tiles = (count + kTile - 1) / kTile;
+    if (n_tiles == 0) n_tiles = 1;
+    if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[0], st));
+    stale_mask_count<<<n_tiles, 256, 0, st>>>(buf->ring.version, count, current_version, max_staleness,
+                                              buf->mask, buf->tile_count);
+    tile_scan<<<1, 1024, 0, st>>>(buf->tile_count, n_tiles, buf->tile_off, buf->state);
+    select_slots<<<(batch + 255) / 256, 256, 0, st>>>(buf->mask, buf->tile_off, n_tiles, buf->state,
+                                                      seed, batch, buf->ring, out->idx, out->action,
+                                                      out->reward, out->done);
+    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+    if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[1], st));
+    int rc = copy_rows(buf->ring.obs, out->obs, buf->ring.next_obs, out->next_obs, buf->row_bytes, batch,
+                       out->idx, 0, 0, buf->desc.capacity, st);
+    if (rc == TJ_OK && buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[2], st));
+    return rc;
+}
+
+int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    if (!hip_events || n == 0) {
+        buf->timed = false;
+        return TJ_OK;
+    }
+    if (n != 3) return TJ_ERR_INVALID_ARG;
+    for (int i = 0; i < 3; ++i) {
+        if (!hip_events[i]) return TJ_ERR_INVALID_ARG;
+        buf->ev[i] = (hipEvent_t)hip_events[i];
+    }
+    buf->timed = true;
+    return TJ_OK;
+}
+
+int tj_buffer_status(tj_buffer *buf, tj_buffer_info *h_out, void *hip_stream)
+{
+    if (!buf || !h_out) return TJ_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint32_t h[4] = {0, 0, 0, 0};
+    TJ_HIP_TRY(hipMemcpyAsync(h, buf->state, sizeof(h), hipMemcpyDeviceToHost, st));
+    TJ_HIP_TRY(hipStreamSynchronize(st));
+    h_out->capacity = buf->desc.capacity;
+    h_out->head = buf->head;
+    h_out->count = buf->count;
+    h_out->last_n_eligible = h[1];
+    h_out->sticky_error = (int32_t)h[0];
+    if (h[0] != 0) {
+        zero_words<<<1, 64, 0, st>>>(buf->state, 1);
+        TJ_HIP_TRY(hipStreamSynchronize(st));
+    }
+    return (int32_t)h[0];
+}
+
+void *tj_buffer_field_ptr(tj_buffer *buf, int field)
+{
+    if (!buf) return nullptr;
+    switch (field) {
+    case 0: return buf->ring.obs;
+    case 1: return buf->ring.next_obs;
+    case 2: return buf->ring.action;
+    case 3: return buf->ring.reward;
+    case 4: return buf->ring.done;
+    case 5: return buf->ring.version;
+    default: return nullptr;
+    }
+}
+
+const char *tj_strerror(int status)
+{
+    switch (status) {
+    case TJ_OK: return "ok";
+    case TJ_ERR_INVALID_ARG: return "invalid argument";
+    case TJ_ERR_SHAPE: return "unsupported shape";
+    case TJ_ERR_ARENA_TOO_SMALL: return "arena too small";
+    case TJ_ERR_NO_ELIGIBLE: return "no eligible transition inside the staleness gate";
+    case TJ_ERR_CAPACITY: return "more rows than the ring holds";
+    case TJ_ERR_DEVICE: return "HIP call failed";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

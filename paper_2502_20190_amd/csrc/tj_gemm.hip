@@ -1,0 +1,246 @@
+// LDS-staged MFMA GEMM for gfx950:  D(i, j) = sum_k P[i][k] * Q[j][k].
+//
+// Block = 256 threads = 4 waves in a 2 x 2 arrangement, block tile 128 x 128,
+// wave tile 64 x 64 = 2 x 2 MFMA tiles of 32 x 32.  A stage holds 128 bytes of
+// k per row (64 bf16 or 32 fp32); rows sit 144 bytes apart in LDS so that the
+// 16-byte operand reads of consecutive rows fall on distinct banks.  The next
+// stage's global loads are issued before the MFMAs of the current one.
+//
+// bf16: v_mfma_f32_32x32x16_bf16, lane l feeds row (l % 32) with k = 8*(l / 32)
+// + 0..7.  fp32: v_mfma_f32_32x32x2_f32 four times per 16-byte operand; lane
+// group g = l / 32 feeds k = 4g + e in the e-th instruction for both operands,
+// a permutation of k that the sum does not see.
+// Accumulator element r of lane l is D(i, j) with i = 8*(r/4) + 4*(l/32) + r%4
+// and j = l % 32, so a lane owns runs of four consecutive i: outputs that are
+// contiguous in i get vector stores.
+#include "tj_gemm.h"
+
+namespace {
+
+constexpr int BI = 128, BJ = 128;
+constexpr int kRowBytes = 128;   // bytes of k per row per stage
+constexpr int kLdsRow = 144;     // padded row pitch in LDS
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <typename T> __device__ __forceinline__ void mma(f32x16 &acc, const uint4 &p, const uint4 &q);
+
+template <> __device__ __forceinline__ void mma<tj_bf16>(f32x16 &acc, const uint4 &p, const uint4 &q)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, p),
+                                                  __builtin_bit_cast(bf16x8, q), acc, 0, 0, 0);
+}
+
+template <> __device__ __forceinline__ void mma<float>(f32x16 &acc, const uint4 &p, const uint4 &q)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(p.x), __uint_as_float(q.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(p.y), __uint_as_float(q.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(p.z), __uint_as_float(q.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(p.w), __uint_as_float(q.w), acc, 0, 0, 0);
+}
+
+template <typename T> __device__ __forceinline__ float vec_sum(const uint4 &v);
+template <> __device__ __forceinline__ float vec_sum<float>(const uint4 &v)
+{
+    return __uint_as_float(v.x) + __uint_as_float(v.y) + __uint_as_float(v.z) + __uint_as_float(v.w);
+}
+template <> __device__ __forceinline__ float vec_sum<tj_bf16>(const uint4 &v)
+{
+    float s = 0.f;
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s += __uint_as_float(w[e] << 16) + __uint_as_float(w[e] & 0xFFFF0000u);
+    return s;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int tiles_seg0)
+{
+    constexpr int VE = TjElem<T>::kVec;
+    constexpr int KE = kRowBytes / (int)sizeof(T);
+    __shared__ __align__(16) uint8_t sP[BI * kLdsRow];
+    __shared__ __align__(16) uint8_t sQ[BJ * kLdsRow];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wi = wave & 1, wj = wave >> 1;
+    const int l32 = lane & 31, lg = lane >> 5;
+
+    const int sidx = (a.n_seg > 1 && (int)blockIdx.y >= tiles_seg0) ? 1 : 0;
+    const TjGemmSeg<T> seg = a.seg[sidx];
+    const int j0 = seg.j_begin + ((int)blockIdx.y - (sidx ? tiles_seg0 : 0)) * BJ;
+    const int j_end = seg.j_end;
+    const int i0 = blockIdx.x * BI;
+    const int z = blockIdx.z;
+    const int k_begin = z * a.k_chunk;
+    const int k_end = min(a.K, k_begin + a.k_chunk);
+
+    // global -> register staging: 4 vectors of P and 4 of Q per thread
+    const int cv = tid & 7;
+    const T *gP[4];
+    const T *gQ[4];
+    bool okP[4], okQ[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = (tid >> 3) + 32 * r;
+        const int i = i0 + row, j = j0 + row;
+        okP[r] = i < a.I;
+        okQ[r] = j < j_end;
+        gP[r] = seg.P + (size_t)(okP[r] ? i : 0) * a.ldp + cv * VE;
+        gQ[r] = a.Q + (size_t)(okQ[r] ? j - seg.q_shift : 0) * a.ldq + cv * VE;
+    }
+    uint4 rP[4], rQ[4];
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    auto gload = [&](int k0) {
+        const bool kin = k0 + cv * VE < k_end;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            rP[r] = (okP[r] && kin) ? *(const uint4 *)(gP[r] + k0) : zero4;
+            rQ[r] = (okQ[r] && kin) ? *(const uint4 *)(gQ[r] + k0) : zero4;
+        }
+    };
+    auto lstore = [&]() {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = (tid >> 3) + 32 * r;
+            *(uint4 *)(sP + row * kLdsRow + cv * 16) = rP[r];
+            *(uint4 *)(sQ + row * kLdsRow + cv * 16) = rQ[r];
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fi][fj][r] = 0.f;
+
+    const bool do_qsum = a.qsum != nullptr && blockIdx.x == 0 && wi == 0;
+    float qs[2] = {0.f, 0.f};
+
+    gload(k_begin);
+    lstore();
+    __syncthreads();
+    for (int k0 = k_begin; k0 < k_end; k0 += KE) {
+        const bool more = k0 + KE < k_end;
+        if (more) gload(k0 + KE);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 pf[2], qf[2];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                pf[f] = *(const uint4 *)(sP + (wi * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
+                qf[f] = *(const uint4 *)(sQ + (wj * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
+            }
+#pragma unroll
+            for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+                for (int fj = 0; fj < 2; ++fj) mma<T>(acc[fi][fj], pf[fi], qf[fj]);
+            if (do_qsum) {
+                qs[0] += vec_sum<T>(qf[0]);
+                qs[1] += vec_sum<T>(qf[1]);
+            }
+        }
+        __syncthreads();
+        if (more) {
+            lstore();
+            __syncthreads();
+        }
+    }
+
+    if (do_qsum) {
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj) {
+            float s = qs[fj] + __shfl_xor(qs[fj], 32, 64);
+            const int j = j0 + wj * 64 + fj * 32 + l32;
+            if (lg == 0 && j < j_end) a.qsum[(size_t)z * a.qsum_zstride + j] = s;
+        }
+    }
+
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi) {
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj) {
+            const int j = j0 + wj * 64 + fj * 32 + l32;
+            if (j >= j_end) continue;
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int ib = i0 + wi * 64 + fi * 32 + rq * 8 + lg * 4;
+                if (ib >= a.I) continue;
+                const int nvalid = min(4, a.I - ib);
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[fi][fj][rq * 4 + e];
+                if (seg.bias) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < nvalid) v[e] += seg.bias[ib + e];
+                }
+                if (a.relu) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                }
+                if (a.mask) {
+                    const T *mp = a.mask + (size_t)j * a.ldmask + ib;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < nvalid && !(TjElem<T>::to_f32(mp[e]) > 0.f)) v[e] = 0.f;
+                }
+                if (a.Ci) {
+                    T *cp = a.Ci + (size_t)j * a.ldci + ib;
+                    if (nvalid == 4) {
+                        if constexpr (sizeof(T) == 2) {
+                            uint2 o;
+                            o.x = (uint32_t)tj_f32_to_bf16(v[0]) | ((uint32_t)tj_f32_to_bf16(v[1]) << 16);
+                            o.y = (uint32_t)tj_f32_to_bf16(v[2]) | ((uint32_t)tj_f32_to_bf16(v[3]) << 16);
+                            *(uint2 *)cp = o;
+                        } else {
+                            *(float4 *)cp = make_float4(v[0], v[1], v[2], v[3]);
+                        }
+                    } else {
+                        for (int e = 0; e < nvalid; ++e) cp[e] = TjElem<T>::from_f32(v[e]);
+                    }
+                }
+                if (a.Cj && j < a.cj_jmax) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < nvalid) a.Cj[(size_t)(ib + e) * a.ldcj + j] = TjElem<T>::from_f32(v[e]);
+                }
+                if (a.Cf) {
+                    float *fp = a.Cf + (size_t)z * a.cf_zstride + (size_t)j * a.ldcf + ib;
+                    if (nvalid == 4 && ((uintptr_t)fp & 15) == 0) {
+                        *(float4 *)fp = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        for (int e = 0; e < nvalid; ++e) fp[e] = v[e];
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
+{
+    constexpr int VE = TjElem<T>::kVec;
+    constexpr int KE = kRowBytes / (int)sizeof(T);
+    // shapes the kernel's loads and its grid assume
+    if (a.n_seg < 1 || a.n_seg > 2 || a.I <= 0 || a.K <= 0 || a.n_split < 1) return TJ_ERR_SHAPE;
+    if (a.ldp % VE || a.ldq % VE || a.K % VE || a.K > a.ldp || a.K > a.ldq) return TJ_ERR_SHAPE;
+    if (a.n_split > 1 && (a.k_chunk % KE || (size_t)a.k_chunk * a.n_split < (size_t)a.K)) return TJ_ERR_SHAPE;
+    if (a.n_split == 1 && a.k_chunk < a.K) return TJ_ERR_SHAPE;
+    if ((a.Ci && a.ldci % VE) || (a.mask && a.ldmask % 4)) return TJ_ERR_SHAPE;
+    int tiles[2] = {0, 0};
+    for (int s = 0; s < a.n_seg; ++s) {
+        if (a.seg[s].j_end <= a.seg[s].j_begin || !a.seg[s].P) return TJ_ERR_SHAPE;
+        tiles[s] = (a.seg[s].j_end - a.seg[s].j_begin + BJ - 1) / BJ;
+    }
+    dim3 grid((a.I + BI - 1) / BI, tiles[0] + tiles[1], a.n_split);
+    gemm_pq<T><<<grid, 256, 0, st>>>(a, tiles[0]);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+template int tj_gemm<float>(const TjGemmArgs<float> &, hipStream_t);
+template int tj_gemm<tj_bf16>(const TjGemmArgs<tj_bf16> &, hipStream_t);

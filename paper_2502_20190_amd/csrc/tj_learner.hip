@@ -1,0 +1,616 @@
+// The Learner's policy update (Algorithm 1 of the paper, batched as a double-DQN
+// step): forward of the online network on [s ; s'] and of the target network on
+// s' as one grouped GEMM per layer, fused TD-target / Huber / loss kernel,
+// backward through Q_online(s), fused Adam, periodic hard target update.
+//
+// Device layout inside the caller's arena (T = fp32 or bf16 compute type, every
+// 2-D buffer has its row pitch padded to a 16-byte multiple, pads stay zero):
+//   theta_on, theta_tg, m, v      fp32 [P]      master state, flat order
+//   gpart                         fp32 [S][Ppad] split-K partial gradients
+//   Wc_on[l]  T [out][ld(in)]     WcT_on[l] T [in][ld(out)]   Wc_tg[l]
+//   X[l]   T [3B][ld(d_l)]   rows: s | s' (online) | s' (target); X[0] has 2B rows
+//   XT[l]  T [d_l][ld(B)]    transposed copy of the s rows
+//   Qout   fp32 [3B][ld4(A)]
+//   dZ[l]  T [B][ld(d_l)]    dZT[l] T [d_l][ld(B)]
+#include "tj_gemm.h"
+#include <math.h>
+#include <string.h>
+#include <vector>
+
+namespace {
+
+// ---------------------------------------------------------------- small kernels
+
+// Cast fp32 [R][C] to T with a padded pitch, and optionally to its transpose,
+// through a 32 x 32 LDS tile.  blockIdx.z selects the job.
+template <typename T> struct CastJob {
+    const float *src;   // [R][C], pitch C
+    T *dst;             // [R][ldd]   (may be null)
+    T *dstT;            // [C][lddT]  (may be null)
+    int R, C, ldd, lddT;
+};
+template <typename T> struct CastJobs {
+    CastJob<T> job[TJ_MAX_LAYERS];
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void cast_transpose(const CastJobs<T> jobs)
+{
+    __shared__ float tile[32][33];
+    const CastJob<T> jb = jobs.job[blockIdx.z];
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    if (r0 >= jb.R || c0 >= jb.C) return;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = r0 + ty + 8 * i, c = c0 + tx;
+        float x = 0.f;
+        if (r < jb.R && c < jb.C) {
+            x = jb.src[(size_t)r * jb.C + c];
+            if (jb.dst) jb.dst[(size_t)r * jb.ldd + c] = TjElem<T>::from_f32(x);
+        }
+        tile[ty + 8 * i][tx] = x;
+    }
+    if (!jb.dstT) return;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = c0 + ty + 8 * i, r = r0 + tx;
+        if (r < jb.R && c < jb.C) jb.dstT[(size_t)c * jb.lddT + r] = TjElem<T>::from_f32(tile[tx][ty + 8 * i]);
+    }
+}
+
+template <typename T> int launch_cast(const CastJobs<T> &jobs, int n_jobs, hipStream_t st)
+{
+    int maxR = 0, maxC = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        maxR = jobs.job[i].R > maxR ? jobs.job[i].R : maxR;
+        maxC = jobs.job[i].C > maxC ? jobs.job[i].C : maxC;
+    }
+    if (n_jobs == 0 || maxR == 0 || maxC == 0) return TJ_OK;
+    dim3 grid((maxC + 31) / 32, (maxR + 31) / 32, n_jobs);
+    cast_transpose<T><<<grid, 256, 0, st>>>(jobs);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+// TD target, Huber loss and its gradient, one thread per transition.
+//   a* = argmax_a Q_on(s',a) (lowest index on ties); y = r + gamma (1-done) Q_tg(s',a*)
+//   d = Q_on(s,a) - y; loss = mean Huber_kappa(d); dL/dQ_on(s,a) = clip(d,-k,k)/B
+// Q rows: [0,B) Q_on(s), [B,2B) Q_on(s'), [2B,3B) Q_tg(s').  The last block to
+// finish adds the per-block partial sums in block order.
+template <typename T>
+__global__ __launch_bounds__(256) void td_huber(const float *__restrict__ Q, int ldq, int B, int A,
+                                                const int32_t *__restrict__ action,
+                                                const float *__restrict__ reward,
+                                                const uint8_t *__restrict__ done, float gamma, float kappa,
+                                                T *__restrict__ dZ, int lddz, T *__restrict__ dZT, int lddzt,
+                                                int32_t *__restrict__ astar, float *__restrict__ loss_part,
+                                                uint32_t *__restrict__ ticket, tj_step_stats *stats_out,
+                                                tj_step_stats *stats_internal, uint32_t t_next)
+{
+    __shared__ float red[256];
+    __shared__ bool last;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    float loss = 0.f;
+    if (j < B) {
+        const float *qn = Q + (size_t)(B + j) * ldq;
+        int best = 0;
+        float bv = qn[0];
+        for (int a = 1; a < A; ++a) {
+            float x = qn[a];
+            if (x > bv) { bv = x; best = a; }
+        }
+        astar[j] = best;
+        int aj = action[j];
+        aj = aj < 0 ? 0 : (aj >= A ? A - 1 : aj);
+        const float not_done = done[j] ? 0.f : 1.f;
+        const float y = reward[j] + gamma * not_done * Q[(size_t)(2 * B + j) * ldq + best];
+        const float d = Q[(size_t)j * ldq + aj] - y;
+        const float ad = fabsf(d);
+        loss = ad <= kappa ? 0.5f * d * d : kappa * (ad - 0.5f * kappa);
+        const float g = fminf(fmaxf(d, -kappa), kappa) / (float)B;
+        const T gz = TjElem<T>::from_f32(g), z0 = TjElem<T>::from_f32(0.f);
+        for (int a = 0; a < A; ++a) {
+            const T val = a == aj ? gz : z0;
+            dZ[(size_t)j * lddz + a] = val;
+            dZT[(size_t)a * lddzt + j] = val;
+        }
+    }
+    red[threadIdx.x] = loss;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        loss_part[blockIdx.x] = red[0];
+        __threadfence();
+        uint32_t prev = atomicAdd(ticket, 1u);
+        last = prev == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (last && threadIdx.x == 0) {
+        __threadfence();
+        float s = 0.f;
+        for (uint32_t b = 0; b < gridDim.x; ++b) s += ((volatile float *)loss_part)[b];
+        tj_step_stats out;
+        out.loss = s / (float)B;
+        out.step = t_next;
+        *stats_internal = out;
+        if (stats_out) *stats_out = out;
+        *ticket = 0;   // ready for the next step
+    }
+}
+
+// Adam on the flat fp32 master state; the gradient is the sum of S partial slices.
+__global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, float *__restrict__ m,
+                                                   float *__restrict__ v, const float *__restrict__ gpart,
+                                                   int S, size_t gstride, size_t P, float lr, float b1,
+                                                   float b2, float eps, float c1, float c2)
+{
+    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= P) return;
+    if (i + 4 <= P) {
+        float4 g = *(const float4 *)(gpart + i);
+        for (int s = 1; s < S; ++s) {
+            const float4 p = *(const float4 *)(gpart + (size_t)s * gstride + i);
+            g.x += p.x; g.y += p.y; g.z += p.z; g.w += p.w;
+        }
+        float4 mm = *(const float4 *)(m + i), vv = *(const float4 *)(v + i), th = *(const float4 *)(theta + i);
+        float ga[4] = {g.x, g.y, g.z, g.w}, ma[4] = {mm.x, mm.y, mm.z, mm.w};
+        float va[4] = {vv.x, vv.y, vv.z, vv.w}, ta[4] = {th.x, th.y, th.z, th.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            ma[e] = b1 * ma[e] + (1.f - b1) * ga[e];
+            va[e] = b2 * va[e] + (1.f - b2) * ga[e] * ga[e];
+            ta[e] -= lr * (ma[e] / c1) / (sqrtf(va[e] / c2) + eps);
+        }
+        *(float4 *)(m + i) = make_float4(ma[0], ma[1], ma[2], ma[3]);
+        *(float4 *)(v + i) = make_float4(va[0], va[1], va[2], va[3]);
+        *(float4 *)(theta + i) = make_float4(ta[0], ta[1], ta[2], ta[3]);
+    } else {
+        for (size_t e = i; e < P; ++e) {
+            float g = gpart[e];
+            for (int s = 1; s < S; ++s) g += gpart[(size_t)s * gstride + e];
+            const float mm = b1 * m[e] + (1.f - b1) * g;
+            const float vv = b2 * v[e] + (1.f - b2) * g * g;
+            m[e] = mm;
+            v[e] = vv;
+            theta[e] -= lr * (mm / c1) / (sqrtf(vv / c2) + eps);
+        }
+    }
+}
+
+struct LayerPlan {
+    int in, out;           // features
+    int ld_in, ld_out;     // padded pitches (elements of T)
+    size_t w_off, b_off;   // offsets into the flat parameter vector
+};
+
+int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+bool desc_ok(const tj_learner_desc *d)
+{
+    if (!d || d->n_layers < 1 || d->n_layers > TJ_MAX_LAYERS) return false;
+    if (!d->in_c || !d->in_h || !d->in_w || !d->max_batch) return false;
+    if (d->precision != TJ_PRECISION_FP32 && d->precision != TJ_PRECISION_BF16) return false;
+    if (d->obs_dtype != TJ_OBS_F32 && d->obs_dtype != TJ_OBS_U8) return false;
+    for (uint32_t i = 0; i < d->n_layers; ++i) {
+        if (d->layers[i].out == 0) return false;
+        if (d->layers[i].kind != TJ_LAYER_LINEAR && d->layers[i].kind != TJ_LAYER_CONV2D) return false;
+        if (d->layers[i].kind == TJ_LAYER_CONV2D && (!d->layers[i].kernel || !d->layers[i].stride)) return false;
+    }
+    return d->layers[d->n_layers - 1].kind == TJ_LAYER_LINEAR;
+}
+
+bool all_linear(const tj_learner_desc *d)
+{
+    for (uint32_t i = 0; i < d->n_layers; ++i)
+        if (d->layers[i].kind != TJ_LAYER_LINEAR) return false;
+    return d->obs_dtype == TJ_OBS_F32;
+}
+
+}  // namespace
+
+struct tj_learner {
+    virtual ~tj_learner() {}
+    virtual int step(const tj_minibatch *mb, tj_step_stats *d_stats, hipStream_t st) = 0;
+    virtual int get_state(int which, float *h_out, size_t n, hipStream_t st) = 0;
+    virtual int set_state(int which, const float *h_in, size_t n, hipStream_t st) = 0;
+    uint64_t t = 0;
+    hipEvent_t ev[5];
+    bool timed = false;
+    int mark(int i, hipStream_t st)
+    {
+        if (timed && hipEventRecord(ev[i], st) != hipSuccess) return TJ_ERR_DEVICE;
+        return TJ_OK;
+    }
+};
+
+namespace {
+
+template <typename T> struct MlpLearner : tj_learner {
+    static constexpr int VE = TjElem<T>::kVec;
+    tj_learner_desc d;
+    int L = 0, A = 0, Bmax = 0, ldB = 0, ldA = 0, S = 1;
+    size_t P = 0, Ppad = 0;
+    std::vector<LayerPlan> lay;
+    float *theta_on = nullptr, *theta_tg = nullptr, *m = nullptr, *v = nullptr, *gpart = nullptr;
+    T *Wc_on[TJ_MAX_LAYERS], *WcT_on[TJ_MAX_LAYERS], *Wc_tg[TJ_MAX_LAYERS];
+    T *X[TJ_MAX_LAYERS], *XT[TJ_MAX_LAYERS], *dZ[TJ_MAX_LAYERS + 1], *dZT[TJ_MAX_LAYERS + 1];
+    size_t wc_bytes = 0;                   // contiguous block of all Wc_on (and of all Wc_tg)
+    uint8_t *act_begin = nullptr;          // activation block, re-zeroed when the batch changes
+    size_t act_bytes = 0;
+    float *Qout = nullptr, *loss_part = nullptr;
+    int32_t *astar = nullptr;
+    uint32_t *ticket = nullptr;
+    tj_step_stats *stats_internal = nullptr;
+    int last_batch = -1;
+
+    // Lays the arena out; with a null base it only measures.
+    size_t plan(void *base)
+    {
+        TjArena a(base);
+        L = (int)d.n_layers;
+        Bmax = (int)d.max_batch;
+        ldB = round_up(Bmax, VE);
+        lay.resize(L);
+        int in = (int)(d.in_c * d.in_h * d.in_w);
+        size_t off = 0;
+        for (int l = 0; l < L; ++l) {
+            lay[l].in = in;
+            lay[l].out = (int)d.layers[l].out;
+            lay[l].ld_in = round_up(in, VE);
+            lay[l].ld_out = round_up(lay[l].out, VE);
+            lay[l].w_off = off; off += (size_t)in * lay[l].out;
+            lay[l].b_off = off; off += lay[l].out;
+            in = lay[l].out;
+        }
+        P = off;
+        Ppad = tj_align_up(P, 64);
+        A = lay[L - 1].out;
+        ldA = round_up(A, 4);
+        // split the batch contraction of the weight-gradient GEMMs so that each
+        // slice still runs a long k loop
+        S = Bmax / 1024;
+        S = S < 1 ? 1 : (S > 8 ? 8 : S);
+        theta_on = (float *)a.take(P * 4);
+        theta_tg = (float *)a.take(P * 4);
+        m = (float *)a.take(P * 4);
+        v = (float *)a.take(P * 4);
+        gpart = (float *)a.take((size_t)S * Ppad * 4);
+        size_t wc0 = a.off;
+        for (int l = 0; l < L; ++l) Wc_on[l] = (T *)a.take((size_t)lay[l].out * lay[l].ld_in * sizeof(T));
+        wc_bytes = a.off - wc0;
+        for (int l = 0; l < L; ++l) Wc_tg[l] = (T *)a.take((size_t)lay[l].out * lay[l].ld_in * sizeof(T));
+        for (int l = 0; l < L; ++l) WcT_on[l] = (T *)a.take((size_t)lay[l].in * lay[l].ld_out * sizeof(T));
+        size_t act0 = a.off;
+        act_begin = base ? (uint8_t *)base + act0 : nullptr;
+        for (int l = 0; l < L; ++l) {
+            const size_t rows = l == 0 ? 2 * (size_t)Bmax : 3 * (size_t)Bmax;
+            X[l] = (T *)a.take(rows * lay[l].ld_in * sizeof(T));
+            XT[l] = (T *)a.take((size_t)lay[l].in * ldB * sizeof(T));
+        }
+        for (int l = 1; l <= L; ++l) {
+            dZ[l] = (T *)a.take((size_t)Bmax * lay[l - 1].ld_out * sizeof(T));
+            dZT[l] = (T *)a.take((size_t)lay[l - 1].out * ldB * sizeof(T));
+        }
+        act_bytes = a.off - act0;
+        Qout = (float *)a.take(3 * (size_t)Bmax * ldA * 4);
+        astar = (int32_t *)a.take((size_t)Bmax * 4);
+        loss_part = (float *)a.take((size_t)((Bmax + 255) / 256) * 4);
+        ticket = (uint32_t *)a.take(4);
+        stats_internal = (tj_step_stats *)a.take(sizeof(tj_step_stats));
+        return a.off;
+    }
+
+    // fp32 master -> compute-type copies (and transposes for the online net)
+    int recast(bool online, hipStream_t st)
+    {
+        CastJobs<T> jobs;
+        for (int l = 0; l < L; ++l) {
+            CastJob<T> &j = jobs.job[l];
+            j.src = (online ? theta_on : theta_tg) + lay[l].w_off;
+            j.dst = online ? Wc_on[l] : Wc_tg[l];
+            j.dstT = online ? WcT_on[l] : nullptr;
+            j.R = lay[l].out; j.C = lay[l].in;
+            j.ldd = lay[l].ld_in; j.lddT = lay[l].ld_out;
+        }
+        return launch_cast<T>(jobs, L, st);
+    }
+
+    int step(const tj_minibatch *mb, tj_step_stats *d_stats, hipStream_t st) override
+    {
+        const int B = (int)mb->batch;
+        if (B < 1 || B > Bmax) return TJ_ERR_SHAPE;
+        if (!mb->obs || !mb->next_obs || !mb->action || !mb->reward || !mb->done) return TJ_ERR_INVALID_ARG;
+        int rc;
+        if (last_batch != B) {
+            // pad columns beyond the batch must read as zero in the batch contraction
+            // (the arena starts zeroed; only a shrinking batch leaves stale columns behind)
+            if (last_batch > B) TJ_HIP_TRY(hipMemsetAsync(act_begin, 0, act_bytes, st));
+            last_batch = B;
+        }
+        const int Kb = round_up(B, VE);
+
+        // network input: [s ; s'] in compute type, and the transpose of s
+        {
+            CastJobs<T> jobs;
+            jobs.job[0] = {(const float *)mb->obs, X[0], XT[0], B, lay[0].in, lay[0].ld_in, ldB};
+            jobs.job[1] = {(const float *)mb->next_obs, X[0] + (size_t)B * lay[0].ld_in, nullptr, B,
+                           lay[0].in, lay[0].ld_in, ldB};
+            if ((rc = launch_cast<T>(jobs, 2, st)) != TJ_OK) return rc;
+        }
+        if ((rc = mark(0, st)) != TJ_OK) return rc;
+
+        // forward: columns j = rows of the stacked batch; [0,2B) online, [2B,3B) target
+        for (int l = 0; l < L; ++l) {
+            TjGemmArgs<T> g;
+            memset(&g, 0, sizeof(g));
+            g.n_seg = 2;
+            g.seg[0] = {0, 2 * B, Wc_on[l], theta_on + lay[l].b_off, 0};
+            g.seg[1] = {2 * B, 3 * B, Wc_tg[l], theta_tg + lay[l].b_off, l == 0 ? B : 0};
+            g.Q = X[l];
+            g.ldp = lay[l].ld_in; g.ldq = lay[l].ld_in;
+            g.I = lay[l].out; g.K = lay[l].ld_in;
+            g.k_chunk = g.K; g.n_split = 1;
+            if (l + 1 < L) {
+                g.relu = 1;
+                g.Ci = X[l + 1]; g.ldci = lay[l].ld_out;
+                g.Cj = XT[l + 1]; g.ldcj = ldB; g.cj_jmax = B;
+            } else {
+                g.Cf = Qout; g.ldcf = ldA;
+            }
+            if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
+        }
+
+        if ((rc = mark(1, st)) != TJ_OK) return rc;
+        const uint32_t t_next = (uint32_t)(t + 1);
+        td_huber<T><<<(B + 255) / 256, 256, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done,
+                                                     d.gamma, d.huber_delta, dZ[L], lay[L - 1].ld_out, dZT[L],
+                                                     ldB, astar, loss_part, ticket, d_stats, stats_internal,
+                                                     t_next);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        if ((rc = mark(2, st)) != TJ_OK) return rc;
+
+        // backward through Q_online(s)
+        for (int l = L; l >= 1; --l) {
+            const LayerPlan &lp = lay[l - 1];
+            {   // dW_l[n][k] = sum_m dZ_l[m][n] X_{l-1}[m][k]; db_l[n] = sum_m dZ_l[m][n]
+                TjGemmArgs<T> g;
+                memset(&g, 0, sizeof(g));
+                g.n_seg = 1;
+                g.seg[0] = {0, lp.out, XT[l - 1], nullptr, 0};
+                g.Q = dZT[l];
+                g.ldp = ldB; g.ldq = ldB;
+                g.I = lp.in; g.K = Kb;
+                g.n_split = S;
+                const int ke = 128 / (int)sizeof(T);
+                g.k_chunk = round_up((Kb + S - 1) / S, ke);
+                g.Cf = gpart + lp.w_off; g.ldcf = lp.in; g.cf_zstride = Ppad;
+                g.qsum = gpart + lp.b_off; g.qsum_zstride = Ppad;
+                if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
+            }
+            if (l >= 2) {   // dX_{l-1}[m][k] = relu'(X_{l-1}) * sum_n dZ_l[m][n] W_l[n][k]
+                TjGemmArgs<T> g;
+                memset(&g, 0, sizeof(g));
+                g.n_seg = 1;
+                g.seg[0] = {0, B, WcT_on[l - 1], nullptr, 0};
+                g.Q = dZ[l];
+                g.ldp = lp.ld_out; g.ldq = lp.ld_out;
+                g.I = lp.in; g.K = lp.ld_out;
+                g.k_chunk = g.K; g.n_split = 1;
+                g.mask = X[l - 1]; g.ldmask = lp.ld_in;
+                g.Ci = dZ[l - 1]; g.ldci = lp.ld_in;
+                g.Cj = dZT[l - 1]; g.ldcj = ldB; g.cj_jmax = B;
+                if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
+            }
+        }
+
+        if ((rc = mark(3, st)) != TJ_OK) return rc;
+        t += 1;
+        const float c1 = (float)(1.0 - pow((double)d.beta1, (double)t));
+        const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
+        adam_update<<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S, Ppad, P, d.lr,
+                                                                   d.beta1, d.beta2, d.eps, c1, c2);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        if ((rc = recast(true, st)) != TJ_OK) return rc;
+        if ((rc = mark(4, st)) != TJ_OK) return rc;
+        if (d.target_interval && t % d.target_interval == 0) {
+            TJ_HIP_TRY(hipMemcpyAsync(theta_tg, theta_on, P * 4, hipMemcpyDeviceToDevice, st));
+            TJ_HIP_TRY(hipMemcpyAsync(Wc_tg[0], Wc_on[0], wc_bytes, hipMemcpyDeviceToDevice, st));
+        }
+        return TJ_OK;
+    }
+
+    int get_state(int which, float *h_out, size_t n, hipStream_t st) override
+    {
+        const float *src = nullptr;
+        switch (which) {
+        case TJ_STATE_PARAMS: src = theta_on; break;
+        case TJ_STATE_TARGET: src = theta_tg; break;
+        case TJ_STATE_ADAM_M: src = m; break;
+        case TJ_STATE_ADAM_V: src = v; break;
+        default: break;
+        }
+        if (src) {
+            if (n != P) return TJ_ERR_INVALID_ARG;
+            TJ_HIP_TRY(hipMemcpyAsync(h_out, src, P * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            return TJ_OK;
+        }
+        if (which == TJ_STATE_GRADS) {
+            if (n != P) return TJ_ERR_INVALID_ARG;
+            std::vector<float> tmp((size_t)S * Ppad);
+            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), gpart, tmp.size() * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            for (size_t i = 0; i < P; ++i) {   // same order as the Adam kernel
+                float g = tmp[i];
+                for (int s = 1; s < S; ++s) g += tmp[(size_t)s * Ppad + i];
+                h_out[i] = g;
+            }
+            return TJ_OK;
+        }
+        if (which == TJ_STATE_QVALS) {
+            if (last_batch < 1 || n != 3 * (size_t)last_batch * A) return TJ_ERR_INVALID_ARG;
+            std::vector<float> tmp(3 * (size_t)last_batch * ldA);
+            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), Qout, tmp.size() * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            for (size_t r = 0; r < 3 * (size_t)last_batch; ++r)
+                for (int a = 0; a < A; ++a) h_out[r * A + a] = tmp[r * ldA + a];
+            return TJ_OK;
+        }
+        if (which == TJ_STATE_ASTAR) {
+            if (last_batch < 1 || n != (size_t)last_batch) return TJ_ERR_INVALID_ARG;
+            std::vector<int32_t> tmp(last_batch);
+            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), astar, tmp.size() * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            for (int j = 0; j < last_batch; ++j) h_out[j] = (float)tmp[j];
+            return TJ_OK;
+        }
+        return TJ_ERR_INVALID_ARG;
+    }
+
+    int set_state(int which, const float *h_in, size_t n, hipStream_t st) override
+    {
+        if (n != P) return TJ_ERR_INVALID_ARG;
+        float *dst = nullptr;
+        switch (which) {
+        case TJ_STATE_PARAMS: dst = theta_on; break;
+        case TJ_STATE_TARGET: dst = theta_tg; break;
+        case TJ_STATE_ADAM_M: dst = m; break;
+        case TJ_STATE_ADAM_V: dst = v; break;
+        default: return TJ_ERR_INVALID_ARG;
+        }
+        TJ_HIP_TRY(hipMemcpyAsync(dst, h_in, P * 4, hipMemcpyHostToDevice, st));
+        int rc = TJ_OK;
+        if (which == TJ_STATE_PARAMS) rc = recast(true, st);
+        if (which == TJ_STATE_TARGET) rc = recast(false, st);
+        TJ_HIP_TRY(hipStreamSynchronize(st));
+        return rc;
+    }
+};
+
+template <typename T>
+int create_mlp(const tj_learner_desc *desc, void *arena, size_t bytes, const float *h_on, const float *h_tg,
+               hipStream_t st, tj_learner **out)
+{
+    MlpLearner<T> *l = new MlpLearner<T>();
+    l->d = *desc;
+    size_t need = l->plan(nullptr);
+    if (bytes < need) { delete l; return TJ_ERR_ARENA_TOO_SMALL; }
+    l->plan(arena);
+    int rc = TJ_OK;
+    if (hipMemsetAsync(arena, 0, need, st) != hipSuccess) rc = TJ_ERR_DEVICE;
+    if (rc == TJ_OK) rc = l->set_state(TJ_STATE_PARAMS, h_on, l->P, st);
+    if (rc == TJ_OK) rc = l->set_state(TJ_STATE_TARGET, h_tg, l->P, st);
+    if (rc != TJ_OK) { delete l; return rc; }
+    *out = l;
+    return TJ_OK;
+}
+
+template <typename T> size_t measure_mlp(const tj_learner_desc *desc)
+{
+    MlpLearner<T> l;
+    l.d = *desc;
+    return l.plan(nullptr);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tj_learner_num_params(const tj_learner_desc *d)
+{
+    if (!desc_ok(d)) return 0;
+    size_t c = d->in_c, h = d->in_h, w = d->in_w, p = 0;
+    for (uint32_t i = 0; i < d->n_layers; ++i) {
+        const tj_layer &L = d->layers[i];
+        if (L.kind == TJ_LAYER_CONV2D) {
+            if (h < L.kernel || w < L.kernel) return 0;
+            p += (size_t)L.out * c * L.kernel * L.kernel + L.out;
+            h = (h - L.kernel) / L.stride + 1;
+            w = (w - L.kernel) / L.stride + 1;
+            c = L.out;
+        } else {
+            p += (size_t)L.out * c * h * w + L.out;
+            c = L.out; h = 1; w = 1;
+        }
+    }
+    return p;
+}
+
+size_t tj_learner_arena_bytes(const tj_learner_desc *d)
+{
+    if (!desc_ok(d) || !all_linear(d)) return 0;
+    return d->precision == TJ_PRECISION_BF16 ? measure_mlp<tj_bf16>(d) : measure_mlp<float>(d);
+}
+
+int tj_learner_create(const tj_learner_desc *d, void *dev_arena, size_t arena_bytes, const float *h_on,
+                      const float *h_tg, void *hip_stream, tj_learner **out)
+{
+    if (!out) return TJ_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!desc_ok(d) || !dev_arena || ((uintptr_t)dev_arena & 255) || !h_on || !h_tg) return TJ_ERR_INVALID_ARG;
+    if (!all_linear(d)) return TJ_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    return d->precision == TJ_PRECISION_BF16 ? create_mlp<tj_bf16>(d, dev_arena, arena_bytes, h_on, h_tg, st, out)
+                                             : create_mlp<float>(d, dev_arena, arena_bytes, h_on, h_tg, st, out);
+}
+
+int tj_learner_destroy(tj_learner *l)
+{
+    if (!l) return TJ_ERR_INVALID_ARG;
+    delete l;
+    return TJ_OK;
+}
+
+int tj_learner_step(tj_learner *l, const tj_minibatch *mb, tj_step_stats *d_stats, void *hip_stream)
+{
+    if (!l || !mb) return TJ_ERR_INVALID_ARG;
+    return l->step(mb, d_stats, (hipStream_t)hip_stream);
+}
+
+int tj_learner_get_state(tj_learner *l, int which, float *h_out, size_t n, void *hip_stream)
+{
+    if (!l || !h_out) return TJ_ERR_INVALID_ARG;
+    return l->get_state(which, h_out, n, (hipStream_t)hip_stream);
+}
+
+int tj_learner_set_state(tj_learner *l, int which, const float *h_in, size_t n, void *hip_stream)
+{
+    if (!l || !h_in) return TJ_ERR_INVALID_ARG;
+    return l->set_state(which, h_in, n, (hipStream_t)hip_stream);
+}
+
+int tj_learner_set_phase_events(tj_learner *l, void *const *hip_events, uint32_t n)
+{
+    if (!l) return TJ_ERR_INVALID_ARG;
+    if (!hip_events || n == 0) {
+        l->timed = false;
+        return TJ_OK;
+    }
+    if (n != 5) return TJ_ERR_INVALID_ARG;
+    for (int i = 0; i < 5; ++i) {
+        if (!hip_events[i]) return TJ_ERR_INVALID_ARG;
+        l->ev[i] = (hipEvent_t)hip_events[i];
+    }
+    l->timed = true;
+    return TJ_OK;
+}
+
+int tj_learner_get_step(tj_learner *l, uint64_t *h_t)
+{
+    if (!l || !h_t) return TJ_ERR_INVALID_ARG;
+    *h_t = l->t;
+    return TJ_OK;
+}
+
+int tj_learner_set_step(tj_learner *l, uint64_t t)
+{
+    if (!l) return TJ_ERR_INVALID_ARG;
+    l->t = t;
+    return TJ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,197 @@
+"""GPU parity: the learner step (forward x3, TD target, Huber, backward, Adam,
+target update) against the CPU oracle, through the C ABI.
+
+Tolerances (relative, per tensor: max|a-b| / max|b|, and for scalars
+|a-b| / |b|): 1e-4 for fp32 compute, 2e-2 for bf16 GEMM operands with fp32
+accumulation.  The oracle's inputs and states come from the seeded generators
+or from the oracle's own earlier steps, never from the GPU."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from paper_2502_20190_amd import synth
+from paper_2502_20190_amd.synth import LIN
+from parity_util import rel_l2, rel_max, rel_scalar, top2_gap
+
+pytestmark = pytest.mark.gpu
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def tj():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2502_20190_amd import binding
+
+    binding.lib()
+    return binding
+
+
+def _batch(wl, seed, n=None):
+    rows = synth.make_chunk(wl, seed, 0, n or wl.batch)
+    rows.pop("version")
+    return rows
+
+
+def _pair(tj, orc, wl, seed=0, max_batch=None, perturb_bias=True):
+    theta = synth.xavier_init(wl.layers, wl.in_chw, seed)
+    target = synth.xavier_init(wl.layers, wl.in_chw, seed + 1)
+    if perturb_bias:     # non-zero biases, so that a bias mix-up shows
+        rng = np.random.default_rng(seed + 50)
+        theta = (theta + 0.02 * rng.standard_normal(theta.size)).astype(np.float32)
+        target = (target + 0.02 * rng.standard_normal(theta.size)).astype(np.float32)
+    g = tj.learner_for_workload(wl, theta, target, max_batch=max_batch)
+    o = orc.Learner(wl.layers, wl.in_chw, obs_dtype=wl.obs_dtype, gamma=wl.gamma, kappa=wl.kappa, lr=wl.lr,
+                    beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, target_interval=wl.target_interval,
+                    emulate_bf16=(wl.precision == "bf16"))
+    o.set_state(orc.PARAMS, theta.astype(np.float64))
+    o.set_state(orc.TARGET, target.astype(np.float64))
+    return g, o
+
+
+def _step_both(tj, orc, g, o, wl, rows, tol, check_state=True):
+    """One step on both sides; compares loss, Q-values, greedy actions, gradients
+    and (optionally) the updated state.  Returns the worst relative error seen."""
+    b = len(rows["action"])
+    mb = tj.Minibatch(b, wl.obs_elems, wl.obs_dtype)
+    mb.load(**rows)
+    theta_before = o.get_state(orc.PARAMS)
+    assert g.step(mb) == tj.TJ_OK
+    oloss = o.step(**rows)
+    gloss, gt = g.read_stats()
+    assert gt == o.t == g.t
+    worst = {}
+    # Q-values of the three passes
+    q = g.get_state(tj.TJ_STATE_QVALS).reshape(3, b, -1)
+    for i, which in enumerate((orc.LAST_Q_S, orc.LAST_Q_NEXT_ONLINE, orc.LAST_Q_NEXT_TARGET)):
+        worst[f"q{i}"] = rel_max(q[i], o.last(which))
+    # greedy actions: equal except where the oracle's own top-2 gap is inside the float noise
+    ga, oa = g.get_state(tj.TJ_STATE_ASTAR).astype(np.int32), o.last_astar()
+    qn = o.last(orc.LAST_Q_NEXT_ONLINE)
+    margin = (1e-5 if wl.precision == "fp32" else 2e-3) * np.abs(qn).max()
+    mism = ga != oa
+    assert (top2_gap(qn)[mism] < margin).all(), "greedy action differs outside the near-tie margin"
+    assert mism.mean() <= 0.01
+    worst["loss"] = rel_scalar(gloss, oloss)
+    worst["grad"] = rel_max(g.get_state(tj.TJ_STATE_GRADS), o.get_state(orc.GRADS))
+    if check_state:
+        # updated weights: compare the update itself too (the weights alone hide it)
+        gth, oth = g.get_state(tj.TJ_STATE_PARAMS), o.get_state(orc.PARAMS)
+        worst["theta"] = rel_max(gth, oth)
+        worst["m"] = rel_max(g.get_state(tj.TJ_STATE_ADAM_M), o.get_state(orc.ADAM_M))
+        worst["v"] = rel_max(g.get_state(tj.TJ_STATE_ADAM_V), o.get_state(orc.ADAM_V))
+        worst["target"] = rel_max(g.get_state(tj.TJ_STATE_TARGET), o.get_state(orc.TARGET))
+    bad = {k: v for k, v in worst.items() if not v < tol}
+    assert not bad, f"beyond {tol}: {bad} (all: {worst})"
+    return worst, (g.get_state(tj.TJ_STATE_PARAMS).astype(np.float64) - theta_before,
+                   o.get_state(orc.PARAMS) - theta_before)
+
+
+def test_c1_ten_free_running_steps(tj, orc):
+    """Config 1 (4-64-64-2 fp32, batch 32, lr 1e-3): all ten steps free-running on
+    both sides stay inside the fp32 tolerance."""
+    wl = synth.WORKLOADS["c1"]
+    g, o = _pair(tj, orc, wl, seed=1, perturb_bias=False)
+    for step in range(wl.steps):
+        worst, _ = _step_both(tj, orc, g, o, wl, _batch(wl, 100 + step), TOL["fp32"])
+    assert g.t == 10
+
+
+def test_c2_first_steps_and_update_direction(tj, orc):
+    """Config 2 (128-256-256-18 fp32, batch 512): three free-running steps; at step
+    one Adam's update is -lr*sign(g) wherever |g| >> eps, which pins the sign."""
+    wl = synth.WORKLOADS["c2"]
+    g, o = _pair(tj, orc, wl, seed=2)
+    for step in range(3):
+        worst, (gd, od) = _step_both(tj, orc, g, o, wl, _batch(wl, 200 + step), TOL["fp32"])
+        if step == 0:
+            big = np.abs(o.get_state(orc.GRADS)) > 1e-5
+            np.testing.assert_allclose(gd[big], -wl.lr * np.sign(o.get_state(orc.GRADS)[big]), rtol=2e-3)
+
+
+def test_midtraining_state_from_the_oracle_side(tj, orc):
+    """Both sides start from the same synthetic mid-training optimizer state
+    (moments, t = 500), loaded through set_state."""
+    wl = replace(synth.WORKLOADS["c2"], batch=256, target_interval=501)
+    g, o = _pair(tj, orc, wl, seed=3)
+    m, v = synth.midtraining_state(g.n_params, 9)
+    g.set_state(tj.TJ_STATE_ADAM_M, m); g.set_state(tj.TJ_STATE_ADAM_V, v); g.t = 500
+    o.set_state(orc.ADAM_M, m.astype(np.float64)); o.set_state(orc.ADAM_V, v.astype(np.float64)); o.t = 500
+    _step_both(tj, orc, g, o, wl, _batch(wl, 31), TOL["fp32"])
+    assert g.t == 501
+    np.testing.assert_array_equal(g.get_state(tj.TJ_STATE_TARGET), g.get_state(tj.TJ_STATE_PARAMS))
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_ragged_shapes_and_batch_changes(tj, orc, precision):
+    """Layer widths and batches that are not multiples of any tile or vector
+    size; the batch shrinks and grows between steps; the target syncs at t=2."""
+    wl = replace(synth.WORKLOADS["c2"], obs_shape=(20,), n_actions=5, precision=precision,
+                 layers=((LIN, 100, 0, 0), (LIN, 36, 0, 0), (LIN, 5, 0, 0)), batch=300,
+                 target_interval=2, lr=1e-3)
+    g, o = _pair(tj, orc, wl, seed=4, max_batch=300)
+    for step, b in enumerate((77, 300, 24, 131, 1)):
+        _step_both(tj, orc, g, o, wl, _batch(wl, 40 + step, b), TOL[precision])
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_multi_tile_mlp(tj, orc, precision):
+    """Several 128 x 128 tiles in every GEMM, a split batch contraction (batch
+    2304 > 2 x 1024) with a ragged last slice."""
+    wl = replace(synth.WORKLOADS["c2"], obs_shape=(136,), n_actions=18, precision=precision,
+                 layers=((LIN, 264, 0, 0), (LIN, 392, 0, 0), (LIN, 18, 0, 0)), batch=2304 + 40)
+    g, o = _pair(tj, orc, wl, seed=5)
+    for step in range(2):
+        _step_both(tj, orc, g, o, wl, _batch(wl, 60 + step), TOL[precision])
+
+
+def test_bf16_against_the_exact_oracle(tj, orc):
+    """bf16 operands against the fp64 oracle without rounding emulation: Q-values
+    and loss inside 2e-2, gradients inside 2e-2 in the L2 norm (single ReLU-mask
+    flips are jumps of size 1/B in single entries)."""
+    wl = replace(synth.WORKLOADS["c3"], obs_shape=(64,), n_actions=8, batch=1024,
+                 layers=((LIN, 256, 0, 0), (LIN, 256, 0, 0), (LIN, 8, 0, 0)))
+    g, _ = _pair(tj, orc, wl, seed=6)
+    theta = g.get_state(tj.TJ_STATE_PARAMS).astype(np.float64)
+    target = g.get_state(tj.TJ_STATE_TARGET).astype(np.float64)
+    exact = orc.Learner(wl.layers, wl.in_chw, gamma=wl.gamma, kappa=wl.kappa, lr=wl.lr,
+                        target_interval=wl.target_interval, emulate_bf16=False)
+    exact.set_state(orc.PARAMS, theta); exact.set_state(orc.TARGET, target)
+    rows = _batch(wl, 70)
+    mb = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype)
+    mb.load(**rows)
+    assert g.step(mb) == tj.TJ_OK
+    oloss = exact.step(**rows)
+    gloss, _ = g.read_stats()
+    q = g.get_state(tj.TJ_STATE_QVALS).reshape(3, wl.batch, -1)
+    assert rel_max(q[0], exact.last(orc.LAST_Q_S)) < 2e-2
+    assert rel_max(q[2], exact.last(orc.LAST_Q_NEXT_TARGET)) < 2e-2
+    assert rel_scalar(gloss, oloss) < 2e-2
+    assert rel_l2(g.get_state(tj.TJ_STATE_GRADS), exact.get_state(orc.GRADS)) < 2e-2
+
+
+def test_c3_full_size_step(tj, orc):
+    """Config 3 at full size (256-1024-1024-1024-32 bf16, batch 8192), the launch
+    configuration the benchmark times, against the bf16-rounding oracle."""
+    wl = synth.WORKLOADS["c3"]
+    g, o = _pair(tj, orc, wl, seed=7)
+    worst, _ = _step_both(tj, orc, g, o, wl, _batch(wl, 80), TOL["bf16"])
+    print("c3 full-size worst relative errors:", worst)
+
+
+def test_learner_argument_errors(tj, orc):
+    import ctypes
+
+    wl = synth.WORKLOADS["c1"]
+    g, _ = _pair(tj, orc, wl, seed=8)
+    mb = tj.Minibatch(64, wl.obs_elems, wl.obs_dtype)          # larger than max_batch = 32
+    assert g.step(mb) == tj.TJ_ERR_SHAPE
+    L = tj.lib()
+    out = np.empty(3, np.float32)
+    assert L.tj_learner_get_state(g.h, tj.TJ_STATE_PARAMS, out.ctypes.data, 3, None) == tj.TJ_ERR_INVALID_ARG
+    assert L.tj_learner_set_state(g.h, tj.TJ_STATE_GRADS, out.ctypes.data, g.n_params, None) == tj.TJ_ERR_INVALID_ARG
+    conv = tj.make_learner_desc([(1, 8, 3, 1), (0, 4, 0, 0)], (1, 8, 8), "u8", "bf16", 8, 0.99, 1.0, 1e-3,
+                                0.9, 0.999, 1e-8, 10)
+    assert L.tj_learner_num_params(ctypes.byref(conv)) == 8 * 9 + 8 + 4 * 8 * 36 + 4
