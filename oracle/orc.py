@@ -62,6 +62,8 @@ def lib():
         L.orc_learner_get_state.restype = _i32
         L.orc_learner_get_state.argtypes = [_vp, _i32, _vp]
         L.orc_learner_forward.argtypes = [_vp, _i32, _vp, _u32, _vp]
+        L.orc_learner_min_abs_preactivation.restype = _dbl
+        L.orc_learner_min_abs_preactivation.argtypes = [_vp, _vp, _u32, _vp]
         L.orc_learner_step.restype = _dbl
         L.orc_learner_step.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _vp, _vp]
         L.orc_learner_last.restype = _i32
@@ -198,6 +200,13 @@ class Learner:
         q = np.empty((b, self.n_actions), np.float64)
         lib().orc_learner_forward(self.h, which, _p(obs), b, _p(q))
         return q
+
+    def min_abs_preactivation(self, obs) -> np.ndarray:
+        """Per sample: the smallest |pre-activation| over the hidden units (online net)."""
+        obs = _c(obs, self.np_dtype)
+        out = np.empty(obs.shape[0], np.float64)
+        lib().orc_learner_min_abs_preactivation(self.h, _p(obs), obs.shape[0], _p(out))
+        return out
 
     def step(self, obs, next_obs, action, reward, done, astar_override=None) -> float:
         obs, next_obs = _c(obs, self.np_dtype), _c(next_obs, self.np_dtype)

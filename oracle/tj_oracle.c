@@ -427,7 +427,7 @@ static void load_input(const orc_learner *l, const void *obs, size_t j, double *
  * the post-ReLU activations are rounded to bf16; bias add and the head output
  * are not. */
 static void forward_batch(const orc_learner *l, const double *theta, const void *obs,
-                          uint32_t batch, double **acts, double *q)
+                          uint32_t batch, double **acts, double *q, double *min_abs_preact)
 {
     double *Wr = NULL;
     const double *P = theta;
@@ -455,6 +455,9 @@ static void forward_batch(const orc_learner *l, const double *theta, const void 
                 if (acts) memcpy(acts[i] + (size_t)j * L->in_size, a, L->in_size * sizeof(double));
                 layer_forward(L, P + L->w_off, P + L->b_off, a, z);
                 if (i + 1 < l->n_layers) {
+                    if (min_abs_preact)
+                        for (size_t e = 0; e < L->out_size; ++e)
+                            if (fabs(z[e]) < min_abs_preact[j]) min_abs_preact[j] = fabs(z[e]);
                     for (size_t e = 0; e < L->out_size; ++e) {
                         double r = z[e] > 0.0 ? z[e] : 0.0;
                         a[e] = l->emulate_bf16 ? bf16_round(r) : r;
@@ -472,7 +475,28 @@ static void forward_batch(const orc_learner *l, const double *theta, const void 
 /* Q-values of a batch under the online (which = 0) or target (1) network. */
 void orc_learner_forward(orc_learner *l, int which, const void *obs, uint32_t batch, double *q)
 {
-    forward_batch(l, which == 0 ? l->theta : l->target, obs, batch, NULL, q);
+    forward_batch(l, which == 0 ? l->theta : l->target, obs, batch, NULL, q, NULL);
+}
+
+/* Distance of a batch from the ReLU kinks: the smallest |pre-activation| over
+ * all hidden units and samples under the online network.  At a kink the loss
+ * gradient jumps, so a comparison of gradients at 1e-4 is only meaningful for
+ * inputs that stay clear of them; tests use this to choose such inputs.
+ * per_sample (optional) receives the minimum of each sample. */
+double orc_learner_min_abs_preactivation(orc_learner *l, const void *obs, uint32_t batch,
+                                         double *per_sample)
+{
+    double *mins = (double *)malloc(batch * sizeof(double));
+    double *q = (double *)malloc((size_t)batch * l->n_actions * sizeof(double));
+    for (uint32_t j = 0; j < batch; ++j) mins[j] = INFINITY;
+    forward_batch(l, l->theta, obs, batch, NULL, q, mins);
+    double m = INFINITY;
+    for (uint32_t j = 0; j < batch; ++j) {
+        if (mins[j] < m) m = mins[j];
+        if (per_sample) per_sample[j] = mins[j];
+    }
+    free(mins); free(q);
+    return m;
 }
 
 /* One learner step on a minibatch.  Returns the loss.
@@ -499,9 +523,9 @@ double orc_learner_step(orc_learner *l, uint32_t batch, const void *obs, const v
         acts[i] = (double *)malloc((size_t)batch * l->L[i].in_size * sizeof(double));
 
     /* forward: Q_online(s) keeps its activations, Q_online(s'), Q_target(s') */
-    forward_batch(l, l->theta, obs, batch, acts, l->q_s);
-    forward_batch(l, l->theta, next_obs, batch, NULL, l->q_next_online);
-    forward_batch(l, l->target, next_obs, batch, NULL, l->q_next_target);
+    forward_batch(l, l->theta, obs, batch, acts, l->q_s, NULL);
+    forward_batch(l, l->theta, next_obs, batch, NULL, l->q_next_online, NULL);
+    forward_batch(l, l->target, next_obs, batch, NULL, l->q_next_target, NULL);
 
     /* double-DQN target, TD error, Huber loss and its gradient wrt Q(s_j, a_j) */
     double *dz = (double *)calloc((size_t)batch * A, sizeof(double));

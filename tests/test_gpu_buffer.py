@@ -101,7 +101,7 @@ def test_row_shapes(tj, orc, obs_elems, obs_dtype, capacity):
 
     wl = replace(synth.WORKLOADS["c2"], capacity=capacity, obs_shape=(obs_elems,), obs_dtype=obs_dtype,
                  version_max=20, current_version=20)
-    gbuf, obuf = _fill_both(tj, orc, wl, 5, 97, capacity + 50)
+    gbuf, obuf = _fill_both(tj, orc, wl, 5, min(97, capacity), capacity + 50)
     everything = obuf.gather(np.arange(capacity, dtype=np.uint32))
     for f in FIELDS:
         np.testing.assert_array_equal(gbuf.field(f).cpu().numpy(), everything[f], err_msg=f)
