@@ -22,17 +22,18 @@ constexpr int kRowBytes = 128;   // bytes of k per row per stage
 constexpr int kLdsRow = 144;     // padded row pitch in LDS
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte operand vector in registers
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <typename T> __device__ __forceinline__ void mma(f32x16 &acc, const uint4 &p, const uint4 &q);
+template <typename T> __device__ __forceinline__ void mma(f32x16 &acc, const u32x4 &p, const u32x4 &q);
 
-template <> __device__ __forceinline__ void mma<tj_bf16>(f32x16 &acc, const uint4 &p, const uint4 &q)
+template <> __device__ __forceinline__ void mma<tj_bf16>(f32x16 &acc, const u32x4 &p, const u32x4 &q)
 {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, p),
                                                   __builtin_bit_cast(bf16x8, q), acc, 0, 0, 0);
 }
 
-template <> __device__ __forceinline__ void mma<float>(f32x16 &acc, const uint4 &p, const uint4 &q)
+template <> __device__ __forceinline__ void mma<float>(f32x16 &acc, const u32x4 &p, const u32x4 &q)
 {
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(p.x), __uint_as_float(q.x), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(p.y), __uint_as_float(q.y), acc, 0, 0, 0);
@@ -40,12 +41,12 @@ template <> __device__ __forceinline__ void mma<float>(f32x16 &acc, const uint4 
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(p.w), __uint_as_float(q.w), acc, 0, 0, 0);
 }
 
-template <typename T> __device__ __forceinline__ float vec_sum(const uint4 &v);
-template <> __device__ __forceinline__ float vec_sum<float>(const uint4 &v)
+template <typename T> __device__ __forceinline__ float vec_sum(const u32x4 &v);
+template <> __device__ __forceinline__ float vec_sum<float>(const u32x4 &v)
 {
     return __uint_as_float(v.x) + __uint_as_float(v.y) + __uint_as_float(v.z) + __uint_as_float(v.w);
 }
-template <> __device__ __forceinline__ float vec_sum<tj_bf16>(const uint4 &v)
+template <> __device__ __forceinline__ float vec_sum<tj_bf16>(const u32x4 &v)
 {
     float s = 0.f;
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -89,22 +90,22 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
         gP[r] = seg.P + (size_t)(okP[r] ? i : 0) * a.ldp + cv * VE;
         gQ[r] = a.Q + (size_t)(okQ[r] ? j - seg.q_shift : 0) * a.ldq + cv * VE;
     }
-    uint4 rP[4], rQ[4];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    u32x4 rP[4], rQ[4];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
     auto gload = [&](int k0) {
         const bool kin = k0 + cv * VE < k_end;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            rP[r] = (okP[r] && kin) ? *(const uint4 *)(gP[r] + k0) : zero4;
-            rQ[r] = (okQ[r] && kin) ? *(const uint4 *)(gQ[r] + k0) : zero4;
+            rP[r] = (okP[r] && kin) ? *(const u32x4 *)(gP[r] + k0) : zero4;
+            rQ[r] = (okQ[r] && kin) ? *(const u32x4 *)(gQ[r] + k0) : zero4;
         }
     };
     auto lstore = [&]() {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = (tid >> 3) + 32 * r;
-            *(uint4 *)(sP + row * kLdsRow + cv * 16) = rP[r];
-            *(uint4 *)(sQ + row * kLdsRow + cv * 16) = rQ[r];
+            *(u32x4 *)(sP + row * kLdsRow + cv * 16) = rP[r];
+            *(u32x4 *)(sQ + row * kLdsRow + cv * 16) = rQ[r];
         }
     };
 
@@ -127,11 +128,11 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
         if (more) gload(k0 + KE);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            uint4 pf[2], qf[2];
+            u32x4 pf[2], qf[2];
 #pragma unroll
             for (int f = 0; f < 2; ++f) {
-                pf[f] = *(const uint4 *)(sP + (wi * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
-                qf[f] = *(const uint4 *)(sQ + (wj * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
+                pf[f] = *(const u32x4 *)(sP + (wi * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
+                qf[f] = *(const u32x4 *)(sQ + (wj * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
             }
 #pragma unroll
             for (int fi = 0; fi < 2; ++fi)
@@ -220,6 +221,293 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
     }
 }
 
+
+// ---------------------------------------------------------------- bf16 kernel
+//
+// Block tile 256 (i) x 128 (j), four waves as 2 x 2, wave tile 128 x 64 = 4 x 2
+// MFMA tiles (128 accumulator registers), stage depth 64 k.  Two blocks fit a
+// CU (55 KB of LDS, < 256 registers), so one block's global-load wait overlaps
+// the other's MFMAs.  The 1-D grid is remapped so that the eight XCDs (which
+// take workgroups round-robin, each with its own L2) own disjoint runs of j
+// tiles and sweep all i tiles of a run: the P operand (weights) stays resident
+// in every L2 and each Q row block is fetched from HBM once.
+// The epilogue stages each 32 x 32 accumulator tile through a wave-private LDS
+// scratch so that global stores are 16 bytes per lane along the contiguous
+// index of each output.
+constexpr int B2I = 256, B2J = 128;
+constexpr int kScratchPitch = 144;   // bytes, >= 32 fp32 and 16-byte aligned
+
+struct TileMap {
+    int tiles_i, tiles_j;   // tile counts (tiles_j over all segments)
+};
+
+__global__ __launch_bounds__(256, 2) void gemm_bf16(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
+                                                    const TileMap tm)
+{
+    typedef tj_bf16 T;
+    constexpr int VE = 8, KE = 64;
+    __shared__ __align__(16) uint8_t sP[B2I * kLdsRow];
+    __shared__ __align__(16) uint8_t sQ[B2J * kLdsRow];
+
+    // XCD-aware tile order: id % 8 = XCD; an XCD walks i fastest inside its j tiles
+    int ti, tj, z;
+    {
+        const int id = blockIdx.x;
+        if (a.n_split > 1) {          // split contraction: slices of one tile land on different XCDs,
+            z = id % a.n_split;       // tiles of one slice share the operand columns they stream
+            const int t = id / a.n_split;
+            ti = t % tm.tiles_i;
+            tj = t / tm.tiles_i;
+        } else {
+            z = 0;
+            const int xcd = id & 7, slot = id >> 3;
+            ti = slot % tm.tiles_i;
+            tj = (slot / tm.tiles_i) * 8 + xcd;
+        }
+        if (tj >= tm.tiles_j) return;
+    }
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wi = wave & 1, wj = wave >> 1;
+    const int l32 = lane & 31, lg = lane >> 5;
+
+    const int sidx = (a.n_seg > 1 && tj >= tiles_seg0) ? 1 : 0;
+    const TjGemmSeg<T> seg = a.seg[sidx];
+    const int j0 = seg.j_begin + (tj - (sidx ? tiles_seg0 : 0)) * B2J;
+    const int j_end = seg.j_end;
+    const int i0 = ti * B2I;
+    const int k_begin = z * a.k_chunk;
+    const int k_end = min(a.K, k_begin + a.k_chunk);
+
+    const int cv = tid & 7, r0 = tid >> 3;
+    const T *gP[8];
+    const T *gQ[4];
+    uint32_t okmask = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int i = i0 + r0 + 32 * r;
+        const bool ok = i < a.I;
+        okmask |= (uint32_t)ok << r;
+        gP[r] = seg.P + (size_t)(ok ? i : 0) * a.ldp + cv * VE;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int j = j0 + r0 + 32 * r;
+        const bool ok = j < j_end;
+        okmask |= (uint32_t)ok << (8 + r);
+        gQ[r] = a.Q + (size_t)(ok ? j - seg.q_shift : 0) * a.ldq + cv * VE;
+    }
+    u32x4 rP[8], rQ[4];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    auto gload = [&](int k0) {
+        const bool kin = k0 + cv * VE < k_end;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) rP[r] = (kin && ((okmask >> r) & 1)) ? *(const u32x4 *)(gP[r] + k0) : zero4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rQ[r] = (kin && ((okmask >> (8 + r)) & 1)) ? *(const u32x4 *)(gQ[r] + k0) : zero4;
+    };
+    auto lstore = [&]() {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) *(u32x4 *)(sP + (r0 + 32 * r) * kLdsRow + cv * 16) = rP[r];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) *(u32x4 *)(sQ + (r0 + 32 * r) * kLdsRow + cv * 16) = rQ[r];
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int fi = 0; fi < 4; ++fi)
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fi][fj][r] = 0.f;
+
+    const bool do_qsum = a.qsum != nullptr && ti == 0 && wi == 0;
+    float qs[2] = {0.f, 0.f};
+    const uint8_t *pbase = sP + (wi * 128 + l32) * kLdsRow + lg * 16;
+    const uint8_t *qbase = sQ + (wj * 64 + l32) * kLdsRow + lg * 16;
+
+    gload(k_begin);
+    lstore();
+    __syncthreads();
+    for (int k0 = k_begin; k0 < k_end; k0 += KE) {
+        const bool more = k0 + KE < k_end;
+        if (more) gload(k0 + KE);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            u32x4 pf[4], qf[2];
+#pragma unroll
+            for (int f = 0; f < 4; ++f) pf[f] = *(const u32x4 *)(pbase + f * 32 * kLdsRow + ks * 32);
+#pragma unroll
+            for (int f = 0; f < 2; ++f) qf[f] = *(const u32x4 *)(qbase + f * 32 * kLdsRow + ks * 32);
+#pragma unroll
+            for (int fi = 0; fi < 4; ++fi)
+#pragma unroll
+                for (int fj = 0; fj < 2; ++fj) mma<T>(acc[fi][fj], pf[fi], qf[fj]);
+            if (do_qsum) {
+                qs[0] += vec_sum<T>(qf[0]);
+                qs[1] += vec_sum<T>(qf[1]);
+            }
+        }
+        __syncthreads();
+        if (more) {
+            lstore();
+            __syncthreads();
+        }
+    }
+
+    if (do_qsum) {
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj) {
+            float s = qs[fj] + __shfl_xor(qs[fj], 32, 64);
+            const int j = j0 + wj * 64 + fj * 32 + l32;
+            if (lg == 0 && j < j_end) a.qsum[(size_t)z * a.qsum_zstride + j] = s;
+        }
+    }
+
+    // ---- epilogue: one 32 x 32 tile at a time through wave-private scratch
+    uint8_t *scr = sP + wave * (32 * kScratchPitch);     // 4.5 KB per wave, inside sP
+#pragma unroll
+    for (int fi = 0; fi < 4; ++fi) {
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj) {
+            const int ibase = i0 + wi * 128 + fi * 32;     // first i of this tile
+            const int jbase = j0 + wj * 64 + fj * 32;      // first j of this tile
+            float v[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) v[r] = acc[fi][fj][r];
+            const int jl = jbase + l32;
+            if (seg.bias) {
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = ibase + rq * 8 + lg * 4 + e;
+                        if (i < a.I) v[rq * 4 + e] += seg.bias[i];
+                    }
+            }
+            if (a.relu) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], 0.f);
+            }
+            if (a.mask && jl < j_end) {
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int ib = ibase + rq * 8 + lg * 4;
+                    const T *mp = a.mask + (size_t)jl * a.ldmask + ib;
+                    if (ib + 3 < a.I) {
+                        const uint2 mv = *(const uint2 *)mp;   // four bf16; positive <=> sign clear and non-zero
+                        const uint32_t w[2] = {mv.x, mv.y};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const uint32_t h = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+                            if (!(tj_bf16_to_f32((T)h) > 0.f)) v[rq * 4 + e] = 0.f;
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (ib + e < a.I && !(tj_bf16_to_f32(mp[e]) > 0.f)) v[rq * 4 + e] = 0.f;
+                    }
+                }
+            }
+            if (a.Ci) {   // rows j, 32 consecutive i (64 bytes) each
+                __syncthreads();
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    uint2 o;
+                    o.x = (uint32_t)tj_f32_to_bf16(v[rq * 4]) | ((uint32_t)tj_f32_to_bf16(v[rq * 4 + 1]) << 16);
+                    o.y = (uint32_t)tj_f32_to_bf16(v[rq * 4 + 2]) | ((uint32_t)tj_f32_to_bf16(v[rq * 4 + 3]) << 16);
+                    *(uint2 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 2) = o;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int vv = lane + 64 * t, jr = vv >> 2, c = vv & 3;
+                    const u32x4 d = *(const u32x4 *)(scr + jr * kScratchPitch + c * 16);
+                    const int j = jbase + jr, i = ibase + c * 8;
+                    if (j < j_end && i < a.I) {
+                        T *cp = a.Ci + (size_t)j * a.ldci + i;
+                        if (i + 8 <= a.I) {
+                            *(u32x4 *)cp = d;
+                        } else {
+                            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (e < a.I - i) cp[e] = (T)((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
+                        }
+                    }
+                }
+            }
+            if (a.Cj) {   // rows i, 32 consecutive j (64 bytes) each
+                __syncthreads();
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        *(T *)(scr + (rq * 8 + lg * 4 + e) * kScratchPitch + l32 * 2) = tj_f32_to_bf16(v[rq * 4 + e]);
+                __syncthreads();
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int vv = lane + 64 * t, ir = vv >> 2, c = vv & 3;
+                    const u32x4 d = *(const u32x4 *)(scr + ir * kScratchPitch + c * 16);
+                    const int i = ibase + ir, j = jbase + c * 8;
+                    const int jmax = min(j_end, a.cj_jmax);
+                    if (i < a.I && j < jmax) {
+                        T *cp = a.Cj + (size_t)i * a.ldcj + j;
+                        if (j + 8 <= jmax && (((uintptr_t)cp) & 15) == 0) {
+                            *(u32x4 *)cp = d;
+                        } else {
+                            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (e < jmax - j) cp[e] = (T)((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
+                        }
+                    }
+                }
+            }
+            if (a.Cf) {   // fp32 rows j, 32 consecutive i (128 bytes) each
+                __syncthreads();
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq)
+                    *(float4 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 4) =
+                        make_float4(v[rq * 4], v[rq * 4 + 1], v[rq * 4 + 2], v[rq * 4 + 3]);
+                __syncthreads();
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int vv = lane + 64 * t, jr = vv >> 3, c = vv & 7;
+                    const float4 d = *(const float4 *)(scr + jr * kScratchPitch + c * 16);
+                    const int j = jbase + jr, i = ibase + c * 4;
+                    if (j < j_end && i < a.I) {
+                        float *fp = a.Cf + (size_t)z * a.cf_zstride + (size_t)j * a.ldcf + i;
+                        if (i + 4 <= a.I && (((uintptr_t)fp) & 15) == 0) {
+                            *(float4 *)fp = d;
+                        } else {
+                            const float w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (e < a.I - i) fp[e] = w[e];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st)
+{
+    TileMap tm;
+    tm.tiles_i = (a.I + B2I - 1) / B2I;
+    tm.tiles_j = tiles[0] + tiles[1];
+    unsigned nblk;
+    if (a.n_split > 1) {
+        nblk = (unsigned)tm.tiles_i * tm.tiles_j * a.n_split;
+    } else {
+        nblk = (unsigned)tm.tiles_i * ((tm.tiles_j + 7) / 8) * 8;
+    }
+    gemm_bf16<<<nblk, 256, 0, st>>>(a, tiles[0], tm);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
 }  // namespace
 
 template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
@@ -237,6 +525,7 @@ template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
         if (a.seg[s].j_end <= a.seg[s].j_begin || !a.seg[s].P) return TJ_ERR_SHAPE;
         tiles[s] = (a.seg[s].j_end - a.seg[s].j_begin + BJ - 1) / BJ;
     }
+    if constexpr (sizeof(T) == 2) return launch_bf16(a, tiles, st);
     dim3 grid((a.I + BI - 1) / BI, tiles[0] + tiles[1], a.n_split);
     gemm_pq<T><<<grid, 256, 0, st>>>(a, tiles[0]);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
