@@ -20,6 +20,7 @@ namespace {
 constexpr int BI = 128, BJ = 128;
 constexpr int kRowBytes = 128;   // bytes of k per row per stage
 constexpr int kLdsRow = 144;     // padded row pitch in LDS
+constexpr int kScratchPitch = 144;   // epilogue scratch row pitch: >= 32 fp32, 16-byte aligned
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte operand vector in registers
@@ -222,6 +223,152 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
 }
 
 
+// Orders this wave's LDS accesses (lane a's write before lane b's read of it) without a block
+// barrier: a wave's LDS instructions execute in order, so only the compiler has to be told.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Bias, ReLU and mask of one 32 x 32 accumulator tile, in place.  v[r] follows the MFMA layout:
+// i = ibase + 8*(r/4) + 4*(lane/32) + r%4, j = jbase + lane%32.  Kept apart from the stores: on this
+// hardware loads and stores share one counter (vmcnt), so a load issued after a tile's stores would
+// wait for those stores to finish.  The kernels run this on every tile first, then store.
+__device__ __forceinline__ void tile_math(const TjGemmArgs<tj_bf16> &a, const TjGemmSeg<tj_bf16> &seg,
+                                          f32x16 &v, const int ibase, const int jbase, const int j_end,
+                                          const int lane)
+{
+    typedef tj_bf16 T;
+    const int l32 = lane & 31, lg = lane >> 5;
+    const int jl = jbase + l32;
+    if (seg.bias) {
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = ibase + rq * 8 + lg * 4 + e;
+                if (i < a.I) v[rq * 4 + e] += seg.bias[i];
+            }
+    }
+    if (a.relu) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], 0.f);
+    }
+    if (a.mask && jl < j_end) {
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            const int ib = ibase + rq * 8 + lg * 4;
+            const T *mp = a.mask + (size_t)jl * a.ldmask + ib;
+            if (ib + 3 < a.I) {
+                const uint2 mv = *(const uint2 *)mp;   // four bf16
+                const uint32_t w[2] = {mv.x, mv.y};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t h = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+                    if (!(tj_bf16_to_f32((T)h) > 0.f)) v[rq * 4 + e] = 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (ib + e < a.I && !(tj_bf16_to_f32(mp[e]) > 0.f)) v[rq * 4 + e] = 0.f;
+            }
+        }
+    }
+}
+
+// The stores of one 32 x 32 tile (values already final), staged through a wave-private LDS
+// scratch of 32 rows x kScratchPitch bytes so that every lane writes 16 contiguous bytes.  The
+// scratch must not be shared with another wave.
+__device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f32x16 &v, uint8_t *scr,
+                                           const int ibase, const int jbase, const int j_end, const int z,
+                                           const int lane)
+{
+    typedef tj_bf16 T;
+    const int l32 = lane & 31, lg = lane >> 5;
+    if (a.Ci) {   // rows j, 32 consecutive i (64 bytes) each
+        wave_sync();
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            uint2 o;
+            o.x = (uint32_t)tj_f32_to_bf16(v[rq * 4]) | ((uint32_t)tj_f32_to_bf16(v[rq * 4 + 1]) << 16);
+            o.y = (uint32_t)tj_f32_to_bf16(v[rq * 4 + 2]) | ((uint32_t)tj_f32_to_bf16(v[rq * 4 + 3]) << 16);
+            *(uint2 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 2) = o;
+        }
+        wave_sync();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int vv = lane + 64 * t, jr = vv >> 2, c = vv & 3;
+            const u32x4 d = *(const u32x4 *)(scr + jr * kScratchPitch + c * 16);
+            const int j = jbase + jr, i = ibase + c * 8;
+            if (j < j_end && i < a.I) {
+                T *cp = a.Ci + (size_t)j * a.ldci + i;
+                if (i + 8 <= a.I) {
+                    *(u32x4 *)cp = d;
+                } else {
+                    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < a.I - i) cp[e] = (T)((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
+                }
+            }
+        }
+    }
+    if (a.Cj) {   // rows i, 32 consecutive j (64 bytes) each
+        wave_sync();
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                *(T *)(scr + (rq * 8 + lg * 4 + e) * kScratchPitch + l32 * 2) = tj_f32_to_bf16(v[rq * 4 + e]);
+        wave_sync();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int vv = lane + 64 * t, ir = vv >> 2, c = vv & 3;
+            const u32x4 d = *(const u32x4 *)(scr + ir * kScratchPitch + c * 16);
+            const int i = ibase + ir, j = jbase + c * 8;
+            const int jmax = min(j_end, a.cj_jmax);
+            if (i < a.I && j < jmax) {
+                T *cp = a.Cj + (size_t)i * a.ldcj + j;
+                if (j + 8 <= jmax && (((uintptr_t)cp) & 15) == 0) {
+                    *(u32x4 *)cp = d;
+                } else {
+                    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < jmax - j) cp[e] = (T)((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
+                }
+            }
+        }
+    }
+    if (a.Cf) {   // fp32 rows j, 32 consecutive i (128 bytes) each
+        wave_sync();
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq)
+            *(float4 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 4) =
+                make_float4(v[rq * 4], v[rq * 4 + 1], v[rq * 4 + 2], v[rq * 4 + 3]);
+        wave_sync();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int vv = lane + 64 * t, jr = vv >> 3, c = vv & 7;
+            const float4 d = *(const float4 *)(scr + jr * kScratchPitch + c * 16);
+            const int j = jbase + jr, i = ibase + c * 4;
+            if (j < j_end && i < a.I) {
+                float *fp = a.Cf + (size_t)z * a.cf_zstride + (size_t)j * a.ldcf + i;
+                if (i + 4 <= a.I && (((uintptr_t)fp) & 15) == 0) {
+                    *(float4 *)fp = d;
+                } else {
+                    const float w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < a.I - i) fp[e] = w[e];
+                }
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- bf16 kernel
 //
 // Block tile 256 (i) x 128 (j), four waves as 2 x 2, wave tile 128 x 64 = 4 x 2
@@ -235,7 +382,6 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
 // scratch so that global stores are 16 bytes per lane along the contiguous
 // index of each output.
 constexpr int B2I = 256, B2J = 128;
-constexpr int kScratchPitch = 144;   // bytes, >= 32 fp32 and 16-byte aligned
 
 struct TileMap {
     int tiles_i, tiles_j;   // tile counts (tiles_j over all segments)
@@ -364,7 +510,13 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16(const TjGemmArgs<tj_bf16> a,
         }
     }
 
-    // ---- epilogue: one 32 x 32 tile at a time through wave-private scratch
+    // ---- epilogue: bias / ReLU / mask on every tile, then the stores, one 32 x 32 tile at a time
+    // through wave-private scratch
+#pragma unroll
+    for (int fi = 0; fi < 4; ++fi)
+#pragma unroll
+        for (int fj = 0; fj < 2; ++fj)
+            tile_math(a, seg, acc[fi][fj], i0 + wi * 128 + fi * 32, j0 + wj * 64 + fj * 32, j_end, lane);
     uint8_t *scr = sP + wave * (32 * kScratchPitch);     // 4.5 KB per wave, inside sP
 #pragma unroll
     for (int fi = 0; fi < 4; ++fi) {
@@ -372,129 +524,328 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16(const TjGemmArgs<tj_bf16> a,
         for (int fj = 0; fj < 2; ++fj) {
             const int ibase = i0 + wi * 128 + fi * 32;     // first i of this tile
             const int jbase = j0 + wj * 64 + fj * 32;      // first j of this tile
-            float v[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) v[r] = acc[fi][fj][r];
-            const int jl = jbase + l32;
-            if (seg.bias) {
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int i = ibase + rq * 8 + lg * 4 + e;
-                        if (i < a.I) v[rq * 4 + e] += seg.bias[i];
-                    }
-            }
-            if (a.relu) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], 0.f);
-            }
-            if (a.mask && jl < j_end) {
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    const int ib = ibase + rq * 8 + lg * 4;
-                    const T *mp = a.mask + (size_t)jl * a.ldmask + ib;
-                    if (ib + 3 < a.I) {
-                        const uint2 mv = *(const uint2 *)mp;   // four bf16; positive <=> sign clear and non-zero
-                        const uint32_t w[2] = {mv.x, mv.y};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const uint32_t h = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-                            if (!(tj_bf16_to_f32((T)h) > 0.f)) v[rq * 4 + e] = 0.f;
-                        }
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (ib + e < a.I && !(tj_bf16_to_f32(mp[e]) > 0.f)) v[rq * 4 + e] = 0.f;
-                    }
-                }
-            }
-            if (a.Ci) {   // rows j, 32 consecutive i (64 bytes) each
-                __syncthreads();
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    uint2 o;
-                    o.x = (uint32_t)tj_f32_to_bf16(v[rq * 4]) | ((uint32_t)tj_f32_to_bf16(v[rq * 4 + 1]) << 16);
-                    o.y = (uint32_t)tj_f32_to_bf16(v[rq * 4 + 2]) | ((uint32_t)tj_f32_to_bf16(v[rq * 4 + 3]) << 16);
-                    *(uint2 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 2) = o;
-                }
-                __syncthreads();
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int vv = lane + 64 * t, jr = vv >> 2, c = vv & 3;
-                    const u32x4 d = *(const u32x4 *)(scr + jr * kScratchPitch + c * 16);
-                    const int j = jbase + jr, i = ibase + c * 8;
-                    if (j < j_end && i < a.I) {
-                        T *cp = a.Ci + (size_t)j * a.ldci + i;
-                        if (i + 8 <= a.I) {
-                            *(u32x4 *)cp = d;
-                        } else {
-                            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (e < a.I - i) cp[e] = (T)((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
-                        }
-                    }
-                }
-            }
-            if (a.Cj) {   // rows i, 32 consecutive j (64 bytes) each
-                __syncthreads();
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        *(T *)(scr + (rq * 8 + lg * 4 + e) * kScratchPitch + l32 * 2) = tj_f32_to_bf16(v[rq * 4 + e]);
-                __syncthreads();
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int vv = lane + 64 * t, ir = vv >> 2, c = vv & 3;
-                    const u32x4 d = *(const u32x4 *)(scr + ir * kScratchPitch + c * 16);
-                    const int i = ibase + ir, j = jbase + c * 8;
-                    const int jmax = min(j_end, a.cj_jmax);
-                    if (i < a.I && j < jmax) {
-                        T *cp = a.Cj + (size_t)i * a.ldcj + j;
-                        if (j + 8 <= jmax && (((uintptr_t)cp) & 15) == 0) {
-                            *(u32x4 *)cp = d;
-                        } else {
-                            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (e < jmax - j) cp[e] = (T)((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
-                        }
-                    }
-                }
-            }
-            if (a.Cf) {   // fp32 rows j, 32 consecutive i (128 bytes) each
-                __syncthreads();
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq)
-                    *(float4 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 4) =
-                        make_float4(v[rq * 4], v[rq * 4 + 1], v[rq * 4 + 2], v[rq * 4 + 3]);
-                __syncthreads();
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int vv = lane + 64 * t, jr = vv >> 3, c = vv & 7;
-                    const float4 d = *(const float4 *)(scr + jr * kScratchPitch + c * 16);
-                    const int j = jbase + jr, i = ibase + c * 4;
-                    if (j < j_end && i < a.I) {
-                        float *fp = a.Cf + (size_t)z * a.cf_zstride + (size_t)j * a.ldcf + i;
-                        if (i + 4 <= a.I && (((uintptr_t)fp) & 15) == 0) {
-                            *(float4 *)fp = d;
-                        } else {
-                            const float w[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (e < a.I - i) fp[e] = w[e];
-                        }
-                    }
-                }
-            }
+            store_tile(a, acc[fi][fj], scr, ibase, jbase, j_end, z, lane);
         }
     }
 }
 
+// ---------------------------------------------------------------- bf16 kernel, direct-to-LDS
+//
+// Block tile 256 (i) x 64*NFJ (j), eight waves as 4 (i) x 2 (j), wave tile
+// 64 x 32*NFJ.  Operands go from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane: the 64 lanes of one instruction fill one
+// contiguous KiB of a stage buffer), NSTAGE buffers form a ring, and the loads of
+// stage s + NSTAGE - 1 are issued before the MFMAs of stage s: nothing is staged
+// in registers and HBM latency is covered by NSTAGE - 1 stages of MFMA work.
+// A stage holds BKB bytes of k per row (128 or 64).  The LDS serves a 16-byte
+// read to 16 lanes per cycle out of 64 four-byte banks, so the operand reads of
+// 16 consecutive rows must cover 16 distinct 16-byte columns of a 256-byte
+// line.  Without padding this is done by an XOR swizzle applied on the global
+// side: the 16-byte vector c of row r is stored at position c ^ ((r >> 1) & 7)
+// (128-byte rows) or c ^ ((r >> 2) & 3) (64-byte rows).
+// Requires whole stages (K and the split chunk multiples of BKB/2 elements);
+// rows past the end are clamped to the last valid row, their results are never
+// stored.  vmcnt counts a wave's outstanding loads in issue order, so waiting
+// for "at most (stages still in flight) x (loads per stage)" means the oldest
+// stage has landed; the barrier that follows extends this to the whole block
+// and also says that every wave is done reading the buffer about to be refilled.
+template <int N> struct IntC { static constexpr int value = N; };
+
+// (bytes of k per row per stage, ring depth) for the 128-, 192- and 256-wide j tiles
+#ifndef TJ_CFG2
+#define TJ_CFG2 128, 3
+#endif
+#ifndef TJ_CFG3
+#define TJ_CFG3 128, 2
+#endif
+#ifndef TJ_CFG4
+#define TJ_CFG4 128, 2
+#endif
+
+template <int NFJ, int BKB, int NSTAGE, bool QSUM>
+__global__ __launch_bounds__(512, (NFJ == 2 && BKB * NSTAGE <= 192) ? 2 : 1) void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
+                                                         const TileMap tm)
+{
+    typedef tj_bf16 T;
+    constexpr int BJ3 = 64 * NFJ;
+    constexpr int KE = BKB / 2;              // k elements per stage
+    constexpr int VPR = BKB / 16;            // 16-byte vectors per row
+    constexpr int RPI = 1024 / BKB;          // rows filled by one load instruction
+    constexpr int CHP = 256 / RPI, CHQ = BJ3 / RPI;
+    constexpr int LP = CHP / 8, LQ = (CHQ + 7) / 8;
+    constexpr int LPS = LP + LQ;             // load instructions per stage per wave
+    constexpr int KS = BKB / 32;             // MFMA k steps per stage
+    constexpr int SZA = 256 * BKB, SZB = BJ3 * BKB;
+    static_assert(NSTAGE >= 2 && NSTAGE <= 6 && (NSTAGE - 1) * LPS < 64, "ring depth");
+    __shared__ __align__(1024) uint8_t sA0[SZA];
+    __shared__ __align__(1024) uint8_t sA1[SZA];
+    __shared__ __align__(1024) uint8_t sA2[NSTAGE > 2 ? SZA : 16];
+    __shared__ __align__(1024) uint8_t sA3[NSTAGE > 3 ? SZA : 16];
+    __shared__ __align__(1024) uint8_t sA4[NSTAGE > 4 ? SZA : 16];
+    __shared__ __align__(1024) uint8_t sA5[NSTAGE > 5 ? SZA : 16];
+    __shared__ __align__(1024) uint8_t sB0[SZB];
+    __shared__ __align__(1024) uint8_t sB1[SZB];
+    __shared__ __align__(1024) uint8_t sB2[NSTAGE > 2 ? SZB : 16];
+    __shared__ __align__(1024) uint8_t sB3[NSTAGE > 3 ? SZB : 16];
+    __shared__ __align__(1024) uint8_t sB4[NSTAGE > 4 ? SZB : 16];
+    __shared__ __align__(1024) uint8_t sB5[NSTAGE > 5 ? SZB : 16];
+    auto bufA = [&](auto u) -> uint8_t * {
+        constexpr int U = decltype(u)::value;
+        if constexpr (U == 0) return sA0; else if constexpr (U == 1) return sA1;
+        else if constexpr (U == 2) return sA2; else if constexpr (U == 3) return sA3;
+        else if constexpr (U == 4) return sA4; else return sA5;
+    };
+    auto bufB = [&](auto u) -> uint8_t * {
+        constexpr int U = decltype(u)::value;
+        if constexpr (U == 0) return sB0; else if constexpr (U == 1) return sB1;
+        else if constexpr (U == 2) return sB2; else if constexpr (U == 3) return sB3;
+        else if constexpr (U == 4) return sB4; else return sB5;
+    };
+
+    int ti, tj, z;
+    {
+        const int id = blockIdx.x;
+        if (a.n_split > 1) {
+            z = id % a.n_split;
+            const int t = id / a.n_split;
+            ti = t % tm.tiles_i;
+            tj = t / tm.tiles_i;
+        } else {
+            z = 0;
+            const int xcd = id & 7, slot = id >> 3;
+            ti = slot % tm.tiles_i;
+            tj = (slot / tm.tiles_i) * 8 + xcd;
+        }
+        if (tj >= tm.tiles_j) return;
+    }
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wi = wave & 3, wj = wave >> 2;
+    const int l32 = lane & 31, lg = lane >> 5;
+
+    const int sidx = (a.n_seg > 1 && tj >= tiles_seg0) ? 1 : 0;
+    const TjGemmSeg<T> seg = a.seg[sidx];
+    const int j0 = seg.j_begin + (tj - (sidx ? tiles_seg0 : 0)) * BJ3;
+    const int j_end = seg.j_end;
+    const int i0 = ti * 256;
+    const int k_begin = z * a.k_chunk;
+    const int k_end = min(a.K, k_begin + a.k_chunk);
+    const int n_stage = k_end > k_begin ? (k_end - k_begin) / KE : 0;
+
+    // This wave's load instructions per stage: P chunks wave + 8 t (t < LP) and Q chunks wave + 8 t
+    // (t < LQ); a chunk = RPI rows.  Q chunks past the end repeat an earlier one (same data to the
+    // same place) so that every wave issues exactly LPS loads.
+    const int lrow = lane / VPR, lpos = lane % VPR;
+    auto swizzle = [](int row) { return VPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };
+    const T *gsrcP[LP];
+    const T *gsrcQ[LQ];
+#pragma unroll
+    for (int t = 0; t < LP; ++t) {
+        const int row = (wave + 8 * t) * RPI + lrow;
+        const int i = min(i0 + row, a.I - 1);
+        gsrcP[t] = seg.P + (size_t)i * a.ldp + (lpos ^ swizzle(row)) * 8 + k_begin;
+    }
+#pragma unroll
+    for (int t = 0; t < LQ; ++t) {
+        int c = wave + 8 * t;
+        if (c >= CHQ) c -= 8;
+        const int row = c * RPI + lrow;
+        const int j = min(j0 + row, j_end - 1);
+        gsrcQ[t] = a.Q + (size_t)(j - seg.q_shift) * a.ldq + (lpos ^ swizzle(row)) * 8 + k_begin;
+    }
+    // global_load_lds_dwordx4: lane l's 16 bytes go to LDS address M0 + 16 l.  Issued as inline
+    // assembly so that the compiler's wait-count pass does not see these loads: it would otherwise
+    // put a vmcnt(0) wait (all stages landed) in front of LDS reads it cannot tell apart from the
+    // buffers being filled.  Completion is tracked by the explicit vmcnt waits in wait_stage().
+    // M0 is written here and by nothing else in this kernel.
+    typedef __attribute__((address_space(3))) uint8_t *lds_ptr_t;
+    auto dma16 = [](const T *src, uint8_t *dst) {
+        const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_ptr_t)dst;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src)
+                     : "memory");
+    };
+    auto issue = [&](uint8_t *sA, uint8_t *sB, int s) {
+#pragma unroll
+        for (int t = 0; t < LP; ++t) dma16(gsrcP[t] + s * KE, sA + (wave + 8 * t) * 1024);
+#pragma unroll
+        for (int t = 0; t < LQ; ++t) {
+            const int c = wave + 8 * t >= CHQ ? wave + 8 * t - 8 : wave + 8 * t;   // wave-uniform
+            dma16(gsrcQ[t] + s * KE, sB + c * 1024);
+        }
+    };
+
+    f32x16 acc[2][NFJ];
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int fj = 0; fj < NFJ; ++fj)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fi][fj][r] = 0.f;
+
+    const bool do_qsum = QSUM && a.qsum != nullptr && ti == 0 && wi == 0;
+    float qs[NFJ];
+#pragma unroll
+    for (int fj = 0; fj < NFJ; ++fj) qs[fj] = 0.f;
+
+    const int swz = (swizzle(l32) ^ lg) * 16;   // tile bases are multiples of 32 rows
+    const int pa_off = (wi * 64 + l32) * BKB, pb_off = (wj * 32 * NFJ + l32) * BKB;
+    // Operand fetch runs one k step ahead of the MFMAs; the scheduling barriers keep the compiler
+    // from hoisting every LDS read of a stage to its top (which costs > 256 registers).
+    auto compute = [&](const uint8_t *sA, const uint8_t *sB) {
+        u32x4 pf[2][2], qf[2][NFJ];
+        auto fetch = [&](int ks, int set) {
+            const int off = swz ^ (ks * 32);
+#pragma unroll
+            for (int f = 0; f < 2; ++f) pf[set][f] = *(const u32x4 *)(sA + pa_off + f * 32 * BKB + off);
+#pragma unroll
+            for (int f = 0; f < NFJ; ++f) qf[set][f] = *(const u32x4 *)(sB + pb_off + f * 32 * BKB + off);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int set = ks & 1;
+            if (ks + 1 < KS) fetch(ks + 1, set ^ 1);
+#pragma unroll
+            for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+                for (int fj = 0; fj < NFJ; ++fj) mma<T>(acc[fi][fj], pf[set][fi], qf[set][fj]);
+            if constexpr (QSUM) {
+                if (do_qsum) {
+#pragma unroll
+                    for (int fj = 0; fj < NFJ; ++fj) qs[fj] += vec_sum<T>(qf[set][fj]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // s_waitcnt vmcnt(n) only (lgkmcnt and expcnt left alone); n < 64
+    auto wait_vm = [&](auto n) {
+        constexpr int N = decltype(n)::value;
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+    };
+    // stage ss has landed for this wave once at most min(NSTAGE-2, n_stage-1-ss) later stages are pending
+    auto wait_stage = [&](int ss) {
+        const int later = min(NSTAGE - 2, n_stage - 1 - ss);
+        if constexpr (NSTAGE >= 6) { if (later >= 4) { wait_vm(IntC<4 * LPS>{}); return; } }
+        if constexpr (NSTAGE >= 5) { if (later >= 3) { wait_vm(IntC<3 * LPS>{}); return; } }
+        if constexpr (NSTAGE >= 4) { if (later >= 2) { wait_vm(IntC<2 * LPS>{}); return; } }
+        if constexpr (NSTAGE >= 3) { if (later >= 1) { wait_vm(IntC<1 * LPS>{}); return; } }
+        wait_vm(IntC<0>{});
+    };
+    // one ring position: wait for stage ss (in buffer U), refill the buffer freed by stage ss-1, compute
+    auto ring_step = [&](auto u, int ss) {
+        constexpr int U = decltype(u)::value;
+        constexpr int UN = (U + NSTAGE - 1) % NSTAGE;
+        wait_stage(ss);
+        // A bare barrier: __syncthreads() carries a fence that would wait for every outstanding
+        // direct load (vmcnt(0)) and with it the stages meant to stay in flight.  The empty asm
+        // statements keep the compiler from moving LDS accesses across the barrier.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (ss + NSTAGE - 1 < n_stage) issue(bufA(IntC<UN>{}), bufB(IntC<UN>{}), ss + NSTAGE - 1);
+        compute(bufA(u), bufB(u));
+    };
+
+    if (0 < n_stage) issue(sA0, sB0, 0);
+    if constexpr (NSTAGE > 2) { if (1 < n_stage) issue(sA1, sB1, 1); }
+    if constexpr (NSTAGE > 3) { if (2 < n_stage) issue(sA2, sB2, 2); }
+    if constexpr (NSTAGE > 4) { if (3 < n_stage) issue(sA3, sB3, 3); }
+    if constexpr (NSTAGE > 5) { if (4 < n_stage) issue(sA4, sB4, 4); }
+    for (int s = 0; s < n_stage; s += NSTAGE) {
+        ring_step(IntC<0>{}, s);
+        if (s + 1 < n_stage) ring_step(IntC<1>{}, s + 1);
+        if constexpr (NSTAGE > 2) { if (s + 2 < n_stage) ring_step(IntC<2>{}, s + 2); }
+        if constexpr (NSTAGE > 3) { if (s + 3 < n_stage) ring_step(IntC<3>{}, s + 3); }
+        if constexpr (NSTAGE > 4) { if (s + 4 < n_stage) ring_step(IntC<4>{}, s + 4); }
+        if constexpr (NSTAGE > 5) { if (s + 5 < n_stage) ring_step(IntC<5>{}, s + 5); }
+    }
+    __syncthreads();   // every wave is done with the operand buffers: the epilogue reuses them
+
+    if constexpr (QSUM) {
+        if (do_qsum) {
+#pragma unroll
+            for (int fj = 0; fj < NFJ; ++fj) {
+                float sum = qs[fj] + __shfl_xor(qs[fj], 32, 64);
+                const int j = j0 + wj * 32 * NFJ + fj * 32 + l32;
+                if (lg == 0 && j < j_end) a.qsum[(size_t)z * a.qsum_zstride + j] = sum;
+            }
+        }
+    }
+
+    // ---- epilogue (as in gemm_bf16): math on every tile first, then the stores
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int fj = 0; fj < NFJ; ++fj)
+            tile_math(a, seg, acc[fi][fj], i0 + wi * 64 + fi * 32, j0 + wj * 32 * NFJ + fj * 32, j_end, lane);
+    constexpr int WPB = SZA / (32 * kScratchPitch) >= 4 ? 4 : SZA / (32 * kScratchPitch);   // waves per buffer
+    static_assert(WPB >= 2 && 7 / WPB < NSTAGE, "epilogue scratch does not fit the P buffers");
+    const int sb = wave / WPB;
+    uint8_t *scr = (sb == 0 ? sA0 : sb == 1 ? sA1 : sb == 2 ? sA2 : sA3) + (wave % WPB) * (32 * kScratchPitch);
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi) {
+#pragma unroll
+        for (int fj = 0; fj < NFJ; ++fj) {
+            const int ibase = i0 + wi * 64 + fi * 32;
+            const int jbase = j0 + wj * 32 * NFJ + fj * 32;
+            store_tile(a, acc[fi][fj], scr, ibase, jbase, j_end, z, lane);
+        }
+    }
+}
+
+template <int NFJ, int BKB, int NSTAGE>
+int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
+{
+    constexpr int BJ3 = 64 * NFJ;
+    TileMap tm;
+    tm.tiles_i = (a.I + 255) / 256;
+    int tiles[2] = {0, 0};
+    for (int s = 0; s < a.n_seg; ++s) tiles[s] = (a.seg[s].j_end - a.seg[s].j_begin + BJ3 - 1) / BJ3;
+    tm.tiles_j = tiles[0] + tiles[1];
+    const unsigned nblk = a.n_split > 1 ? (unsigned)tm.tiles_i * tm.tiles_j * a.n_split
+                                        : (unsigned)tm.tiles_i * ((tm.tiles_j + 7) / 8) * 8;
+    if (a.qsum)
+        gemm_bf16_dlds<NFJ, BKB, NSTAGE, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
+    else
+        gemm_bf16_dlds<NFJ, BKB, NSTAGE, false><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
 int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st)
 {
+    // The direct-to-LDS kernel needs whole 64-k stages in every split slice and enough work to
+    // fill its 256-row tiles; everything else takes the register-staged kernel.
+    const bool whole_stages = a.K % 64 == 0 && (a.n_split == 1 || a.k_chunk % 64 == 0);
+    int jtot = 0;
+    for (int s = 0; s < a.n_seg; ++s) jtot += a.seg[s].j_end - a.seg[s].j_begin;
+    if (whole_stages && a.I >= 128 && jtot >= 128) {
+        // pick the j extent of the tile (128 / 192 / 256) that needs the fewest rounds of 256 blocks,
+        // weighted by the tile's work; ties go to the larger tile
+        int best = 2;
+        long best_cost = -1;
+        for (int nfj = 2; nfj <= 4; ++nfj) {
+            long t = 0;
+            for (int s = 0; s < a.n_seg; ++s) t += (a.seg[s].j_end - a.seg[s].j_begin + 64 * nfj - 1) / (64 * nfj);
+            t *= (long)((a.I + 255) / 256) * a.n_split;
+            const long cost = ((t + 255) / 256) * nfj;
+            if (best_cost < 0 || cost <= best_cost) { best = nfj; best_cost = cost; }
+        }
+#ifdef TJ_FORCE_NFJ
+        best = TJ_FORCE_NFJ;   // tuning builds only
+#endif
+        if (best == 2) {
+            // more tiles than CUs: the shallow-stage variant fits two blocks per CU, so one block's
+            // epilogue overlaps the other's main loop; otherwise one block per CU with deep stages
+            long t = 0;
+            for (int s = 0; s < a.n_seg; ++s) t += (a.seg[s].j_end - a.seg[s].j_begin + 127) / 128;
+            t *= (long)((a.I + 255) / 256) * a.n_split;
+            return t > 256 ? launch_dlds<2, 64, 3>(a, st) : launch_dlds<2, TJ_CFG2>(a, st);
+        }
+        if (best == 3) return launch_dlds<3, TJ_CFG3>(a, st);
+        return launch_dlds<4, TJ_CFG4>(a, st);
+    }
     TileMap tm;
     tm.tiles_i = (a.I + B2I - 1) / B2I;
     tm.tiles_j = tiles[0] + tiles[1];
