@@ -92,7 +92,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="c3", help="workload: c1, c2 or c3")
+    ap.add_argument("--config", default="c3", help="workload: c1 ... c5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's learner step (0 = auto)")
     args = ap.parse_args()
@@ -108,7 +108,7 @@ def main():
 
     wl = synth.WORKLOADS[args.config]
     torch.cuda.set_device(0)
-    buf, versions = fill_ring(tj, synth, wl, 65_536)
+    buf, versions = fill_ring(tj, synth, wl, 65_536 if wl.obs_dtype == "f32" else 16_384)
     theta = synth.xavier_init(wl.layers, wl.in_chw, 1)
     target = synth.xavier_init(wl.layers, wl.in_chw, 2)
     lrn = tj.learner_for_workload(wl, theta, target)
@@ -149,7 +149,10 @@ def main():
         "adam_recast_ms": ms(lev, 3, 4),
     }
     n_layers = len(wl.layers)
-    n_gemm_launch = 3 * n_layers - 1
+    n_conv = sum(1 for l in wl.layers if l[0] == synth.CONV)
+    # forward: one grouped launch per linear layer, two (online, target) per convolution;
+    # backward: a weight-gradient GEMM per layer and an input-gradient GEMM per layer but the first
+    n_gemm_launch = (n_layers + n_conv) + n_layers + (n_layers - 1)
     flops = gemm_flops_per_step(wl, synth)
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
     achieved = flops / (gemm_ms * 1e-3) / 1e12

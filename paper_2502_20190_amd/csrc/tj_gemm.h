@@ -55,6 +55,7 @@ template <typename T> struct TjGemmArgs {
     const T *Q;          // [rows][ldq]
     int ldp, ldq;        // row strides in elements (multiples of a 16-byte vector)
     int I, K;            // rows of P; contraction length (rows are zero padded to a vector multiple)
+    const float *bias_j; // optional bias per column j (convolutions: j = output channel)
     int relu;            // max(x, 0) after bias
     const T *mask;       // optional: D(i,j) = 0 where mask[j*ldmask + i] <= 0 (ReLU derivative)
     int ldmask;

@@ -179,6 +179,11 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
                     for (int e = 0; e < 4; ++e)
                         if (e < nvalid) v[e] += seg.bias[ib + e];
                 }
+                if (a.bias_j) {
+                    const float bj = a.bias_j[j];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += bj;
+                }
                 if (a.relu) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
@@ -251,6 +256,11 @@ __device__ __forceinline__ void tile_math(const TjGemmArgs<tj_bf16> &a, const Tj
                 const int i = ibase + rq * 8 + lg * 4 + e;
                 if (i < a.I) v[rq * 4 + e] += seg.bias[i];
             }
+    }
+    if (a.bias_j && jl < j_end) {
+        const float bj = a.bias_j[jl];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] += bj;
     }
     if (a.relu) {
 #pragma unroll
@@ -385,7 +395,29 @@ constexpr int B2I = 256, B2J = 128;
 
 struct TileMap {
     int tiles_i, tiles_j;   // tile counts (tiles_j over all segments)
+    int spread_i;           // 1: the XCDs split the i tiles (few j tiles), 0: they split the j tiles
 };
+
+// Tile of a block without a split contraction: id % 8 is the XCD the block lands on.
+__device__ __forceinline__ bool xcd_tile(const TileMap &tm, int id, int &ti, int &tj)
+{
+    const int xcd = id & 7, slot = id >> 3;
+    if (tm.spread_i) {
+        tj = slot % tm.tiles_j;
+        ti = (slot / tm.tiles_j) * 8 + xcd;
+    } else {
+        ti = slot % tm.tiles_i;
+        tj = (slot / tm.tiles_i) * 8 + xcd;
+    }
+    return ti < tm.tiles_i && tj < tm.tiles_j;
+}
+
+inline unsigned xcd_grid(TileMap &tm)
+{
+    tm.spread_i = tm.tiles_j < 8 && tm.tiles_i > tm.tiles_j;
+    return tm.spread_i ? (unsigned)tm.tiles_j * ((tm.tiles_i + 7) / 8) * 8
+                       : (unsigned)tm.tiles_i * ((tm.tiles_j + 7) / 8) * 8;
+}
 
 __global__ __launch_bounds__(256, 2) void gemm_bf16(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
                                                     const TileMap tm)
@@ -406,9 +438,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16(const TjGemmArgs<tj_bf16> a,
             tj = t / tm.tiles_i;
         } else {
             z = 0;
-            const int xcd = id & 7, slot = id >> 3;
-            ti = slot % tm.tiles_i;
-            tj = (slot / tm.tiles_i) * 8 + xcd;
+            if (!xcd_tile(tm, id, ti, tj)) return;
         }
         if (tj >= tm.tiles_j) return;
     }
@@ -612,9 +642,7 @@ __global__ __launch_bounds__(512, (NFJ == 2 && BKB * NSTAGE <= 192) ? 2 : 1) voi
             tj = t / tm.tiles_i;
         } else {
             z = 0;
-            const int xcd = id & 7, slot = id >> 3;
-            ti = slot % tm.tiles_i;
-            tj = (slot / tm.tiles_i) * 8 + xcd;
+            if (!xcd_tile(tm, id, ti, tj)) return;
         }
         if (tj >= tm.tiles_j) return;
     }
@@ -804,8 +832,8 @@ int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
     int tiles[2] = {0, 0};
     for (int s = 0; s < a.n_seg; ++s) tiles[s] = (a.seg[s].j_end - a.seg[s].j_begin + BJ3 - 1) / BJ3;
     tm.tiles_j = tiles[0] + tiles[1];
-    const unsigned nblk = a.n_split > 1 ? (unsigned)tm.tiles_i * tm.tiles_j * a.n_split
-                                        : (unsigned)tm.tiles_i * ((tm.tiles_j + 7) / 8) * 8;
+    tm.spread_i = 0;
+    const unsigned nblk = a.n_split > 1 ? (unsigned)tm.tiles_i * tm.tiles_j * a.n_split : xcd_grid(tm);
     if (a.qsum)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else
@@ -820,9 +848,10 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
     const bool whole_stages = a.K % 64 == 0 && (a.n_split == 1 || a.k_chunk % 64 == 0);
     int jtot = 0;
     for (int s = 0; s < a.n_seg; ++s) jtot += a.seg[s].j_end - a.seg[s].j_begin;
-    if (whole_stages && a.I >= 128 && jtot >= 128) {
+    if (whole_stages && a.I >= 128 && jtot >= 1) {
         // pick the j extent of the tile (128 / 192 / 256) that needs the fewest rounds of 256 blocks,
         // weighted by the tile's work; ties go to the larger tile
+        if (jtot <= 64) return launch_dlds<1, 128, 3>(a, st);   // narrow outputs (conv channels)
         int best = 2;
         long best_cost = -1;
         for (int nfj = 2; nfj <= 4; ++nfj) {
@@ -849,12 +878,8 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
     TileMap tm;
     tm.tiles_i = (a.I + B2I - 1) / B2I;
     tm.tiles_j = tiles[0] + tiles[1];
-    unsigned nblk;
-    if (a.n_split > 1) {
-        nblk = (unsigned)tm.tiles_i * tm.tiles_j * a.n_split;
-    } else {
-        nblk = (unsigned)tm.tiles_i * ((tm.tiles_j + 7) / 8) * 8;
-    }
+    tm.spread_i = 0;
+    const unsigned nblk = a.n_split > 1 ? (unsigned)tm.tiles_i * tm.tiles_j * a.n_split : xcd_grid(tm);
     gemm_bf16<<<nblk, 256, 0, st>>>(a, tiles[0], tm);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }

@@ -13,6 +13,7 @@
 //   Qout   fp32 [3B][ld4(A)]
 //   dZ[l]  T [B][ld(d_l)]    dZT[l] T [d_l][ld(B)]
 #include "tj_gemm.h"
+#include "tj_conv.h"
 #include <math.h>
 #include <string.h>
 #include <vector>
@@ -261,7 +262,9 @@ template <typename T> struct MlpLearner : tj_learner {
             lay[l].in = in;
             lay[l].out = (int)d.layers[l].out;
             lay[l].ld_in = round_up(in, VE);
-            lay[l].ld_out = round_up(lay[l].out, VE);
+            // (bf16) a narrow head is padded to one whole 64-k stage, so that the input-gradient
+            // GEMM that contracts over it can use the direct-to-LDS kernel; the pads stay zero
+            lay[l].ld_out = round_up(lay[l].out, (sizeof(T) == 2 && l == L - 1 && in >= 128) ? 64 : VE);
             lay[l].w_off = off; off += (size_t)in * lay[l].out;
             lay[l].b_off = off; off += lay[l].out;
             in = lay[l].out;
@@ -398,7 +401,7 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.seg[0] = {0, B, WcT_on[l - 1], nullptr, 0};
                 g.Q = dZ[l];
                 g.ldp = lp.ld_out; g.ldq = lp.ld_out;
-                g.I = lp.in; g.K = lp.ld_out;
+                g.I = lp.in; g.K = lp.ld_out;   // pad columns are zero in both operands
                 g.k_chunk = g.K; g.n_split = 1;
                 g.mask = X[l - 1]; g.ldmask = lp.ld_in;
                 g.Ci = dZ[l - 1]; g.ldci = lp.ld_in;
@@ -491,6 +494,425 @@ template <typename T> struct MlpLearner : tj_learner {
     }
 };
 
+// ---------------------------------------------------------------- convolutional Q-networks
+//
+// Convolutions first, then linear layers.  Activations are channels-last; a convolution is the
+// GEMM  act_out[m][oc] = relu(sum_k patch[m][k] W[oc][k] + b[oc])  on an explicit patch matrix
+// (rows m = (image, oh, ow), k = (kh, kw, c)), its weight gradient contracts the transposed
+// patch matrix with dZ^T over m (split many ways, reduced and un-permuted afterwards), its input
+// gradient is a GEMM to a patch-gradient matrix followed by a gather (col2im) with the ReLU mask.
+// Images are ordered s | s' | s'(target copy from layer 1 on).
+//   act[l]      input of layer l: conv [n_img][H][W][C]; linear [3B][ldK]
+//   patches[l]  [n_img*OH*OW][ldK]      patchesT[l] [K][ld(B*OH*OW)]   (conv)
+//   XT[l]       [K][ld(B)]                                               (linear)
+//   dZ[l]       gradient wrt the output of layer l: conv [B*OH*OW][OC], linear [B][ldO]; dZT[l]
+//   dpatch[l]   [B*OH*OW][ldK] (conv, l > 0)   part[l]  fp32 [n_split][O*K + O (padded)]
+template <typename T> struct ConvLearner : tj_learner {
+    static constexpr int VE = TjElem<T>::kVec;
+    struct NLayer {
+        int kind;
+        tjconv::ConvGeom g;
+        int O, C, S, K, ldK, ldO;       // weight [O][C][S]; K = C*S
+        int OHW;                        // conv: OH*OW
+        size_t w_off, b_off;
+        int n_split;
+        size_t part_stride;
+        T *Wc_on, *WcT_on, *Wc_tg, *patches, *patchesT, *XT, *dZ, *dZT, *dpatch;
+        float *part;
+    };
+    tj_learner_desc d;
+    int L = 0, A = 0, Bmax = 0, ldB = 0, ldA = 0;
+    size_t P = 0, Ppad = 0;
+    std::vector<NLayer> lay;
+    T *act[TJ_MAX_LAYERS + 1];
+    float *theta_on = nullptr, *theta_tg = nullptr, *m = nullptr, *v = nullptr, *grad = nullptr;
+    T *wc_on_begin = nullptr, *wc_tg_begin = nullptr;
+    size_t wc_bytes = 0;
+    uint8_t *act_begin = nullptr;
+    size_t act_bytes = 0;
+    float *Qout = nullptr, *loss_part = nullptr;
+    int32_t *astar = nullptr;
+    uint32_t *ticket = nullptr;
+    tj_step_stats *stats_internal = nullptr;
+    int last_batch = -1;
+    bool shape_ok = true;
+
+    size_t plan(void *base)
+    {
+        TjArena a(base);
+        L = (int)d.n_layers;
+        Bmax = (int)d.max_batch;
+        ldB = round_up(Bmax, VE);
+        lay.assign(L, NLayer());
+        int c = (int)d.in_c, h = (int)d.in_h, w = (int)d.in_w;
+        bool seen_linear = false, prev_conv = false;
+        size_t off = 0;
+        shape_ok = d.layers[0].kind == TJ_LAYER_CONV2D;
+        for (int l = 0; l < L; ++l) {
+            NLayer &y = lay[l];
+            y.kind = (int)d.layers[l].kind;
+            if (y.kind == TJ_LAYER_CONV2D) {
+                if (seen_linear) shape_ok = false;
+                tjconv::ConvGeom &g = y.g;
+                g.C = c; g.H = h; g.W = w; g.k = (int)d.layers[l].kernel; g.s = (int)d.layers[l].stride;
+                if (h < g.k || w < g.k) { shape_ok = false; g.k = 1; g.s = 1; }
+                g.OC = (int)d.layers[l].out;
+                g.OH = (h - g.k) / g.s + 1; g.OW = (w - g.k) / g.s + 1;
+                g.K = c * g.k * g.k;
+                y.O = g.OC; y.C = c; y.S = g.k * g.k; y.K = g.K; y.OHW = g.OH * g.OW;
+                y.ldK = round_up(y.K, VE);
+                y.ldO = y.O;
+                if (y.O % VE) shape_ok = false;            // channels-last rows must be whole vectors
+                c = g.OC; h = g.OH; w = g.OW;
+                prev_conv = true;
+            } else {
+                seen_linear = true;
+                y.O = (int)d.layers[l].out;
+                if (prev_conv) { y.C = c; y.S = h * w; } else { y.C = c * h * w; y.S = 1; }
+                y.K = y.C * y.S; y.OHW = 1;
+                y.ldK = round_up(y.K, VE);
+                if (prev_conv && y.K % VE) shape_ok = false;
+                y.ldO = round_up(y.O, (sizeof(T) == 2 && l == L - 1 && y.K >= 128) ? 64 : VE);
+                c = y.O; h = 1; w = 1;
+                prev_conv = false;
+            }
+            y.w_off = off; off += (size_t)y.O * y.K;
+            y.b_off = off; off += y.O;
+            // weight-gradient contraction length and its split
+            const size_t Ms = (size_t)Bmax * y.OHW;
+            size_t ns = Ms / 4096;
+            y.n_split = (int)(ns < 1 ? 1 : (ns > 128 ? 128 : ns));
+            y.part_stride = tj_align_up((size_t)y.O * y.K + y.O, 64);
+        }
+        if (lay[L - 1].kind != TJ_LAYER_LINEAR) shape_ok = false;
+        P = off;
+        Ppad = tj_align_up(P, 64);
+        A = lay[L - 1].O;
+        ldA = round_up(A, 4);
+        theta_on = (float *)a.take(P * 4);
+        theta_tg = (float *)a.take(P * 4);
+        m = (float *)a.take(P * 4);
+        v = (float *)a.take(P * 4);
+        grad = (float *)a.take(Ppad * 4);
+        size_t wc0 = a.off;
+        for (int l = 0; l < L; ++l) lay[l].Wc_on = (T *)a.take((size_t)lay[l].O * lay[l].ldK * sizeof(T));
+        wc_bytes = a.off - wc0;
+        wc_on_begin = lay[0].Wc_on;
+        for (int l = 0; l < L; ++l) lay[l].Wc_tg = (T *)a.take((size_t)lay[l].O * lay[l].ldK * sizeof(T));
+        wc_tg_begin = lay[0].Wc_tg;
+        for (int l = 0; l < L; ++l) lay[l].WcT_on = (T *)a.take((size_t)lay[l].K * lay[l].ldO * sizeof(T));
+        for (int l = 0; l < L; ++l) lay[l].part = (float *)a.take((size_t)lay[l].n_split * lay[l].part_stride * 4);
+        size_t act0 = a.off;
+        act_begin = base ? (uint8_t *)base + act0 : nullptr;
+        const size_t B = (size_t)Bmax;
+        for (int l = 0; l < L; ++l) {
+            NLayer &y = lay[l];
+            if (y.kind == TJ_LAYER_CONV2D) {
+                const size_t n_img = l == 0 ? 2 * B : 3 * B;
+                act[l] = (T *)a.take(n_img * y.g.H * y.g.W * y.g.C * sizeof(T));
+                y.patches = (T *)a.take(n_img * y.OHW * y.ldK * sizeof(T));
+                y.patchesT = (T *)a.take((size_t)y.K * round_up((int)(B * y.OHW), VE) * sizeof(T));
+                y.XT = nullptr;
+                y.dZ = (T *)a.take(B * y.OHW * y.O * sizeof(T));
+                y.dZT = (T *)a.take((size_t)y.O * round_up((int)(B * y.OHW), VE) * sizeof(T));
+                y.dpatch = l > 0 ? (T *)a.take(B * y.OHW * y.ldK * sizeof(T)) : nullptr;
+            } else {
+                act[l] = (T *)a.take(3 * B * y.ldK * sizeof(T));
+                y.patches = y.patchesT = y.dpatch = nullptr;
+                y.XT = (T *)a.take((size_t)y.K * ldB * sizeof(T));
+                y.dZ = (T *)a.take(B * y.ldO * sizeof(T));
+                y.dZT = (T *)a.take((size_t)y.O * ldB * sizeof(T));
+            }
+        }
+        act_bytes = a.off - act0;
+        Qout = (float *)a.take(3 * B * ldA * 4);
+        astar = (int32_t *)a.take(B * 4);
+        loss_part = (float *)a.take((size_t)((Bmax + 255) / 256) * 4);
+        ticket = (uint32_t *)a.take(4);
+        stats_internal = (tj_step_stats *)a.take(sizeof(tj_step_stats));
+        return a.off;
+    }
+
+    int recast(bool online, hipStream_t st)
+    {
+        for (int l = 0; l < L; ++l) {
+            NLayer &y = lay[l];
+            const size_t n = (size_t)y.O * y.K;
+            tjconv::permute_cast<T><<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+                (online ? theta_on : theta_tg) + y.w_off, online ? y.Wc_on : y.Wc_tg, y.ldK,
+                online ? y.WcT_on : nullptr, y.ldO, y.O, y.C, y.S);
+        }
+        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+    }
+
+    static dim3 grid1(size_t n) { return dim3((unsigned)((n + 255) / 256)); }
+
+    int transpose(const T *src, int lds, T *dst, int ldd, int R, int Cc, hipStream_t st)
+    {
+        dim3 grid((Cc + 31) / 32, (R + 31) / 32);
+        tjconv::transpose2d<T><<<grid, 256, 0, st>>>(src, lds, dst, ldd, R, Cc);
+        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+    }
+
+    int step(const tj_minibatch *mb, tj_step_stats *d_stats, hipStream_t st) override
+    {
+        const int B = (int)mb->batch;
+        if (B < 1 || B > Bmax) return TJ_ERR_SHAPE;
+        if (!mb->obs || !mb->next_obs || !mb->action || !mb->reward || !mb->done) return TJ_ERR_INVALID_ARG;
+        int rc;
+        if (last_batch != B) {
+            if (last_batch > B) TJ_HIP_TRY(hipMemsetAsync(act_begin, 0, act_bytes, st));
+            last_batch = B;
+        }
+        const int Kb = round_up(B, VE);
+
+        {   // observations -> channels-last compute type, images s | s'
+            const tjconv::ConvGeom &g = lay[0].g;
+            const size_t px = (size_t)B * g.H * g.W, img = (size_t)g.H * g.W * g.C;
+            if (d.obs_dtype == TJ_OBS_U8) {
+                tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->obs, act[0], B, g.C, g.H,
+                                                                       g.W, 1.0f / 255.0f);
+                tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->next_obs,
+                                                                       act[0] + (size_t)B * img, B, g.C, g.H, g.W,
+                                                                       1.0f / 255.0f);
+            } else {
+                tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)mb->obs, act[0], B, g.C, g.H, g.W,
+                                                                     1.0f);
+                tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)mb->next_obs,
+                                                                     act[0] + (size_t)B * img, B, g.C, g.H, g.W, 1.0f);
+            }
+            if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        }
+        if ((rc = mark(0, st)) != TJ_OK) return rc;
+
+        // ---- forward
+        for (int l = 0; l < L; ++l) {
+            NLayer &y = lay[l];
+            if (y.kind == TJ_LAYER_CONV2D) {
+                const tjconv::ConvGeom &g = y.g;
+                const size_t n_img = l == 0 ? 2 * (size_t)B : 3 * (size_t)B;
+                const size_t rows = n_img * y.OHW, Ms = (size_t)B * y.OHW;
+                const int run = g.k * g.C;
+                const bool vec = sizeof(T) == 2 && run % 8 == 0 && (g.s * g.C) % 8 == 0 && (g.W * g.C) % 8 == 0 &&
+                                 y.ldK % 8 == 0;
+                if (vec)
+                    tjconv::im2col<T, 8><<<grid1(rows * g.k * (run / 8)), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
+                else
+                    tjconv::im2col<T, 1><<<grid1(rows * g.k * run), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
+                {
+                    dim3 grid((unsigned)((Ms + 255) / 256), (unsigned)y.K);
+                    tjconv::im2col_t<T><<<grid, 256, 0, st>>>(act[l], y.patchesT, g, Ms,
+                                                              round_up((int)((size_t)Bmax * y.OHW), VE));
+                }
+                if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                for (int net = 0; net < 2; ++net) {   // online on s and s', target on s'
+                    const size_t row0 = net == 0 ? 0 : (l == 0 ? Ms : 2 * Ms);
+                    const size_t nrow = net == 0 ? 2 * Ms : Ms;
+                    TjGemmArgs<T> gm;
+                    memset(&gm, 0, sizeof(gm));
+                    gm.n_seg = 1;
+                    gm.seg[0] = {0, y.O, y.patches + row0 * y.ldK, nullptr, 0};
+                    gm.Q = net == 0 ? y.Wc_on : y.Wc_tg;
+                    gm.ldp = y.ldK; gm.ldq = y.ldK;
+                    gm.I = (int)nrow; gm.K = y.ldK; gm.k_chunk = gm.K; gm.n_split = 1;
+                    gm.bias_j = (net == 0 ? theta_on : theta_tg) + y.b_off;
+                    gm.relu = 1;
+                    gm.Cj = act[l + 1] + (net == 0 ? 0 : 2 * Ms * y.O); gm.ldcj = y.O; gm.cj_jmax = y.O;
+                    if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                }
+            } else {
+                if (l > 0 && lay[l - 1].kind == TJ_LAYER_CONV2D)   // transposed input of the s rows
+                    if ((rc = transpose(act[l], y.ldK, y.XT, ldB, B, y.K, st)) != TJ_OK) return rc;
+                TjGemmArgs<T> gm;
+                memset(&gm, 0, sizeof(gm));
+                gm.n_seg = 2;
+                gm.seg[0] = {0, 2 * B, y.Wc_on, theta_on + y.b_off, 0};
+                gm.seg[1] = {2 * B, 3 * B, y.Wc_tg, theta_tg + y.b_off, 0};
+                gm.Q = act[l];
+                gm.ldp = y.ldK; gm.ldq = y.ldK;
+                gm.I = y.O; gm.K = y.ldK; gm.k_chunk = gm.K; gm.n_split = 1;
+                if (l + 1 < L) {
+                    gm.relu = 1;
+                    gm.Ci = act[l + 1]; gm.ldci = lay[l + 1].ldK;
+                    gm.Cj = lay[l + 1].XT; gm.ldcj = ldB; gm.cj_jmax = B;
+                } else {
+                    gm.Cf = Qout; gm.ldcf = ldA;
+                }
+                if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+            }
+        }
+        if ((rc = mark(1, st)) != TJ_OK) return rc;
+
+        const uint32_t t_next = (uint32_t)(t + 1);
+        td_huber<T><<<(B + 255) / 256, 256, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done, d.gamma,
+                                                     d.huber_delta, lay[L - 1].dZ, lay[L - 1].ldO, lay[L - 1].dZT,
+                                                     ldB, astar, loss_part, ticket, d_stats, stats_internal, t_next);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        if ((rc = mark(2, st)) != TJ_OK) return rc;
+
+        // ---- backward through Q_online(s)
+        for (int l = L - 1; l >= 0; --l) {
+            NLayer &y = lay[l];
+            const bool conv = y.kind == TJ_LAYER_CONV2D;
+            const size_t Ms = (size_t)B * y.OHW;
+            const int Kc = conv ? round_up((int)Ms, VE) : Kb;      // contraction of the weight gradient
+            const int ldm = conv ? round_up((int)((size_t)Bmax * y.OHW), VE) : ldB;
+            {   // dW[o][k] = sum_m dZ[m][o] X[m][k] (k in kernel order), db[o] = sum_m dZ[m][o]
+                TjGemmArgs<T> gm;
+                memset(&gm, 0, sizeof(gm));
+                gm.n_seg = 1;
+                gm.seg[0] = {0, y.O, conv ? y.patchesT : y.XT, nullptr, 0};
+                gm.Q = y.dZT;
+                gm.ldp = ldm;   // pitches follow the largest batch, so pad columns are never written
+                gm.ldq = ldm;
+                gm.I = y.K; gm.K = Kc;
+                int ns = y.n_split;
+                const int ke = 128 / (int)sizeof(T);
+                gm.k_chunk = round_up((Kc + ns - 1) / ns, ke);
+                gm.n_split = ns;
+                gm.Cf = y.part; gm.ldcf = y.K; gm.cf_zstride = y.part_stride;
+                gm.qsum = y.part + (size_t)y.O * y.K; gm.qsum_zstride = y.part_stride;
+                if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                const size_t n = (size_t)y.O * y.K + y.O;
+                tjconv::reduce_permute<<<grid1(n), 256, 0, st>>>(y.part, y.part_stride, ns, grad + y.w_off,
+                                                                 grad + y.b_off, y.O, y.C, y.S);
+                if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+            }
+            if (l == 0) break;
+            NLayer &below = lay[l - 1];
+            if (!conv) {   // dX[m][k] = relu'(X) * sum_o dZ[m][o] W[o][k]
+                TjGemmArgs<T> gm;
+                memset(&gm, 0, sizeof(gm));
+                gm.n_seg = 1;
+                gm.seg[0] = {0, B, y.WcT_on, nullptr, 0};
+                gm.Q = y.dZ;
+                gm.ldp = y.ldO; gm.ldq = y.ldO;
+                gm.I = y.K; gm.K = y.ldO; gm.k_chunk = gm.K; gm.n_split = 1;
+                gm.mask = act[l]; gm.ldmask = y.ldK;
+                gm.Ci = below.dZ; gm.ldci = y.ldK;
+                if (below.kind == TJ_LAYER_LINEAR) { gm.Cj = below.dZT; gm.ldcj = ldB; gm.cj_jmax = B; }
+                if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+            } else {       // patch gradients, then the gather back onto the input pixels with the ReLU mask
+                TjGemmArgs<T> gm;
+                memset(&gm, 0, sizeof(gm));
+                gm.n_seg = 1;
+                gm.seg[0] = {0, y.K, y.dZ, nullptr, 0};
+                gm.Q = y.WcT_on;
+                gm.ldp = y.O; gm.ldq = y.ldO;
+                gm.I = (int)Ms; gm.K = y.O; gm.k_chunk = gm.K; gm.n_split = 1;
+                gm.Cj = y.dpatch; gm.ldcj = y.ldK; gm.cj_jmax = y.K;
+                if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                const size_t n = (size_t)B * y.g.H * y.g.W * y.g.C;
+                tjconv::col2im_mask<T><<<grid1(n), 256, 0, st>>>(y.dpatch, y.ldK, act[l], below.dZ, y.g, (size_t)B);
+                if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+            }
+            if (below.kind == TJ_LAYER_CONV2D) {   // dZ^T of a conv layer: [OC][B*OH*OW]
+                const int Mb = (int)((size_t)B * below.OHW);
+                if ((rc = transpose(below.dZ, below.O, below.dZT, round_up((int)((size_t)Bmax * below.OHW), VE), Mb,
+                                    below.O, st)) != TJ_OK)
+                    return rc;
+            }
+        }
+        if ((rc = mark(3, st)) != TJ_OK) return rc;
+
+        t += 1;
+        const float c1 = (float)(1.0 - pow((double)d.beta1, (double)t));
+        const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
+        adam_update<<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
+                                                                   d.beta2, d.eps, c1, c2);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        if ((rc = recast(true, st)) != TJ_OK) return rc;
+        if ((rc = mark(4, st)) != TJ_OK) return rc;
+        if (d.target_interval && t % d.target_interval == 0) {
+            TJ_HIP_TRY(hipMemcpyAsync(theta_tg, theta_on, P * 4, hipMemcpyDeviceToDevice, st));
+            TJ_HIP_TRY(hipMemcpyAsync(wc_tg_begin, wc_on_begin, wc_bytes, hipMemcpyDeviceToDevice, st));
+        }
+        return TJ_OK;
+    }
+
+    int get_state(int which, float *h_out, size_t n, hipStream_t st) override
+    {
+        const float *src = nullptr;
+        switch (which) {
+        case TJ_STATE_PARAMS: src = theta_on; break;
+        case TJ_STATE_TARGET: src = theta_tg; break;
+        case TJ_STATE_ADAM_M: src = m; break;
+        case TJ_STATE_ADAM_V: src = v; break;
+        case TJ_STATE_GRADS: src = grad; break;
+        default: break;
+        }
+        if (src) {
+            if (n != P) return TJ_ERR_INVALID_ARG;
+            TJ_HIP_TRY(hipMemcpyAsync(h_out, src, P * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            return TJ_OK;
+        }
+        if (which == TJ_STATE_QVALS) {
+            if (last_batch < 1 || n != 3 * (size_t)last_batch * A) return TJ_ERR_INVALID_ARG;
+            std::vector<float> tmp(3 * (size_t)last_batch * ldA);
+            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), Qout, tmp.size() * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            for (size_t r = 0; r < 3 * (size_t)last_batch; ++r)
+                for (int a = 0; a < A; ++a) h_out[r * A + a] = tmp[r * ldA + a];
+            return TJ_OK;
+        }
+        if (which == TJ_STATE_ASTAR) {
+            if (last_batch < 1 || n != (size_t)last_batch) return TJ_ERR_INVALID_ARG;
+            std::vector<int32_t> tmp(last_batch);
+            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), astar, tmp.size() * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            for (int j = 0; j < last_batch; ++j) h_out[j] = (float)tmp[j];
+            return TJ_OK;
+        }
+        return TJ_ERR_INVALID_ARG;
+    }
+
+    int set_state(int which, const float *h_in, size_t n, hipStream_t st) override
+    {
+        if (n != P) return TJ_ERR_INVALID_ARG;
+        float *dst = nullptr;
+        switch (which) {
+        case TJ_STATE_PARAMS: dst = theta_on; break;
+        case TJ_STATE_TARGET: dst = theta_tg; break;
+        case TJ_STATE_ADAM_M: dst = m; break;
+        case TJ_STATE_ADAM_V: dst = v; break;
+        default: return TJ_ERR_INVALID_ARG;
+        }
+        TJ_HIP_TRY(hipMemcpyAsync(dst, h_in, P * 4, hipMemcpyHostToDevice, st));
+        int rc = TJ_OK;
+        if (which == TJ_STATE_PARAMS) rc = recast(true, st);
+        if (which == TJ_STATE_TARGET) rc = recast(false, st);
+        TJ_HIP_TRY(hipStreamSynchronize(st));
+        return rc;
+    }
+};
+
+template <typename L>
+int create_learner(const tj_learner_desc *desc, void *arena, size_t bytes, const float *h_on, const float *h_tg,
+                   hipStream_t st, tj_learner **out)
+{
+    L *l = new L();
+    l->d = *desc;
+    size_t need = l->plan(nullptr);
+    if (bytes < need) { delete l; return TJ_ERR_ARENA_TOO_SMALL; }
+    l->plan(arena);
+    int rc = TJ_OK;
+    if (hipMemsetAsync(arena, 0, need, st) != hipSuccess) rc = TJ_ERR_DEVICE;
+    if (rc == TJ_OK) rc = l->set_state(TJ_STATE_PARAMS, h_on, l->P, st);
+    if (rc == TJ_OK) rc = l->set_state(TJ_STATE_TARGET, h_tg, l->P, st);
+    if (rc != TJ_OK) { delete l; return rc; }
+    *out = l;
+    return TJ_OK;
+}
+
+template <typename T> size_t measure_conv(const tj_learner_desc *desc)
+{
+    ConvLearner<T> l;
+    l.d = *desc;
+    size_t n = l.plan(nullptr);
+    return l.shape_ok ? n : 0;
+}
+
 template <typename T>
 int create_mlp(const tj_learner_desc *desc, void *arena, size_t bytes, const float *h_on, const float *h_tg,
                hipStream_t st, tj_learner **out)
@@ -542,7 +964,8 @@ size_t tj_learner_num_params(const tj_learner_desc *d)
 
 size_t tj_learner_arena_bytes(const tj_learner_desc *d)
 {
-    if (!desc_ok(d) || !all_linear(d)) return 0;
+    if (!desc_ok(d)) return 0;
+    if (!all_linear(d)) return d->precision == TJ_PRECISION_BF16 ? measure_conv<tj_bf16>(d) : measure_conv<float>(d);
     return d->precision == TJ_PRECISION_BF16 ? measure_mlp<tj_bf16>(d) : measure_mlp<float>(d);
 }
 
@@ -552,8 +975,13 @@ int tj_learner_create(const tj_learner_desc *d, void *dev_arena, size_t arena_by
     if (!out) return TJ_ERR_INVALID_ARG;
     *out = nullptr;
     if (!desc_ok(d) || !dev_arena || ((uintptr_t)dev_arena & 255) || !h_on || !h_tg) return TJ_ERR_INVALID_ARG;
-    if (!all_linear(d)) return TJ_ERR_SHAPE;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (!all_linear(d)) {
+        if (tj_learner_arena_bytes(d) == 0) return TJ_ERR_SHAPE;
+        return d->precision == TJ_PRECISION_BF16
+                   ? create_learner<ConvLearner<tj_bf16>>(d, dev_arena, arena_bytes, h_on, h_tg, st, out)
+                   : create_learner<ConvLearner<float>>(d, dev_arena, arena_bytes, h_on, h_tg, st, out);
+    }
     return d->precision == TJ_PRECISION_BF16 ? create_mlp<tj_bf16>(d, dev_arena, arena_bytes, h_on, h_tg, st, out)
                                              : create_mlp<float>(d, dev_arena, arena_bytes, h_on, h_tg, st, out);
 }

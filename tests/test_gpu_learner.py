@@ -79,9 +79,24 @@ def _pair(tj, orc, wl, seed=0, max_batch=None, perturb_bias=True, hidden_bias=No
     return g, o
 
 
-def _step_both(tj, orc, g, o, wl, rows, tol, check_state=True):
+def _load_oracle_state_into_gpu(tj, orc, g, o):
+    """Teacher forcing, in the allowed direction: the GPU learner takes the ORACLE's state
+    (the oracle never receives anything from the GPU).  With bf16 operands, free-running
+    trajectories drift apart after a few Adam steps (an update of +-lr on every weight whose
+    tiny gradient changes sign), so multi-step bf16 comparisons restart each step from the
+    oracle's state and compare one step at a time."""
+    g.set_state(tj.TJ_STATE_PARAMS, o.get_state(orc.PARAMS))
+    g.set_state(tj.TJ_STATE_TARGET, o.get_state(orc.TARGET))
+    g.set_state(tj.TJ_STATE_ADAM_M, o.get_state(orc.ADAM_M))
+    g.set_state(tj.TJ_STATE_ADAM_V, o.get_state(orc.ADAM_V))
+    g.t = o.t
+
+
+def _step_both(tj, orc, g, o, wl, rows, tol, check_state=True, sync=False):
     """One step on both sides; compares loss, Q-values, greedy actions, gradients
     and (optionally) the updated state.  Returns the worst relative error seen."""
+    if sync:
+        _load_oracle_state_into_gpu(tj, orc, g, o)
     b = len(rows["action"])
     mb = tj.Minibatch(b, wl.obs_elems, wl.obs_dtype)
     mb.load(**rows)
@@ -226,3 +241,49 @@ def test_learner_argument_errors(tj, orc):
     conv = tj.make_learner_desc([(1, 8, 3, 1), (0, 4, 0, 0)], (1, 8, 8), "u8", "bf16", 8, 0.99, 1.0, 1e-3,
                                 0.9, 0.999, 1e-8, 10)
     assert L.tj_learner_num_params(ctypes.byref(conv)) == 8 * 9 + 8 + 4 * 8 * 36 + 4
+    assert L.tj_learner_arena_bytes(ctypes.byref(conv)) > 0
+    # channels-last rows must be whole 16-byte vectors: 6 output channels are refused
+    bad = tj.make_learner_desc([(1, 6, 3, 1), (0, 4, 0, 0)], (1, 8, 8), "u8", "bf16", 8, 0.99, 1.0, 1e-3,
+                               0.9, 0.999, 1e-8, 10)
+    assert L.tj_learner_arena_bytes(ctypes.byref(bad)) == 0
+
+
+# ---------------------------------------------------------------- convolutional Q-networks
+
+def _conv_workload(precision, obs_dtype="u8", batch=24, in_chw=(2, 14, 14), layers=None, n_actions=4):
+    from paper_2502_20190_amd.synth import CONV
+
+    layers = layers or ((CONV, 8, 4, 2), (CONV, 16, 3, 1), (LIN, 32, 0, 0), (LIN, n_actions, 0, 0))
+    return replace(synth.WORKLOADS["c4"], obs_shape=in_chw, obs_dtype=obs_dtype, n_actions=n_actions,
+                   layers=layers, precision=precision, batch=batch, lr=1e-3, target_interval=2)
+
+
+@pytest.mark.parametrize("precision,obs_dtype", [("fp32", "u8"), ("bf16", "u8"), ("fp32", "f32")])
+def test_small_conv_net(tj, orc, precision, obs_dtype):
+    """Two convolutions (4x4/2, 3x3/1) and two linear layers on 2x14x14 frames: patch matrices,
+    channels-last permutations of the weights, col2im input gradients, target sync at t = 2."""
+    wl = _conv_workload(precision, obs_dtype)
+    g, o = _pair(tj, orc, wl, seed=11)
+    for step, b in enumerate((24, 24, 7)):
+        rows = _batch_clear_of_kinks(o, wl, 300 + step, b) if precision == "fp32" else _batch(wl, 300 + step, b)
+        _step_both(tj, orc, g, o, wl, rows, TOL[precision], sync=(precision == "bf16" and step > 0))
+
+
+def test_conv_stride_and_kernel_variants(tj, orc):
+    """8x8/4 on 4 channels (the first Nature-DQN layer's geometry at small size) followed by 4x4/2."""
+    from paper_2502_20190_amd.synth import CONV
+
+    wl = _conv_workload("bf16", batch=10, in_chw=(4, 36, 36),
+                        layers=((CONV, 16, 8, 4), (CONV, 16, 4, 2), (LIN, 24, 0, 0), (LIN, 6, 0, 0)), n_actions=6)
+    g, o = _pair(tj, orc, wl, seed=12)
+    for step in range(2):
+        _step_both(tj, orc, g, o, wl, _batch(wl, 320 + step), TOL["bf16"], sync=step > 0)
+
+
+def test_c4_nature_dqn_shape_small_batch(tj, orc):
+    """Config 4's network (4x84x84 u8 frames, conv 8x8/4x32, 4x4/2x64, 3x3/1x64, FC 3136-512-18, bf16)
+    at batch 16, against the bf16-rounding oracle."""
+    wl = replace(synth.WORKLOADS["c4"], batch=16)
+    g, o = _pair(tj, orc, wl, seed=13)
+    worst, _ = _step_both(tj, orc, g, o, wl, _batch(wl, 340), TOL["bf16"])
+    print("c4 network, batch 16, worst relative errors:", worst)
