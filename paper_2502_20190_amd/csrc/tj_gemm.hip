@@ -241,9 +241,9 @@ __device__ __forceinline__ void wave_sync()
 // i = ibase + 8*(r/4) + 4*(lane/32) + r%4, j = jbase + lane%32.  Kept apart from the stores: on this
 // hardware loads and stores share one counter (vmcnt), so a load issued after a tile's stores would
 // wait for those stores to finish.  The kernels run this on every tile first, then store.
-__device__ __forceinline__ void tile_math(const TjGemmArgs<tj_bf16> &a, const TjGemmSeg<tj_bf16> &seg,
-                                          f32x16 &v, const int ibase, const int jbase, const int j_end,
-                                          const int lane)
+__device__ __forceinline__ f32x16 tile_math_edge(const TjGemmArgs<tj_bf16> &a, const TjGemmSeg<tj_bf16> &seg,
+                                              f32x16 v, const int ibase, const int jbase, const int j_end,
+                                              const int lane)
 {
     typedef tj_bf16 T;
     const int l32 = lane & 31, lg = lane >> 5;
@@ -286,12 +286,13 @@ __device__ __forceinline__ void tile_math(const TjGemmArgs<tj_bf16> &a, const Tj
             }
         }
     }
+    return v;
 }
 
 // The stores of one 32 x 32 tile (values already final), staged through a wave-private LDS
 // scratch of 32 rows x kScratchPitch bytes so that every lane writes 16 contiguous bytes.  The
 // scratch must not be shared with another wave.
-__device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f32x16 &v, uint8_t *scr,
+__device__ __forceinline__ void store_tile_edge(const TjGemmArgs<tj_bf16> &a, const f32x16 v, uint8_t *scr,
                                            const int ibase, const int jbase, const int j_end, const int z,
                                            const int lane)
 {
@@ -376,6 +377,117 @@ __device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f
                 }
             }
         }
+    }
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// Two floats -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// Interior tiles (all 32 x 32 outputs in range, 16-byte aligned bias): the same math and stores
+// without per-element guards (the guarded versions above serve the edge tiles).
+__device__ __forceinline__ void tile_math(const TjGemmArgs<tj_bf16> &a, const TjGemmSeg<tj_bf16> &seg,
+                                          f32x16 &v, const int ibase, const int jbase, const int j_end,
+                                          const int lane)
+{
+    const bool interior = ibase + 32 <= a.I && jbase + 32 <= j_end && (((uintptr_t)seg.bias) & 15) == 0;
+    if (!interior) {
+        v = tile_math_edge(a, seg, v, ibase, jbase, j_end, lane);
+        return;
+    }
+    const int l32 = lane & 31, lg = lane >> 5;
+    if (seg.bias) {
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            const float4 b = *(const float4 *)(seg.bias + ibase + rq * 8 + lg * 4);
+            v[rq * 4 + 0] += b.x; v[rq * 4 + 1] += b.y; v[rq * 4 + 2] += b.z; v[rq * 4 + 3] += b.w;
+        }
+    }
+    if (a.bias_j) {
+        const float bj = a.bias_j[jbase + l32];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] += bj;
+    }
+    if (a.relu) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], 0.f);
+    }
+    if (a.mask) {
+        const tj_bf16 *mp = a.mask + (size_t)(jbase + l32) * a.ldmask + ibase + lg * 4;
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            const uint2 mv = *(const uint2 *)(mp + rq * 8);   // four bf16: positive <=> as int16 > 0
+            if (!((int16_t)(mv.x & 0xFFFFu) > 0)) v[rq * 4 + 0] = 0.f;
+            if (!((int16_t)(mv.x >> 16) > 0)) v[rq * 4 + 1] = 0.f;
+            if (!((int16_t)(mv.y & 0xFFFFu) > 0)) v[rq * 4 + 2] = 0.f;
+            if (!((int16_t)(mv.y >> 16) > 0)) v[rq * 4 + 3] = 0.f;
+        }
+    }
+}
+
+__device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f32x16 &v, uint8_t *scr,
+                                           const int ibase, const int jbase, const int j_end, const int z,
+                                           const int lane)
+{
+    typedef tj_bf16 T;
+    bool interior = ibase + 32 <= a.I && jbase + 32 <= j_end;
+    if (a.Cj) interior = interior && jbase + 32 <= a.cj_jmax && ((a.ldcj | jbase) & 7) == 0;
+    if (a.Cf) interior = interior && ((((uintptr_t)(a.Cf + (size_t)z * a.cf_zstride)) | (uintptr_t)(a.ldcf * 4)) & 15) == 0;
+    if (!interior) {
+        if (jbase < j_end && ibase < a.I) store_tile_edge(a, v, scr, ibase, jbase, j_end, z, lane);
+        return;
+    }
+    const int l32 = lane & 31, lg = lane >> 5;
+    if (a.Ci) {   // rows j, 32 consecutive i (64 bytes) each
+        wave_sync();
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            uint2 o;
+            o.x = pack_bf16(v[rq * 4], v[rq * 4 + 1]);
+            o.y = pack_bf16(v[rq * 4 + 2], v[rq * 4 + 3]);
+            *(uint2 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 2) = o;
+        }
+        wave_sync();
+        T *cp = a.Ci + (size_t)(jbase + (lane >> 2)) * a.ldci + ibase + (lane & 3) * 8;
+        const uint8_t *sp = scr + (lane >> 2) * kScratchPitch + (lane & 3) * 16;
+        *(u32x4 *)cp = *(const u32x4 *)sp;
+        *(u32x4 *)(cp + (size_t)16 * a.ldci) = *(const u32x4 *)(sp + 16 * kScratchPitch);
+    }
+    if (a.Cj) {   // rows i, 32 consecutive j (64 bytes) each
+        wave_sync();
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            const uint32_t p01 = pack_bf16(v[rq * 4], v[rq * 4 + 1]), p23 = pack_bf16(v[rq * 4 + 2], v[rq * 4 + 3]);
+            uint8_t *wp = scr + (rq * 8 + lg * 4) * kScratchPitch + l32 * 2;
+            *(T *)(wp) = (T)(p01 & 0xFFFFu);
+            *(T *)(wp + kScratchPitch) = (T)(p01 >> 16);
+            *(T *)(wp + 2 * kScratchPitch) = (T)(p23 & 0xFFFFu);
+            *(T *)(wp + 3 * kScratchPitch) = (T)(p23 >> 16);
+        }
+        wave_sync();
+        T *cp = a.Cj + (size_t)(ibase + (lane >> 2)) * a.ldcj + jbase + (lane & 3) * 8;
+        const uint8_t *sp = scr + (lane >> 2) * kScratchPitch + (lane & 3) * 16;
+        *(u32x4 *)cp = *(const u32x4 *)sp;
+        *(u32x4 *)(cp + (size_t)16 * a.ldcj) = *(const u32x4 *)(sp + 16 * kScratchPitch);
+    }
+    if (a.Cf) {   // fp32 rows j, 32 consecutive i (128 bytes) each
+        wave_sync();
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq)
+            *(float4 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 4) =
+                make_float4(v[rq * 4], v[rq * 4 + 1], v[rq * 4 + 2], v[rq * 4 + 3]);
+        wave_sync();
+        float *fp = a.Cf + (size_t)z * a.cf_zstride + (size_t)(jbase + (lane >> 3)) * a.ldcf + ibase + (lane & 7) * 4;
+        const uint8_t *sp = scr + (lane >> 3) * kScratchPitch + (lane & 7) * 16;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            *(float4 *)(fp + (size_t)(8 * t) * a.ldcf) = *(const float4 *)(sp + 8 * t * kScratchPitch);
     }
 }
 
