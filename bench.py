@@ -146,7 +146,7 @@ def main():
     ph = {
         "mask_scan_select_ms": ms(bev, 0, 1), "gather_ms": ms(bev, 1, 2),
         "forward_gemm_ms": ms(lev, 0, 1), "td_huber_ms": ms(lev, 1, 2), "backward_gemm_ms": ms(lev, 2, 3),
-        "adam_recast_ms": ms(lev, 3, 4),
+        "adam_ms": ms(lev, 3, 4),
     }
     n_layers = len(wl.layers)
     n_conv = sum(1 for l in wl.layers if l[0] == synth.CONV)
@@ -175,7 +175,7 @@ def main():
         "phases_ms": ph,
         "gather": {"bound": "hbm", "achieved": gather_bytes / (ph["gather_ms"] * 1e-3) / 1e9,
                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": gather_bytes},
-        "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_recast_ms"] * 1e-3) / 1e9,
+        "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9,
                  "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": adam_bytes},
         "loss": loss,
     }

@@ -212,8 +212,8 @@ int tj_learner_set_step(tj_learner *lrn, uint64_t t);
  *   [0] start, [1] after mask + scan + select, [2] after the row gather
  * (n must be 3), and every tj_learner_step records
  *   [0] after the input cast, [1] after the forward GEMMs, [2] after the TD /
- *   Huber kernel, [3] after the backward GEMMs, [4] after Adam and the weight
- *   recast (n must be 5),
+ *   Huber kernel, [3] after the backward GEMMs, [4] after the Adam kernel (the
+ *   transposed weight copies for the next step follow it) (n must be 5),
  * on the call's stream.  The caller reads them after synchronising. */
 int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n);
 int tj_learner_set_phase_events(tj_learner *lrn, void *const *hip_events, uint32_t n);

@@ -68,6 +68,7 @@ template <typename T> struct TjGemmArgs {
     int n_split;         // gridDim.z
     float *qsum;         // optional: qsum[z*qsum_zstride + j] = sum over this z's k of Q[j][k]
     size_t qsum_zstride;
+
 };
 
 template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st);

@@ -953,14 +953,19 @@ int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 
+// The direct-to-LDS kernel needs whole 64-k stages in every split slice and enough rows to fill
+// its 256-row tiles; everything else takes the register-staged kernel.
+bool uses_dlds(const TjGemmArgs<tj_bf16> &a)
+{
+    const bool whole_stages = a.K % 64 == 0 && (a.n_split == 1 || a.k_chunk % 64 == 0);
+    return whole_stages && a.I >= 128;
+}
+
 int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st)
 {
-    // The direct-to-LDS kernel needs whole 64-k stages in every split slice and enough work to
-    // fill its 256-row tiles; everything else takes the register-staged kernel.
-    const bool whole_stages = a.K % 64 == 0 && (a.n_split == 1 || a.k_chunk % 64 == 0);
     int jtot = 0;
     for (int s = 0; s < a.n_seg; ++s) jtot += a.seg[s].j_end - a.seg[s].j_begin;
-    if (whole_stages && a.I >= 128 && jtot >= 1) {
+    if (uses_dlds(a)) {
         // pick the j extent of the tile (128 / 192 / 256) that needs the fewest rounds of 256 blocks,
         // weighted by the tile's work; ties go to the larger tile
         if (jtot <= 64) return launch_dlds<1, 128, 3>(a, st);   // narrow outputs (conv channels)

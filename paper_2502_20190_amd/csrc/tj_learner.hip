@@ -6,7 +6,7 @@
 // Device layout inside the caller's arena (T = fp32 or bf16 compute type, every
 // 2-D buffer has its row pitch padded to a 16-byte multiple, pads stay zero):
 //   theta_on, theta_tg, m, v      fp32 [P]      master state, flat order
-//   gpart                         fp32 [S][Ppad] split-K partial gradients
+//   gpart                         fp32 [S][Ppad] split-K partial gradients, summed into slice 0
 //   Wc_on[l]  T [out][ld(in)]     WcT_on[l] T [in][ld(out)]   Wc_tg[l]
 //   X[l]   T [3B][ld(d_l)]   rows: s | s' (online) | s' (target); X[0] has 2B rows
 //   XT[l]  T [d_l][ld(B)]    transposed copy of the s rows
@@ -143,11 +143,36 @@ __global__ __launch_bounds__(256) void td_huber(const float *__restrict__ Q, int
     }
 }
 
-// Adam on the flat fp32 master state; the gradient is the sum of S partial slices.
+// Where Adam also writes the compute-type copy of a weight block: flat parameters [begin, end)
+// go to dst[0 .. end-begin) (only blocks whose copy has no row padding).
+template <typename T> struct EmitTable {
+    int n;
+    size_t begin[TJ_MAX_LAYERS], end[TJ_MAX_LAYERS];
+    T *dst[TJ_MAX_LAYERS];
+};
+
+template <typename T> __device__ __forceinline__ void emit4(T *dst, const float (&x)[4]);
+template <> __device__ __forceinline__ void emit4<float>(float *dst, const float (&x)[4])
+{
+    *(float4 *)dst = make_float4(x[0], x[1], x[2], x[3]);
+}
+template <> __device__ __forceinline__ void emit4<tj_bf16>(tj_bf16 *dst, const float (&x)[4])
+{
+    uint2 o;
+    o.x = (uint32_t)tj_f32_to_bf16(x[0]) | ((uint32_t)tj_f32_to_bf16(x[1]) << 16);
+    o.y = (uint32_t)tj_f32_to_bf16(x[2]) | ((uint32_t)tj_f32_to_bf16(x[3]) << 16);
+    *(uint2 *)dst = o;
+}
+
+// Adam on the flat fp32 master state (bias-corrected, eps outside the square root); the gradient
+// is the sum of S slices (S = 1 when the weight-gradient GEMMs reduced their own split).  Also
+// emits the compute-type copy of the weights: 16 B read and 12 B + sizeof(T) written per parameter.
+template <typename T>
 __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, float *__restrict__ m,
                                                    float *__restrict__ v, const float *__restrict__ gpart,
                                                    int S, size_t gstride, size_t P, float lr, float b1,
-                                                   float b2, float eps, float c1, float c2)
+                                                   float b2, float eps, float c1, float c2,
+                                                   const EmitTable<T> tab)
 {
     const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= P) return;
@@ -169,6 +194,16 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
         *(float4 *)(m + i) = make_float4(ma[0], ma[1], ma[2], ma[3]);
         *(float4 *)(v + i) = make_float4(va[0], va[1], va[2], va[3]);
         *(float4 *)(theta + i) = make_float4(ta[0], ta[1], ta[2], ta[3]);
+        for (int k = 0; k < tab.n; ++k) {
+            if (i + 4 <= tab.begin[k] || i >= tab.end[k]) continue;
+            if (i >= tab.begin[k] && i + 4 <= tab.end[k] && ((i - tab.begin[k]) & 3) == 0) {
+                emit4<T>(tab.dst[k] + (i - tab.begin[k]), ta);
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (i + e >= tab.begin[k] && i + e < tab.end[k])
+                        tab.dst[k][i + e - tab.begin[k]] = TjElem<T>::from_f32(ta[e]);
+            }
+        }
     } else {
         for (size_t e = i; e < P; ++e) {
             float g = gpart[e];
@@ -177,7 +212,36 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
             const float vv = b2 * v[e] + (1.f - b2) * g * g;
             m[e] = mm;
             v[e] = vv;
-            theta[e] -= lr * (mm / c1) / (sqrtf(vv / c2) + eps);
+            const float th = theta[e] - lr * (mm / c1) / (sqrtf(vv / c2) + eps);
+            theta[e] = th;
+            for (int k = 0; k < tab.n; ++k)
+                if (e >= tab.begin[k] && e < tab.end[k]) tab.dst[k][e - tab.begin[k]] = TjElem<T>::from_f32(th);
+        }
+    }
+}
+
+// Adds the split slices 1..S-1 of the flat gradient into slice 0 (fixed order: deterministic).
+__global__ __launch_bounds__(256) void reduce_slices(float *__restrict__ g, size_t gstride, int S, size_t n)
+{
+    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= n) return;
+    if (i + 4 <= n) {
+        float4 p[8];
+        float4 sum = *(const float4 *)(g + i);
+        for (int s0 = 1; s0 < S; s0 += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < S) p[u] = *(const float4 *)(g + (size_t)(s0 + u) * gstride + i);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < S) { sum.x += p[u].x; sum.y += p[u].y; sum.z += p[u].z; sum.w += p[u].w; }
+        }
+        *(float4 *)(g + i) = sum;
+    } else {
+        for (size_t e = i; e < n; ++e) {
+            float sum = g[e];
+            for (int s = 1; s < S; ++s) sum += g[(size_t)s * gstride + e];
+            g[e] = sum;
         }
     }
 }
@@ -308,13 +372,17 @@ template <typename T> struct MlpLearner : tj_learner {
     }
 
     // fp32 master -> compute-type copies (and transposes for the online net)
-    int recast(bool online, hipStream_t st)
+    // Adam writes the straight copy of every weight block whose rows need no padding
+    bool adam_emits(int l) const { return lay[l].ld_in == lay[l].in; }
+
+    int recast(bool online, hipStream_t st, bool after_adam = false)
     {
         CastJobs<T> jobs;
         for (int l = 0; l < L; ++l) {
             CastJob<T> &j = jobs.job[l];
             j.src = (online ? theta_on : theta_tg) + lay[l].w_off;
             j.dst = online ? Wc_on[l] : Wc_tg[l];
+            if (after_adam && adam_emits(l)) j.dst = nullptr;
             j.dstT = online ? WcT_on[l] : nullptr;
             j.R = lay[l].out; j.C = lay[l].in;
             j.ldd = lay[l].ld_in; j.lddT = lay[l].ld_out;
@@ -410,15 +478,27 @@ template <typename T> struct MlpLearner : tj_learner {
             }
         }
 
+        if (S > 1) {   // the split slices of every weight gradient are summed, in slice order, into slice 0
+            reduce_slices<<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(gpart, Ppad, S, P);
+            if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        }
         if ((rc = mark(3, st)) != TJ_OK) return rc;
         t += 1;
         const float c1 = (float)(1.0 - pow((double)d.beta1, (double)t));
         const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
-        adam_update<<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S, Ppad, P, d.lr,
-                                                                   d.beta1, d.beta2, d.eps, c1, c2);
+        EmitTable<T> tab;
+        tab.n = 0;
+        for (int l = 0; l < L; ++l) {
+            if (!adam_emits(l)) continue;
+            tab.begin[tab.n] = lay[l].w_off;
+            tab.end[tab.n] = lay[l].w_off + (size_t)lay[l].in * lay[l].out;
+            tab.dst[tab.n++] = Wc_on[l];
+        }
+        adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, 1, Ppad, P, d.lr,
+                                                                      d.beta1, d.beta2, d.eps, c1, c2, tab);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
-        if ((rc = recast(true, st)) != TJ_OK) return rc;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
+        if ((rc = recast(true, st, true)) != TJ_OK) return rc;   // transposed copies (and padded blocks)
         if (d.target_interval && t % d.target_interval == 0) {
             TJ_HIP_TRY(hipMemcpyAsync(theta_tg, theta_on, P * 4, hipMemcpyDeviceToDevice, st));
             TJ_HIP_TRY(hipMemcpyAsync(Wc_tg[0], Wc_on[0], wc_bytes, hipMemcpyDeviceToDevice, st));
@@ -442,16 +522,10 @@ template <typename T> struct MlpLearner : tj_learner {
             TJ_HIP_TRY(hipStreamSynchronize(st));
             return TJ_OK;
         }
-        if (which == TJ_STATE_GRADS) {
+        if (which == TJ_STATE_GRADS) {   // slice 0 holds the sum over the split slices
             if (n != P) return TJ_ERR_INVALID_ARG;
-            std::vector<float> tmp((size_t)S * Ppad);
-            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), gpart, tmp.size() * 4, hipMemcpyDeviceToHost, st));
+            TJ_HIP_TRY(hipMemcpyAsync(h_out, gpart, P * 4, hipMemcpyDeviceToHost, st));
             TJ_HIP_TRY(hipStreamSynchronize(st));
-            for (size_t i = 0; i < P; ++i) {   // same order as the Adam kernel
-                float g = tmp[i];
-                for (int s = 1; s < S; ++s) g += tmp[(size_t)s * Ppad + i];
-                h_out[i] = g;
-            }
             return TJ_OK;
         }
         if (which == TJ_STATE_QVALS) {
@@ -818,8 +892,10 @@ template <typename T> struct ConvLearner : tj_learner {
         t += 1;
         const float c1 = (float)(1.0 - pow((double)d.beta1, (double)t));
         const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
-        adam_update<<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
-                                                                   d.beta2, d.eps, c1, c2);
+        EmitTable<T> tab;
+        tab.n = 0;   // the conv path's weight copies are permuted: recast() writes them
+        adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
+                                                                      d.beta2, d.eps, c1, c2, tab);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = recast(true, st)) != TJ_OK) return rc;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
