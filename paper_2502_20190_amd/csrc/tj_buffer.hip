@@ -152,6 +152,23 @@ __global__ __launch_bounds__(256) void select_slots(
 
 // ---------------------------------------------------------------- row copies
 
+// Streaming copies: rows are touched once, so loads and stores bypass the caches' LRU
+// (nontemporal) and leave L2 to the tag array and the learner's operands.
+template <typename V> __device__ __forceinline__ V ld_stream(const V *p) { return __builtin_nontemporal_load(p); }
+template <typename V> __device__ __forceinline__ void st_stream(V *p, V v) { __builtin_nontemporal_store(v, p); }
+template <> __device__ __forceinline__ uint4 ld_stream<uint4>(const uint4 *p)
+{
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    const u4 v = __builtin_nontemporal_load((const u4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+template <> __device__ __forceinline__ void st_stream<uint4>(uint4 *p, uint4 v)
+{
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    const u4 w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, (u4 *)p);
+}
+
 // mode 0 (gather): dst row r <- src row idx[r];  mode 1 (insert): dst row
 // (head + r) mod cap <- src row r.  Rows are `vpr` vectors of type V.
 // blockIdx.x = row, blockIdx.y = chunk of 256*U vectors inside the row,
@@ -180,12 +197,12 @@ __global__ __launch_bounds__(256) void copy_rows_wide(const V *__restrict__ src0
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         uint32_t c = c0 + u * 256;
-        if (c < vpr) tmp[u] = sp[c];
+        if (c < vpr) tmp[u] = ld_stream(sp + c);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         uint32_t c = c0 + u * 256;
-        if (c < vpr) dp[c] = tmp[u];
+        if (c < vpr) st_stream(dp + c, tmp[u]);
     }
 }
 
@@ -218,12 +235,12 @@ __global__ __launch_bounds__(256) void copy_rows_narrow(const V *__restrict__ sr
         } else {
             srow = r; drow = head + r; if (drow >= cap) drow -= cap;
         }
-        tmp[u] = src[srow * vpr + c];
+        tmp[u] = ld_stream(src + srow * vpr + c);
         daddr[u] = drow * vpr + c;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (live[u]) dst[daddr[u]] = tmp[u];
+        if (live[u]) st_stream(dst + daddr[u], tmp[u]);
 }
 
 // The four scalar fields of an insert: slot (head + i) mod cap <- row i.
@@ -272,7 +289,7 @@ int launch_copy_rows(const void *s0, void *d0, const void *s1, void *d1, uint32_
                                                      idx, mode, head, cap);
         }
     } else {
-        constexpr int U = 4;
+        constexpr int U = 2;
         // rows * vpr must fit 32 bits: callers split larger jobs
         uint64_t total = (uint64_t)rows * vpr;
         dim3 grid((uint32_t)((total + 256 * U - 1) / (256 * U)), 1, 2);

@@ -487,7 +487,7 @@ __device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f
         const uint8_t *sp = scr + (lane >> 3) * kScratchPitch + (lane & 7) * 16;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
-            *(float4 *)(fp + (size_t)(8 * t) * a.ldcf) = *(const float4 *)(sp + 8 * t * kScratchPitch);
+            *(u32x4 *)(fp + (size_t)(8 * t) * a.ldcf) = *(const u32x4 *)(sp + 8 * t * kScratchPitch);
     }
 }
 

@@ -143,6 +143,20 @@ __global__ __launch_bounds__(256) void td_huber(const float *__restrict__ Q, int
     }
 }
 
+// Streaming (nontemporal) 16-byte accesses: optimizer state and gradient slices are touched once
+// per step and are larger than L2, so they should not displace the GEMM operands there.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld4_stream(const float *p)
+{
+    const f32x4_t v = __builtin_nontemporal_load((const f32x4_t *)p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4_stream(float *p, float a, float b, float c, float d)
+{
+    const f32x4_t v = {a, b, c, d};
+    __builtin_nontemporal_store(v, (f32x4_t *)p);
+}
+
 // Where Adam also writes the compute-type copy of a weight block: flat parameters [begin, end)
 // go to dst[0 .. end-begin) (only blocks whose copy has no row padding).
 template <typename T> struct EmitTable {
@@ -177,12 +191,12 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
     const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= P) return;
     if (i + 4 <= P) {
-        float4 g = *(const float4 *)(gpart + i);
+        float4 g = ld4_stream(gpart + i);
         for (int s = 1; s < S; ++s) {
-            const float4 p = *(const float4 *)(gpart + (size_t)s * gstride + i);
+            const float4 p = ld4_stream(gpart + (size_t)s * gstride + i);
             g.x += p.x; g.y += p.y; g.z += p.z; g.w += p.w;
         }
-        float4 mm = *(const float4 *)(m + i), vv = *(const float4 *)(v + i), th = *(const float4 *)(theta + i);
+        float4 mm = ld4_stream(m + i), vv = ld4_stream(v + i), th = ld4_stream(theta + i);
         float ga[4] = {g.x, g.y, g.z, g.w}, ma[4] = {mm.x, mm.y, mm.z, mm.w};
         float va[4] = {vv.x, vv.y, vv.z, vv.w}, ta[4] = {th.x, th.y, th.z, th.w};
 #pragma unroll
@@ -191,9 +205,9 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
             va[e] = b2 * va[e] + (1.f - b2) * ga[e] * ga[e];
             ta[e] -= lr * (ma[e] / c1) / (sqrtf(va[e] / c2) + eps);
         }
-        *(float4 *)(m + i) = make_float4(ma[0], ma[1], ma[2], ma[3]);
-        *(float4 *)(v + i) = make_float4(va[0], va[1], va[2], va[3]);
-        *(float4 *)(theta + i) = make_float4(ta[0], ta[1], ta[2], ta[3]);
+        st4_stream(m + i, ma[0], ma[1], ma[2], ma[3]);
+        st4_stream(v + i, va[0], va[1], va[2], va[3]);
+        st4_stream(theta + i, ta[0], ta[1], ta[2], ta[3]);
         for (int k = 0; k < tab.n; ++k) {
             if (i + 4 <= tab.begin[k] || i >= tab.end[k]) continue;
             if (i >= tab.begin[k] && i + 4 <= tab.end[k] && ((i - tab.begin[k]) & 3) == 0) {
@@ -227,11 +241,11 @@ __global__ __launch_bounds__(256) void reduce_slices(float *__restrict__ g, size
     if (i >= n) return;
     if (i + 4 <= n) {
         float4 p[8];
-        float4 sum = *(const float4 *)(g + i);
+        float4 sum = ld4_stream(g + i);
         for (int s0 = 1; s0 < S; s0 += 8) {
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (s0 + u < S) p[u] = *(const float4 *)(g + (size_t)(s0 + u) * gstride + i);
+                if (s0 + u < S) p[u] = ld4_stream(g + (size_t)(s0 + u) * gstride + i);
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (s0 + u < S) { sum.x += p[u].x; sum.y += p[u].y; sum.z += p[u].z; sum.w += p[u].w; }
