@@ -34,7 +34,8 @@ struct RingPtrs {
 
 // ---------------------------------------------------------------- sampler
 
-// One block per tile of 1024 slots, four waves, each wave 4 x 64 slots.
+// One block per tile of 1024 slots, four waves, each wave 4 x 64 slots: coalesced read of the
+// tags, wave ballot -> mask words, popcount -> tile count.
 __global__ __launch_bounds__(256) void stale_mask_count(const int32_t *__restrict__ version,
                                                         uint32_t count, int64_t cur, int64_t max_st,
                                                         unsigned long long *__restrict__ mask,
@@ -67,8 +68,10 @@ __global__ __launch_bounds__(256) void stale_mask_count(const int32_t *__restric
         tile_count[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
 }
 
-// Exclusive scan of the tile counts by one block of 1024 threads; K to state[1];
-// K == 0 raises the sticky status.
+// Exclusive scan of the tile counts by one block of 1024 threads, four counts per thread and
+// pass (one pass covers 4096 tiles = 4M slots); K to state[1]; K == 0 raises the sticky status.
+// A ticket shared by all mask blocks would save this launch but costs more: thousands of atomics
+// on one address serialise at about 25 ns each.
 __global__ __launch_bounds__(1024) void tile_scan(const uint32_t *__restrict__ tile_count,
                                                   uint32_t n_tiles, uint32_t *__restrict__ tile_off,
                                                   uint32_t *__restrict__ state)
@@ -78,10 +81,13 @@ __global__ __launch_bounds__(1024) void tile_scan(const uint32_t *__restrict__ t
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry = 0;
     __syncthreads();
-    for (uint32_t base = 0; base < n_tiles; base += 1024) {
-        uint32_t t = base + threadIdx.x;
-        uint32_t c = t < n_tiles ? tile_count[t] : 0;
-        uint32_t incl = c;                      // inclusive scan inside the wave
+    for (uint32_t base = 0; base < n_tiles; base += 4096) {
+        const uint32_t t = base + threadIdx.x * 4;
+        uint32_t c[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = t + e < n_tiles ? tile_count[t + e] : 0;
+        const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+        uint32_t incl = mine;                      // inclusive scan inside the wave
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             uint32_t up = __shfl_up(incl, d, 64);
@@ -91,7 +97,12 @@ __global__ __launch_bounds__(1024) void tile_scan(const uint32_t *__restrict__ t
         __syncthreads();
         uint32_t before = carry;
         for (uint32_t w = 0; w < wave; ++w) before += wave_sum[w];
-        if (t < n_tiles) tile_off[t] = before + incl - c;
+        uint32_t run = before + incl - mine;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (t + e < n_tiles) tile_off[t + e] = run;
+            run += c[e];
+        }
         __syncthreads();
         if (threadIdx.x == 1023) carry = before + incl;
         __syncthreads();
@@ -110,8 +121,8 @@ __device__ __forceinline__ uint64_t splitmix64(uint64_t seed, uint64_t j)
     return z ^ (z >> 31);
 }
 
-// One thread per draw.
-__global__ __launch_bounds__(256) void select_slots(
+// One thread per draw, one wave per block (the kernel is a chain of dependent loads).
+__global__ __launch_bounds__(64) void select_slots(
     const unsigned long long *__restrict__ mask, const uint32_t *__restrict__ tile_off,
     uint32_t n_tiles, const uint32_t *__restrict__ state, uint64_t seed, uint32_t batch,
     RingPtrs ring, uint32_t *__restrict__ idx, int32_t *__restrict__ action,
@@ -439,7 +450,7 @@ int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t m
     stale_mask_count<<<n_tiles, 256, 0, st>>>(buf->ring.version, count, current_version, max_staleness,
                                               buf->mask, buf->tile_count);
     tile_scan<<<1, 1024, 0, st>>>(buf->tile_count, n_tiles, buf->tile_off, buf->state);
-    select_slots<<<(batch + 255) / 256, 256, 0, st>>>(buf->mask, buf->tile_off, n_tiles, buf->state,
+    select_slots<<<(batch + 63) / 64, 64, 0, st>>>(buf->mask, buf->tile_off, n_tiles, buf->state,
                                                       seed, batch, buf->ring, out->idx, out->action,
                                                       out->reward, out->done);
     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;

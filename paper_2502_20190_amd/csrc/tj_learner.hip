@@ -74,32 +74,37 @@ template <typename T> int launch_cast(const CastJobs<T> &jobs, int n_jobs, hipSt
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 
-// TD target, Huber loss and its gradient, one thread per transition.
+// TD target, Huber loss and its gradient, one thread per transition, one wave per block (many
+// small blocks: the kernel is latency bound).
 //   a* = argmax_a Q_on(s',a) (lowest index on ties); y = r + gamma (1-done) Q_tg(s',a*)
 //   d = Q_on(s,a) - y; loss = mean Huber_kappa(d); dL/dQ_on(s,a) = clip(d,-k,k)/B
-// Q rows: [0,B) Q_on(s), [B,2B) Q_on(s'), [2B,3B) Q_tg(s').  The last block to
-// finish adds the per-block partial sums in block order.
+// Q rows: [0,B) Q_on(s), [B,2B) Q_on(s'), [2B,3B) Q_tg(s'); ldq is a multiple of 4 floats.  The
+// last block to finish adds the per-block partial sums in block order.
+constexpr int kTdBlock = 64;
+
 template <typename T>
-__global__ __launch_bounds__(256) void td_huber(const float *__restrict__ Q, int ldq, int B, int A,
-                                                const int32_t *__restrict__ action,
-                                                const float *__restrict__ reward,
-                                                const uint8_t *__restrict__ done, float gamma, float kappa,
-                                                T *__restrict__ dZ, int lddz, T *__restrict__ dZT, int lddzt,
-                                                int32_t *__restrict__ astar, float *__restrict__ loss_part,
-                                                uint32_t *__restrict__ ticket, tj_step_stats *stats_out,
-                                                tj_step_stats *stats_internal, uint32_t t_next)
+__global__ __launch_bounds__(kTdBlock) void td_huber(const float *__restrict__ Q, int ldq, int B, int A,
+                                                     const int32_t *__restrict__ action,
+                                                     const float *__restrict__ reward,
+                                                     const uint8_t *__restrict__ done, float gamma, float kappa,
+                                                     T *__restrict__ dZ, int lddz, T *__restrict__ dZT, int lddzt,
+                                                     int32_t *__restrict__ astar, float *__restrict__ loss_part,
+                                                     uint32_t *__restrict__ ticket, tj_step_stats *stats_out,
+                                                     tj_step_stats *stats_internal, uint32_t t_next)
 {
-    __shared__ float red[256];
     __shared__ bool last;
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int j = blockIdx.x * kTdBlock + threadIdx.x;
     float loss = 0.f;
     if (j < B) {
-        const float *qn = Q + (size_t)(B + j) * ldq;
+        const float4 *qn = (const float4 *)(Q + (size_t)(B + j) * ldq);
         int best = 0;
-        float bv = qn[0];
-        for (int a = 1; a < A; ++a) {
-            float x = qn[a];
-            if (x > bv) { bv = x; best = a; }
+        float bv = -INFINITY;
+        for (int a4 = 0; a4 < (A + 3) / 4; ++a4) {   // pad columns of Q are never written: guard by A
+            const float4 x = qn[a4];
+            const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (a4 * 4 + e < A && (xs[e] > bv || (a4 == 0 && e == 0))) { bv = xs[e]; best = a4 * 4 + e; }
         }
         astar[j] = best;
         int aj = action[j];
@@ -117,29 +122,30 @@ __global__ __launch_bounds__(256) void td_huber(const float *__restrict__ Q, int
             dZT[(size_t)a * lddzt + j] = val;
         }
     }
-    red[threadIdx.x] = loss;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-        __syncthreads();
-    }
+    // wave reduction in a fixed order
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) loss += __shfl_down(loss, off, 64);
     if (threadIdx.x == 0) {
-        loss_part[blockIdx.x] = red[0];
+        loss_part[blockIdx.x] = loss;
         __threadfence();
         uint32_t prev = atomicAdd(ticket, 1u);
         last = prev == gridDim.x - 1;
     }
     __syncthreads();
-    if (last && threadIdx.x == 0) {
+    if (last) {   // block partials: strided per lane, then the same fixed shuffle tree
         __threadfence();
         float s = 0.f;
-        for (uint32_t b = 0; b < gridDim.x; ++b) s += ((volatile float *)loss_part)[b];
-        tj_step_stats out;
-        out.loss = s / (float)B;
-        out.step = t_next;
-        *stats_internal = out;
-        if (stats_out) *stats_out = out;
-        *ticket = 0;   // ready for the next step
+        for (uint32_t b = threadIdx.x; b < gridDim.x; b += kTdBlock) s += ((volatile float *)loss_part)[b];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+        if (threadIdx.x == 0) {
+            tj_step_stats out;
+            out.loss = s / (float)B;
+            out.step = t_next;
+            *stats_internal = out;
+            if (stats_out) *stats_out = out;
+            *ticket = 0;   // ready for the next step
+        }
     }
 }
 
@@ -379,7 +385,7 @@ template <typename T> struct MlpLearner : tj_learner {
         act_bytes = a.off - act0;
         Qout = (float *)a.take(3 * (size_t)Bmax * ldA * 4);
         astar = (int32_t *)a.take((size_t)Bmax * 4);
-        loss_part = (float *)a.take((size_t)((Bmax + 255) / 256) * 4);
+        loss_part = (float *)a.take((size_t)((Bmax + kTdBlock - 1) / kTdBlock) * 4);
         ticket = (uint32_t *)a.take(4);
         stats_internal = (tj_step_stats *)a.take(sizeof(tj_step_stats));
         return a.off;
@@ -451,7 +457,7 @@ template <typename T> struct MlpLearner : tj_learner {
 
         if ((rc = mark(1, st)) != TJ_OK) return rc;
         const uint32_t t_next = (uint32_t)(t + 1);
-        td_huber<T><<<(B + 255) / 256, 256, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done,
+        td_huber<T><<<(B + kTdBlock - 1) / kTdBlock, kTdBlock, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done,
                                                      d.gamma, d.huber_delta, dZ[L], lay[L - 1].ld_out, dZT[L],
                                                      ldB, astar, loss_part, ticket, d_stats, stats_internal,
                                                      t_next);
@@ -715,7 +721,7 @@ template <typename T> struct ConvLearner : tj_learner {
         act_bytes = a.off - act0;
         Qout = (float *)a.take(3 * B * ldA * 4);
         astar = (int32_t *)a.take(B * 4);
-        loss_part = (float *)a.take((size_t)((Bmax + 255) / 256) * 4);
+        loss_part = (float *)a.take((size_t)((Bmax + kTdBlock - 1) / kTdBlock) * 4);
         ticket = (uint32_t *)a.take(4);
         stats_internal = (tj_step_stats *)a.take(sizeof(tj_step_stats));
         return a.off;
@@ -832,7 +838,7 @@ template <typename T> struct ConvLearner : tj_learner {
         if ((rc = mark(1, st)) != TJ_OK) return rc;
 
         const uint32_t t_next = (uint32_t)(t + 1);
-        td_huber<T><<<(B + 255) / 256, 256, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done, d.gamma,
+        td_huber<T><<<(B + kTdBlock - 1) / kTdBlock, kTdBlock, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done, d.gamma,
                                                      d.huber_delta, lay[L - 1].dZ, lay[L - 1].ldO, lay[L - 1].dZT,
                                                      ldB, astar, loss_part, ticket, d_stats, stats_internal, t_next);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
