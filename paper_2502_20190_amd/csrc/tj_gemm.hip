@@ -292,13 +292,15 @@ __device__ __forceinline__ f32x16 tile_math_edge(const TjGemmArgs<tj_bf16> &a, c
 // The stores of one 32 x 32 tile (values already final), staged through a wave-private LDS
 // scratch of 32 rows x kScratchPitch bytes so that every lane writes 16 contiguous bytes.  The
 // scratch must not be shared with another wave.
+enum { kOutCi = 1, kOutCj = 2, kOutCf = 4, kOutAll = 7 };
+
 __device__ __forceinline__ void store_tile_edge(const TjGemmArgs<tj_bf16> &a, const f32x16 v, uint8_t *scr,
                                            const int ibase, const int jbase, const int j_end, const int z,
-                                           const int lane)
+                                           const int lane, const int which)
 {
     typedef tj_bf16 T;
     const int l32 = lane & 31, lg = lane >> 5;
-    if (a.Ci) {   // rows j, 32 consecutive i (64 bytes) each
+    if (a.Ci && (which & kOutCi)) {   // rows j, 32 consecutive i (64 bytes) each
         wave_sync();
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
@@ -326,7 +328,7 @@ __device__ __forceinline__ void store_tile_edge(const TjGemmArgs<tj_bf16> &a, co
             }
         }
     }
-    if (a.Cj) {   // rows i, 32 consecutive j (64 bytes) each
+    if (a.Cj && (which & kOutCj)) {   // rows i, 32 consecutive j (64 bytes) each
         wave_sync();
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq)
@@ -353,7 +355,7 @@ __device__ __forceinline__ void store_tile_edge(const TjGemmArgs<tj_bf16> &a, co
             }
         }
     }
-    if (a.Cf) {   // fp32 rows j, 32 consecutive i (128 bytes) each
+    if (a.Cf && (which & kOutCf)) {   // fp32 rows j, 32 consecutive i (128 bytes) each
         wave_sync();
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq)
@@ -433,18 +435,18 @@ __device__ __forceinline__ void tile_math(const TjGemmArgs<tj_bf16> &a, const Tj
 
 __device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f32x16 &v, uint8_t *scr,
                                            const int ibase, const int jbase, const int j_end, const int z,
-                                           const int lane)
+                                           const int lane, const int which = kOutAll)
 {
     typedef tj_bf16 T;
     bool interior = ibase + 32 <= a.I && jbase + 32 <= j_end;
     if (a.Cj) interior = interior && jbase + 32 <= a.cj_jmax && ((a.ldcj | jbase) & 7) == 0;
     if (a.Cf) interior = interior && ((((uintptr_t)(a.Cf + (size_t)z * a.cf_zstride)) | (uintptr_t)(a.ldcf * 4)) & 15) == 0;
     if (!interior) {
-        if (jbase < j_end && ibase < a.I) store_tile_edge(a, v, scr, ibase, jbase, j_end, z, lane);
+        if (jbase < j_end && ibase < a.I) store_tile_edge(a, v, scr, ibase, jbase, j_end, z, lane, which);
         return;
     }
     const int l32 = lane & 31, lg = lane >> 5;
-    if (a.Ci) {   // rows j, 32 consecutive i (64 bytes) each
+    if (a.Ci && (which & kOutCi)) {   // rows j, 32 consecutive i (64 bytes) each
         wave_sync();
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
@@ -459,7 +461,7 @@ __device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f
         *(u32x4 *)cp = *(const u32x4 *)sp;
         *(u32x4 *)(cp + (size_t)16 * a.ldci) = *(const u32x4 *)(sp + 16 * kScratchPitch);
     }
-    if (a.Cj) {   // rows i, 32 consecutive j (64 bytes) each
+    if (a.Cj && (which & kOutCj)) {   // rows i, 32 consecutive j (64 bytes) each
         wave_sync();
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
@@ -476,7 +478,7 @@ __device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f
         *(u32x4 *)cp = *(const u32x4 *)sp;
         *(u32x4 *)(cp + (size_t)16 * a.ldcj) = *(const u32x4 *)(sp + 16 * kScratchPitch);
     }
-    if (a.Cf) {   // fp32 rows j, 32 consecutive i (128 bytes) each
+    if (a.Cf && (which & kOutCf)) {   // fp32 rows j, 32 consecutive i (128 bytes) each
         wave_sync();
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq)
@@ -489,6 +491,58 @@ __device__ __forceinline__ void store_tile(const TjGemmArgs<tj_bf16> &a, const f
         for (int t = 0; t < 4; ++t)
             *(u32x4 *)(fp + (size_t)(8 * t) * a.ldcf) = *(const u32x4 *)(sp + 8 * t * kScratchPitch);
     }
+}
+
+// Two 32 x 32 tiles that are neighbours along the contiguous index of a bf16 output are stored
+// together, so that every store instruction writes whole 128-byte lines (8 lanes per row).
+// Ci: tiles v0 | v1 neighbours in i (rows j, 64 consecutive i); the caller has checked that
+// both are interior.
+__device__ __forceinline__ void store_pair_ci(const TjGemmArgs<tj_bf16> &a, const f32x16 &v0, const f32x16 &v1,
+                                              uint8_t *scr, const int ibase, const int jbase, const int lane)
+{
+    const int l32 = lane & 31, lg = lane >> 5;
+    wave_sync();
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+        uint2 o0, o1;
+        o0.x = pack_bf16(v0[rq * 4], v0[rq * 4 + 1]); o0.y = pack_bf16(v0[rq * 4 + 2], v0[rq * 4 + 3]);
+        o1.x = pack_bf16(v1[rq * 4], v1[rq * 4 + 1]); o1.y = pack_bf16(v1[rq * 4 + 2], v1[rq * 4 + 3]);
+        *(uint2 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 2) = o0;
+        *(uint2 *)(scr + l32 * kScratchPitch + 64 + (rq * 8 + lg * 4) * 2) = o1;
+    }
+    wave_sync();
+    tj_bf16 *cp = a.Ci + (size_t)(jbase + (lane >> 3)) * a.ldci + ibase + (lane & 7) * 8;
+    const uint8_t *sp = scr + (lane >> 3) * kScratchPitch + (lane & 7) * 16;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) *(u32x4 *)(cp + (size_t)(8 * t) * a.ldci) = *(const u32x4 *)(sp + 8 * t * kScratchPitch);
+}
+
+// Cj: tiles v0 | v1 neighbours in j (rows i, 64 consecutive j).
+__device__ __forceinline__ void store_pair_cj(const TjGemmArgs<tj_bf16> &a, const f32x16 &v0, const f32x16 &v1,
+                                              uint8_t *scr, const int ibase, const int jbase, const int lane)
+{
+    typedef tj_bf16 T;
+    const int l32 = lane & 31, lg = lane >> 5;
+    wave_sync();
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+        const uint32_t a01 = pack_bf16(v0[rq * 4], v0[rq * 4 + 1]), a23 = pack_bf16(v0[rq * 4 + 2], v0[rq * 4 + 3]);
+        const uint32_t b01 = pack_bf16(v1[rq * 4], v1[rq * 4 + 1]), b23 = pack_bf16(v1[rq * 4 + 2], v1[rq * 4 + 3]);
+        uint8_t *wp = scr + (rq * 8 + lg * 4) * kScratchPitch + l32 * 2;
+        *(T *)(wp) = (T)(a01 & 0xFFFFu);
+        *(T *)(wp + kScratchPitch) = (T)(a01 >> 16);
+        *(T *)(wp + 2 * kScratchPitch) = (T)(a23 & 0xFFFFu);
+        *(T *)(wp + 3 * kScratchPitch) = (T)(a23 >> 16);
+        *(T *)(wp + 64) = (T)(b01 & 0xFFFFu);
+        *(T *)(wp + 64 + kScratchPitch) = (T)(b01 >> 16);
+        *(T *)(wp + 64 + 2 * kScratchPitch) = (T)(b23 & 0xFFFFu);
+        *(T *)(wp + 64 + 3 * kScratchPitch) = (T)(b23 >> 16);
+    }
+    wave_sync();
+    T *cp = a.Cj + (size_t)(ibase + (lane >> 3)) * a.ldcj + jbase + (lane & 7) * 8;
+    const uint8_t *sp = scr + (lane >> 3) * kScratchPitch + (lane & 7) * 16;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) *(u32x4 *)(cp + (size_t)(8 * t) * a.ldcj) = *(const u32x4 *)(sp + 8 * t * kScratchPitch);
 }
 
 // ---------------------------------------------------------------- bf16 kernel
@@ -705,7 +759,9 @@ template <int N> struct IntC { static constexpr int value = N; };
 #endif
 
 template <int NFJ, int BKB, int NSTAGE, bool QSUM>
-__global__ __launch_bounds__(512, (NFJ == 2 && BKB * NSTAGE <= 192) ? 2 : 1) void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu((NFJ == 2 && BKB * NSTAGE <= 192) ? 4 : 2,
+                                                                      (NFJ == 2 && BKB * NSTAGE <= 192) ? 4 : 2)))
+void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
                                                          const TileMap tm)
 {
     typedef tj_bf16 T;
@@ -924,14 +980,42 @@ __global__ __launch_bounds__(512, (NFJ == 2 && BKB * NSTAGE <= 192) ? 2 : 1) voi
     static_assert(WPB >= 2 && 7 / WPB < NSTAGE, "epilogue scratch does not fit the P buffers");
     const int sb = wave / WPB;
     uint8_t *scr = (sb == 0 ? sA0 : sb == 1 ? sA1 : sb == 2 ? sA2 : sA3) + (wave % WPB) * (32 * kScratchPitch);
-#pragma unroll
-    for (int fi = 0; fi < 2; ++fi) {
+    const int ib0 = i0 + wi * 64, jb0 = j0 + wj * 32 * NFJ;
+    if (a.Ci) {
 #pragma unroll
         for (int fj = 0; fj < NFJ; ++fj) {
-            const int ibase = i0 + wi * 64 + fi * 32;
-            const int jbase = j0 + wj * 32 * NFJ + fj * 32;
-            store_tile(a, acc[fi][fj], scr, ibase, jbase, j_end, z, lane);
+            const int jb = jb0 + fj * 32;
+            if (ib0 + 64 <= a.I && jb + 32 <= j_end) {
+                store_pair_ci(a, acc[0][fj], acc[1][fj], scr, ib0, jb, lane);
+            } else {
+                store_tile(a, acc[0][fj], scr, ib0, jb, j_end, z, lane, kOutCi);
+                store_tile(a, acc[1][fj], scr, ib0 + 32, jb, j_end, z, lane, kOutCi);
+            }
         }
+    }
+    if (a.Cj) {
+        const int jmax = min(j_end, a.cj_jmax);
+#pragma unroll
+        for (int fi = 0; fi < 2; ++fi) {
+#pragma unroll
+            for (int fj = 0; fj + 1 < NFJ; fj += 2) {
+                const int jb = jb0 + fj * 32;
+                if (ib0 + fi * 32 + 32 <= a.I && jb + 64 <= jmax && ((a.ldcj | jb) & 7) == 0) {
+                    store_pair_cj(a, acc[fi][fj], acc[fi][fj + 1], scr, ib0 + fi * 32, jb, lane);
+                } else {
+                    store_tile(a, acc[fi][fj], scr, ib0 + fi * 32, jb, j_end, z, lane, kOutCj);
+                    store_tile(a, acc[fi][fj + 1], scr, ib0 + fi * 32, jb + 32, j_end, z, lane, kOutCj);
+                }
+            }
+            if (NFJ & 1) store_tile(a, acc[fi][NFJ - 1], scr, ib0 + fi * 32, jb0 + (NFJ - 1) * 32, j_end, z, lane, kOutCj);
+        }
+    }
+    if (a.Cf) {
+#pragma unroll
+        for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+            for (int fj = 0; fj < NFJ; ++fj)
+                store_tile(a, acc[fi][fj], scr, ib0 + fi * 32, jb0 + fj * 32, j_end, z, lane, kOutCf);
     }
 }
 
