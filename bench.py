@@ -24,10 +24,12 @@ PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
 
-def gemm_flops_per_step(wl, synth):
+def gemm_flops_per_step(wl, synth, head_in_td_phase):
     """Algorithmic flops of the dense contractions of one step: three forward
     passes (2*B*W each), weight gradients (2*B*W) and input gradients for every
-    layer but the first (2*B*W_l)."""
+    layer but the first (2*B*W_l).  Where the head layer's forward runs fused
+    with the TD kernel (bf16, at most 32 actions) its flops are left out, since
+    its time falls into the TD phase, not the GEMM phases."""
     shapes = synth.layer_shapes(wl.layers, wl.in_chw)
     per_sample = []
     for kind, ws, fin, fout, out_chw in shapes:
@@ -35,7 +37,7 @@ def gemm_flops_per_step(wl, synth):
         for x in ws:
             w *= x
         per_sample.append(2 * w * (out_chw[1] * out_chw[2] if kind == synth.CONV else 1))
-    fwd = sum(per_sample)
+    fwd = sum(per_sample[:-1] if head_in_td_phase else per_sample)
     bwd = sum(per_sample) + sum(per_sample[1:])
     return wl.batch * (3 * fwd + bwd)
 
@@ -95,6 +97,9 @@ def main():
     ap.add_argument("--config", default="c3", help="workload: c1 ... c5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's learner step (0 = auto)")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="record the per-phase HIP events on every n-th timed step (each event costs "
+                         "about 5 us of stream time, so recording them on every step slows the loop)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no collectives are part of it)",
@@ -126,13 +131,19 @@ def main():
     torch.cuda.synchronize()
 
     K = args.steps
-    bev = [tj.HipEvents(3) for _ in range(K)]
-    lev = [tj.HipEvents(5) for _ in range(K)]
+    every = max(1, args.event_every)
+    sampled = list(range(0, K, every))
+    bev = [tj.HipEvents(3) for _ in sampled]
+    lev = [tj.HipEvents(5) for _ in sampled]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        L.tj_buffer_set_phase_events(buf.h, bev[i].ev, 3)
-        L.tj_learner_set_phase_events(lrn.h, lev[i].ev, 5)
+        if i % every == 0:
+            L.tj_buffer_set_phase_events(buf.h, bev[i // every].ev, 3)
+            L.tj_learner_set_phase_events(lrn.h, lev[i // every].ev, 5)
+        elif i % every == 1:
+            L.tj_buffer_set_phase_events(buf.h, None, 0)
+            L.tj_learner_set_phase_events(lrn.h, None, 0)
         one_step(args.warmup + i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -142,18 +153,20 @@ def main():
     loss, t = lrn.read_stats()
     assert st == tj.TJ_OK and t == args.warmup + K and np.isfinite(loss)
 
-    ms = lambda evs, a, b: sum(e.elapsed_ms(a, b) for e in evs) / K
+    ms = lambda evs, a, b: sum(e.elapsed_ms(a, b) for e in evs) / len(evs)
     ph = {
         "mask_scan_select_ms": ms(bev, 0, 1), "gather_ms": ms(bev, 1, 2),
-        "forward_gemm_ms": ms(lev, 0, 1), "td_huber_ms": ms(lev, 1, 2), "backward_gemm_ms": ms(lev, 2, 3),
+        "forward_gemm_ms": ms(lev, 0, 1),
+        ("head_td_ms" if wl.precision == "bf16" and wl.layers[-1][1] <= 32 else "td_huber_ms"): ms(lev, 1, 2), "backward_gemm_ms": ms(lev, 2, 3),
         "adam_ms": ms(lev, 3, 4),
     }
     n_layers = len(wl.layers)
     n_conv = sum(1 for l in wl.layers if l[0] == synth.CONV)
     # forward: one grouped launch per linear layer, two (online, target) per convolution;
     # backward: a weight-gradient GEMM per layer and an input-gradient GEMM per layer but the first
-    n_gemm_launch = (n_layers + n_conv) + n_layers + (n_layers - 1)
-    flops = gemm_flops_per_step(wl, synth)
+    fused_head = wl.precision == "bf16" and wl.layers[-1][1] <= 32
+    n_gemm_launch = (n_layers + n_conv - (1 if fused_head else 0)) + n_layers + (n_layers - 1)
+    flops = gemm_flops_per_step(wl, synth, fused_head)
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
     achieved = flops / (gemm_ms * 1e-3) / 1e12
     peak = PEAK_TFLOPS[wl.precision]
@@ -172,7 +185,7 @@ def main():
                      "frac": achieved / peak, "traffic": None,
                      "kernel": "gemm_pq", "launches_per_step": n_gemm_launch,
                      "flops_per_launch": flops / n_gemm_launch, "avg_launch_ms": gemm_ms / n_gemm_launch},
-        "phases_ms": ph,
+        "phases_ms": ph, "phase_events_on_steps": len(sampled),
         "gather": {"bound": "hbm", "achieved": gather_bytes / (ph["gather_ms"] * 1e-3) / 1e9,
                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": gather_bytes},
         "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9,
@@ -182,7 +195,7 @@ def main():
     out["gather"]["frac"] = out["gather"]["achieved"] / PEAK_HBM_GBS
     out["adam"]["frac"] = out["adam"]["achieved"] / PEAK_HBM_GBS
     if not args.no_cpu_baseline:
-        rows = args.cpu_rows or max(8, min(wl.batch, int(3e11 / (flops / wl.batch))))
+        rows = args.cpu_rows or max(8, min(wl.batch, int(3e11 / (gemm_flops_per_step(wl, synth, False) / wl.batch))))
         out["cpu_baseline"] = cpu_baseline(wl, synth, buf, versions, theta, target, rows)
     print(json.dumps(out))
 

@@ -23,7 +23,7 @@ namespace {
 // ---------------------------------------------------------------- small kernels
 
 // Cast fp32 [R][C] to T with a padded pitch, and optionally to its transpose,
-// through a 32 x 32 LDS tile.  blockIdx.z selects the job.
+// through an LDS tile.  blockIdx.z selects the job.
 template <typename T> struct CastJob {
     const float *src;   // [R][C], pitch C
     T *dst;             // [R][ldd]   (may be null)
@@ -34,30 +34,81 @@ template <typename T> struct CastJobs {
     CastJob<T> job[TJ_MAX_LAYERS];
 };
 
+template <typename T> struct CastPack;
+template <> struct CastPack<float> {
+    typedef float4 Vec;   // 16 bytes of T
+    __device__ static void store4(float *p, float a, float b, float c, float d) { *(float4 *)p = make_float4(a, b, c, d); }
+    __device__ static Vec pack(const float *x) { return make_float4(x[0], x[1], x[2], x[3]); }
+};
+template <> struct CastPack<tj_bf16> {
+    typedef uint4 Vec;
+    __device__ static uint32_t two(float a, float b) { return (uint32_t)tj_f32_to_bf16(a) | ((uint32_t)tj_f32_to_bf16(b) << 16); }
+    __device__ static void store4(tj_bf16 *p, float a, float b, float c, float d) { *(uint2 *)p = make_uint2(two(a, b), two(c, d)); }
+    __device__ static Vec pack(const float *x)
+    {
+        return make_uint4(two(x[0], x[1]), two(x[2], x[3]), two(x[4], x[5]), two(x[6], x[7]));
+    }
+};
+
+// 64 x 64 tiles: float4 loads, 8- or 16-byte stores of the straight copy, and 16-byte stores of the
+// transposed copy out of an LDS tile (a vector of the transpose covers consecutive source rows).
+// Vector stores may run into the pad elements of a row (inside the pitch): those are written as
+// zero, which is what they hold anyway.  `vec` = the source is 16-byte aligned with C % 4 == 0.
 template <typename T>
 __global__ __launch_bounds__(256) void cast_transpose(const CastJobs<T> jobs)
 {
-    __shared__ float tile[32][33];
+    constexpr int VE = TjElem<T>::kVec;
+    __shared__ float tile[64][65];
     const CastJob<T> jb = jobs.job[blockIdx.z];
-    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     if (r0 >= jb.R || c0 >= jb.C) return;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const bool vec = (((uintptr_t)jb.src & 15) == 0) && (jb.C % 4 == 0);
+    const int tc = (threadIdx.x & 15) * 4, tr = threadIdx.x >> 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int r = r0 + ty + 8 * i, c = c0 + tx;
-        float x = 0.f;
+        const int r = r0 + tr + 16 * i, c = c0 + tc;
+        float x[4] = {0.f, 0.f, 0.f, 0.f};
         if (r < jb.R && c < jb.C) {
-            x = jb.src[(size_t)r * jb.C + c];
-            if (jb.dst) jb.dst[(size_t)r * jb.ldd + c] = TjElem<T>::from_f32(x);
+            const float *sp = jb.src + (size_t)r * jb.C + c;
+            if (vec) {
+                const float4 v = *(const float4 *)sp;
+                x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < jb.C) x[e] = sp[e];
+            }
+            if (jb.dst) {
+                T *dp = jb.dst + (size_t)r * jb.ldd + c;
+                if (c + 4 <= jb.ldd) {
+                    CastPack<T>::store4(dp, x[0], x[1], x[2], x[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < jb.C) dp[e] = TjElem<T>::from_f32(x[e]);
+                }
+            }
         }
-        tile[ty + 8 * i][tx] = x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[tr + 16 * i][tc + e] = x[e];
     }
     if (!jb.dstT) return;
     __syncthreads();
+    constexpr int VPC = 64 / VE;   // vectors per tile column
+    for (int v = threadIdx.x; v < 64 * VPC; v += 256) {
+        const int c = c0 + v / VPC, rq = (v % VPC) * VE, r = r0 + rq;
+        if (c >= jb.C || r >= jb.R) continue;
+        float x[VE];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = c0 + ty + 8 * i, r = r0 + tx;
-        if (r < jb.R && c < jb.C) jb.dstT[(size_t)c * jb.lddT + r] = TjElem<T>::from_f32(tile[tx][ty + 8 * i]);
+        for (int u = 0; u < VE; ++u) x[u] = tile[rq + u][v / VPC];
+        T *dp = jb.dstT + (size_t)c * jb.lddT + r;
+        if (r + VE <= jb.lddT) {
+            *(typename CastPack<T>::Vec *)dp = CastPack<T>::pack(x);
+        } else {
+#pragma unroll
+            for (int u = 0; u < VE; ++u)
+                if (r + u < jb.R) dp[u] = TjElem<T>::from_f32(x[u]);
+        }
     }
 }
 
@@ -69,7 +120,7 @@ template <typename T> int launch_cast(const CastJobs<T> &jobs, int n_jobs, hipSt
         maxC = jobs.job[i].C > maxC ? jobs.job[i].C : maxC;
     }
     if (n_jobs == 0 || maxR == 0 || maxC == 0) return TJ_OK;
-    dim3 grid((maxC + 31) / 32, (maxR + 31) / 32, n_jobs);
+    dim3 grid((maxC + 63) / 64, (maxR + 63) / 64, n_jobs);
     cast_transpose<T><<<grid, 256, 0, st>>>(jobs);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
@@ -78,9 +129,16 @@ template <typename T> int launch_cast(const CastJobs<T> &jobs, int n_jobs, hipSt
 // small blocks: the kernel is latency bound).
 //   a* = argmax_a Q_on(s',a) (lowest index on ties); y = r + gamma (1-done) Q_tg(s',a*)
 //   d = Q_on(s,a) - y; loss = mean Huber_kappa(d); dL/dQ_on(s,a) = clip(d,-k,k)/B
-// Q rows: [0,B) Q_on(s), [B,2B) Q_on(s'), [2B,3B) Q_tg(s'); ldq is a multiple of 4 floats.  The
-// last block to finish adds the per-block partial sums in block order.
+// Q rows: [0,B) Q_on(s), [B,2B) Q_on(s'), [2B,3B) Q_tg(s'); ldq is a multiple of 4 floats.  Each
+// block leaves the sum of its losses in loss_part; the optimizer kernel adds them up.
 constexpr int kTdBlock = 64;
+
+__device__ __forceinline__ float huber_and_grad(float d, float kappa, int B, float *g)
+{
+    const float ad = fabsf(d);
+    *g = fminf(fmaxf(d, -kappa), kappa) / (float)B;
+    return ad <= kappa ? 0.5f * d * d : kappa * (ad - 0.5f * kappa);
+}
 
 template <typename T>
 __global__ __launch_bounds__(kTdBlock) void td_huber(const float *__restrict__ Q, int ldq, int B, int A,
@@ -88,11 +146,8 @@ __global__ __launch_bounds__(kTdBlock) void td_huber(const float *__restrict__ Q
                                                      const float *__restrict__ reward,
                                                      const uint8_t *__restrict__ done, float gamma, float kappa,
                                                      T *__restrict__ dZ, int lddz, T *__restrict__ dZT, int lddzt,
-                                                     int32_t *__restrict__ astar, float *__restrict__ loss_part,
-                                                     uint32_t *__restrict__ ticket, tj_step_stats *stats_out,
-                                                     tj_step_stats *stats_internal, uint32_t t_next)
+                                                     int32_t *__restrict__ astar, float *__restrict__ loss_part)
 {
-    __shared__ bool last;
     const int j = blockIdx.x * kTdBlock + threadIdx.x;
     float loss = 0.f;
     if (j < B) {
@@ -111,10 +166,8 @@ __global__ __launch_bounds__(kTdBlock) void td_huber(const float *__restrict__ Q
         aj = aj < 0 ? 0 : (aj >= A ? A - 1 : aj);
         const float not_done = done[j] ? 0.f : 1.f;
         const float y = reward[j] + gamma * not_done * Q[(size_t)(2 * B + j) * ldq + best];
-        const float d = Q[(size_t)j * ldq + aj] - y;
-        const float ad = fabsf(d);
-        loss = ad <= kappa ? 0.5f * d * d : kappa * (ad - 0.5f * kappa);
-        const float g = fminf(fmaxf(d, -kappa), kappa) / (float)B;
+        float g;
+        loss = huber_and_grad(Q[(size_t)j * ldq + aj] - y, kappa, B, &g);
         const T gz = TjElem<T>::from_f32(g), z0 = TjElem<T>::from_f32(0.f);
         for (int a = 0; a < A; ++a) {
             const T val = a == aj ? gz : z0;
@@ -125,27 +178,170 @@ __global__ __launch_bounds__(kTdBlock) void td_huber(const float *__restrict__ Q
     // wave reduction in a fixed order
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) loss += __shfl_down(loss, off, 64);
-    if (threadIdx.x == 0) {
-        loss_part[blockIdx.x] = loss;
-        __threadfence();
-        uint32_t prev = atomicAdd(ticket, 1u);
-        last = prev == gridDim.x - 1;
+    if (threadIdx.x == 0) loss_part[blockIdx.x] = loss;
+}
+
+// Head layer and TD step in one kernel (bf16 compute type, at most 32 actions).  The head's
+// forward is bound by reading its input rows once, so the three Q tiles of 32 transitions are
+// computed by one block and consumed in place:
+//   Q_on(s), Q_on(s'), Q_tg(s') = X W^T + b  for the block's rows  ->  Q (kept for inspection),
+//   then the TD target, Huber loss and dL/dQ exactly as td_huber.
+// 12 waves: 3 Q tiles x 4 interleaved quarters of the contraction.  Each wave streams its own
+// 32 x 64-element operand pieces: whole 128-byte lines from global memory (8 lanes per row),
+// through a wave-private, XOR-swizzled LDS slab, into the MFMA operand layout (lane (r, h)
+// holds 8 consecutive k of row r); no block barrier in the loop.
+typedef float headf32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 headbf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t headu32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kHeadRows = 32;    // transitions per block
+constexpr int kHeadSplit = 4;    // waves sharing one tile's contraction
+constexpr int kHeadWaves = 3 * kHeadSplit;
+constexpr int kHeadThreads = 64 * kHeadWaves;
+
+struct HeadTdArgs {
+    const tj_bf16 *X; int ldx;             // head input, rows row0[g] + j for tile g
+    int row0[3];
+    const tj_bf16 *W_on, *W_tg; int ldw;   // [A][ldw]
+    const float *b_on, *b_tg;
+    int B, A, K;
+    float *Q; int ldq;                     // [3B][ldq]
+    const int32_t *action; const float *reward; const uint8_t *done;
+    float gamma, kappa;
+    tj_bf16 *dZ; int lddz;                 // [B][lddz]
+    tj_bf16 *dZT; int lddzt;               // [A][lddzt]
+    int32_t *astar;
+    float *loss_part;                      // one per block
+};
+
+__device__ __forceinline__ void head_wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kHeadThreads) void head_td(const HeadTdArgs a)
+{
+    // per wave: 256 16-byte slots of X and 256 of W (32 rows x 8 pieces, piece p of row r in slot
+    // 8 r + (p ^ (r & 7))); afterwards the same memory holds the waves' partial tiles
+    __shared__ headu32x4 stage[kHeadWaves][2][256];
+    __shared__ float qs[3][kHeadRows][33];
+    __shared__ int s_aj[kHeadRows];
+    __shared__ float s_g[kHeadRows];
+    typedef float PartTile[kHeadRows][36];   // [transition][action]
+    static_assert(sizeof(PartTile) * kHeadWaves <= sizeof(stage), "partial tiles must fit the staging slabs");
+    PartTile *part = (PartTile *)&stage[0][0][0];
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int grp = w / kHeadSplit, kq = w % kHeadSplit;
+    const int r = lane & 31, h = lane >> 5;
+    const int j0 = blockIdx.x * kHeadRows;
+    const tj_bf16 *xbase = a.X + ((size_t)a.row0[grp] + j0) * a.ldx;
+    const tj_bf16 *wbase = grp == 2 ? a.W_tg : a.W_on;
+    const headu32x4 zero = {0u, 0u, 0u, 0u};
+    const int lrow = lane >> 3, lpiece = lane & 7;   // loader role: row 8 t + lrow, 16-byte piece lpiece
+    const int n_trip = (a.K + 63) / 64;
+    headf32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // two trips of loads stay in flight per wave (register sets 0 and 1)
+    headu32x4 xr[2][4], wr[2][4];
+    auto fetch = [&](int set, int trip) {
+        const int k = trip * 64 + lpiece * 8;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int row = 8 * t + lrow;
+            xr[set][t] = (k < a.K && j0 + row < a.B) ? *(const headu32x4 *)(xbase + (size_t)row * a.ldx + k) : zero;
+            wr[set][t] = (k < a.K && row < a.A) ? *(const headu32x4 *)(wbase + (size_t)row * a.ldw + k) : zero;
+        }
+    };
+    auto consume = [&](int set) {
+        head_wave_sync();   // the last trip's operand reads precede these writes
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int row = 8 * t + lrow, slot = 8 * row + (lpiece ^ (row & 7));
+            stage[w][0][slot] = xr[set][t];
+            stage[w][1][slot] = wr[set][t];
+        }
+        head_wave_sync();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int slot = 8 * r + ((2 * s + h) ^ (r & 7));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(headbf16x8, stage[w][1][slot]),
+                                                          __builtin_bit_cast(headbf16x8, stage[w][0][slot]), acc,
+                                                          0, 0, 0);
+        }
+    };
+    // fetches past the end of the contraction load nothing and contribute zeros
+    fetch(0, kq);
+    fetch(1, kq + kHeadSplit);
+    for (int trip = kq; trip < n_trip; trip += 2 * kHeadSplit) {
+        consume(0);
+        fetch(0, trip + 2 * kHeadSplit);
+        consume(1);
+        fetch(1, trip + 3 * kHeadSplit);
+    }
+    __syncthreads();   // every wave is done with its slab before the partial tiles overwrite them
+    // acc[4*q + e] = partial Q(transition r, action 8*q + 4*h + e)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        *(float4 *)&part[w][r][8 * q + 4 * h] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    __syncthreads();
+    for (int e = threadIdx.x; e < 3 * kHeadRows * 32; e += kHeadThreads) {
+        const int g = e >> 10, j = (e >> 5) & 31, i = e & 31;
+        float q = part[g * kHeadSplit][j][i];
+#pragma unroll
+        for (int s = 1; s < kHeadSplit; ++s) q += part[g * kHeadSplit + s][j][i];
+        if (i < a.A) q += (g == 2 ? a.b_tg : a.b_on)[i];
+        qs[g][j][i] = q;
+        if (i < a.A && j0 + j < a.B) a.Q[((size_t)g * a.B + j0 + j) * a.ldq + i] = q;
     }
     __syncthreads();
-    if (last) {   // block partials: strided per lane, then the same fixed shuffle tree
-        __threadfence();
-        float s = 0.f;
-        for (uint32_t b = threadIdx.x; b < gridDim.x; b += kTdBlock) s += ((volatile float *)loss_part)[b];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
-        if (threadIdx.x == 0) {
-            tj_step_stats out;
-            out.loss = s / (float)B;
-            out.step = t_next;
-            *stats_internal = out;
-            if (stats_out) *stats_out = out;
-            *ticket = 0;   // ready for the next step
+    if (w == 0) {
+        float loss = 0.f, g = 0.f;
+        int aj = -1;
+        const int j = j0 + lane;
+        if (lane < kHeadRows && j < a.B) {
+            int best = 0;
+            float bv = qs[1][lane][0];
+            for (int i = 1; i < a.A; ++i) {
+                const float x = qs[1][lane][i];
+                if (x > bv) { bv = x; best = i; }
+            }
+            a.astar[j] = best;
+            aj = a.action[j];
+            aj = aj < 0 ? 0 : (aj >= a.A ? a.A - 1 : aj);
+            const float not_done = a.done[j] ? 0.f : 1.f;
+            const float y = a.reward[j] + a.gamma * not_done * qs[2][lane][best];
+            loss = huber_and_grad(qs[0][lane][aj] - y, a.kappa, a.B, &g);
         }
+        if (lane < kHeadRows) { s_aj[lane] = aj; s_g[lane] = g; }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) loss += __shfl_down(loss, off, 64);
+        if (lane == 0) a.loss_part[blockIdx.x] = loss;
+    }
+    __syncthreads();
+    // dL/dQ as whole 16-byte vectors: rows of dZ (pad columns up to the vector are zero), and the
+    // block's 32 columns of dZ^T (columns past the batch, inside the pitch, are zero)
+    const int nva = (a.A + 7) / 8;
+    for (int e = threadIdx.x; e < kHeadRows * nva; e += kHeadThreads) {
+        const int j = e / nva, vc = e % nva;
+        if (j0 + j >= a.B) continue;
+        const int aj = s_aj[j];
+        const uint32_t gz = tj_f32_to_bf16(s_g[j]);
+        headu32x4 o = zero;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (aj == 8 * vc + 2 * u || aj == 8 * vc + 2 * u + 1) o[u] = gz << (16 * (aj & 1));
+        *(headu32x4 *)(a.dZ + (size_t)(j0 + j) * a.lddz + 8 * vc) = o;
+    }
+    for (int e = threadIdx.x; e < a.A * (kHeadRows / 8); e += kHeadThreads) {
+        const int arow = e >> 2, vc = e & 3;
+        if (j0 + 8 * vc >= a.lddzt) continue;
+        headu32x4 o = zero;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s_aj[8 * vc + u] == arow) o[u >> 1] |= (uint32_t)tj_f32_to_bf16(s_g[8 * vc + u]) << (16 * (u & 1));
+        *(headu32x4 *)(a.dZT + (size_t)arow * a.lddzt + j0 + 8 * vc) = o;
     }
 }
 
@@ -184,6 +380,16 @@ template <> __device__ __forceinline__ void emit4<tj_bf16>(tj_bf16 *dst, const f
     *(uint2 *)dst = o;
 }
 
+// The step's loss: the TD kernel's per-block sums, added in a fixed order (strided per lane,
+// then one shuffle tree) by the first wave of the optimizer kernel, which runs after every
+// TD block has finished.
+struct LossFinal {
+    const float *part;
+    int n_part, B;
+    uint32_t t_next;
+    tj_step_stats *out, *internal;   // out: caller's (may be null)
+};
+
 // Adam on the flat fp32 master state (bias-corrected, eps outside the square root); the gradient
 // is the sum of S slices (S = 1 when the weight-gradient GEMMs reduced their own split).  Also
 // emits the compute-type copy of the weights: 16 B read and 12 B + sizeof(T) written per parameter.
@@ -192,8 +398,21 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
                                                    float *__restrict__ v, const float *__restrict__ gpart,
                                                    int S, size_t gstride, size_t P, float lr, float b1,
                                                    float b2, float eps, float c1, float c2,
-                                                   const EmitTable<T> tab)
+                                                   const EmitTable<T> tab, const LossFinal lf)
 {
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+        float s = 0.f;
+        for (int b = threadIdx.x; b < lf.n_part; b += 64) s += lf.part[b];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+        if (threadIdx.x == 0) {
+            tj_step_stats o;
+            o.loss = s / (float)lf.B;
+            o.step = lf.t_next;
+            *lf.internal = o;
+            if (lf.out) *lf.out = o;
+        }
+    }
     const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= P) return;
     if (i + 4 <= P) {
@@ -314,6 +533,64 @@ struct tj_learner {
 
 namespace {
 
+// The head layer's forward and the TD step, between phase marks 1 and 2.  bf16 with at most 32
+// actions: the fused kernel (mark 1 before it); otherwise a GEMM into Q, mark 1, td_huber.
+// X rows row0[0] + j, row0[1] + j, row0[2] + j hold the head's input for s, s' (online), s' (target).
+template <typename T> struct HeadTd {
+    const T *X; int ldx; int row0[3];
+    const T *W_on, *W_tg; int ldw;
+    const float *b_on, *b_tg;
+    int B, A, K;
+    float *Q; int ldq;
+    T *dZ; int lddz; T *dZT; int lddzt;
+    int32_t *astar; float *loss_part;
+};
+
+template <typename T> constexpr bool head_fused(int A) { return sizeof(T) == 2 && A <= 32; }
+template <typename T> int td_blocks(int B, int A)
+{
+    return head_fused<T>(A) ? (B + kHeadRows - 1) / kHeadRows : (B + kTdBlock - 1) / kTdBlock;
+}
+
+template <typename T>
+int run_head_td(tj_learner *self, const HeadTd<T> &h, const tj_minibatch *mb, float gamma, float kappa,
+                hipStream_t st)
+{
+    int rc;
+    if constexpr (sizeof(T) == 2) {
+        if (head_fused<T>(h.A)) {
+            if ((rc = self->mark(1, st)) != TJ_OK) return rc;
+            HeadTdArgs a;
+            a.X = h.X; a.ldx = h.ldx;
+            for (int g = 0; g < 3; ++g) a.row0[g] = h.row0[g];
+            a.W_on = h.W_on; a.W_tg = h.W_tg; a.ldw = h.ldw; a.b_on = h.b_on; a.b_tg = h.b_tg;
+            a.B = h.B; a.A = h.A; a.K = h.K; a.Q = h.Q; a.ldq = h.ldq;
+            a.action = mb->action; a.reward = mb->reward; a.done = mb->done;
+            a.gamma = gamma; a.kappa = kappa;
+            a.dZ = h.dZ; a.lddz = h.lddz; a.dZT = h.dZT; a.lddzt = h.lddzt;
+            a.astar = h.astar; a.loss_part = h.loss_part;
+            head_td<<<td_blocks<T>(h.B, h.A), kHeadThreads, 0, st>>>(a);
+            return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+        }
+    }
+    TjGemmArgs<T> g;
+    memset(&g, 0, sizeof(g));
+    g.n_seg = 2;
+    g.seg[0] = {0, 2 * h.B, h.W_on, h.b_on, 0};
+    g.seg[1] = {2 * h.B, 3 * h.B, h.W_tg, h.b_tg, 2 * h.B - h.row0[2]};
+    g.Q = h.X;
+    g.ldp = h.ldw; g.ldq = h.ldx;
+    g.I = h.A; g.K = h.K;
+    g.k_chunk = g.K; g.n_split = 1;
+    g.Cf = h.Q; g.ldcf = h.ldq;
+    if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
+    if ((rc = self->mark(1, st)) != TJ_OK) return rc;
+    td_huber<T><<<td_blocks<T>(h.B, h.A), kTdBlock, 0, st>>>(h.Q, h.ldq, h.B, h.A, mb->action, mb->reward, mb->done,
+                                                             gamma, kappa, h.dZ, h.lddz, h.dZT, h.lddzt, h.astar,
+                                                             h.loss_part);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
 template <typename T> struct MlpLearner : tj_learner {
     static constexpr int VE = TjElem<T>::kVec;
     tj_learner_desc d;
@@ -328,7 +605,6 @@ template <typename T> struct MlpLearner : tj_learner {
     size_t act_bytes = 0;
     float *Qout = nullptr, *loss_part = nullptr;
     int32_t *astar = nullptr;
-    uint32_t *ticket = nullptr;
     tj_step_stats *stats_internal = nullptr;
     int last_batch = -1;
 
@@ -385,8 +661,7 @@ template <typename T> struct MlpLearner : tj_learner {
         act_bytes = a.off - act0;
         Qout = (float *)a.take(3 * (size_t)Bmax * ldA * 4);
         astar = (int32_t *)a.take((size_t)Bmax * 4);
-        loss_part = (float *)a.take((size_t)((Bmax + kTdBlock - 1) / kTdBlock) * 4);
-        ticket = (uint32_t *)a.take(4);
+        loss_part = (float *)a.take((size_t)((Bmax + kHeadRows - 1) / kHeadRows) * 4);
         stats_internal = (tj_step_stats *)a.take(sizeof(tj_step_stats));
         return a.off;
     }
@@ -435,7 +710,7 @@ template <typename T> struct MlpLearner : tj_learner {
         if ((rc = mark(0, st)) != TJ_OK) return rc;
 
         // forward: columns j = rows of the stacked batch; [0,2B) online, [2B,3B) target
-        for (int l = 0; l < L; ++l) {
+        for (int l = 0; l + 1 < L; ++l) {
             TjGemmArgs<T> g;
             memset(&g, 0, sizeof(g));
             g.n_seg = 2;
@@ -445,23 +720,24 @@ template <typename T> struct MlpLearner : tj_learner {
             g.ldp = lay[l].ld_in; g.ldq = lay[l].ld_in;
             g.I = lay[l].out; g.K = lay[l].ld_in;
             g.k_chunk = g.K; g.n_split = 1;
-            if (l + 1 < L) {
-                g.relu = 1;
-                g.Ci = X[l + 1]; g.ldci = lay[l].ld_out;
-                g.Cj = XT[l + 1]; g.ldcj = ldB; g.cj_jmax = B;
-            } else {
-                g.Cf = Qout; g.ldcf = ldA;
-            }
+            g.relu = 1;
+            g.Ci = X[l + 1]; g.ldci = lay[l].ld_out;
+            g.Cj = XT[l + 1]; g.ldcj = ldB; g.cj_jmax = B;
             if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
         }
-
-        if ((rc = mark(1, st)) != TJ_OK) return rc;
-        const uint32_t t_next = (uint32_t)(t + 1);
-        td_huber<T><<<(B + kTdBlock - 1) / kTdBlock, kTdBlock, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done,
-                                                     d.gamma, d.huber_delta, dZ[L], lay[L - 1].ld_out, dZT[L],
-                                                     ldB, astar, loss_part, ticket, d_stats, stats_internal,
-                                                     t_next);
-        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        {   // head layer and TD step
+            const LayerPlan &lh = lay[L - 1];
+            HeadTd<T> h;
+            h.X = X[L - 1]; h.ldx = lh.ld_in;
+            h.row0[0] = 0; h.row0[1] = B; h.row0[2] = L == 1 ? B : 2 * B;
+            h.W_on = Wc_on[L - 1]; h.W_tg = Wc_tg[L - 1]; h.ldw = lh.ld_in;
+            h.b_on = theta_on + lh.b_off; h.b_tg = theta_tg + lh.b_off;
+            h.B = B; h.A = A; h.K = lh.ld_in;
+            h.Q = Qout; h.ldq = ldA;
+            h.dZ = dZ[L]; h.lddz = lh.ld_out; h.dZT = dZT[L]; h.lddzt = ldB;
+            h.astar = astar; h.loss_part = loss_part;
+            if ((rc = run_head_td<T>(this, h, mb, d.gamma, d.huber_delta, st)) != TJ_OK) return rc;
+        }
         if ((rc = mark(2, st)) != TJ_OK) return rc;
 
         // backward through Q_online(s)
@@ -514,8 +790,9 @@ template <typename T> struct MlpLearner : tj_learner {
             tab.end[tab.n] = lay[l].w_off + (size_t)lay[l].in * lay[l].out;
             tab.dst[tab.n++] = Wc_on[l];
         }
+        const LossFinal lf = {loss_part, td_blocks<T>(B, A), B, (uint32_t)t, d_stats, stats_internal};
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, 1, Ppad, P, d.lr,
-                                                                      d.beta1, d.beta2, d.eps, c1, c2, tab);
+                                                                      d.beta1, d.beta2, d.eps, c1, c2, tab, lf);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
         if ((rc = recast(true, st, true)) != TJ_OK) return rc;   // transposed copies (and padded blocks)
@@ -626,7 +903,6 @@ template <typename T> struct ConvLearner : tj_learner {
     size_t act_bytes = 0;
     float *Qout = nullptr, *loss_part = nullptr;
     int32_t *astar = nullptr;
-    uint32_t *ticket = nullptr;
     tj_step_stats *stats_internal = nullptr;
     int last_batch = -1;
     bool shape_ok = true;
@@ -721,8 +997,7 @@ template <typename T> struct ConvLearner : tj_learner {
         act_bytes = a.off - act0;
         Qout = (float *)a.take(3 * B * ldA * 4);
         astar = (int32_t *)a.take(B * 4);
-        loss_part = (float *)a.take((size_t)((Bmax + kTdBlock - 1) / kTdBlock) * 4);
-        ticket = (uint32_t *)a.take(4);
+        loss_part = (float *)a.take((size_t)((Bmax + kHeadRows - 1) / kHeadRows) * 4);
         stats_internal = (tj_step_stats *)a.take(sizeof(tj_step_stats));
         return a.off;
     }
@@ -825,23 +1100,26 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.Q = act[l];
                 gm.ldp = y.ldK; gm.ldq = y.ldK;
                 gm.I = y.O; gm.K = y.ldK; gm.k_chunk = gm.K; gm.n_split = 1;
-                if (l + 1 < L) {
-                    gm.relu = 1;
-                    gm.Ci = act[l + 1]; gm.ldci = lay[l + 1].ldK;
-                    gm.Cj = lay[l + 1].XT; gm.ldcj = ldB; gm.cj_jmax = B;
-                } else {
-                    gm.Cf = Qout; gm.ldcf = ldA;
-                }
+                if (l + 1 == L) break;   // the head layer runs with the TD step below
+                gm.relu = 1;
+                gm.Ci = act[l + 1]; gm.ldci = lay[l + 1].ldK;
+                gm.Cj = lay[l + 1].XT; gm.ldcj = ldB; gm.cj_jmax = B;
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
             }
         }
-        if ((rc = mark(1, st)) != TJ_OK) return rc;
-
-        const uint32_t t_next = (uint32_t)(t + 1);
-        td_huber<T><<<(B + kTdBlock - 1) / kTdBlock, kTdBlock, 0, st>>>(Qout, ldA, B, A, mb->action, mb->reward, mb->done, d.gamma,
-                                                     d.huber_delta, lay[L - 1].dZ, lay[L - 1].ldO, lay[L - 1].dZT,
-                                                     ldB, astar, loss_part, ticket, d_stats, stats_internal, t_next);
-        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        {   // head layer and TD step
+            NLayer &y = lay[L - 1];
+            HeadTd<T> h;
+            h.X = act[L - 1]; h.ldx = y.ldK;
+            h.row0[0] = 0; h.row0[1] = B; h.row0[2] = 2 * B;
+            h.W_on = y.Wc_on; h.W_tg = y.Wc_tg; h.ldw = y.ldK;
+            h.b_on = theta_on + y.b_off; h.b_tg = theta_tg + y.b_off;
+            h.B = B; h.A = A; h.K = y.ldK;
+            h.Q = Qout; h.ldq = ldA;
+            h.dZ = y.dZ; h.lddz = y.ldO; h.dZT = y.dZT; h.lddzt = ldB;
+            h.astar = astar; h.loss_part = loss_part;
+            if ((rc = run_head_td<T>(this, h, mb, d.gamma, d.huber_delta, st)) != TJ_OK) return rc;
+        }
         if ((rc = mark(2, st)) != TJ_OK) return rc;
 
         // ---- backward through Q_online(s)
@@ -914,8 +1192,9 @@ template <typename T> struct ConvLearner : tj_learner {
         const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
         EmitTable<T> tab;
         tab.n = 0;   // the conv path's weight copies are permuted: recast() writes them
+        const LossFinal lf = {loss_part, td_blocks<T>(B, A), B, (uint32_t)t, d_stats, stats_internal};
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
-                                                                      d.beta2, d.eps, c1, c2, tab);
+                                                                      d.beta2, d.eps, c1, c2, tab, lf);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = recast(true, st)) != TJ_OK) return rc;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
