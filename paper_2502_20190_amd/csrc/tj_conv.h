@@ -28,6 +28,34 @@ __global__ __launch_bounds__(256) void to_nhwc(const S *__restrict__ src, T *__r
     for (int c = 0; c < C; ++c) dp[c] = TjElem<T>::from_f32((float)sp[(size_t)c * H * W] * scale);
 }
 
+// u8 planes with C = 4 -> channels-last bf16, eight pixels per thread: one 8-byte load per plane,
+// four 16-byte stores.  H*W must be a multiple of 8.
+__global__ __launch_bounds__(256) void to_nhwc_u8c4(const uint8_t *__restrict__ src, tj_bf16 *__restrict__ dst,
+                                                    size_t n_img, int HW, float scale)
+{
+    const size_t groups = n_img * (size_t)(HW / 8);
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= groups) return;
+    const size_t img = t / (HW / 8), p0 = (t % (HW / 8)) * 8;
+    const uint8_t *sp = src + img * 4 * (size_t)HW + p0;
+    uint64_t pl[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) pl[c] = *(const uint64_t *)(sp + (size_t)c * HW);
+    uint4 *dp = (uint4 *)(dst + (img * HW + p0) * 4);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {   // pixels 2q, 2q+1
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {   // (pixel 2q + e/2, channels 2(e%2), 2(e%2)+1)
+            const int px = 2 * q + (e >> 1), c = 2 * (e & 1);
+            const float lo = (float)((pl[c] >> (8 * px)) & 0xFF) * scale;
+            const float hi = (float)((pl[c + 1] >> (8 * px)) & 0xFF) * scale;
+            w[e] = (uint32_t)tj_f32_to_bf16(lo) | ((uint32_t)tj_f32_to_bf16(hi) << 16);
+        }
+        dp[q] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 // Patch matrix: row m = (img, oh, ow), column (kh*k + kw)*C + c.  One thread copies a
 // run of `vec` elements (vec = 8 when the runs are 16-byte aligned, else 1).
 template <typename T, int VEC>
@@ -120,6 +148,51 @@ __global__ __launch_bounds__(256) void col2im_mask(const T *__restrict__ dpatch,
     dz[t] = TjElem<T>::from_f32(sum);
 }
 
+// The same for bf16 with C a multiple of 8: one thread owns 8 channels of a pixel (16-byte loads
+// of the patch gradients and of the mask, one 16-byte store); same summation order.
+__global__ __launch_bounds__(256) void col2im_mask_v8(const tj_bf16 *__restrict__ dpatch, int ldk,
+                                                      const tj_bf16 *__restrict__ act, tj_bf16 *__restrict__ dz,
+                                                      ConvGeom g, size_t n_img)
+{
+    const int C8 = g.C / 8;
+    const size_t total = n_img * g.H * g.W * C8;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int c0 = (int)(t % C8) * 8;
+    const size_t p = t / C8;
+    const int x = (int)(p % g.W), y = (int)((p / g.W) % g.H);
+    const size_t img = p / ((size_t)g.W * g.H);
+    float sum[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sum[e] = 0.f;
+    for (int kh = y % g.s; kh < g.k; kh += g.s) {
+        const int oh = (y - kh) / g.s;
+        if (y < kh || oh >= g.OH) continue;
+        for (int kw = x % g.s; kw < g.k; kw += g.s) {
+            const int ow = (x - kw) / g.s;
+            if (x < kw || ow >= g.OW) continue;
+            const size_t m = (img * g.OH + oh) * g.OW + ow;
+            const uint4 v = *(const uint4 *)(dpatch + m * ldk + (kh * g.k + kw) * g.C + c0);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                sum[2 * e] += tj_bf16_to_f32((tj_bf16)(w[e] & 0xFFFF));
+                sum[2 * e + 1] += tj_bf16_to_f32((tj_bf16)(w[e] >> 16));
+            }
+        }
+    }
+    const uint4 mv = *(const uint4 *)(act + p * g.C + c0);
+    const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float lo = tj_bf16_to_f32((tj_bf16)(mw[e] & 0xFFFF)) > 0.f ? sum[2 * e] : 0.f;
+        const float hi = tj_bf16_to_f32((tj_bf16)(mw[e] >> 16)) > 0.f ? sum[2 * e + 1] : 0.f;
+        o[e] = (uint32_t)tj_f32_to_bf16(lo) | ((uint32_t)tj_f32_to_bf16(hi) << 16);
+    }
+    *(uint4 *)(dz + p * g.C + c0) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // fp32 master weights [O][C][S] (S = kh*kw of a convolution, or the H*W positions a linear layer
 // sees after a convolution; S = 1 for a plain linear layer) -> compute-type copy [O][ldk] with
 // k = s*C + c, and optionally its transpose [K][ldo].
@@ -138,25 +211,32 @@ __global__ __launch_bounds__(256) void permute_cast(const float *__restrict__ w,
 }
 
 // Sums n_part partial weight-gradient slices (kernel order [O][s*C + c], pitch K) and bias
-// partials into the flat gradient in parameter order ([O][C][S], then bias [O]).
+// partials into the flat gradient in parameter order ([O][C][S], then bias [O]).  A block owns 32
+// consecutive elements of a slice; its 8 thread rows each add every 8th slice (128-byte coalesced
+// reads), then the 8 sums are added in a fixed order: deterministic for a given n_part.
 __global__ __launch_bounds__(256) void reduce_permute(const float *__restrict__ part, size_t zstride, int n_part,
                                                       float *__restrict__ gw, float *__restrict__ gb, int O,
                                                       int C, int S)
 {
+    __shared__ float sh[8][33];
     const int K = C * S;
     const size_t total = (size_t)O * K + O;
-    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= total) return;
+    const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const size_t src = (size_t)blockIdx.x * 32 + col;     // element of a slice: [o][s*C + c], then bias
     float sum = 0.f;
-    if (t < (size_t)O * K) {
-        const int s = (int)(t % S), c = (int)((t / S) % C), o = (int)(t / ((size_t)S * C));
-        const size_t src = (size_t)o * K + s * C + c;
-        for (int z = 0; z < n_part; ++z) sum += part[(size_t)z * zstride + src];
-        gw[t] = sum;
+    if (src < total)
+        for (int z = grp; z < n_part; z += 8) sum += part[(size_t)z * zstride + src];
+    sh[grp][col] = sum;
+    __syncthreads();
+    if (grp != 0 || src >= total) return;
+#pragma unroll
+    for (int g = 1; g < 8; ++g) sum += sh[g][col];
+    if (src < (size_t)O * K) {
+        const int o = (int)(src / K), kk = (int)(src % K);
+        const int s_ = kk / C, c = kk % C;
+        gw[((size_t)o * C + c) * S + s_] = sum;
     } else {
-        const size_t o = t - (size_t)O * K;
-        for (int z = 0; z < n_part; ++z) sum += part[(size_t)z * zstride + (size_t)O * K + o];
-        gb[o] = sum;
+        gb[src - (size_t)O * K] = sum;
     }
 }
 

@@ -41,6 +41,60 @@ template <> struct TjElem<tj_bf16> {
     __host__ __device__ static float to_f32(tj_bf16 x) { return tj_bf16_to_f32(x); }
 };
 
+// Gather form of an operand: a convolution as a GEMM without a patch matrix.  Row m of the
+// operand is patch m = (img, oh, ow) of a channels-last image batch [img][H][W][C]; its column
+// k = (kh, kw, c) lies at  origin(m) + (k / run) * krow_stride + k % run,  run = kw_size * C: one
+// kernel row (kw, c) is a contiguous run of the image.  Divisions by ohw and ow are multiplications
+// by mg = ceil(2^32 / d) (exact while m * d < 2^32, which tj_gather_make checks).
+struct TjGather {
+    int on;
+    int ohw, ow;
+    uint32_t mg_ohw, mg_ow;
+    int64_t img_stride;          // elements between images
+    int oh_stride, ow_stride;    // elements between patch origins (stride * W * C, stride * C)
+    int run, krow_stride;        // elements per kernel row, elements between image rows (W * C)
+};
+
+__host__ __device__ inline int64_t tj_gather_origin(const TjGather &g, uint32_t m)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t img = __umulhi(m, g.mg_ohw);
+#else
+    const uint32_t img = (uint32_t)(((uint64_t)m * g.mg_ohw) >> 32);
+#endif
+    const uint32_t r = m - img * (uint32_t)g.ohw;
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t oh = __umulhi(r, g.mg_ow);
+#else
+    const uint32_t oh = (uint32_t)(((uint64_t)r * g.mg_ow) >> 32);
+#endif
+    const uint32_t ow = r - oh * (uint32_t)g.ow;
+    return (int64_t)img * g.img_stride + (int64_t)oh * g.oh_stride + (int64_t)ow * g.ow_stride;
+}
+
+__host__ __device__ inline int tj_gather_koff(const TjGather &g, int k)
+{
+    const int kh = k / g.run;
+    return kh * g.krow_stride + (k - kh * g.run);
+}
+
+// Fills g for an image batch [n][H][W][C], square kernel ksz, stride; false if the geometry does
+// not fit the 16-byte operand vectors or the exact-division range for max_rows patches.
+inline bool tj_gather_make(TjGather &g, int C, int H, int W, int ksz, int stride, int OH, int OW, size_t max_rows)
+{
+    g.on = 1;
+    g.ohw = OH * OW; g.ow = OW;
+    g.mg_ohw = (uint32_t)((((uint64_t)1 << 32) + g.ohw - 1) / g.ohw);
+    g.mg_ow = (uint32_t)((((uint64_t)1 << 32) + g.ow - 1) / g.ow);
+    g.img_stride = (int64_t)H * W * C;
+    g.oh_stride = stride * W * C; g.ow_stride = stride * C;
+    g.run = ksz * C; g.krow_stride = W * C;
+    if (g.ohw < 2 || g.ow < 2) return false;   // ceil(2^32 / 1) does not fit 32 bits
+    if (max_rows * (uint64_t)g.ohw >= ((uint64_t)1 << 32)) return false;
+    // every 8-element vector of a patch row must be 16-byte aligned and inside one kernel row
+    return g.run % 8 == 0 && g.ow_stride % 8 == 0 && g.krow_stride % 8 == 0 && (H * W * C) % 8 == 0;
+}
+
 // A run of output columns j that share one P operand (weights) and bias.
 template <typename T> struct TjGemmSeg {
     int j_begin, j_end;  // columns [j_begin, j_end) of D
@@ -68,7 +122,21 @@ template <typename T> struct TjGemmArgs {
     int n_split;         // gridDim.z
     float *qsum;         // optional: qsum[z*qsum_zstride + j] = sum over this z's k of Q[j][k]
     size_t qsum_zstride;
-
+    TjGather gather;     // gather.on: P rows are patches of seg[0].P (bf16, one segment of at most 64
+                         // columns, whole 64-k stages, no split); ldp is ignored
 };
 
 template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st);
+
+// Weight and bias gradient of a convolution layer from the channels-last output gradient and the
+// channels-last layer input (bf16, 32 or 64 output channels), split over the patch rows:
+//   part[z][o*K + k] = sum over slice z of dZ[m][o] * patch[m][k],  part[z][O*K + o] = sum dZ[m][o].
+struct TjConvWgradArgs {
+    const tj_bf16 *dZ; int O;   // [M rounded up to 32][O]; rows past M must be zero
+    const tj_bf16 *act;         // layer input [img][H][W][C]
+    TjGather g;                 // patch geometry of this layer
+    int M, K;                   // patches, patch length
+    float *part; size_t zstride;
+    int n_split, m_chunk;       // patch rows per slice, a multiple of 32; n_split * m_chunk >= M
+};
+int tj_conv_wgrad(const TjConvWgradArgs &a, hipStream_t st);

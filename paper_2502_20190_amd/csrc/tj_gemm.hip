@@ -758,9 +758,9 @@ template <int N> struct IntC { static constexpr int value = N; };
 #define TJ_CFG4 128, 2
 #endif
 
-template <int NFJ, int BKB, int NSTAGE, bool QSUM>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu((NFJ == 2 && BKB * NSTAGE <= 192) ? 4 : 2,
-                                                                      (NFJ == 2 && BKB * NSTAGE <= 192) ? 4 : 2)))
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu((NFJ <= 2 && BKB * NSTAGE <= 192) ? 4 : 2,
+                                                                      (NFJ <= 2 && BKB * NSTAGE <= 192) ? 4 : 2)))
 void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
                                                          const TileMap tm)
 {
@@ -830,8 +830,8 @@ void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
     const int n_stage = k_end > k_begin ? (k_end - k_begin) / KE : 0;
 
     // This wave's load instructions per stage: P chunks wave + 8 t (t < LP) and Q chunks wave + 8 t
-    // (t < LQ); a chunk = RPI rows.  Q chunks past the end repeat an earlier one (same data to the
-    // same place) so that every wave issues exactly LPS loads.
+    // (t < LQ); a chunk = RPI rows.  Q chunk numbers wrap around CHQ: a chunk past the end repeats an
+    // earlier one (same data to the same place) so that every wave issues exactly LPS loads.
     const int lrow = lane / VPR, lpos = lane % VPR;
     auto swizzle = [](int row) { return VPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };
     const T *gsrcP[LP];
@@ -840,12 +840,17 @@ void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
     for (int t = 0; t < LP; ++t) {
         const int row = (wave + 8 * t) * RPI + lrow;
         const int i = min(i0 + row, a.I - 1);
-        gsrcP[t] = seg.P + (size_t)i * a.ldp + (lpos ^ swizzle(row)) * 8 + k_begin;
+        if constexpr (GATHER)
+            gsrcP[t] = seg.P + tj_gather_origin(a.gather, (uint32_t)i);
+        else
+            gsrcP[t] = seg.P + (size_t)i * a.ldp + (lpos ^ swizzle(row)) * 8 + k_begin;
     }
+    // gather form: the k of this lane's vector is the same for all its P rows (the swizzle of a
+    // lane's rows does not depend on t), so one offset per stage serves every P load
+    const int kposP = (lpos ^ swizzle(wave * RPI + lrow)) * 8 + k_begin;
 #pragma unroll
     for (int t = 0; t < LQ; ++t) {
-        int c = wave + 8 * t;
-        if (c >= CHQ) c -= 8;
+        const int c = (wave + 8 * t) % CHQ;
         const int row = c * RPI + lrow;
         const int j = min(j0 + row, j_end - 1);
         gsrcQ[t] = a.Q + (size_t)(j - seg.q_shift) * a.ldq + (lpos ^ swizzle(row)) * 8 + k_begin;
@@ -862,11 +867,12 @@ void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
                      : "memory");
     };
     auto issue = [&](uint8_t *sA, uint8_t *sB, int s) {
+        const int offP = GATHER ? tj_gather_koff(a.gather, kposP + s * KE) : s * KE;
 #pragma unroll
-        for (int t = 0; t < LP; ++t) dma16(gsrcP[t] + s * KE, sA + (wave + 8 * t) * 1024);
+        for (int t = 0; t < LP; ++t) dma16(gsrcP[t] + offP, sA + (wave + 8 * t) * 1024);
 #pragma unroll
         for (int t = 0; t < LQ; ++t) {
-            const int c = wave + 8 * t >= CHQ ? wave + 8 * t - 8 : wave + 8 * t;   // wave-uniform
+            const int c = (wave + 8 * t) % CHQ;   // wave-uniform
             dma16(gsrcQ[t] + s * KE, sB + c * 1024);
         }
     };
@@ -1019,7 +1025,7 @@ void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
     }
 }
 
-template <int NFJ, int BKB, int NSTAGE>
+template <int NFJ, int BKB, int NSTAGE, bool GATHER = false>
 int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
 {
     constexpr int BJ3 = 64 * NFJ;
@@ -1030,7 +1036,9 @@ int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
     tm.tiles_j = tiles[0] + tiles[1];
     tm.spread_i = 0;
     const unsigned nblk = a.n_split > 1 ? (unsigned)tm.tiles_i * tm.tiles_j * a.n_split : xcd_grid(tm);
-    if (a.qsum)
+    if constexpr (GATHER)
+        gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
+    else if (a.qsum)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
@@ -1049,6 +1057,10 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
 {
     int jtot = 0;
     for (int s = 0; s < a.n_seg; ++s) jtot += a.seg[s].j_end - a.seg[s].j_begin;
+    if (a.gather.on) {
+        if (a.n_seg != 1 || jtot > 64 || a.K % 64 || a.n_split != 1 || a.qsum || a.I < 1) return TJ_ERR_SHAPE;
+        return launch_dlds<1, 64, 3, true>(a, st);   // short contractions: two blocks per CU overlap their phases
+    }
     if (uses_dlds(a)) {
         // pick the j extent of the tile (128 / 192 / 256) that needs the fewest rounds of 256 blocks,
         // weighted by the tile's work; ties go to the larger tile
@@ -1093,7 +1105,8 @@ template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
     constexpr int KE = kRowBytes / (int)sizeof(T);
     // shapes the kernel's loads and its grid assume
     if (a.n_seg < 1 || a.n_seg > 2 || a.I <= 0 || a.K <= 0 || a.n_split < 1) return TJ_ERR_SHAPE;
-    if (a.ldp % VE || a.ldq % VE || a.K % VE || a.K > a.ldp || a.K > a.ldq) return TJ_ERR_SHAPE;
+    if (a.gather.on && sizeof(T) != 2) return TJ_ERR_SHAPE;
+    if ((!a.gather.on && (a.ldp % VE || a.K > a.ldp)) || a.ldq % VE || a.K % VE || a.K > a.ldq) return TJ_ERR_SHAPE;
     if (a.n_split > 1 && (a.k_chunk % KE || (size_t)a.k_chunk * a.n_split < (size_t)a.K)) return TJ_ERR_SHAPE;
     if (a.n_split == 1 && a.k_chunk < a.K) return TJ_ERR_SHAPE;
     if ((a.Ci && a.ldci % VE) || (a.mask && a.ldmask % 4)) return TJ_ERR_SHAPE;

@@ -888,6 +888,8 @@ template <typename T> struct ConvLearner : tj_learner {
         size_t w_off, b_off;
         int n_split;
         size_t part_stride;
+        bool implicit;                  // conv without patch matrices: operand gathers (bf16, 32/64 channels)
+        TjGather gth;
         T *Wc_on, *WcT_on, *Wc_tg, *patches, *patchesT, *XT, *dZ, *dZT, *dpatch;
         float *part;
     };
@@ -933,9 +935,14 @@ template <typename T> struct ConvLearner : tj_learner {
                 y.ldK = round_up(y.K, VE);
                 y.ldO = y.O;
                 if (y.O % VE) shape_ok = false;            // channels-last rows must be whole vectors
+                y.implicit = false;
+                if (sizeof(T) == 2 && (y.O == 32 || y.O == 64) && y.K % 64 == 0)
+                    y.implicit = tj_gather_make(y.gth, g.C, g.H, g.W, g.k, g.s, g.OH, g.OW,
+                                                3 * (size_t)Bmax * y.OHW);
                 c = g.OC; h = g.OH; w = g.OW;
                 prev_conv = true;
             } else {
+                y.implicit = false;
                 seen_linear = true;
                 y.O = (int)d.layers[l].out;
                 if (prev_conv) { y.C = c; y.S = h * w; } else { y.C = c * h * w; y.S = 1; }
@@ -952,6 +959,12 @@ template <typename T> struct ConvLearner : tj_learner {
             const size_t Ms = (size_t)Bmax * y.OHW;
             size_t ns = Ms / 4096;
             y.n_split = (int)(ns < 1 ? 1 : (ns > 128 ? 128 : ns));
+            if (y.implicit) {   // about 512 blocks, each with at least four 32-row stages
+                const size_t njb = ((size_t)y.K + 255) / 256, stages = (Ms + 31) / 32;
+                ns = 512 / njb;
+                if (ns > stages / 4) ns = stages / 4;
+                y.n_split = (int)(ns < 1 ? 1 : ns);
+            }
             y.part_stride = tj_align_up((size_t)y.O * y.K + y.O, 64);
         }
         if (lay[L - 1].kind != TJ_LAYER_LINEAR) shape_ok = false;
@@ -980,11 +993,16 @@ template <typename T> struct ConvLearner : tj_learner {
             if (y.kind == TJ_LAYER_CONV2D) {
                 const size_t n_img = l == 0 ? 2 * B : 3 * B;
                 act[l] = (T *)a.take(n_img * y.g.H * y.g.W * y.g.C * sizeof(T));
-                y.patches = (T *)a.take(n_img * y.OHW * y.ldK * sizeof(T));
-                y.patchesT = (T *)a.take((size_t)y.K * round_up((int)(B * y.OHW), VE) * sizeof(T));
                 y.XT = nullptr;
-                y.dZ = (T *)a.take(B * y.OHW * y.O * sizeof(T));
-                y.dZT = (T *)a.take((size_t)y.O * round_up((int)(B * y.OHW), VE) * sizeof(T));
+                if (y.implicit) {   // no patch matrices; dZ rows padded (zero) to whole 32-row stages
+                    y.patches = y.patchesT = y.dZT = nullptr;
+                    y.dZ = (T *)a.take((B * y.OHW + 32) * y.O * sizeof(T));
+                } else {
+                    y.patches = (T *)a.take(n_img * y.OHW * y.ldK * sizeof(T));
+                    y.patchesT = (T *)a.take((size_t)y.K * round_up((int)(B * y.OHW), VE) * sizeof(T));
+                    y.dZ = (T *)a.take(B * y.OHW * y.O * sizeof(T));
+                    y.dZT = (T *)a.take((size_t)y.O * round_up((int)(B * y.OHW), VE) * sizeof(T));
+                }
                 y.dpatch = l > 0 ? (T *)a.take(B * y.OHW * y.ldK * sizeof(T)) : nullptr;
             } else {
                 act[l] = (T *)a.take(3 * B * y.ldK * sizeof(T));
@@ -1038,7 +1056,21 @@ template <typename T> struct ConvLearner : tj_learner {
         {   // observations -> channels-last compute type, images s | s'
             const tjconv::ConvGeom &g = lay[0].g;
             const size_t px = (size_t)B * g.H * g.W, img = (size_t)g.H * g.W * g.C;
-            if (d.obs_dtype == TJ_OBS_U8) {
+            bool fast = false;
+            if constexpr (sizeof(T) == 2) {
+                fast = d.obs_dtype == TJ_OBS_U8 && g.C == 4 && (g.H * g.W) % 8 == 0 &&
+                       (((uintptr_t)mb->obs | (uintptr_t)mb->next_obs) & 7) == 0;
+                if (fast) {
+                    const size_t groups = (size_t)B * (g.H * g.W / 8);
+                    tjconv::to_nhwc_u8c4<<<grid1(groups), 256, 0, st>>>((const uint8_t *)mb->obs, act[0], (size_t)B,
+                                                                        g.H * g.W, 1.0f / 255.0f);
+                    tjconv::to_nhwc_u8c4<<<grid1(groups), 256, 0, st>>>((const uint8_t *)mb->next_obs,
+                                                                        act[0] + (size_t)B * img, (size_t)B,
+                                                                        g.H * g.W, 1.0f / 255.0f);
+                }
+            }
+            if (fast) {
+            } else if (d.obs_dtype == TJ_OBS_U8) {
                 tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->obs, act[0], B, g.C, g.H,
                                                                        g.W, 1.0f / 255.0f);
                 tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->next_obs,
@@ -1062,25 +1094,31 @@ template <typename T> struct ConvLearner : tj_learner {
                 const size_t n_img = l == 0 ? 2 * (size_t)B : 3 * (size_t)B;
                 const size_t rows = n_img * y.OHW, Ms = (size_t)B * y.OHW;
                 const int run = g.k * g.C;
-                const bool vec = sizeof(T) == 2 && run % 8 == 0 && (g.s * g.C) % 8 == 0 && (g.W * g.C) % 8 == 0 &&
-                                 y.ldK % 8 == 0;
-                if (vec)
-                    tjconv::im2col<T, 8><<<grid1(rows * g.k * (run / 8)), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
-                else
-                    tjconv::im2col<T, 1><<<grid1(rows * g.k * run), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
-                {
+                if (!y.implicit) {
+                    const bool vec = sizeof(T) == 2 && run % 8 == 0 && (g.s * g.C) % 8 == 0 &&
+                                     (g.W * g.C) % 8 == 0 && y.ldK % 8 == 0;
+                    if (vec)
+                        tjconv::im2col<T, 8><<<grid1(rows * g.k * (run / 8)), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
+                    else
+                        tjconv::im2col<T, 1><<<grid1(rows * g.k * run), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
                     dim3 grid((unsigned)((Ms + 255) / 256), (unsigned)y.K);
                     tjconv::im2col_t<T><<<grid, 256, 0, st>>>(act[l], y.patchesT, g, Ms,
                                                               round_up((int)((size_t)Bmax * y.OHW), VE));
+                    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
                 }
-                if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
                 for (int net = 0; net < 2; ++net) {   // online on s and s', target on s'
                     const size_t row0 = net == 0 ? 0 : (l == 0 ? Ms : 2 * Ms);
                     const size_t nrow = net == 0 ? 2 * Ms : Ms;
                     TjGemmArgs<T> gm;
                     memset(&gm, 0, sizeof(gm));
                     gm.n_seg = 1;
-                    gm.seg[0] = {0, y.O, y.patches + row0 * y.ldK, nullptr, 0};
+                    if (y.implicit) {   // patches gathered from the images themselves
+                        const size_t img0 = row0 / y.OHW;
+                        gm.seg[0] = {0, y.O, act[l] + img0 * (size_t)g.H * g.W * g.C, nullptr, 0};
+                        gm.gather = y.gth;
+                    } else {
+                        gm.seg[0] = {0, y.O, y.patches + row0 * y.ldK, nullptr, 0};
+                    }
                     gm.Q = net == 0 ? y.Wc_on : y.Wc_tg;
                     gm.ldp = y.ldK; gm.ldq = y.ldK;
                     gm.I = (int)nrow; gm.K = y.ldK; gm.k_chunk = gm.K; gm.n_split = 1;
@@ -1129,7 +1167,24 @@ template <typename T> struct ConvLearner : tj_learner {
             const size_t Ms = (size_t)B * y.OHW;
             const int Kc = conv ? round_up((int)Ms, VE) : Kb;      // contraction of the weight gradient
             const int ldm = conv ? round_up((int)((size_t)Bmax * y.OHW), VE) : ldB;
-            {   // dW[o][k] = sum_m dZ[m][o] X[m][k] (k in kernel order), db[o] = sum_m dZ[m][o]
+            bool wgrad_done = false;
+            if constexpr (sizeof(T) == 2) {
+                if (conv && y.implicit) {   // straight from dZ and the layer input
+                    TjConvWgradArgs wa;
+                    wa.dZ = y.dZ; wa.O = y.O; wa.act = act[l]; wa.g = y.gth;
+                    wa.M = (int)Ms; wa.K = y.K;
+                    wa.part = y.part; wa.zstride = y.part_stride;
+                    wa.n_split = y.n_split;
+                    wa.m_chunk = round_up((int)((Ms + y.n_split - 1) / y.n_split), 32);
+                    if ((rc = tj_conv_wgrad(wa, st)) != TJ_OK) return rc;
+                    const size_t n = (size_t)y.O * y.K + y.O;
+                    tjconv::reduce_permute<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride, y.n_split, grad + y.w_off,
+                                                                     grad + y.b_off, y.O, y.C, y.S);
+                    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                    wgrad_done = true;
+                }
+            }
+            if (!wgrad_done) {   // dW[o][k] = sum_m dZ[m][o] X[m][k] (k in kernel order), db[o] = sum_m dZ[m][o]
                 TjGemmArgs<T> gm;
                 memset(&gm, 0, sizeof(gm));
                 gm.n_seg = 1;
@@ -1146,7 +1201,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.qsum = y.part + (size_t)y.O * y.K; gm.qsum_zstride = y.part_stride;
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
                 const size_t n = (size_t)y.O * y.K + y.O;
-                tjconv::reduce_permute<<<grid1(n), 256, 0, st>>>(y.part, y.part_stride, ns, grad + y.w_off,
+                tjconv::reduce_permute<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride, ns, grad + y.w_off,
                                                                  grad + y.b_off, y.O, y.C, y.S);
                 if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
             }
@@ -1175,10 +1230,18 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.Cj = y.dpatch; gm.ldcj = y.ldK; gm.cj_jmax = y.K;
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
                 const size_t n = (size_t)B * y.g.H * y.g.W * y.g.C;
-                tjconv::col2im_mask<T><<<grid1(n), 256, 0, st>>>(y.dpatch, y.ldK, act[l], below.dZ, y.g, (size_t)B);
+                bool v8 = false;
+                if constexpr (sizeof(T) == 2) {
+                    v8 = y.g.C % 8 == 0 && y.ldK % 8 == 0;
+                    if (v8)
+                        tjconv::col2im_mask_v8<<<grid1(n / 8), 256, 0, st>>>(y.dpatch, y.ldK, act[l], below.dZ, y.g,
+                                                                            (size_t)B);
+                }
+                if (!v8)
+                    tjconv::col2im_mask<T><<<grid1(n), 256, 0, st>>>(y.dpatch, y.ldK, act[l], below.dZ, y.g, (size_t)B);
                 if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
             }
-            if (below.kind == TJ_LAYER_CONV2D) {   // dZ^T of a conv layer: [OC][B*OH*OW]
+            if (below.kind == TJ_LAYER_CONV2D && !below.implicit) {   // dZ^T of a conv layer: [OC][B*OH*OW]
                 const int Mb = (int)((size_t)B * below.OHW);
                 if ((rc = transpose(below.dZ, below.O, below.dZT, round_up((int)((size_t)Bmax * below.OHW), VE), Mb,
                                     below.O, st)) != TJ_OK)

@@ -280,6 +280,19 @@ def test_conv_stride_and_kernel_variants(tj, orc):
         _step_both(tj, orc, g, o, wl, _batch(wl, 320 + step), TOL["bf16"], sync=step > 0)
 
 
+def test_gathered_conv_operands_with_ragged_batches(tj, orc):
+    """Layers that take the patch-matrix-free path (bf16, 32 / 64 output channels, patch length a multiple
+    of 64): 8x8/4 -> 32 channels, 4x4/2 -> 64 channels.  Patch counts that are not multiples of the
+    32-row stages (21 * 64, 21 * 9, 5 * 9) and a shrinking batch exercise the zero pad rows."""
+    from paper_2502_20190_amd.synth import CONV
+
+    wl = _conv_workload("bf16", batch=21, in_chw=(4, 36, 36),
+                        layers=((CONV, 32, 8, 4), (CONV, 64, 4, 2), (LIN, 24, 0, 0), (LIN, 6, 0, 0)), n_actions=6)
+    g, o = _pair(tj, orc, wl, seed=14)
+    for step, b in enumerate((21, 21, 5)):
+        _step_both(tj, orc, g, o, wl, _batch(wl, 360 + step, b), TOL["bf16"], sync=step > 0)
+
+
 def test_c4_nature_dqn_shape_small_batch(tj, orc):
     """Config 4's network (4x84x84 u8 frames, conv 8x8/4x32, 4x4/2x64, 3x3/1x64, FC 3136-512-18, bf16)
     at batch 16, against the bf16-rounding oracle."""
