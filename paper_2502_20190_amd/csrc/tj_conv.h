@@ -193,51 +193,24 @@ __global__ __launch_bounds__(256) void col2im_mask_v8(const tj_bf16 *__restrict_
     *(uint4 *)(dz + p * g.C + c0) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-// fp32 master weights [O][C][S] (S = kh*kw of a convolution, or the H*W positions a linear layer
-// sees after a convolution; S = 1 for a plain linear layer) -> compute-type copy [O][ldk] with
-// k = s*C + c, and optionally its transpose [K][ldo].
-template <typename T>
-__global__ __launch_bounds__(256) void permute_cast(const float *__restrict__ w, T *__restrict__ wc, int ldk,
-                                                    T *__restrict__ wct, int ldo, int O, int C, int S)
-{
-    const size_t total = (size_t)O * C * S;
-    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= total) return;
-    const int s = (int)(t % S), c = (int)((t / S) % C), o = (int)(t / ((size_t)S * C));
-    const T val = TjElem<T>::from_f32(w[t]);
-    const int kk = s * C + c;
-    wc[(size_t)o * ldk + kk] = val;
-    if (wct) wct[(size_t)kk * ldo + o] = val;
-}
-
-// Sums n_part partial weight-gradient slices (kernel order [O][s*C + c], pitch K) and bias
-// partials into the flat gradient in parameter order ([O][C][S], then bias [O]).  A block owns 32
-// consecutive elements of a slice; its 8 thread rows each add every 8th slice (128-byte coalesced
-// reads), then the 8 sums are added in a fixed order: deterministic for a given n_part.
-__global__ __launch_bounds__(256) void reduce_permute(const float *__restrict__ part, size_t zstride, int n_part,
-                                                      float *__restrict__ gw, float *__restrict__ gb, int O,
-                                                      int C, int S)
+// Sums n_part partial gradient slices of n elements each into dst.  A block owns 32 consecutive
+// elements; its 8 thread rows each add every 8th slice (128-byte coalesced reads), then the 8 sums
+// are added in a fixed order: deterministic for a given n_part.
+__global__ __launch_bounds__(256) void reduce_parts(const float *__restrict__ part, size_t zstride, int n_part,
+                                                    float *__restrict__ dst, size_t n)
 {
     __shared__ float sh[8][33];
-    const int K = C * S;
-    const size_t total = (size_t)O * K + O;
     const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
-    const size_t src = (size_t)blockIdx.x * 32 + col;     // element of a slice: [o][s*C + c], then bias
+    const size_t e = (size_t)blockIdx.x * 32 + col;
     float sum = 0.f;
-    if (src < total)
-        for (int z = grp; z < n_part; z += 8) sum += part[(size_t)z * zstride + src];
+    if (e < n)
+        for (int z = grp; z < n_part; z += 8) sum += part[(size_t)z * zstride + e];
     sh[grp][col] = sum;
     __syncthreads();
-    if (grp != 0 || src >= total) return;
+    if (grp != 0 || e >= n) return;
 #pragma unroll
     for (int g = 1; g < 8; ++g) sum += sh[g][col];
-    if (src < (size_t)O * K) {
-        const int o = (int)(src / K), kk = (int)(src % K);
-        const int s_ = kk / C, c = kk % C;
-        gw[((size_t)o * C + c) * S + s_] = sum;
-    } else {
-        gb[src - (size_t)O * K] = sum;
-    }
+    dst[e] = sum;
 }
 
 }  // namespace tjconv

@@ -1020,16 +1020,43 @@ template <typename T> struct ConvLearner : tj_learner {
         return a.off;
     }
 
-    int recast(bool online, hipStream_t st)
+    // Master state (theta, m, v, grad) is kept in the kernels' own order: per layer W[O][k] with
+    // k = s*C + c (s = kernel position or, for a linear layer after a convolution, pixel), then the
+    // bias.  The caller's order W[O][C][S] appears only in get_state / set_state.
+    void permute_host(const float *src, float *dst, bool to_internal) const
     {
         for (int l = 0; l < L; ++l) {
-            NLayer &y = lay[l];
-            const size_t n = (size_t)y.O * y.K;
-            tjconv::permute_cast<T><<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
-                (online ? theta_on : theta_tg) + y.w_off, online ? y.Wc_on : y.Wc_tg, y.ldK,
-                online ? y.WcT_on : nullptr, y.ldO, y.O, y.C, y.S);
+            const NLayer &y = lay[l];
+            for (int o = 0; o < y.O; ++o)
+                for (int c = 0; c < y.C; ++c)
+                    for (int s = 0; s < y.S; ++s) {
+                        const size_t user = y.w_off + ((size_t)o * y.C + c) * y.S + s;
+                        const size_t mine = y.w_off + (size_t)o * y.K + (size_t)s * y.C + c;
+                        if (to_internal) dst[mine] = src[user]; else dst[user] = src[mine];
+                    }
+            for (int o = 0; o < y.O; ++o) dst[y.b_off + o] = src[y.b_off + o];
         }
-        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+    }
+
+    // Adam writes the straight copy of every weight block whose rows need no padding
+    bool adam_emits(int l) const { return lay[l].ldK == lay[l].K; }
+
+    // fp32 master -> compute-type copies (and the transposes the input-gradient GEMMs contract over)
+    int recast(bool online, hipStream_t st, bool after_adam = false)
+    {
+        CastJobs<T> jobs;
+        int n = 0;
+        for (int l = 0; l < L; ++l) {
+            NLayer &y = lay[l];
+            CastJob<T> j;
+            j.src = (online ? theta_on : theta_tg) + y.w_off;
+            j.dst = online ? y.Wc_on : y.Wc_tg;
+            if (after_adam && adam_emits(l)) j.dst = nullptr;
+            j.dstT = (online && l > 0) ? y.WcT_on : nullptr;   // the first layer has no input gradient
+            j.R = y.O; j.C = y.K; j.ldd = y.ldK; j.lddT = y.ldO;
+            if (j.dst || j.dstT) jobs.job[n++] = j;
+        }
+        return launch_cast<T>(jobs, n, st);
     }
 
     static dim3 grid1(size_t n) { return dim3((unsigned)((n + 255) / 256)); }
@@ -1177,9 +1204,9 @@ template <typename T> struct ConvLearner : tj_learner {
                     wa.n_split = y.n_split;
                     wa.m_chunk = round_up((int)((Ms + y.n_split - 1) / y.n_split), 32);
                     if ((rc = tj_conv_wgrad(wa, st)) != TJ_OK) return rc;
-                    const size_t n = (size_t)y.O * y.K + y.O;
-                    tjconv::reduce_permute<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride, y.n_split, grad + y.w_off,
-                                                                     grad + y.b_off, y.O, y.C, y.S);
+                    const size_t n = (size_t)y.O * y.K + y.O;   // weights, then bias: one block of the gradient
+                    tjconv::reduce_parts<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride,
+                                                                                         y.n_split, grad + y.w_off, n);
                     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
                     wgrad_done = true;
                 }
@@ -1201,8 +1228,8 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.qsum = y.part + (size_t)y.O * y.K; gm.qsum_zstride = y.part_stride;
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
                 const size_t n = (size_t)y.O * y.K + y.O;
-                tjconv::reduce_permute<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride, ns, grad + y.w_off,
-                                                                 grad + y.b_off, y.O, y.C, y.S);
+                tjconv::reduce_parts<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride, ns,
+                                                                                     grad + y.w_off, n);
                 if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
             }
             if (l == 0) break;
@@ -1254,13 +1281,19 @@ template <typename T> struct ConvLearner : tj_learner {
         const float c1 = (float)(1.0 - pow((double)d.beta1, (double)t));
         const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
         EmitTable<T> tab;
-        tab.n = 0;   // the conv path's weight copies are permuted: recast() writes them
+        tab.n = 0;
+        for (int l = 0; l < L; ++l) {
+            if (!adam_emits(l)) continue;
+            tab.begin[tab.n] = lay[l].w_off;
+            tab.end[tab.n] = lay[l].w_off + (size_t)lay[l].O * lay[l].K;
+            tab.dst[tab.n++] = lay[l].Wc_on;
+        }
         const LossFinal lf = {loss_part, td_blocks<T>(B, A), B, (uint32_t)t, d_stats, stats_internal};
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
                                                                       d.beta2, d.eps, c1, c2, tab, lf);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
-        if ((rc = recast(true, st)) != TJ_OK) return rc;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
+        if ((rc = recast(true, st, true)) != TJ_OK) return rc;
         if (d.target_interval && t % d.target_interval == 0) {
             TJ_HIP_TRY(hipMemcpyAsync(theta_tg, theta_on, P * 4, hipMemcpyDeviceToDevice, st));
             TJ_HIP_TRY(hipMemcpyAsync(wc_tg_begin, wc_on_begin, wc_bytes, hipMemcpyDeviceToDevice, st));
@@ -1281,8 +1314,10 @@ template <typename T> struct ConvLearner : tj_learner {
         }
         if (src) {
             if (n != P) return TJ_ERR_INVALID_ARG;
-            TJ_HIP_TRY(hipMemcpyAsync(h_out, src, P * 4, hipMemcpyDeviceToHost, st));
+            std::vector<float> tmp(P);
+            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), src, P * 4, hipMemcpyDeviceToHost, st));
             TJ_HIP_TRY(hipStreamSynchronize(st));
+            permute_host(tmp.data(), h_out, false);
             return TJ_OK;
         }
         if (which == TJ_STATE_QVALS) {
@@ -1316,11 +1351,13 @@ template <typename T> struct ConvLearner : tj_learner {
         case TJ_STATE_ADAM_V: dst = v; break;
         default: return TJ_ERR_INVALID_ARG;
         }
-        TJ_HIP_TRY(hipMemcpyAsync(dst, h_in, P * 4, hipMemcpyHostToDevice, st));
+        std::vector<float> tmp(P);
+        permute_host(h_in, tmp.data(), true);
+        TJ_HIP_TRY(hipMemcpyAsync(dst, tmp.data(), P * 4, hipMemcpyHostToDevice, st));
         int rc = TJ_OK;
         if (which == TJ_STATE_PARAMS) rc = recast(true, st);
         if (which == TJ_STATE_TARGET) rc = recast(false, st);
-        TJ_HIP_TRY(hipStreamSynchronize(st));
+        TJ_HIP_TRY(hipStreamSynchronize(st));   // tmp lives until the copy is done
         return rc;
     }
 };
