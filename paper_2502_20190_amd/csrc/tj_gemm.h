@@ -140,3 +140,19 @@ struct TjConvWgradArgs {
     int n_split, m_chunk;       // patch rows per slice, a multiple of 32; n_split * m_chunk >= M
 };
 int tj_conv_wgrad(const TjConvWgradArgs &a, hipStream_t st);
+
+// First convolution of a pixel network straight from u8 frame stacks [B][4][H][W] (32 output
+// channels, square kernel k with k % 4 == 0, even stride): out = relu(conv(x / 255) + b) for the
+// images s (online weights), s' (online) and s' (target), channels-last bf16 [3B*OH*OW][32];
+// act0 (optional) receives the channels-last bf16 copy of the s images.  Weights are bf16
+// [32][16 k^2] with the patch index ordered (kh, kw, c).
+struct TjConvFirstArgs {
+    const uint8_t *obs, *next_obs;
+    int B, H, W, k, s, OH, OW;
+    const tj_bf16 *W_on, *W_tg;
+    const float *b_on, *b_tg;
+    tj_bf16 *act0, *out;
+    float scale;
+};
+bool tj_conv_first_fits(int C, int H, int W, int k, int s, int O);
+int tj_conv_first(const TjConvFirstArgs &a, hipStream_t st);

@@ -908,6 +908,7 @@ template <typename T> struct ConvLearner : tj_learner {
     tj_step_stats *stats_internal = nullptr;
     int last_batch = -1;
     bool shape_ok = true;
+    bool first_fused = false;   // layer 0 runs straight from the u8 frames (tj_conv_first)
 
     size_t plan(void *base)
     {
@@ -968,6 +969,9 @@ template <typename T> struct ConvLearner : tj_learner {
             y.part_stride = tj_align_up((size_t)y.O * y.K + y.O, 64);
         }
         if (lay[L - 1].kind != TJ_LAYER_LINEAR) shape_ok = false;
+        first_fused = sizeof(T) == 2 && d.obs_dtype == TJ_OBS_U8 && lay[0].kind == TJ_LAYER_CONV2D &&
+                      lay[0].implicit && lay[0].ldK == lay[0].K &&
+                      tj_conv_first_fits(lay[0].g.C, lay[0].g.H, lay[0].g.W, lay[0].g.k, lay[0].g.s, lay[0].O);
         P = off;
         Ppad = tj_align_up(P, 64);
         A = lay[L - 1].O;
@@ -1080,7 +1084,23 @@ template <typename T> struct ConvLearner : tj_learner {
         }
         const int Kb = round_up(B, VE);
 
-        {   // observations -> channels-last compute type, images s | s'
+        bool first_done = false;
+        if constexpr (sizeof(T) == 2) {
+            if (first_fused && (((uintptr_t)mb->obs | (uintptr_t)mb->next_obs) & 3) == 0) {
+                const tjconv::ConvGeom &g = lay[0].g;
+                TjConvFirstArgs fa;
+                fa.obs = (const uint8_t *)mb->obs; fa.next_obs = (const uint8_t *)mb->next_obs;
+                fa.B = B; fa.H = g.H; fa.W = g.W; fa.k = g.k; fa.s = g.s; fa.OH = g.OH; fa.OW = g.OW;
+                fa.W_on = lay[0].Wc_on; fa.W_tg = lay[0].Wc_tg;
+                fa.b_on = theta_on + lay[0].b_off; fa.b_tg = theta_tg + lay[0].b_off;
+                fa.act0 = act[0]; fa.out = act[1];
+                fa.scale = 1.0f / 255.0f;
+                if ((rc = mark(0, st)) != TJ_OK) return rc;
+                if ((rc = tj_conv_first(fa, st)) != TJ_OK) return rc;
+                first_done = true;
+            }
+        }
+        if (!first_done) {   // observations -> channels-last compute type, images s | s'
             const tjconv::ConvGeom &g = lay[0].g;
             const size_t px = (size_t)B * g.H * g.W, img = (size_t)g.H * g.W * g.C;
             bool fast = false;
@@ -1110,11 +1130,11 @@ template <typename T> struct ConvLearner : tj_learner {
                                                                      act[0] + (size_t)B * img, B, g.C, g.H, g.W, 1.0f);
             }
             if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+            if ((rc = mark(0, st)) != TJ_OK) return rc;
         }
-        if ((rc = mark(0, st)) != TJ_OK) return rc;
 
         // ---- forward
-        for (int l = 0; l < L; ++l) {
+        for (int l = first_done ? 1 : 0; l < L; ++l) {
             NLayer &y = lay[l];
             if (y.kind == TJ_LAYER_CONV2D) {
                 const tjconv::ConvGeom &g = y.g;
