@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--config", default="c3", help="workload: c1 ... c5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's learner step (0 = auto)")
+    ap.add_argument("--insert-rows", type=int, default=0,
+                    help="also push this many new transitions per step into the ring on a second stream "
+                         "(tj_buffer_insert_concurrent) while the learner loops")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record the per-phase HIP events on every n-th timed step (each event costs "
                          "about 5 us of stream time, so recording them on every step slows the loop)")
@@ -120,7 +123,13 @@ def main():
     mb = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype)
     L = tj.lib()
 
+    side = torch.cuda.Stream() if args.insert_rows else None
+    fresh = synth.make_chunk_device(wl, synth.MASTER_SEED, 10_000, args.insert_rows) if args.insert_rows else None
+
     def one_step(i):
+        if fresh is not None:
+            buf.insert_concurrent(fresh["obs"], fresh["next_obs"], fresh["action"], fresh["reward"],
+                                  fresh["done"], fresh["version"], side)
         rc = buf.sample(mb, wl.current_version, wl.max_staleness, i)
         rc = rc or lrn.step(mb)
         if rc != tj.TJ_OK:
@@ -192,6 +201,11 @@ def main():
                  "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": adam_bytes},
         "loss": loss,
     }
+    if args.insert_rows:
+        ins_bytes = args.insert_rows * (wl.record_bytes + 4)
+        out["concurrent_insert"] = {"rows_per_step": args.insert_rows, "rows_per_s": args.insert_rows * K / wall,
+                                    "GB_per_s_written": ins_bytes * K / wall / 1e9,
+                                    "last_excluded_len": int(info.last_excluded_len)}
     out["gather"]["frac"] = out["gather"]["achieved"] / PEAK_HBM_GBS
     out["adam"]["frac"] = out["adam"]["achieved"] / PEAK_HBM_GBS
     if not args.no_cpu_baseline:

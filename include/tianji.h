@@ -78,6 +78,8 @@ typedef struct {
     uint64_t capacity, head, count; /* ring state (host side)                    */
     uint64_t last_n_eligible;       /* K of the most recent tj_sample            */
     int32_t sticky_error;           /* TJ_OK or TJ_ERR_NO_ELIGIBLE               */
+    uint64_t last_excluded_begin;   /* arc of slots the last tj_sample left out   */
+    uint64_t last_excluded_len;     /* because an insert into them was in flight  */
 } tj_buffer_info;
 
 /* Bytes of device memory tj_buffer_create needs for `desc` (0 if desc is bad). */
@@ -103,13 +105,35 @@ int tj_buffer_insert(tj_buffer *buf, uint32_t n, const void *d_obs, const void *
                      const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
                      const int32_t *d_version, void *hip_stream);
 
+/* Buffer receive while the learner keeps sampling (Section 3.1: the buffer
+ * loop and the learner loop run asynchronously, the learner does not wait for
+ * the actors' pushes).  Same effect as tj_buffer_insert, but `insert_stream`
+ * may differ from the stream tj_sample runs on, and the library orders the
+ * two itself:
+ *  - the copy waits, on the device, for every tj_sample issued before this
+ *    call (it may overwrite slots those samples still read);
+ *  - a later tj_sample leaves out the slots of every insert that was issued
+ *    before it but had not finished when its first kernel ran on the device:
+ *    slot s is skipped iff (s - begin) mod capacity < len for the arc
+ *    [begin, begin+len) those inserts cover, which holds the oldest
+ *    transitions of the ring.  The arc the last tj_sample used is reported by
+ *    tj_buffer_status.
+ * head and count advance at the call, as for tj_buffer_insert.  All concurrent
+ * inserts of one buffer go to the same insert_stream; tj_sample calls of one
+ * buffer go to one stream at a time (they share the sampler's scratch).  The
+ * source rows must stay valid until the copy has run. */
+int tj_buffer_insert_concurrent(tj_buffer *buf, uint32_t n, const void *d_obs, const void *d_next_obs,
+                                const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
+                                const int32_t *d_version, void *insert_stream);
+
 /* Learner load (Section 3.1, learner loop): a slot i < count is eligible iff
  * 0 <= current_version - version[i] <= max_staleness.  With E the ascending
  * list of eligible slots and K = |E|, draw j (0 <= j < batch) takes
  * E[floor(SplitMix64(seed, j) * K / 2^64)] (uniform, with replacement), and
  * minibatch row j is a copy of that ring row.  out->batch must equal `batch`
  * and every pointer in *out is a device pointer of that many rows.  The mask is
- * recomputed from the version tags on every call.  K == 0: idx is filled with
+ * recomputed from the version tags on every call.  Slots under an unfinished
+ * tj_buffer_insert_concurrent are not eligible.  K == 0: idx is filled with
  * 0xFFFFFFFF, the other minibatch fields are left untouched and the sticky
  * status becomes TJ_ERR_NO_ELIGIBLE (see tj_buffer_status). */
 int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,

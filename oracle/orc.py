@@ -32,6 +32,8 @@ def lib():
         L.orc_mulhi64.argtypes = [_u64, _u64]
         L.orc_sample.restype = _i32
         L.orc_sample.argtypes = [_vp, _u64, _i64, _i64, _u64, _u32, _vp, _vp]
+        L.orc_sample_excluding.restype = _i32
+        L.orc_sample_excluding.argtypes = [_vp, _u64, _u64, _u64, _u64, _i64, _i64, _u64, _u32, _vp, _vp]
         L.orc_buffer_create.restype = _vp
         L.orc_buffer_create.argtypes = [_u64, _u32, _u32]
         L.orc_buffer_destroy.argtypes = [_vp]
@@ -101,6 +103,16 @@ def sample(version, count, cur, max_st, seed, batch):
     idx = np.empty(batch, dtype=np.uint32)
     K = C.c_uint64(0)
     st = lib().orc_sample(_p(version), count, cur, max_st, seed, batch, _p(idx), C.byref(K))
+    return st, idx, K.value
+
+
+def sample_excluding(version, count, capacity, ex_begin, ex_len, cur, max_st, seed, batch):
+    """As sample(), with the slots (ex_begin + t) mod capacity, t < ex_len, not eligible."""
+    version = _c(version, np.int32)
+    idx = np.empty(batch, dtype=np.uint32)
+    K = C.c_uint64(0)
+    st = lib().orc_sample_excluding(_p(version), count, capacity, ex_begin, ex_len, cur, max_st, seed, batch,
+                                    _p(idx), C.byref(K))
     return st, idx, K.value
 
 

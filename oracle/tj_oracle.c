@@ -68,14 +68,20 @@ uint64_t orc_mulhi64(uint64_t a, uint64_t b)
  * E is the ascending list of eligible slots, K = |E|.  Draw j picks
  * E[ mulhi64(rng64(seed, j), K) ], with replacement.
  * Returns 0 on success, -4 if K == 0 (idx filled with 0xFFFFFFFF). */
-int orc_sample(const int32_t *version, uint64_t count, int64_t cur, int64_t max_st,
-               uint64_t seed, uint32_t batch, uint32_t *idx, uint64_t *K_out)
+/* Sampling while an insert into the arc [ex_begin, ex_begin + ex_len) (mod capacity) has not
+ * finished (Section 3.1: buffer and learner loops run asynchronously): slots of the arc are not
+ * eligible; everything else as orc_sample. */
+int orc_sample_excluding(const int32_t *version, uint64_t count, uint64_t capacity, uint64_t ex_begin,
+                         uint64_t ex_len, int64_t cur, int64_t max_st, uint64_t seed, uint32_t batch,
+                         uint32_t *idx, uint64_t *K_out)
 {
     uint64_t *E = (uint64_t *)malloc((count ? count : 1) * sizeof(uint64_t));
     uint64_t K = 0;
     for (uint64_t i = 0; i < count; ++i) {
+        /* i = (ex_begin + t) mod capacity for some t < ex_len  <=>  (i - ex_begin) mod capacity < ex_len */
+        int in_arc = ((i + capacity - ex_begin % capacity) % capacity) < ex_len;
         int64_t staleness = cur - (int64_t)version[i];
-        if (staleness >= 0 && staleness <= max_st) E[K++] = i;
+        if (!in_arc && staleness >= 0 && staleness <= max_st) E[K++] = i;
     }
     if (K_out) *K_out = K;
     if (K == 0) {
@@ -89,6 +95,12 @@ int orc_sample(const int32_t *version, uint64_t count, int64_t cur, int64_t max_
     }
     free(E);
     return 0;
+}
+
+int orc_sample(const int32_t *version, uint64_t count, int64_t cur, int64_t max_st,
+               uint64_t seed, uint32_t batch, uint32_t *idx, uint64_t *K_out)
+{
+    return orc_sample_excluding(version, count, count ? count : 1, 0, 0, cur, max_st, seed, batch, idx, K_out);
 }
 
 /* ------------------------------------------------------------------ */

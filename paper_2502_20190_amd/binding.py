@@ -26,7 +26,7 @@ TJ_MAX_LAYERS = 8
  TJ_STATE_ASTAR) = range(7)
 
 EXPORTS = [
-    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_sample",
+    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample",
     "tj_buffer_status", "tj_buffer_field_ptr", "tj_learner_num_params", "tj_learner_arena_bytes",
     "tj_learner_create", "tj_learner_destroy", "tj_learner_step", "tj_learner_get_state",
     "tj_learner_set_state", "tj_learner_get_step", "tj_learner_set_step", "tj_strerror",
@@ -45,7 +45,8 @@ class tj_minibatch(C.Structure):
 
 class tj_buffer_info(C.Structure):
     _fields_ = [("capacity", C.c_uint64), ("head", C.c_uint64), ("count", C.c_uint64),
-                ("last_n_eligible", C.c_uint64), ("sticky_error", C.c_int32)]
+                ("last_n_eligible", C.c_uint64), ("sticky_error", C.c_int32),
+                ("last_excluded_begin", C.c_uint64), ("last_excluded_len", C.c_uint64)]
 
 
 class tj_layer(C.Structure):
@@ -85,6 +86,8 @@ def lib():
         L.tj_buffer_destroy.argtypes = [vp]
         L.tj_buffer_insert.restype = i32
         L.tj_buffer_insert.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp, vp]
+        L.tj_buffer_insert_concurrent.restype = i32
+        L.tj_buffer_insert_concurrent.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp, vp]
         L.tj_sample.restype = i32
         L.tj_sample.argtypes = [vp, u32, i64, i64, u64, C.POINTER(tj_minibatch), vp]
         L.tj_buffer_status.restype = i32
@@ -213,6 +216,15 @@ class Buffer:
         _check(lib().tj_buffer_insert(self.h, n, obs.data_ptr(), next_obs.data_ptr(), action.data_ptr(),
                                       reward.data_ptr(), done.data_ptr(), version.data_ptr(),
                                       _stream_ptr(stream)), "tj_buffer_insert")
+
+    def insert_concurrent(self, obs, next_obs, action, reward, done, version, stream) -> None:
+        """Insert on `stream` (a torch stream other than the sampling stream); the source tensors are
+        kept alive by the caller until that stream has run the copy."""
+        n = int(action.shape[0])
+        _check(lib().tj_buffer_insert_concurrent(self.h, n, obs.data_ptr(), next_obs.data_ptr(),
+                                                 action.data_ptr(), reward.data_ptr(), done.data_ptr(),
+                                                 version.data_ptr(), _stream_ptr(stream)),
+               "tj_buffer_insert_concurrent")
 
     def insert_host(self, rows: dict, stream=None) -> None:
         import torch

@@ -5,7 +5,8 @@
 //   obs, next_obs  [N][row_bytes]      action i32 [N]   reward f32 [N]
 //   done u8 [N]    version i32 [N]
 //   mask  u64 [ceil(N/64)]  bit b of word w = slot 64w+b is eligible
-//   tile_count / tile_off u32 [ceil(N/1024)]   state u32 [4] {sticky, K, -, -}
+//   tile_count / tile_off u32 [ceil(N/1024)]
+//   state u32 [8] {sticky, K, arc begin, arc length, rows inserted so far (u64), -, -}
 //
 // tj_sample = four kernels on one stream:
 //   1 stale_mask_count : coalesced read of the tags, wave ballot -> mask words,
@@ -36,11 +37,15 @@ struct RingPtrs {
 
 // One block per tile of 1024 slots, four waves, each wave 4 x 64 slots: coalesced read of the
 // tags, wave ballot -> mask words, popcount -> tile count.
+// Slots of the arc [ex_begin, ex_begin + ex_len) (mod cap), which an unfinished concurrent insert
+// is overwriting, are not eligible.
 __global__ __launch_bounds__(256) void stale_mask_count(const int32_t *__restrict__ version,
                                                         uint32_t count, int64_t cur, int64_t max_st,
                                                         unsigned long long *__restrict__ mask,
-                                                        uint32_t *__restrict__ tile_count)
+                                                        uint32_t *__restrict__ tile_count,
+                                                        const uint32_t *__restrict__ state, uint32_t cap)
 {
+    const uint32_t ex_begin = state[2], ex_len = state[3];
     __shared__ uint32_t wave_cnt[4];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t base = blockIdx.x * kTile + wave * 256;
@@ -49,7 +54,8 @@ __global__ __launch_bounds__(256) void stale_mask_count(const int32_t *__restric
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         uint32_t s = base + r * 64 + lane;
-        ok[r] = s < count;
+        const uint32_t d = s >= ex_begin ? s - ex_begin : s + (cap - ex_begin);
+        ok[r] = s < count && d >= ex_len;
         v[r] = ok[r] ? version[s] : 0;
     }
     uint32_t cnt = 0;
@@ -272,6 +278,28 @@ __global__ __launch_bounds__(256) void insert_scalars(RingPtrs ring, uint32_t n,
     ring.version[s] = version[i];
 }
 
+// Last kernel of an insert on its stream: every kernel that wrote the rows has finished, so the
+// running total of inserted rows may advance.
+__global__ void publish_rows(uint32_t *state, unsigned long long total)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        __hip_atomic_store((unsigned long long *)(state + 4), total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Before a sample that may overlap concurrent inserts: the arc of slots whose insert had been
+// issued (rows_issued, host count at the call) but had not finished when this kernel ran.  One
+// snapshot serves all blocks of the mask kernel, and tj_buffer_status reports it.
+__global__ void snapshot_arc(uint32_t *state, unsigned long long rows_issued, unsigned long long cap)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const unsigned long long done =
+        __hip_atomic_load((unsigned long long *)(state + 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long len = rows_issued > done ? rows_issued - done : 0;
+    if (len > cap) len = cap;
+    state[2] = (uint32_t)(done % cap);
+    state[3] = (uint32_t)len;
+}
+
 __global__ void zero_words(uint32_t *p, uint32_t n)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -338,7 +366,7 @@ size_t layout(const tj_buffer_desc *d, TjArena &a, RingPtrs *ring, unsigned long
     unsigned long long *m = (unsigned long long *)a.take(n_tiles * kWordsPerTile * 8);
     uint32_t *tc = (uint32_t *)a.take(n_tiles * 4);
     uint32_t *to = (uint32_t *)a.take(n_tiles * 4);
-    uint32_t *s = (uint32_t *)a.take(16);
+    uint32_t *s = (uint32_t *)a.take(32);
     if (ring) *ring = r;
     if (mask) *mask = m;
     if (tile_count) *tile_count = tc;
@@ -364,6 +392,15 @@ struct tj_buffer {
     uint64_t head, count;
     hipEvent_t ev[3];
     bool timed;
+    // Concurrent inserts: rows_issued counts every row ever passed to an insert call (host side, at
+    // the call); its device twin in state[4..5] advances when an insert's kernels have run.  The
+    // difference, taken on the device just before a sample's mask kernel, is the arc that sample
+    // leaves out.  sample_done marks the end of the latest tj_sample.
+    uint64_t rows_issued = 0;
+    bool concurrent_used = false;
+    hipEvent_t sample_done = nullptr;
+    hipStream_t last_sample_stream = nullptr;
+    bool sampled = false;
 };
 
 extern "C" {
@@ -390,7 +427,7 @@ int tj_buffer_create(const tj_buffer_desc *desc, void *dev_arena, size_t arena_b
     b->n_tiles = (uint32_t)((desc->capacity + kTile - 1) / kTile);
     b->head = b->count = 0;
     b->timed = false;
-    zero_words<<<1, 64, 0, (hipStream_t)hip_stream>>>(b->state, 4);
+    zero_words<<<1, 64, 0, (hipStream_t)hip_stream>>>(b->state, 8);
     if (hipGetLastError() != hipSuccess) {
         delete b;
         return TJ_ERR_DEVICE;
@@ -402,20 +439,16 @@ int tj_buffer_create(const tj_buffer_desc *desc, void *dev_arena, size_t arena_b
 int tj_buffer_destroy(tj_buffer *buf)
 {
     if (!buf) return TJ_ERR_INVALID_ARG;
+    if (buf->sample_done) (void)hipEventDestroy(buf->sample_done);
     delete buf;
     return TJ_OK;
 }
 
-int tj_buffer_insert(tj_buffer *buf, uint32_t n, const void *d_obs, const void *d_next_obs,
-                     const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
-                     const int32_t *d_version, void *hip_stream)
+static int insert_rows(tj_buffer *buf, uint32_t n, const void *d_obs, const void *d_next_obs,
+                       const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
+                       const int32_t *d_version, hipStream_t st)
 {
-    if (!buf) return TJ_ERR_INVALID_ARG;
-    if (n == 0) return TJ_OK;
-    if (!d_obs || !d_next_obs || !d_action || !d_reward || !d_done || !d_version) return TJ_ERR_INVALID_ARG;
     const uint64_t cap = buf->desc.capacity;
-    if ((uint64_t)n > cap) return TJ_ERR_CAPACITY;
-    hipStream_t st = (hipStream_t)hip_stream;
     // narrow rows use a flat 32-bit vector index: split very large inserts
     const uint32_t max_rows = 1u << 20;
     for (uint32_t done_rows = 0; done_rows < n; done_rows += max_rows) {
@@ -428,10 +461,44 @@ int tj_buffer_insert(tj_buffer *buf, uint32_t n, const void *d_obs, const void *
     }
     insert_scalars<<<(n + 255) / 256, 256, 0, st>>>(buf->ring, n, d_action, d_reward, d_done, d_version,
                                                     buf->head, cap);
+    publish_rows<<<1, 64, 0, st>>>(buf->state, (unsigned long long)(buf->rows_issued + n));
     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+    buf->rows_issued += n;
     buf->head = (buf->head + n) % cap;
     buf->count = buf->count + n < cap ? buf->count + n : cap;
     return TJ_OK;
+}
+
+int tj_buffer_insert(tj_buffer *buf, uint32_t n, const void *d_obs, const void *d_next_obs,
+                     const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
+                     const int32_t *d_version, void *hip_stream)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    if (n == 0) return TJ_OK;
+    if (!d_obs || !d_next_obs || !d_action || !d_reward || !d_done || !d_version) return TJ_ERR_INVALID_ARG;
+    if ((uint64_t)n > buf->desc.capacity) return TJ_ERR_CAPACITY;
+    return insert_rows(buf, n, d_obs, d_next_obs, d_action, d_reward, d_done, d_version, (hipStream_t)hip_stream);
+}
+
+int tj_buffer_insert_concurrent(tj_buffer *buf, uint32_t n, const void *d_obs, const void *d_next_obs,
+                                const int32_t *d_action, const float *d_reward, const uint8_t *d_done,
+                                const int32_t *d_version, void *insert_stream)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    if (n == 0) return TJ_OK;
+    if (!d_obs || !d_next_obs || !d_action || !d_reward || !d_done || !d_version) return TJ_ERR_INVALID_ARG;
+    if ((uint64_t)n > buf->desc.capacity) return TJ_ERR_CAPACITY;
+    hipStream_t st = (hipStream_t)insert_stream;
+    // Samples issued so far may still be reading the slots about to be overwritten.  Once concurrent
+    // inserts are in use every tj_sample records sample_done at its end; the first concurrent insert
+    // records it here, behind whatever the sampling stream has been given so far.
+    if (!buf->concurrent_used && buf->sampled) {
+        if (!buf->sample_done) TJ_HIP_TRY(hipEventCreateWithFlags(&buf->sample_done, hipEventDisableTiming));
+        TJ_HIP_TRY(hipEventRecord(buf->sample_done, buf->last_sample_stream));
+    }
+    if (buf->sample_done) TJ_HIP_TRY(hipStreamWaitEvent(st, buf->sample_done, 0));
+    buf->concurrent_used = true;
+    return insert_rows(buf, n, d_obs, d_next_obs, d_action, d_reward, d_done, d_version, st);
 }
 
 int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
@@ -446,9 +513,16 @@ int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t m
     // only the tiles that hold valid slots take part (at least one, so K is always written)
     uint32_t n_tiles = (count + kTile - 1) / kTile;
     if (n_tiles == 0) n_tiles = 1;
+    // With concurrent inserts in play, the arc to leave out is taken on the device, in stream order
+    // just before the mask kernel; otherwise it stays empty (state[2..3] = 0).
+    if (buf->concurrent_used) {
+        snapshot_arc<<<1, 64, 0, st>>>(buf->state, (unsigned long long)buf->rows_issued,
+                                       (unsigned long long)buf->desc.capacity);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+    }
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[0], st));
     stale_mask_count<<<n_tiles, 256, 0, st>>>(buf->ring.version, count, current_version, max_staleness,
-                                              buf->mask, buf->tile_count);
+                                              buf->mask, buf->tile_count, buf->state, (uint32_t)buf->desc.capacity);
     tile_scan<<<1, 1024, 0, st>>>(buf->tile_count, n_tiles, buf->tile_off, buf->state);
     select_slots<<<(batch + 63) / 64, 64, 0, st>>>(buf->mask, buf->tile_off, n_tiles, buf->state,
                                                       seed, batch, buf->ring, out->idx, out->action,
@@ -458,6 +532,12 @@ int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t m
     int rc = copy_rows(buf->ring.obs, out->obs, buf->ring.next_obs, out->next_obs, buf->row_bytes, batch,
                        out->idx, 0, 0, buf->desc.capacity, st);
     if (rc == TJ_OK && buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[2], st));
+    buf->last_sample_stream = st;
+    buf->sampled = true;
+    if (rc == TJ_OK && buf->concurrent_used) {   // later concurrent inserts wait for this point
+        if (!buf->sample_done) TJ_HIP_TRY(hipEventCreateWithFlags(&buf->sample_done, hipEventDisableTiming));
+        TJ_HIP_TRY(hipEventRecord(buf->sample_done, st));
+    }
     return rc;
 }
 
@@ -481,7 +561,7 @@ int tj_buffer_status(tj_buffer *buf, tj_buffer_info *h_out, void *hip_stream)
 {
     if (!buf || !h_out) return TJ_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)hip_stream;
-    uint32_t h[4] = {0, 0, 0, 0};
+    uint32_t h[4] = {0, 0, 0, 0};   // sticky, K, arc begin, arc length of the last sample
     TJ_HIP_TRY(hipMemcpyAsync(h, buf->state, sizeof(h), hipMemcpyDeviceToHost, st));
     TJ_HIP_TRY(hipStreamSynchronize(st));
     h_out->capacity = buf->desc.capacity;
@@ -489,6 +569,8 @@ int tj_buffer_status(tj_buffer *buf, tj_buffer_info *h_out, void *hip_stream)
     h_out->count = buf->count;
     h_out->last_n_eligible = h[1];
     h_out->sticky_error = (int32_t)h[0];
+    h_out->last_excluded_begin = h[3] ? h[2] : 0;
+    h_out->last_excluded_len = h[3];
     if (h[0] != 0) {
         zero_words<<<1, 64, 0, st>>>(buf->state, 1);
         TJ_HIP_TRY(hipStreamSynchronize(st));

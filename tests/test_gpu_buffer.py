@@ -234,3 +234,101 @@ def test_full_size_device_filled_ring(tj, orc, name):
         pi = torch.from_numpy(oidx.astype(np.int64)).cuda()
         for f in FIELDS:
             assert torch.equal(getattr(mb, f), gbuf.field(f)[pi]), f
+
+
+# ---------------------------------------------------------------- inserts concurrent with sampling
+
+def _busy(stream, ms_target=3.0):
+    """Keeps `stream` occupied for a few milliseconds with ordinary torch work, so that what is
+    queued behind it is still pending when the host goes on."""
+    import torch
+
+    with torch.cuda.stream(stream):
+        a = torch.empty(256 * 1024 * 1024 // 4, device="cuda", dtype=torch.float32)
+        for _ in range(int(ms_target / 0.15) + 1):   # ~0.15 ms per 256 MiB fill
+            a.fill_(1.0)
+    return a
+
+
+def test_sampling_leaves_out_slots_under_an_unfinished_insert(tj, orc):
+    """An insert queued on a second stream behind other work is still pending when tj_sample is
+    issued: the sample must skip exactly the arc reported by tj_buffer_status, and agree bit for
+    bit with the oracle's sampler given that arc and the ring contents from before the insert.
+    Once the insert stream has drained, the new rows are visible."""
+    import torch
+
+    wl = synth.small_variant(synth.WORKLOADS["c2"], capacity=6000, batch=256)
+    gbuf, obuf = _fill_both(tj, orc, wl, 21, 2000, 6000 + 1500)      # full ring, head = 1500
+    side = torch.cuda.Stream()
+    cur, max_st = wl.current_version, 40
+    new_rows = [synth.make_chunk(wl, 22, c, n) for c, n in ((0, 700), (1, 4300))]   # the second one wraps
+    dev_rows = [{k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in r.items()} for r in new_rows]
+    _sync()
+    keep = _busy(side)
+    for r in dev_rows:
+        gbuf.insert_concurrent(r["obs"], r["next_obs"], r["action"], r["reward"], r["done"], r["version"], side)
+    mb = tj.Minibatch(wl.batch, gbuf.obs_elems, gbuf.obs_dtype)
+    assert gbuf.sample(mb, cur, max_st, 5) == tj.TJ_OK
+    st, info = gbuf.status()
+    assert st == tj.TJ_OK
+    ex_begin, ex_len = int(info.last_excluded_begin), int(info.last_excluded_len)
+    assert (ex_begin, ex_len) == (1500, 5000), "both inserts should still have been pending"
+    assert (info.head, info.count) == ((1500 + 5000) % 6000, 6000)
+    ost, oidx, oK = orc.sample_excluding(obuf.versions(), obuf.count, wl.capacity, ex_begin, ex_len, cur, max_st,
+                                         5, wl.batch)
+    assert ost == 0 and info.last_n_eligible == oK
+    got = mb.host()
+    np.testing.assert_array_equal(got["idx"], oidx)
+    want = obuf.gather(oidx)                       # contents from before the inserts
+    for f in FIELDS:
+        np.testing.assert_array_equal(got[f], want[f], err_msg=f)
+    side.synchronize()
+    del keep
+    for r in new_rows:
+        assert obuf.insert(**r) == 0
+    _compare_sample(tj, gbuf, obuf, wl.batch, cur, max_st, 6)
+    _, info = gbuf.status()
+    assert info.last_excluded_len == 0
+    whole = obuf.gather(np.arange(wl.capacity, dtype=np.uint32))
+    for f in ("obs", "next_obs", "done"):
+        np.testing.assert_array_equal(gbuf.field(f).cpu().numpy().reshape(wl.capacity, -1),
+                                      whole[f].reshape(wl.capacity, -1), err_msg=f)
+    np.testing.assert_array_equal(gbuf.field("version").cpu().numpy(), obuf.versions())
+
+
+def test_insert_stream_races_sampling_stream(tj, orc):
+    """Inserts stream in on a second stream, unsynchronised with the host, while the first stream
+    samples: every sample must equal the oracle's for the arc it reports (rows outside the arc are
+    fully determined by the inserts issued so far), whatever the interleaving was."""
+    import torch
+
+    wl = synth.small_variant(synth.WORKLOADS["c2"], capacity=20000, batch=512)
+    gbuf, obuf = _fill_both(tj, orc, wl, 31, 5000, 20000)
+    side = torch.cuda.Stream()
+    cur, max_st = wl.current_version, 60
+    mbs = [tj.Minibatch(wl.batch, gbuf.obs_elems, gbuf.obs_dtype) for _ in range(2)]
+    arcs_seen = 0
+    for it in range(24):
+        rows = synth.make_chunk(wl, 32, it, 1111 + 37 * it)
+        dev = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in rows.items()}
+        _sync()                                     # the upload is done; from here on no host sync
+        if it % 3 == 0:
+            keep = _busy(side, 1.0)
+        gbuf.insert_concurrent(dev["obs"], dev["next_obs"], dev["action"], dev["reward"], dev["done"],
+                               dev["version"], side)
+        assert obuf.insert(**rows) == 0             # the oracle's ring: state after the insert
+        mb = mbs[it % 2]
+        assert gbuf.sample(mb, cur, max_st, 100 + it) == tj.TJ_OK
+        st, info = gbuf.status()                    # synchronises the sampling stream only
+        ex_begin, ex_len = int(info.last_excluded_begin), int(info.last_excluded_len)
+        arcs_seen += ex_len > 0
+        ost, oidx, oK = orc.sample_excluding(obuf.versions(), obuf.count, wl.capacity, ex_begin, ex_len, cur,
+                                             max_st, 100 + it, wl.batch)
+        assert st == ost == 0 and info.last_n_eligible == oK
+        got = mb.host()
+        np.testing.assert_array_equal(got["idx"], oidx)
+        want = obuf.gather(oidx)
+        for f in FIELDS:
+            np.testing.assert_array_equal(got[f], want[f], err_msg=f"{f} at iteration {it}")
+    side.synchronize()
+    assert arcs_seen > 0, "no sample ever overlapped an unfinished insert"

@@ -72,6 +72,38 @@ def test_sample_matches_bruteforce_enumeration(orc, seed):
             assert idx[j] == E[k]
 
 
+@pytest.mark.parametrize("seed", [3, 4])
+def test_sample_excluding_an_arc_matches_set_enumeration(orc, seed):
+    """Sampling while an insert is in flight (Section 3.1, asynchronous buffer and learner loops):
+    the slots of the arc are written out as a literal set, wrap-around included."""
+    rng = np.random.default_rng(seed)
+    saw_wrap = False
+    for _ in range(60):
+        n = int(rng.integers(2, 65))
+        count = int(rng.integers(1, n + 1))
+        version = rng.integers(0, 12, size=n).astype(np.int32)
+        cur, max_st = int(rng.integers(0, 14)), int(rng.integers(0, 6))
+        ex_begin, ex_len = int(rng.integers(0, n)), int(rng.integers(0, n + 1))
+        arc = {(ex_begin + t) % n for t in range(ex_len)}
+        saw_wrap |= ex_begin + ex_len > n
+        full = _eligible_bruteforce(version, count, cur, max_st)
+        E = [i for i in full if i not in arc]
+        st, idx, K = orc.sample_excluding(version, count, n, ex_begin, ex_len, cur, max_st, seed, 16)
+        assert K == len(E) == len(full) - len(arc.intersection(full))
+        if not E:
+            assert st == -4 and (idx == 0xFFFFFFFF).all()
+            continue
+        assert st == 0 and not arc.intersection(int(i) for i in idx)
+        for j in range(16):
+            assert idx[j] == E[(orc.rng64(seed, j) * len(E)) >> 64]
+        if ex_len == 0:   # no insert in flight: the plain sampler
+            np.testing.assert_array_equal(idx, orc.sample(version, count, cur, max_st, seed, 16)[1])
+    assert saw_wrap
+    # the whole ring under an insert: nothing is eligible
+    v = np.zeros(8, np.int32)
+    assert orc.sample_excluding(v, 8, 8, 5, 8, 0, 0, 1, 4)[0] == -4
+
+
 def test_sampling_distribution_uniform_on_eligible(orc):
     version = np.array([5, 9, 3, 9, 8, 7, 1, 9, 6, 9, 2, 9, 10, 4, 8, 0, 9, 9], dtype=np.int32)
     count, cur, max_st = 16, 9, 1   # last two slots are beyond count; 10 > cur is ineligible
