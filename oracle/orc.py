@@ -32,6 +32,8 @@ def lib():
         L.orc_mulhi64.argtypes = [_u64, _u64]
         L.orc_sample.restype = _i32
         L.orc_sample.argtypes = [_vp, _u64, _i64, _i64, _u64, _u32, _vp, _vp]
+        L.orc_actor_act.restype = None
+        L.orc_actor_act.argtypes = [_vp, _vp, _u32, C.c_double, _u64, _vp, _vp, _vp]
         L.orc_sample_excluding.restype = _i32
         L.orc_sample_excluding.argtypes = [_vp, _u64, _u64, _u64, _u64, _i64, _i64, _u64, _u32, _vp, _vp]
         L.orc_buffer_create.restype = _vp
@@ -212,6 +214,15 @@ class Learner:
         q = np.empty((b, self.n_actions), np.float64)
         lib().orc_learner_forward(self.h, which, _p(obs), b, _p(q))
         return q
+
+    def act(self, obs, epsilon: float, seed: int):
+        """Epsilon-greedy actions under the online network: (action, q, greedy)."""
+        obs = _c(obs, self.np_dtype)
+        n = obs.shape[0]
+        action, greedy = np.empty(n, np.int32), np.empty(n, np.int32)
+        q = np.empty((n, self.n_actions), np.float64)
+        lib().orc_actor_act(self.h, _p(obs), n, C.c_double(epsilon), seed, _p(action), _p(q), _p(greedy))
+        return action, q, greedy
 
     def min_abs_preactivation(self, obs) -> np.ndarray:
         """Per sample: the smallest |pre-activation| over the hidden units (online net)."""

@@ -490,6 +490,31 @@ void orc_learner_forward(orc_learner *l, int which, const void *obs, uint32_t ba
     forward_batch(l, which == 0 ? l->theta : l->target, obs, batch, NULL, q, NULL);
 }
 
+/* Policy inference (Algorithm 1, step 1): an epsilon-greedy action for each observation under
+ * the online network.  greedy_j = argmax_a Q(s_j, a), lowest index on ties.  Draw j takes two
+ * outputs of the sampler's generator: u = rng64(seed, 2j) decides (explore iff its top 24 bits are
+ * below floor(epsilon * 2^24)), v = rng64(seed, 2j + 1) picks the uniform action floor(v * A / 2^64).
+ * q (optional) receives the Q-values, greedy (optional) the greedy actions. */
+void orc_actor_act(orc_learner *l, const void *obs, uint32_t n, double epsilon, uint64_t seed,
+                   int32_t *action, double *q, int32_t *greedy)
+{
+    const int A = l->n_actions;
+    double *qq = (double *)malloc((size_t)n * A * sizeof(double));
+    forward_batch(l, l->theta, obs, n, NULL, qq, NULL);
+    double scaled = epsilon * 16777216.0;
+    uint64_t threshold = scaled <= 0.0 ? 0 : (scaled >= 16777216.0 ? 16777216u : (uint64_t)scaled);
+    for (uint32_t j = 0; j < n; ++j) {
+        int best = 0;
+        for (int a = 1; a < A; ++a)
+            if (qq[(size_t)j * A + a] > qq[(size_t)j * A + best]) best = a;
+        if (greedy) greedy[j] = best;
+        uint64_t u = orc_rng64(seed, 2 * (uint64_t)j), v = orc_rng64(seed, 2 * (uint64_t)j + 1);
+        action[j] = (u >> 40) < threshold ? (int32_t)orc_mulhi64(v, (uint64_t)A) : best;
+    }
+    if (q) memcpy(q, qq, (size_t)n * A * sizeof(double));
+    free(qq);
+}
+
 /* Distance of a batch from the ReLU kinks: the smallest |pre-activation| over
  * all hidden units and samples under the online network.  At a kink the loss
  * gradient jumps, so a comparison of gradients at 1e-4 is only meaningful for

@@ -158,6 +158,40 @@ def test_mlp_forward_against_numpy(orc):
         np.testing.assert_allclose(l.forward(which, x), h, rtol=1e-12, atol=1e-12)
 
 
+def test_epsilon_greedy_policy_inference(orc):
+    """Algorithm 1, step 1.  Pins: epsilon = 0 is the plain argmax of the forward pass (numpy); the
+    decision and the uniform action are literal integer functions of the published generator;
+    epsilon = 1 explores always and uniformly (chi-square); the explore rate matches epsilon;
+    actions of a shorter batch are a prefix; the online network (not the target) is used."""
+    layers = [(LIN, 16, 0, 0), (LIN, 5, 0, 0)]
+    l, theta, target = _make(orc, layers, (6, 1, 1), seed=3)
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((4000, 6)).astype(np.float32)
+    q_on, q_tg = l.forward(0, x), l.forward(1, x)
+    a0, q0, g0 = l.act(x, 0.0, 77)
+    np.testing.assert_array_equal(a0, q_on.argmax(axis=1))
+    np.testing.assert_array_equal(g0, a0)
+    np.testing.assert_allclose(q0, q_on, rtol=0, atol=0)
+    assert (q_on.argmax(axis=1) != q_tg.argmax(axis=1)).any()        # would notice the wrong network
+    for eps in (0.05, 0.5, 1.0):
+        a, _, g = l.act(x, eps, 123)
+        thr = int(eps * 2 ** 24)
+        explore = np.array([(orc.rng64(123, 2 * j) >> 40) < thr for j in range(len(x))])
+        uniform = np.array([(orc.rng64(123, 2 * j + 1) * 5) >> 64 for j in range(len(x))])
+        np.testing.assert_array_equal(a, np.where(explore, uniform, g))
+        np.testing.assert_array_equal(g, g0)
+        assert abs(explore.mean() - eps) < 4 * np.sqrt(eps * (1 - eps) / len(x)) + 1e-12
+        np.testing.assert_array_equal(l.act(x[:57], eps, 123)[0], a[:57])
+    a1 = l.act(x, 1.0, 5)[0]
+    counts = np.bincount(a1, minlength=5)
+    chi2 = ((counts - len(x) / 5) ** 2 / (len(x) / 5)).sum()
+    assert chi2 < 18.47                                               # 4 degrees of freedom, p = 0.001
+    # a tie goes to the lowest index
+    tie = orc.Learner([(LIN, 3, 0, 0)], (2, 1, 1))
+    tie.set_state(orc.PARAMS, np.array([1, 0, 1, 0, 0, 0, 0.5, 0.5, 0.2], np.float64))
+    assert tie.act(np.array([[1.0, 3.0]], np.float32), 0.0, 0)[0][0] == 0
+
+
 def test_conv_1x1_is_a_per_pixel_linear_layer(orc):
     rng = np.random.default_rng(8)
     layers = [(CONV, 5, 1, 1), (LIN, 5 * 3 * 4, 0, 0)]
