@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--insert-rows", type=int, default=0,
                     help="also push this many new transitions per step into the ring on a second stream "
                          "(tj_buffer_insert_concurrent) while the learner loops")
+    ap.add_argument("--actor-rows", type=int, default=0,
+                    help="after the learner loop, also time epsilon-greedy policy inference (tj_actor_act) "
+                         "on this many observations per call (at most twice the batch)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record the per-phase HIP events on every n-th timed step (each event costs "
                          "about 5 us of stream time, so recording them on every step slows the loop)")
@@ -208,6 +211,18 @@ def main():
                                     "last_excluded_len": int(info.last_excluded_len)}
     out["gather"]["frac"] = out["gather"]["achieved"] / PEAK_HBM_GBS
     out["adam"]["frac"] = out["adam"]["achieved"] / PEAK_HBM_GBS
+    if args.actor_rows:
+        rows = synth.make_chunk_device(wl, synth.MASTER_SEED, 20_000, args.actor_rows)
+        for i in range(5):
+            lrn.act(rows["obs"], 0.05, i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(50):
+            lrn.act(rows["obs"], 0.05, 100 + i)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 50
+        out["actor_inference"] = {"rows_per_call": args.actor_rows, "ms_per_call": dt * 1e3,
+                                  "actions_per_s": args.actor_rows / dt, "epsilon": 0.05}
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or max(8, min(wl.batch, int(3e11 / (gemm_flops_per_step(wl, synth, False) / wl.batch))))
         out["cpu_baseline"] = cpu_baseline(wl, synth, buf, versions, theta, target, rows)

@@ -217,6 +217,21 @@ int tj_learner_destroy(tj_learner *lrn);
 int tj_learner_step(tj_learner *lrn, const tj_minibatch *mb, tj_step_stats *d_stats,
                     void *hip_stream);
 
+/* Policy inference (Algorithm 1, step 1: choose the action with the
+ * epsilon-greedy policy of the current weights) for n observations, with the
+ * learner's online network: greedy_j = argmax_a Q(s_j, a), lowest index on
+ * ties.  Draw j uses two outputs of tj_sample's generator: u = SplitMix64(seed,
+ * 2j) decides (explore iff its top 24 bits are below floor(epsilon * 2^24)),
+ * v = SplitMix64(seed, 2j+1) gives the uniform action floor(v * A / 2^64).
+ * d_obs: device, [n][obs elements] in the learner's observation dtype;
+ * d_action, d_version: device int32[n] (the version is the learner's step
+ * count, i.e. the version of the weights that chose the action: Section 2.2,
+ * actors hold different policy versions); d_q: optional device float[n][A].
+ * n <= 2 * max_batch.  Runs on hip_stream in the learner's activation
+ * buffers: never concurrently with tj_learner_step of the same handle. */
+int tj_actor_act(tj_learner *lrn, uint32_t n, const void *d_obs, float epsilon, uint64_t seed,
+                 int32_t *d_action, int32_t *d_version, float *d_q, void *hip_stream);
+
 /* Synchronising host copies of learner state (h_out / h_in: host pointers to n
  * floats; n must match the size given at the enum).  set_state accepts PARAMS,
  * TARGET, ADAM_M, ADAM_V and refreshes the derived weight copies. */

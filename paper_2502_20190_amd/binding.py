@@ -26,7 +26,7 @@ TJ_MAX_LAYERS = 8
  TJ_STATE_ASTAR) = range(7)
 
 EXPORTS = [
-    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample",
+    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_actor_act",
     "tj_buffer_status", "tj_buffer_field_ptr", "tj_learner_num_params", "tj_learner_arena_bytes",
     "tj_learner_create", "tj_learner_destroy", "tj_learner_step", "tj_learner_get_state",
     "tj_learner_set_state", "tj_learner_get_step", "tj_learner_set_step", "tj_strerror",
@@ -86,6 +86,8 @@ def lib():
         L.tj_buffer_destroy.argtypes = [vp]
         L.tj_buffer_insert.restype = i32
         L.tj_buffer_insert.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp, vp]
+        L.tj_actor_act.restype = i32
+        L.tj_actor_act.argtypes = [vp, u32, vp, C.c_float, u64, vp, vp, vp, vp]
         L.tj_buffer_insert_concurrent.restype = i32
         L.tj_buffer_insert_concurrent.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp, vp]
         L.tj_sample.restype = i32
@@ -310,6 +312,20 @@ class Learner:
     def step(self, mb: Minibatch, stream=None) -> int:
         self.last_batch = mb.batch
         return lib().tj_learner_step(self.h, C.byref(mb.c), self.stats.data_ptr(), _stream_ptr(stream))
+
+    def act(self, obs, epsilon: float, seed: int, want_q: bool = False, stream=None):
+        """Epsilon-greedy actions for a device tensor of observations [n, obs elements]:
+        (action int32[n], version int32[n], q float32[n, A] or None), all device tensors."""
+        import torch
+
+        n = int(obs.shape[0])
+        action = torch.empty(n, dtype=torch.int32, device=obs.device)
+        version = torch.empty(n, dtype=torch.int32, device=obs.device)
+        q = torch.empty((n, self.n_actions), dtype=torch.float32, device=obs.device) if want_q else None
+        _check(lib().tj_actor_act(self.h, n, obs.data_ptr(), epsilon, seed & (2**64 - 1), action.data_ptr(),
+                                  version.data_ptr(), q.data_ptr() if want_q else None, _stream_ptr(stream)),
+               "tj_actor_act")
+        return action, version, q
 
     def read_stats(self):
         raw = self.stats.cpu().numpy()

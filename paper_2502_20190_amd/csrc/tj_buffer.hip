@@ -119,14 +119,6 @@ __global__ __launch_bounds__(1024) void tile_scan(const uint32_t *__restrict__ t
     }
 }
 
-__device__ __forceinline__ uint64_t splitmix64(uint64_t seed, uint64_t j)
-{
-    uint64_t z = seed + (j + 1) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
 // One thread per draw, one wave per block (the kernel is a chain of dependent loads).
 __global__ __launch_bounds__(64) void select_slots(
     const unsigned long long *__restrict__ mask, const uint32_t *__restrict__ tile_off,
@@ -141,7 +133,7 @@ __global__ __launch_bounds__(64) void select_slots(
         idx[j] = kInvalid;
         return;
     }
-    uint32_t k = (uint32_t)__umul64hi(splitmix64(seed, j), (uint64_t)K);
+    uint32_t k = (uint32_t)__umul64hi(tj_splitmix64(seed, j), (uint64_t)K);
     // last tile t with tile_off[t] <= k
     uint32_t lo = 0, hi = n_tiles;
     while (hi - lo > 1) {

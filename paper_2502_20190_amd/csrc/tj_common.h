@@ -28,3 +28,12 @@ struct TjArena {
         return p;
     }
 };
+
+// SplitMix64 (Steele, Lea, Flood 2014) as a counter-based generator: output j of stream `seed`.
+__device__ __forceinline__ uint64_t tj_splitmix64(uint64_t seed, uint64_t j)
+{
+    uint64_t z = seed + (j + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}

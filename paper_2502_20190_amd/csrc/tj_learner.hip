@@ -181,6 +181,36 @@ __global__ __launch_bounds__(kTdBlock) void td_huber(const float *__restrict__ Q
     if (threadIdx.x == 0) loss_part[blockIdx.x] = loss;
 }
 
+// Epsilon-greedy action per observation from its Q row (Algorithm 1, step 1).  Two draws of the
+// sampler's generator per observation: the top 24 bits of draw 2j against the threshold decide,
+// draw 2j+1 scaled by mul-high picks the uniform action.
+__global__ __launch_bounds__(256) void egreedy(const float *__restrict__ Q, int ldq, uint32_t n, int A,
+                                               uint32_t threshold, uint64_t seed, int32_t version,
+                                               int32_t *__restrict__ action, int32_t *__restrict__ version_out,
+                                               float *__restrict__ q_out)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float *q = Q + (size_t)j * ldq;
+    int best = 0;
+    float bv = q[0];
+    if (q_out) q_out[(size_t)j * A] = bv;
+    for (int a = 1; a < A; ++a) {
+        const float x = q[a];
+        if (q_out) q_out[(size_t)j * A + a] = x;
+        if (x > bv) { bv = x; best = a; }
+    }
+    const uint64_t u = tj_splitmix64(seed, 2 * (uint64_t)j), v = tj_splitmix64(seed, 2 * (uint64_t)j + 1);
+    action[j] = (uint32_t)(u >> 40) < threshold ? (int32_t)__umul64hi(v, (uint64_t)A) : best;
+    version_out[j] = version;
+}
+
+inline uint32_t egreedy_threshold(float epsilon)
+{
+    const double scaled = (double)epsilon * 16777216.0;
+    return scaled <= 0.0 ? 0u : (scaled >= 16777216.0 ? 16777216u : (uint32_t)scaled);
+}
+
 // Head layer and TD step in one kernel (bf16 compute type, at most 32 actions).  The head's
 // forward is bound by reading its input rows once, so the three Q tiles of 32 transitions are
 // computed by one block and consumed in place:
@@ -521,6 +551,8 @@ struct tj_learner {
     virtual int step(const tj_minibatch *mb, tj_step_stats *d_stats, hipStream_t st) = 0;
     virtual int get_state(int which, float *h_out, size_t n, hipStream_t st) = 0;
     virtual int set_state(int which, const float *h_in, size_t n, hipStream_t st) = 0;
+    virtual int infer(uint32_t n, const void *d_obs, float epsilon, uint64_t seed, int32_t *d_action,
+                    int32_t *d_version, float *d_q, hipStream_t st) = 0;
     uint64_t t = 0;
     hipEvent_t ev[5];
     bool timed = false;
@@ -801,6 +833,40 @@ template <typename T> struct MlpLearner : tj_learner {
             TJ_HIP_TRY(hipMemcpyAsync(Wc_tg[0], Wc_on[0], wc_bytes, hipMemcpyDeviceToDevice, st));
         }
         return TJ_OK;
+    }
+
+    // Policy inference on n <= 2*Bmax observations: online forward in the step's own buffers
+    // (rows [0, n) of every X_l), then the epsilon-greedy kernel on the Q rows.
+    int infer(uint32_t n_, const void *d_obs, float epsilon, uint64_t seed, int32_t *d_action, int32_t *d_version,
+            float *d_q, hipStream_t st) override
+    {
+        const int n = (int)n_;
+        if (n < 1 || n > 2 * Bmax) return TJ_ERR_SHAPE;
+        if (!d_obs || !d_action || !d_version || !(epsilon >= 0.f && epsilon <= 1.f)) return TJ_ERR_INVALID_ARG;
+        int rc;
+        CastJobs<T> jobs;
+        jobs.job[0] = {(const float *)d_obs, X[0], nullptr, n, lay[0].in, lay[0].ld_in, ldB};
+        if ((rc = launch_cast<T>(jobs, 1, st)) != TJ_OK) return rc;
+        for (int l = 0; l < L; ++l) {
+            TjGemmArgs<T> g;
+            memset(&g, 0, sizeof(g));
+            g.n_seg = 1;
+            g.seg[0] = {0, n, Wc_on[l], theta_on + lay[l].b_off, 0};
+            g.Q = X[l];
+            g.ldp = lay[l].ld_in; g.ldq = lay[l].ld_in;
+            g.I = lay[l].out; g.K = lay[l].ld_in;
+            g.k_chunk = g.K; g.n_split = 1;
+            if (l + 1 < L) {
+                g.relu = 1;
+                g.Ci = X[l + 1]; g.ldci = lay[l].ld_out;
+            } else {
+                g.Cf = Qout; g.ldcf = ldA;
+            }
+            if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
+        }
+        egreedy<<<(n + 255) / 256, 256, 0, st>>>(Qout, ldA, (uint32_t)n, A, egreedy_threshold(epsilon), seed,
+                                                 (int32_t)t, d_action, d_version, d_q);
+        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
     }
 
     int get_state(int which, float *h_out, size_t n, hipStream_t st) override
@@ -1321,6 +1387,81 @@ template <typename T> struct ConvLearner : tj_learner {
         return TJ_OK;
     }
 
+    // Policy inference on n <= 2*Bmax observations with the online network, in the step's buffers.
+    int infer(uint32_t n_, const void *d_obs, float epsilon, uint64_t seed, int32_t *d_action, int32_t *d_version,
+            float *d_q, hipStream_t st) override
+    {
+        const int n = (int)n_;
+        if (n < 1 || n > 2 * Bmax) return TJ_ERR_SHAPE;
+        if (!d_obs || !d_action || !d_version || !(epsilon >= 0.f && epsilon <= 1.f)) return TJ_ERR_INVALID_ARG;
+        int rc;
+        {
+            const tjconv::ConvGeom &g = lay[0].g;
+            const size_t px = (size_t)n * g.H * g.W;
+            bool fast = false;
+            if constexpr (sizeof(T) == 2) {
+                fast = d.obs_dtype == TJ_OBS_U8 && g.C == 4 && (g.H * g.W) % 8 == 0 && ((uintptr_t)d_obs & 7) == 0;
+                if (fast)
+                    tjconv::to_nhwc_u8c4<<<grid1((size_t)n * (g.H * g.W / 8)), 256, 0, st>>>(
+                        (const uint8_t *)d_obs, act[0], (size_t)n, g.H * g.W, 1.0f / 255.0f);
+            }
+            if (!fast) {
+                if (d.obs_dtype == TJ_OBS_U8)
+                    tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)d_obs, act[0], n, g.C, g.H,
+                                                                           g.W, 1.0f / 255.0f);
+                else
+                    tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)d_obs, act[0], n, g.C, g.H, g.W,
+                                                                         1.0f);
+            }
+            if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        }
+        for (int l = 0; l < L; ++l) {
+            NLayer &y = lay[l];
+            TjGemmArgs<T> gm;
+            memset(&gm, 0, sizeof(gm));
+            gm.n_seg = 1;
+            gm.ldp = y.ldK; gm.ldq = y.ldK;
+            gm.K = y.ldK; gm.k_chunk = gm.K; gm.n_split = 1;
+            if (y.kind == TJ_LAYER_CONV2D) {
+                const tjconv::ConvGeom &g = y.g;
+                const size_t rows = (size_t)n * y.OHW;
+                if (y.implicit) {
+                    gm.seg[0] = {0, y.O, act[l], nullptr, 0};
+                    gm.gather = y.gth;
+                } else {
+                    const int run = g.k * g.C;
+                    const bool vec = sizeof(T) == 2 && run % 8 == 0 && (g.s * g.C) % 8 == 0 &&
+                                     (g.W * g.C) % 8 == 0 && y.ldK % 8 == 0;
+                    if (vec)
+                        tjconv::im2col<T, 8><<<grid1(rows * g.k * (run / 8)), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
+                    else
+                        tjconv::im2col<T, 1><<<grid1(rows * g.k * run), 256, 0, st>>>(act[l], y.patches, g, rows, y.ldK);
+                    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                    gm.seg[0] = {0, y.O, y.patches, nullptr, 0};
+                }
+                gm.Q = y.Wc_on;
+                gm.I = (int)rows;
+                gm.bias_j = theta_on + y.b_off;
+                gm.relu = 1;
+                gm.Cj = act[l + 1]; gm.ldcj = y.O; gm.cj_jmax = y.O;
+            } else {
+                gm.seg[0] = {0, n, y.Wc_on, theta_on + y.b_off, 0};
+                gm.Q = act[l];
+                gm.I = y.O;
+                if (l + 1 < L) {
+                    gm.relu = 1;
+                    gm.Ci = act[l + 1]; gm.ldci = lay[l + 1].ldK;
+                } else {
+                    gm.Cf = Qout; gm.ldcf = ldA;
+                }
+            }
+            if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+        }
+        egreedy<<<(n + 255) / 256, 256, 0, st>>>(Qout, ldA, (uint32_t)n, A, egreedy_threshold(epsilon), seed,
+                                                 (int32_t)t, d_action, d_version, d_q);
+        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+    }
+
     int get_state(int which, float *h_out, size_t n, hipStream_t st) override
     {
         const float *src = nullptr;
@@ -1492,6 +1633,13 @@ int tj_learner_step(tj_learner *l, const tj_minibatch *mb, tj_step_stats *d_stat
 {
     if (!l || !mb) return TJ_ERR_INVALID_ARG;
     return l->step(mb, d_stats, (hipStream_t)hip_stream);
+}
+
+int tj_actor_act(tj_learner *l, uint32_t n, const void *d_obs, float epsilon, uint64_t seed, int32_t *d_action,
+                 int32_t *d_version, float *d_q, void *hip_stream)
+{
+    if (!l) return TJ_ERR_INVALID_ARG;
+    return l->infer(n, d_obs, epsilon, seed, d_action, d_version, d_q, (hipStream_t)hip_stream);
 }
 
 int tj_learner_get_state(tj_learner *l, int which, float *h_out, size_t n, void *hip_stream)

@@ -300,3 +300,62 @@ def test_c4_nature_dqn_shape_small_batch(tj, orc):
     g, o = _pair(tj, orc, wl, seed=13)
     worst, _ = _step_both(tj, orc, g, o, wl, _batch(wl, 340), TOL["bf16"])
     print("c4 network, batch 16, worst relative errors:", worst)
+
+
+# ---------------------------------------------------------------- policy inference (Algorithm 1, step 1)
+
+def _check_act(tj, orc, g, o, wl, obs, eps, seed, tol):
+    import torch
+
+    dev = torch.from_numpy(np.ascontiguousarray(obs)).cuda()
+    ga, gv, gq = g.act(dev, eps, seed, want_q=True)
+    torch.cuda.synchronize()
+    ga, gv, gq = ga.cpu().numpy(), gv.cpu().numpy(), gq.cpu().numpy()
+    oa, oq, ogreedy = o.act(obs, eps, seed)
+    assert (gv == g.t).all()
+    assert rel_max(gq, oq) < tol
+    # explore decisions and uniform actions are integer functions of the generator: identical;
+    # greedy actions may differ only where the oracle's own top-2 gap is inside the float noise
+    margin = (1e-5 if wl.precision == "fp32" else 2e-3) * np.abs(oq).max()
+    mism = ga != oa
+    assert (top2_gap(oq)[mism] < margin).all() and mism.mean() <= 0.01
+    thr = int(eps * 2 ** 24)
+    explore = np.array([(orc.rng64(seed, 2 * j) >> 40) < thr for j in range(len(oa))])
+    np.testing.assert_array_equal(ga[explore], oa[explore])
+    assert not (mism & explore).any()
+    return explore.mean()
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_epsilon_greedy_inference_mlp(tj, orc, precision):
+    wl = replace(synth.small_variant(synth.WORKLOADS["c2"], capacity=4096, batch=300), precision=precision)
+    g, o = _pair(tj, orc, wl, seed=15)
+    obs = _batch(wl, 400, 517)["obs"]                       # more rows than the batch (n <= 2 * max_batch)
+    for eps, seed in ((0.0, 1), (0.05, 2), (1.0, 3)):
+        rate = _check_act(tj, orc, g, o, wl, obs, eps, seed, TOL[precision])
+        assert abs(rate - eps) < 0.05
+    # after a learner step the stamp is the new version and the actions follow the new weights
+    _step_both(tj, orc, g, o, wl, _batch(wl, 401), TOL[precision])
+    _check_act(tj, orc, g, o, wl, obs[:64], 0.1, 4, TOL[precision])
+    import torch
+
+    assert g.t == 1
+    dev = torch.from_numpy(obs).cuda()
+    L = tj.lib()
+    a = torch.empty(len(obs), dtype=torch.int32, device="cuda")
+    assert L.tj_actor_act(g.h, 2 * wl.batch + 1, dev.data_ptr(), 0.1, 0, a.data_ptr(), a.data_ptr(), None,
+                          None) == tj.TJ_ERR_SHAPE
+    assert L.tj_actor_act(g.h, 8, dev.data_ptr(), 1.5, 0, a.data_ptr(), a.data_ptr(), None,
+                          None) == tj.TJ_ERR_INVALID_ARG
+
+
+def test_epsilon_greedy_inference_conv(tj, orc):
+    """Pixel network (the gathered-operand layers and a linear tail), u8 frames."""
+    from paper_2502_20190_amd.synth import CONV
+
+    wl = _conv_workload("bf16", batch=12, in_chw=(4, 36, 36),
+                        layers=((CONV, 32, 8, 4), (CONV, 64, 4, 2), (LIN, 24, 0, 0), (LIN, 6, 0, 0)), n_actions=6)
+    g, o = _pair(tj, orc, wl, seed=16)
+    obs = _batch(wl, 410, 19)["obs"]
+    for eps, seed in ((0.0, 5), (0.3, 6)):
+        _check_act(tj, orc, g, o, wl, obs, eps, seed, TOL["bf16"])
