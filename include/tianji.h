@@ -245,14 +245,48 @@ int tj_learner_set_step(tj_learner *lrn, uint64_t t);
 
 /* ---------------------------------------------------------------- timing */
 
+/* ---------------------------------------------------------------- balance */
+
+/* Production / consumption balance (Section 3.3, Eq. 2-3; Appendix D.1).  From
+ * the measured consumption throughput TR_L of the learner and production
+ * throughput TR_A of the actors (transitions per second), the batch B of this
+ * deployment and the serial reference (batch B_s, buffer N_s, staleness ratio
+ * P = B_s / N_s, Eq. 2), computes the staleness gate for tj_sample that keeps
+ * the consumed share of the eligible pool at P:  each policy version tags
+ * R = B * TR_A / TR_L transitions, v = max_staleness + 1 versions are
+ * eligible, and N_c / N_s' = B / (v R) = P gives v = (N_s / B_s) * TR_L / TR_A,
+ * rounded to the nearest whole number, at least 1, and cut to what `capacity`
+ * ring slots can hold.  Host arithmetic; all pointers are host pointers.
+ * Returns TJ_ERR_INVALID_ARG for non-positive rates or sizes or N_s < B_s. */
+typedef struct {
+    double tr_learner, tr_actor;          /* TR_L, TR_A: transitions per second  */
+    uint64_t batch;                       /* B                                    */
+    uint64_t serial_batch, serial_buffer; /* B_s, N_s                             */
+    uint64_t capacity;                    /* ring slots                           */
+} tj_balance_in;
+
+typedef struct {
+    int64_t max_staleness;           /* the gate: v - 1                               */
+    double rows_per_version;         /* R                                              */
+    double window;                   /* N_s' = v R, transitions eligible when steady   */
+    double ratio, target_ratio;      /* B / N_s' achieved, and P                       */
+    double throughput;               /* min(TR_L, TR_A), the objective of Eq. 3        */
+    int32_t bottleneck;              /* 0 balanced within 5 %, 1 production, 2 consumption */
+    int32_t window_exceeds_capacity; /* 1 if v was cut to fit the ring                 */
+} tj_balance_out;
+
+int tj_balance_plan(const tj_balance_in *in, tj_balance_out *out);
+
 /* Optional phase timing for benchmarks.  `hip_events` is a host array of
  * hipEvent_t (created by the caller with timing enabled, passed as void*), or
  * NULL / n == 0 to switch timing off.  While set, every tj_sample records
  *   [0] start, [1] after mask + scan + select, [2] after the row gather
  * (n must be 3), and every tj_learner_step records
- *   [0] after the input cast, [1] after the forward GEMMs, [2] after the TD /
- *   Huber kernel, [3] after the backward GEMMs, [4] after the Adam kernel (the
- *   transposed weight copies for the next step follow it) (n must be 5),
+ *   [0] after the input cast, [1] after the forward GEMMs (before the fused
+ *   head-layer + TD kernel where that is used, else after the head GEMM),
+ *   [2] after the TD / Huber kernel, [3] after the backward GEMMs and the
+ *   slice reduction, [4] after the Adam kernel (the transposed weight copies
+ *   for the next step follow it) (n must be 5),
  * on the call's stream.  The caller reads them after synchronising. */
 int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n);
 int tj_learner_set_phase_events(tj_learner *lrn, void *const *hip_events, uint32_t n);

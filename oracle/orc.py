@@ -118,6 +118,17 @@ def sample_excluding(version, count, capacity, ex_begin, ex_len, cur, max_st, se
     return st, idx, K.value
 
 
+def balance_plan(tr_learner, tr_actor, batch, serial_batch, serial_buffer, capacity):
+    """(status, dict) of the production / consumption balance (Eq. 2-3)."""
+    out = np.zeros(7, np.float64)
+    f = lib().orc_balance_plan
+    f.restype = _i32
+    f.argtypes = [C.c_double, C.c_double, _u64, _u64, _u64, _u64, _vp]
+    st = f(tr_learner, tr_actor, batch, serial_batch, serial_buffer, capacity, _p(out))
+    keys = ("max_staleness", "rows_per_version", "window", "ratio", "target_ratio", "throughput", "cut")
+    return st, dict(zip(keys, out))
+
+
 class Buffer:
     def __init__(self, capacity: int, obs_elems: int, obs_dtype: str):
         self.capacity, self.obs_elems = capacity, obs_elems

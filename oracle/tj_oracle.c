@@ -669,3 +669,34 @@ int orc_num_threads(void)
     return 1;
 #endif
 }
+
+/* ------------------------------------------------------------------ */
+/* Production / consumption balance (Section 3.3, Eq. 2-3; Appendix D.1) */
+/* ------------------------------------------------------------------ */
+
+/* Serial staleness ratio P = B_s / N_s (Eq. 2).  The learner makes TR_L / B policy versions per
+ * second while TR_A transitions per second arrive, so R = TR_A / (TR_L / B) transitions carry one
+ * version tag; with v versions inside the gate the eligible pool is v R and one batch is the
+ * share B / (v R) of it.  Setting that share to P: v = B / (P R).  v is rounded to the nearest
+ * whole number, is at least 1, and v R may not exceed the ring.  out: {max_staleness, R, pool,
+ * share, P, min(TR_L, TR_A), cut flag}. */
+int orc_balance_plan(double tr_learner, double tr_actor, uint64_t batch, uint64_t serial_batch,
+                     uint64_t serial_buffer, uint64_t capacity, double *out)
+{
+    if (!(tr_learner > 0) || !(tr_actor > 0) || !batch || !serial_batch || serial_buffer < serial_batch || !capacity)
+        return -1;
+    double P = (double)serial_batch / (double)serial_buffer;
+    double versions_per_s = tr_learner / (double)batch;
+    double R = tr_actor / versions_per_s;
+    double v = floor((double)batch / (P * R) + 0.5);
+    if (v < 1) v = 1;
+    double cut = 0;
+    if (v * R > (double)capacity) {
+        cut = 1;
+        v = floor((double)capacity / R);
+        if (v < 1) v = 1;
+    }
+    out[0] = v - 1; out[1] = R; out[2] = v * R; out[3] = (double)batch / (v * R); out[4] = P;
+    out[5] = tr_learner < tr_actor ? tr_learner : tr_actor; out[6] = cut;
+    return 0;
+}

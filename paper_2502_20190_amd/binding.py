@@ -26,7 +26,7 @@ TJ_MAX_LAYERS = 8
  TJ_STATE_ASTAR) = range(7)
 
 EXPORTS = [
-    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_actor_act",
+    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_actor_act", "tj_balance_plan",
     "tj_buffer_status", "tj_buffer_field_ptr", "tj_learner_num_params", "tj_learner_arena_bytes",
     "tj_learner_create", "tj_learner_destroy", "tj_learner_step", "tj_learner_get_state",
     "tj_learner_set_state", "tj_learner_get_step", "tj_learner_set_step", "tj_strerror",
@@ -47,6 +47,28 @@ class tj_buffer_info(C.Structure):
     _fields_ = [("capacity", C.c_uint64), ("head", C.c_uint64), ("count", C.c_uint64),
                 ("last_n_eligible", C.c_uint64), ("sticky_error", C.c_int32),
                 ("last_excluded_begin", C.c_uint64), ("last_excluded_len", C.c_uint64)]
+
+
+class tj_balance_in(C.Structure):
+    _fields_ = [("tr_learner", C.c_double), ("tr_actor", C.c_double), ("batch", C.c_uint64),
+                ("serial_batch", C.c_uint64), ("serial_buffer", C.c_uint64), ("capacity", C.c_uint64)]
+
+
+class tj_balance_out(C.Structure):
+    _fields_ = [("max_staleness", C.c_int64), ("rows_per_version", C.c_double), ("window", C.c_double),
+                ("ratio", C.c_double), ("target_ratio", C.c_double), ("throughput", C.c_double),
+                ("bottleneck", C.c_int32), ("window_exceeds_capacity", C.c_int32)]
+
+
+def balance_plan(tr_learner, tr_actor, batch, serial_batch, serial_buffer, capacity):
+    """(status, tj_balance_out): the staleness gate that keeps the consumed share of the pool at
+    the serial ratio (host arithmetic in the library)."""
+    i = tj_balance_in(tr_learner, tr_actor, batch, serial_batch, serial_buffer, capacity)
+    o = tj_balance_out()
+    f = lib().tj_balance_plan
+    f.restype = C.c_int
+    f.argtypes = [C.c_void_p, C.c_void_p]
+    return f(C.byref(i), C.byref(o)), o
 
 
 class tj_layer(C.Structure):

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtianji_hip.so")
-SOURCES = ["tj_buffer.hip", "tj_gemm.hip", "tj_conv_wgrad.hip", "tj_conv_first.hip", "tj_learner.hip"]
+SOURCES = ["tj_buffer.hip", "tj_gemm.hip", "tj_conv_wgrad.hip", "tj_conv_first.hip", "tj_balance.hip", "tj_learner.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
