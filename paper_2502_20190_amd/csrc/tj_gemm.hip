@@ -759,10 +759,8 @@ template <int N> struct IntC { static constexpr int value = N; };
 #endif
 
 template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu((NFJ <= 2 && BKB * NSTAGE <= 192) ? 4 : 2,
-                                                                      (NFJ <= 2 && BKB * NSTAGE <= 192) ? 4 : 2)))
-void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
-                                                         const TileMap tm)
+__device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const int tiles_seg0, const TileMap &tm,
+                                          const int block_id)
 {
     typedef tj_bf16 T;
     constexpr int BJ3 = 64 * NFJ;
@@ -802,7 +800,7 @@ void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
 
     int ti, tj, z;
     {
-        const int id = blockIdx.x;
+        const int id = block_id;
         if (a.n_split > 1) {
             z = id % a.n_split;
             const int t = id / a.n_split;
@@ -1025,17 +1023,54 @@ void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
     }
 }
 
-template <int NFJ, int BKB, int NSTAGE, bool GATHER = false>
-int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
+#define TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE)                                                             \
+    __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2, \
+                                                              ((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2)))
+
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false>
+__global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
+                                                              const TileMap tm)
+{
+    dlds_body<NFJ, BKB, NSTAGE, QSUM, GATHER>(a, tiles_seg0, tm, (int)blockIdx.x);
+}
+
+// Two independent GEMMs in one launch (e.g. the weight gradient and the input gradient of a layer,
+// which both start from the same dZ): blocks [0, nblk0) work on the first, the rest on the second,
+// so the two share one ramp-up and one tail instead of running back to back.
+struct GemmPair {
+    TjGemmArgs<tj_bf16> a[2];
+    int tiles_seg0[2];
+    TileMap tm[2];
+    int nblk0;
+};
+
+template <int NFJ, int BKB, int NSTAGE>
+__global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPair p)
+{
+    // one call site: the body's LDS buffers must exist once
+    const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
+    dlds_body<NFJ, BKB, NSTAGE, true>(p.a[which], p.tiles_seg0[which], p.tm[which],
+                                      (int)blockIdx.x - which * p.nblk0);
+}
+
+// Tile map and grid size of one problem for the 256 x 64*NFJ tiles.
+template <int NFJ> unsigned plan_dlds(const TjGemmArgs<tj_bf16> &a, TileMap &tm, int tiles[2])
 {
     constexpr int BJ3 = 64 * NFJ;
-    TileMap tm;
     tm.tiles_i = (a.I + 255) / 256;
-    int tiles[2] = {0, 0};
+    tiles[0] = tiles[1] = 0;
     for (int s = 0; s < a.n_seg; ++s) tiles[s] = (a.seg[s].j_end - a.seg[s].j_begin + BJ3 - 1) / BJ3;
     tm.tiles_j = tiles[0] + tiles[1];
     tm.spread_i = 0;
-    const unsigned nblk = a.n_split > 1 ? (unsigned)tm.tiles_i * tm.tiles_j * a.n_split : xcd_grid(tm);
+    return a.n_split > 1 ? (unsigned)tm.tiles_i * tm.tiles_j * a.n_split : xcd_grid(tm);
+}
+
+template <int NFJ, int BKB, int NSTAGE, bool GATHER = false>
+int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
+{
+    TileMap tm;
+    int tiles[2];
+    const unsigned nblk = plan_dlds<NFJ>(a, tm, tiles);
     if constexpr (GATHER)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else if (a.qsum)
@@ -1097,24 +1132,51 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 
-}  // namespace
 
-template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
+// Shapes the kernels' loads and grids assume.
+template <typename T> int check_args(const TjGemmArgs<T> &a, int tiles[2])
 {
     constexpr int VE = TjElem<T>::kVec;
     constexpr int KE = kRowBytes / (int)sizeof(T);
-    // shapes the kernel's loads and its grid assume
     if (a.n_seg < 1 || a.n_seg > 2 || a.I <= 0 || a.K <= 0 || a.n_split < 1) return TJ_ERR_SHAPE;
     if (a.gather.on && sizeof(T) != 2) return TJ_ERR_SHAPE;
     if ((!a.gather.on && (a.ldp % VE || a.K > a.ldp)) || a.ldq % VE || a.K % VE || a.K > a.ldq) return TJ_ERR_SHAPE;
     if (a.n_split > 1 && (a.k_chunk % KE || (size_t)a.k_chunk * a.n_split < (size_t)a.K)) return TJ_ERR_SHAPE;
     if (a.n_split == 1 && a.k_chunk < a.K) return TJ_ERR_SHAPE;
     if ((a.Ci && a.ldci % VE) || (a.mask && a.ldmask % 4)) return TJ_ERR_SHAPE;
-    int tiles[2] = {0, 0};
+    tiles[0] = tiles[1] = 0;
     for (int s = 0; s < a.n_seg; ++s) {
         if (a.seg[s].j_end <= a.seg[s].j_begin || !a.seg[s].P) return TJ_ERR_SHAPE;
         tiles[s] = (a.seg[s].j_end - a.seg[s].j_begin + BJ - 1) / BJ;
     }
+    return TJ_OK;
+}
+
+}  // namespace
+
+int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, hipStream_t st)
+{
+    int tiles[2], rc;
+    if ((rc = check_args(a0, tiles)) != TJ_OK || (rc = check_args(a1, tiles)) != TJ_OK) return rc;
+    if (a0.gather.on || a1.gather.on || !uses_dlds(a0) || !uses_dlds(a1)) {   // no common kernel: one after the other
+        if ((rc = tj_gemm<tj_bf16>(a0, st)) != TJ_OK) return rc;
+        return tj_gemm<tj_bf16>(a1, st);
+    }
+    GemmPair p;
+    p.a[0] = a0; p.a[1] = a1;
+    const unsigned n0 = plan_dlds<2>(a0, p.tm[0], tiles);
+    p.tiles_seg0[0] = tiles[0];
+    const unsigned n1 = plan_dlds<2>(a1, p.tm[1], tiles);
+    p.tiles_seg0[1] = tiles[0];
+    p.nblk0 = (int)n0;
+    gemm_bf16_dlds_pair<2, 64, 3><<<n0 + n1, 512, 0, st>>>(p);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
+{
+    int tiles[2], rc;
+    if ((rc = check_args(a, tiles)) != TJ_OK) return rc;
     if constexpr (sizeof(T) == 2) return launch_bf16(a, tiles, st);
     dim3 grid((a.I + BI - 1) / BI, tiles[0] + tiles[1], a.n_split);
     gemm_pq<T><<<grid, 256, 0, st>>>(a, tiles[0]);

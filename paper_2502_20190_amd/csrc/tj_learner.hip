@@ -772,11 +772,13 @@ template <typename T> struct MlpLearner : tj_learner {
         }
         if ((rc = mark(2, st)) != TJ_OK) return rc;
 
-        // backward through Q_online(s)
+        // backward through Q_online(s).  The weight gradient and the input gradient of a layer both
+        // start from dZ_l and are independent: one paired launch where the kernels allow it.
         for (int l = L; l >= 1; --l) {
             const LayerPlan &lp = lay[l - 1];
+            TjGemmArgs<T> gw, gd;
             {   // dW_l[n][k] = sum_m dZ_l[m][n] X_{l-1}[m][k]; db_l[n] = sum_m dZ_l[m][n]
-                TjGemmArgs<T> g;
+                TjGemmArgs<T> &g = gw;
                 memset(&g, 0, sizeof(g));
                 g.n_seg = 1;
                 g.seg[0] = {0, lp.out, XT[l - 1], nullptr, 0};
@@ -788,10 +790,9 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.k_chunk = round_up((Kb + S - 1) / S, ke);
                 g.Cf = gpart + lp.w_off; g.ldcf = lp.in; g.cf_zstride = Ppad;
                 g.qsum = gpart + lp.b_off; g.qsum_zstride = Ppad;
-                if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
             }
             if (l >= 2) {   // dX_{l-1}[m][k] = relu'(X_{l-1}) * sum_n dZ_l[m][n] W_l[n][k]
-                TjGemmArgs<T> g;
+                TjGemmArgs<T> &g = gd;
                 memset(&g, 0, sizeof(g));
                 g.n_seg = 1;
                 g.seg[0] = {0, B, WcT_on[l - 1], nullptr, 0};
@@ -802,8 +803,15 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.mask = X[l - 1]; g.ldmask = lp.ld_in;
                 g.Ci = dZ[l - 1]; g.ldci = lp.ld_in;
                 g.Cj = dZT[l - 1]; g.ldcj = ldB; g.cj_jmax = B;
-                if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
             }
+            if constexpr (sizeof(T) == 2) {
+                if (l >= 2) {
+                    if ((rc = tj_gemm_pair(gw, gd, st)) != TJ_OK) return rc;
+                    continue;
+                }
+            }
+            if ((rc = tj_gemm<T>(gw, st)) != TJ_OK) return rc;
+            if (l >= 2 && (rc = tj_gemm<T>(gd, st)) != TJ_OK) return rc;
         }
 
         if (S > 1) {   // the split slices of every weight gradient are summed, in slice order, into slice 0
