@@ -56,9 +56,12 @@ template <> __device__ __forceinline__ float vec_sum<tj_bf16>(const u32x4 &v)
     return s;
 }
 
-template <typename T>
+// NF = 32-wide fragments per wave and dimension: block tile 64*NF square (four waves, 2 x 2).  NF = 1 gives
+// small problems four times as many blocks to spread over the CUs.
+template <typename T, int NF>
 __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int tiles_seg0)
 {
+    constexpr int BI = 64 * NF, BJ = 64 * NF;
     constexpr int VE = TjElem<T>::kVec;
     constexpr int KE = kRowBytes / (int)sizeof(T);
     __shared__ __align__(16) uint8_t sP[BI * kLdsRow];
@@ -77,13 +80,13 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
     const int k_begin = z * a.k_chunk;
     const int k_end = min(a.K, k_begin + a.k_chunk);
 
-    // global -> register staging: 4 vectors of P and 4 of Q per thread
+    // global -> register staging: 2*NF vectors of P and of Q per thread
     const int cv = tid & 7;
-    const T *gP[4];
-    const T *gQ[4];
-    bool okP[4], okQ[4];
+    const T *gP[2 * NF];
+    const T *gQ[2 * NF];
+    bool okP[2 * NF], okQ[2 * NF];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < 2 * NF; ++r) {
         const int row = (tid >> 3) + 32 * r;
         const int i = i0 + row, j = j0 + row;
         okP[r] = i < a.I;
@@ -91,35 +94,37 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
         gP[r] = seg.P + (size_t)(okP[r] ? i : 0) * a.ldp + cv * VE;
         gQ[r] = a.Q + (size_t)(okQ[r] ? j - seg.q_shift : 0) * a.ldq + cv * VE;
     }
-    u32x4 rP[4], rQ[4];
+    u32x4 rP[2 * NF], rQ[2 * NF];
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     auto gload = [&](int k0) {
         const bool kin = k0 + cv * VE < k_end;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 2 * NF; ++r) {
             rP[r] = (okP[r] && kin) ? *(const u32x4 *)(gP[r] + k0) : zero4;
             rQ[r] = (okQ[r] && kin) ? *(const u32x4 *)(gQ[r] + k0) : zero4;
         }
     };
     auto lstore = [&]() {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 2 * NF; ++r) {
             const int row = (tid >> 3) + 32 * r;
             *(u32x4 *)(sP + row * kLdsRow + cv * 16) = rP[r];
             *(u32x4 *)(sQ + row * kLdsRow + cv * 16) = rQ[r];
         }
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[NF][NF];
 #pragma unroll
-    for (int fi = 0; fi < 2; ++fi)
+    for (int fi = 0; fi < NF; ++fi)
 #pragma unroll
-        for (int fj = 0; fj < 2; ++fj)
+        for (int fj = 0; fj < NF; ++fj)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[fi][fj][r] = 0.f;
 
     const bool do_qsum = a.qsum != nullptr && blockIdx.x == 0 && wi == 0;
-    float qs[2] = {0.f, 0.f};
+    float qs[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) qs[f] = 0.f;
 
     gload(k_begin);
     lstore();
@@ -129,19 +134,19 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
         if (more) gload(k0 + KE);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            u32x4 pf[2], qf[2];
+            u32x4 pf[NF], qf[NF];
 #pragma unroll
-            for (int f = 0; f < 2; ++f) {
-                pf[f] = *(const u32x4 *)(sP + (wi * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
-                qf[f] = *(const u32x4 *)(sQ + (wj * 64 + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
+            for (int f = 0; f < NF; ++f) {
+                pf[f] = *(const u32x4 *)(sP + (wi * 32 * NF + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
+                qf[f] = *(const u32x4 *)(sQ + (wj * 32 * NF + f * 32 + l32) * kLdsRow + ks * 32 + lg * 16);
             }
 #pragma unroll
-            for (int fi = 0; fi < 2; ++fi)
+            for (int fi = 0; fi < NF; ++fi)
 #pragma unroll
-                for (int fj = 0; fj < 2; ++fj) mma<T>(acc[fi][fj], pf[fi], qf[fj]);
+                for (int fj = 0; fj < NF; ++fj) mma<T>(acc[fi][fj], pf[fi], qf[fj]);
             if (do_qsum) {
-                qs[0] += vec_sum<T>(qf[0]);
-                qs[1] += vec_sum<T>(qf[1]);
+#pragma unroll
+                for (int f = 0; f < NF; ++f) qs[f] += vec_sum<T>(qf[f]);
             }
         }
         __syncthreads();
@@ -153,22 +158,22 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
 
     if (do_qsum) {
 #pragma unroll
-        for (int fj = 0; fj < 2; ++fj) {
+        for (int fj = 0; fj < NF; ++fj) {
             float s = qs[fj] + __shfl_xor(qs[fj], 32, 64);
-            const int j = j0 + wj * 64 + fj * 32 + l32;
+            const int j = j0 + wj * 32 * NF + fj * 32 + l32;
             if (lg == 0 && j < j_end) a.qsum[(size_t)z * a.qsum_zstride + j] = s;
         }
     }
 
 #pragma unroll
-    for (int fi = 0; fi < 2; ++fi) {
+    for (int fi = 0; fi < NF; ++fi) {
 #pragma unroll
-        for (int fj = 0; fj < 2; ++fj) {
-            const int j = j0 + wj * 64 + fj * 32 + l32;
+        for (int fj = 0; fj < NF; ++fj) {
+            const int j = j0 + wj * 32 * NF + fj * 32 + l32;
             if (j >= j_end) continue;
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                const int ib = i0 + wi * 64 + fi * 32 + rq * 8 + lg * 4;
+                const int ib = i0 + wi * 32 * NF + fi * 32 + rq * 8 + lg * 4;
                 if (ib >= a.I) continue;
                 const int nvalid = min(4, a.I - ib);
                 float v[4];
@@ -1179,7 +1184,14 @@ template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
     if ((rc = check_args(a, tiles)) != TJ_OK) return rc;
     if constexpr (sizeof(T) == 2) return launch_bf16(a, tiles, st);
     dim3 grid((a.I + BI - 1) / BI, tiles[0] + tiles[1], a.n_split);
-    gemm_pq<T><<<grid, 256, 0, st>>>(a, tiles[0]);
+    if ((long)grid.x * grid.y * grid.z < 128) {   // too few 128 x 128 tiles to fill the chip: 64 x 64 tiles
+        int t64[2] = {0, 0};
+        for (int s = 0; s < a.n_seg; ++s) t64[s] = (a.seg[s].j_end - a.seg[s].j_begin + 63) / 64;
+        dim3 g64((a.I + 63) / 64, t64[0] + t64[1], a.n_split);
+        gemm_pq<T, 1><<<g64, 256, 0, st>>>(a, t64[0]);
+    } else {
+        gemm_pq<T, 2><<<grid, 256, 0, st>>>(a, tiles[0]);
+    }
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 

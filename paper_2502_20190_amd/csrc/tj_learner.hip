@@ -667,7 +667,8 @@ template <typename T> struct MlpLearner : tj_learner {
         ldA = round_up(A, 4);
         // split the batch contraction of the weight-gradient GEMMs so that each
         // slice still runs a long k loop
-        S = Bmax / 1024;
+        // (fp32 nets here are small: more slices give the few output tiles enough blocks)
+        S = Bmax / (sizeof(T) == 4 ? 64 : 1024);
         S = S < 1 ? 1 : (S > 8 ? 8 : S);
         theta_on = (float *)a.take(P * 4);
         theta_tg = (float *)a.take(P * 4);
