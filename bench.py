@@ -20,6 +20,11 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM traffic of the GEMM launches of one c3 step, from two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, WRITE_SIZE; see profiles/c3_gemm_counters.md), scaled by what the same counters read
+# for the streaming kernels of known size in the same runs (reduce_slices, adam_update: FETCH_SIZE
+# reads half the bytes, WRITE_SIZE all of them).  Valid for the GEMM source it was taken with.
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 886.3e6, "gemm_source_sha256_16": "7beb0e67975fe575"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
@@ -40,6 +45,22 @@ def gemm_flops_per_step(wl, synth, head_in_td_phase):
     fwd = sum(per_sample[:-1] if head_in_td_phase else per_sample)
     bwd = sum(per_sample) + sum(per_sample[1:])
     return wl.batch * (3 * fwd + bwd)
+
+
+def gemm_traffic(cfg, n_launch):
+    """Counter-measured HBM bytes per GEMM launch, or None when there is no measurement for this
+    workload or the GEMM source has changed since it was taken."""
+    import hashlib
+
+    rec = GEMM_TRAFFIC.get(cfg)
+    if rec is None:
+        return None
+    src = os.path.join(ROOT, "paper_2502_20190_amd", "csrc", "tj_gemm.hip")
+    try:
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return rec["bytes_per_step"] / n_launch if sha == rec["gemm_source_sha256_16"] else None
 
 
 def fill_ring(tj, synth, wl, chunk_rows):
@@ -177,7 +198,11 @@ def main():
     # forward: one grouped launch per linear layer, two (online, target) per convolution;
     # backward: a weight-gradient GEMM per layer and an input-gradient GEMM per layer but the first
     fused_head = wl.precision == "bf16" and wl.layers[-1][1] <= 32
-    n_gemm_launch = (n_layers + n_conv - (1 if fused_head else 0)) + n_layers + (n_layers - 1)
+    if wl.precision == "bf16" and n_conv == 0:
+        # forward: hidden layers; backward: weight and input gradient of a layer share one launch
+        n_gemm_launch = (n_layers - (1 if fused_head else 0)) + n_layers
+    else:
+        n_gemm_launch = (n_layers + n_conv - (1 if fused_head else 0)) + n_layers + (n_layers - 1)
     flops = gemm_flops_per_step(wl, synth, fused_head)
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
     achieved = flops / (gemm_ms * 1e-3) / 1e12
@@ -194,7 +219,7 @@ def main():
                    "batch": wl.batch, "max_staleness": wl.max_staleness, "n_eligible": int(info.last_n_eligible),
                    "layers": [l[1] for l in wl.layers], "params": P},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak, "traffic": gemm_traffic(wl.name.split("-")[0], n_gemm_launch),
                      "kernel": "gemm_pq", "launches_per_step": n_gemm_launch,
                      "flops_per_launch": flops / n_gemm_launch, "avg_launch_ms": gemm_ms / n_gemm_launch},
         "phases_ms": ph, "phase_events_on_steps": len(sampled),

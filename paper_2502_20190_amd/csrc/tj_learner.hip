@@ -1035,6 +1035,12 @@ template <typename T> struct ConvLearner : tj_learner {
             const size_t Ms = (size_t)Bmax * y.OHW;
             size_t ns = Ms / 4096;
             y.n_split = (int)(ns < 1 ? 1 : (ns > 128 ? 128 : ns));
+            if (y.kind == TJ_LAYER_LINEAR) {   // enough slices to fill the chip with 256 x 128 tiles
+                const size_t tiles = (((size_t)y.K + 255) / 256) * (((size_t)y.O + 127) / 128);
+                ns = tiles >= 256 ? 1 : 256 / tiles;
+                if (ns > (size_t)Bmax / 256) ns = (size_t)Bmax / 256;
+                y.n_split = (int)(ns < 1 ? 1 : (ns > 8 ? 8 : ns));
+            }
             if (y.implicit) {   // about 512 blocks, each with at least four 32-row stages
                 const size_t njb = ((size_t)y.K + 255) / 256, stages = (Ms + 31) / 32;
                 ns = 512 / njb;
