@@ -182,6 +182,72 @@ class Buffer:
         return out
 
 
+class FrameBuffer:
+    """One u8 frame per slot; observation stacks of `stack` frames are rebuilt when sampling."""
+
+    def __init__(self, capacity: int, frame_elems: int, stack: int):
+        L = lib()
+        L.orc_frame_buffer_create.restype = _vp
+        L.orc_frame_buffer_create.argtypes = [_u64, _u32, _u32]
+        L.orc_frame_buffer_destroy.argtypes = [_vp]
+        L.orc_frame_buffer_insert.restype = _i32
+        L.orc_frame_buffer_insert.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _vp]
+        L.orc_frame_buffer_sample.restype = _i32
+        L.orc_frame_buffer_sample.argtypes = [_vp, _u32, _i64, _i64, _u64, _vp, _vp]
+        L.orc_frame_buffer_gather.argtypes = [_vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp]
+        for f in ("count", "head"):
+            getattr(L, "orc_frame_buffer_" + f).restype = _u64
+            getattr(L, "orc_frame_buffer_" + f).argtypes = [_vp]
+        for f in ("ages", "versions"):
+            getattr(L, "orc_frame_buffer_" + f).restype = _vp
+            getattr(L, "orc_frame_buffer_" + f).argtypes = [_vp]
+        self.capacity, self.frame_elems, self.stack = capacity, frame_elems, stack
+        self.h = L.orc_frame_buffer_create(capacity, frame_elems, stack)
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().orc_frame_buffer_destroy(self.h)
+            self.h = None
+
+    def insert(self, frame, action, reward, done, version) -> int:
+        frame = _c(frame, np.uint8)
+        action, reward = _c(action, np.int32), _c(reward, np.float32)
+        done, version = _c(done, np.uint8), _c(version, np.int32)
+        return lib().orc_frame_buffer_insert(self.h, len(action), _p(frame), _p(action), _p(reward), _p(done),
+                                             _p(version))
+
+    @property
+    def count(self) -> int:
+        return lib().orc_frame_buffer_count(self.h)
+
+    @property
+    def head(self) -> int:
+        return lib().orc_frame_buffer_head(self.h)
+
+    def ages(self) -> np.ndarray:
+        ptr = lib().orc_frame_buffer_ages(self.h)
+        return np.ctypeslib.as_array(C.cast(ptr, C.POINTER(C.c_uint8)), shape=(self.capacity,)).copy()
+
+    def versions(self) -> np.ndarray:
+        ptr = lib().orc_frame_buffer_versions(self.h)
+        return np.ctypeslib.as_array(C.cast(ptr, C.POINTER(C.c_int32)), shape=(self.capacity,)).copy()
+
+    def sample(self, batch, cur, max_st, seed):
+        idx = np.empty(batch, dtype=np.uint32)
+        K = C.c_uint64(0)
+        st = lib().orc_frame_buffer_sample(self.h, batch, cur, max_st, seed, _p(idx), C.byref(K))
+        return st, idx, K.value
+
+    def gather(self, idx):
+        idx = _c(idx, np.uint32)
+        b, row = len(idx), self.stack * self.frame_elems
+        out = {"obs": np.empty((b, row), np.uint8), "next_obs": np.empty((b, row), np.uint8),
+               "action": np.empty(b, np.int32), "reward": np.empty(b, np.float32), "done": np.empty(b, np.uint8)}
+        lib().orc_frame_buffer_gather(self.h, _p(idx), b, _p(out["obs"]), _p(out["next_obs"]), _p(out["action"]),
+                                      _p(out["reward"]), _p(out["done"]))
+        return out
+
+
 class Learner:
     """layers: rows (kind, out, kernel, stride); in_chw: (C, H, W) of one observation."""
 

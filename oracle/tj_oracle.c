@@ -188,6 +188,127 @@ void orc_buffer_gather(const orc_buffer *b, const uint32_t *idx, uint32_t batch,
 }
 
 /* ------------------------------------------------------------------ */
+/* Frame ring: one frame per slot, observation stacks rebuilt at sampling  */
+/* ------------------------------------------------------------------ */
+
+/* Pixel observations are stacks of the last k frames, so consecutive transitions share k-1 frames
+ * of s and s' (Section 4.1 uses Atari with the usual stacked-frame network input).  This ring
+ * stores each frame once.  Rows are inserted in time order of one environment stream; row t holds
+ * frame f_t, action a_t, reward r_t, done_t and the version tag.  Transition t is
+ *   s = (f_{t-b(0)}, ..., f_{t-b(k-1)}),  b(p) = min(k-1-p, age_t),
+ *   s' = the stack of row t+1 built the same way with age_{t+1},
+ * where age_t = steps since the start of row t's episode, capped at k-1 (a row starts an episode
+ * if it is the first ever or follows a row with done = 1): early in an episode the first frame is
+ * repeated.  A slot is usable iff it is valid, is not the newest row (its successor is missing),
+ * and, once the ring has wrapped, its look-back does not reach past the oldest slot. */
+typedef struct {
+    uint64_t capacity, head, count;
+    uint32_t frame_elems, stack;
+    uint8_t *frame, *done, *age;
+    int32_t *action, *version;
+    float *reward;
+    int has_prev;
+    uint8_t prev_done, prev_age;
+} orc_frame_buffer;
+
+orc_frame_buffer *orc_frame_buffer_create(uint64_t capacity, uint32_t frame_elems, uint32_t stack)
+{
+    orc_frame_buffer *b = (orc_frame_buffer *)calloc(1, sizeof(orc_frame_buffer));
+    b->capacity = capacity; b->frame_elems = frame_elems; b->stack = stack;
+    b->frame = (uint8_t *)calloc(capacity, frame_elems);
+    b->done = (uint8_t *)calloc(capacity, 1);
+    b->age = (uint8_t *)calloc(capacity, 1);
+    b->action = (int32_t *)calloc(capacity, 4);
+    b->version = (int32_t *)calloc(capacity, 4);
+    b->reward = (float *)calloc(capacity, 4);
+    return b;
+}
+
+void orc_frame_buffer_destroy(orc_frame_buffer *b)
+{
+    if (!b) return;
+    free(b->frame); free(b->done); free(b->age); free(b->action); free(b->version); free(b->reward);
+    free(b);
+}
+
+int orc_frame_buffer_insert(orc_frame_buffer *b, uint32_t n, const uint8_t *frames, const int32_t *action,
+                            const float *reward, const uint8_t *done, const int32_t *version)
+{
+    if ((uint64_t)n > b->capacity) return -5;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint64_t s = b->head;
+        uint8_t age = 0;
+        if (b->has_prev && !b->prev_done) age = (uint32_t)b->prev_age + 1 < b->stack ? (uint8_t)(b->prev_age + 1) : (uint8_t)(b->stack - 1);
+        memcpy(b->frame + s * b->frame_elems, frames + (size_t)i * b->frame_elems, b->frame_elems);
+        b->action[s] = action[i]; b->reward[s] = reward[i]; b->done[s] = done[i]; b->version[s] = version[i];
+        b->age[s] = age;
+        b->has_prev = 1; b->prev_done = done[i]; b->prev_age = age;
+        b->head = (b->head + 1) % b->capacity;
+        if (b->count < b->capacity) b->count += 1;
+    }
+    return 0;
+}
+
+uint64_t orc_frame_buffer_count(const orc_frame_buffer *b) { return b->count; }
+uint64_t orc_frame_buffer_head(const orc_frame_buffer *b) { return b->head; }
+const uint8_t *orc_frame_buffer_ages(const orc_frame_buffer *b) { return b->age; }
+const int32_t *orc_frame_buffer_versions(const orc_frame_buffer *b) { return b->version; }
+
+static int frame_slot_usable(const orc_frame_buffer *b, uint64_t i)
+{
+    if (i >= b->count) return 0;
+    uint64_t newest = (b->head + b->capacity - 1) % b->capacity;
+    if (i == newest) return 0;
+    if (b->count == b->capacity) {
+        uint64_t from_oldest = (i + b->capacity - b->head) % b->capacity;   /* the oldest slot is at head */
+        if (from_oldest < b->age[i]) return 0;
+    }
+    return 1;
+}
+
+int orc_frame_buffer_sample(const orc_frame_buffer *b, uint32_t batch, int64_t cur, int64_t max_st,
+                            uint64_t seed, uint32_t *idx, uint64_t *K_out)
+{
+    uint64_t *E = (uint64_t *)malloc((b->count ? b->count : 1) * sizeof(uint64_t));
+    uint64_t K = 0;
+    for (uint64_t i = 0; i < b->count; ++i) {
+        int64_t staleness = cur - (int64_t)b->version[i];
+        if (frame_slot_usable(b, i) && staleness >= 0 && staleness <= max_st) E[K++] = i;
+    }
+    if (K_out) *K_out = K;
+    if (K == 0) {
+        for (uint32_t j = 0; j < batch; ++j) idx[j] = 0xFFFFFFFFu;
+        free(E);
+        return -4;
+    }
+    for (uint32_t j = 0; j < batch; ++j) idx[j] = (uint32_t)E[orc_mulhi64(orc_rng64(seed, j), K)];
+    free(E);
+    return 0;
+}
+
+static void frame_stack_of(const orc_frame_buffer *b, uint64_t t, uint8_t *out)
+{
+    for (uint32_t p = 0; p < b->stack; ++p) {
+        uint32_t back = b->stack - 1 - p;
+        if (back > b->age[t]) back = b->age[t];
+        uint64_t src = (t + b->capacity - back) % b->capacity;
+        memcpy(out + (size_t)p * b->frame_elems, b->frame + src * b->frame_elems, b->frame_elems);
+    }
+}
+
+void orc_frame_buffer_gather(const orc_frame_buffer *b, const uint32_t *idx, uint32_t batch, uint8_t *obs,
+                             uint8_t *next_obs, int32_t *action, float *reward, uint8_t *done)
+{
+    size_t row = (size_t)b->stack * b->frame_elems;
+    for (uint32_t j = 0; j < batch; ++j) {
+        uint64_t t = idx[j];
+        frame_stack_of(b, t, obs + (size_t)j * row);
+        frame_stack_of(b, (t + 1) % b->capacity, next_obs + (size_t)j * row);
+        action[j] = b->action[t]; reward[j] = b->reward[t]; done[j] = b->done[t];
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Q-network: a chain of conv2d / linear layers, ReLU after all but last */
 /* ------------------------------------------------------------------ */
 
