@@ -80,6 +80,21 @@ def fill_ring(tj, synth, wl, chunk_rows):
     return buf, torch.cat(versions).numpy()
 
 
+def fill_frame_ring(tj, synth, wl, chunk_rows):
+    import torch
+
+    buf = tj.FrameBuffer(wl.capacity, wl.obs_shape[1] * wl.obs_shape[2], wl.obs_shape[0])
+    c = 0
+    for start in range(0, wl.capacity, chunk_rows):
+        n = min(chunk_rows, wl.capacity - start)
+        rows = synth.make_frame_stream_device(wl, synth.MASTER_SEED, c, n, start)
+        st = buf.insert(rows["frame"], rows["action"], rows["reward"], rows["done"], rows["version"])
+        assert st == tj.TJ_OK
+        c += 1
+    torch.cuda.synchronize()
+    return buf, None
+
+
 def cpu_baseline(wl, synth, buf, versions, theta, target, budget_rows):
     """The CPU oracle on a bounded sample: sampling over the full tag array with
     the full batch, then one learner step on `budget_rows` rows (copied from the
@@ -121,6 +136,9 @@ def main():
     ap.add_argument("--insert-rows", type=int, default=0,
                     help="also push this many new transitions per step into the ring on a second stream "
                          "(tj_buffer_insert_concurrent) while the learner loops")
+    ap.add_argument("--frame-ring", action="store_true",
+                    help="pixel workloads: keep the replay ring as one frame per slot (tj_frame_buffer) and "
+                         "rebuild the observation stacks in the gather")
     ap.add_argument("--actor-rows", type=int, default=0,
                     help="after the learner loop, also time epsilon-greedy policy inference (tj_actor_act) "
                          "on this many observations per call (at most twice the batch)")
@@ -140,7 +158,14 @@ def main():
 
     wl = synth.WORKLOADS[args.config]
     torch.cuda.set_device(0)
-    buf, versions = fill_ring(tj, synth, wl, 65_536 if wl.obs_dtype == "f32" else 16_384)
+    if args.frame_ring:
+        if wl.obs_dtype != "u8" or args.insert_rows:
+            print("bench.py: --frame-ring needs a pixel workload and no --insert-rows", file=sys.stderr)
+            sys.exit(2)
+        args.no_cpu_baseline = True          # the baseline leg samples from the two-stack ring
+        buf, versions = fill_frame_ring(tj, synth, wl, 65_536)
+    else:
+        buf, versions = fill_ring(tj, synth, wl, 65_536 if wl.obs_dtype == "f32" else 16_384)
     theta = synth.xavier_init(wl.layers, wl.in_chw, 1)
     target = synth.xavier_init(wl.layers, wl.in_chw, 2)
     lrn = tj.learner_for_workload(wl, theta, target)
@@ -163,6 +188,7 @@ def main():
         one_step(i)
     torch.cuda.synchronize()
 
+    set_buf_events = L.tj_frame_buffer_set_phase_events if args.frame_ring else L.tj_buffer_set_phase_events
     K = args.steps
     every = max(1, args.event_every)
     sampled = list(range(0, K, every))
@@ -172,15 +198,15 @@ def main():
     t0 = time.perf_counter()
     for i in range(K):
         if i % every == 0:
-            L.tj_buffer_set_phase_events(buf.h, bev[i // every].ev, 3)
+            set_buf_events(buf.h, bev[i // every].ev, 3)
             L.tj_learner_set_phase_events(lrn.h, lev[i // every].ev, 5)
         elif i % every == 1:
-            L.tj_buffer_set_phase_events(buf.h, None, 0)
+            set_buf_events(buf.h, None, 0)
             L.tj_learner_set_phase_events(lrn.h, None, 0)
         one_step(args.warmup + i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    L.tj_buffer_set_phase_events(buf.h, None, 0)
+    set_buf_events(buf.h, None, 0)
     L.tj_learner_set_phase_events(lrn.h, None, 0)
     st, info = buf.status()
     loss, t = lrn.read_stats()
@@ -210,12 +236,15 @@ def main():
     P = synth.num_params(wl.layers, wl.in_chw)
     adam_bytes = (30 if wl.precision == "bf16" else 28) * P
     gather_bytes = 2 * wl.batch * wl.record_bytes
+    if args.frame_ring:   # k + 1 distinct frames read, 2k planes written, plus the scalars
+        k, fe = wl.obs_shape[0], wl.obs_shape[1] * wl.obs_shape[2]
+        gather_bytes = wl.batch * ((k + 1) * fe + 2 * k * fe + 2 * 9)
     out = {
         "metric": "learner transitions consumed/sec at 1 MI355X",
         "value": wl.batch * K / wall, "unit": "transitions/s", "n_gpus": 1, "steps": K,
         "warmup": args.warmup, "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.precision, "data": "synthetic",
-        "config": {"workload": wl.name, "ring_slots": wl.capacity, "obs_elems": wl.obs_elems,
+        "config": {"workload": wl.name + ("+frame-ring" if args.frame_ring else ""), "ring_slots": wl.capacity, "obs_elems": wl.obs_elems,
                    "batch": wl.batch, "max_staleness": wl.max_staleness, "n_eligible": int(info.last_n_eligible),
                    "layers": [l[1] for l in wl.layers], "params": P},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",

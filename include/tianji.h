@@ -147,6 +147,45 @@ int tj_buffer_status(tj_buffer *buf, tj_buffer_info *h_out, void *hip_stream);
  * 3 reward, 4 done, 5 version.  NULL on a bad argument. */
 void *tj_buffer_field_ptr(tj_buffer *buf, int field);
 
+/* ---------------------------------------------------------------- frame ring */
+
+/* Replay ring for pixel observations that stores every frame once (Section 4.1
+ * evaluates on Atari, whose network input is a stack of the last k frames, so
+ * consecutive transitions share k-1 frames of s and s').  Rows are inserted in
+ * time order of ONE environment stream: row t holds the u8 frame f_t, a_t, r_t,
+ * done_t and the version tag.  Transition t, rebuilt at sampling time, is
+ *   s  = (f_{t-b(0)}, ..., f_{t-b(k-1)}),  b(p) = min(k-1-p, age_t),
+ *   s' = the stack of row t+1 built in the same way,
+ * with age_t = rows since the start of row t's episode, capped at k-1 (a row
+ * starts an episode if it is the first ever or follows done = 1), i.e. early in
+ * an episode the first frame is repeated.  A slot is eligible iff it passes the
+ * staleness gate of tj_sample, is not the newest row, and, once the ring has
+ * wrapped, its look-back does not reach past the oldest slot.  Everything else
+ * (arena ownership, streams, error reporting, the draw of the indices, the
+ * minibatch layout with obs rows of k * frame_elems bytes) is as for tj_buffer. */
+typedef struct tj_frame_buffer tj_frame_buffer;
+
+typedef struct {
+    uint64_t capacity;    /* ring slots, 2 * stack <= capacity < 2^32 - 1        */
+    uint32_t frame_elems; /* bytes of one u8 frame                               */
+    uint32_t stack;       /* k, 1 <= k <= 16                                     */
+} tj_frame_buffer_desc;
+
+size_t tj_frame_buffer_arena_bytes(const tj_frame_buffer_desc *desc);
+int tj_frame_buffer_create(const tj_frame_buffer_desc *desc, void *dev_arena, size_t arena_bytes,
+                           void *hip_stream, tj_frame_buffer **out);
+int tj_frame_buffer_destroy(tj_frame_buffer *buf);
+/* d_frame: device, u8 [n][frame_elems]; the others device [n].  n > capacity
+ * returns TJ_ERR_CAPACITY and writes nothing. */
+int tj_frame_buffer_insert(tj_frame_buffer *buf, uint32_t n, const uint8_t *d_frame, const int32_t *d_action,
+                           const float *d_reward, const uint8_t *d_done, const int32_t *d_version,
+                           void *hip_stream);
+int tj_frame_sample(tj_frame_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+                    uint64_t seed, const tj_minibatch *out, void *hip_stream);
+int tj_frame_buffer_status(tj_frame_buffer *buf, tj_buffer_info *h_out, void *hip_stream);
+/* Device pointers for tests: 0 frames, 1 ages (u8), 2 action, 3 reward, 4 done, 5 version. */
+void *tj_frame_buffer_field_ptr(tj_frame_buffer *buf, int field);
+
 /* ---------------------------------------------------------------- learner */
 
 typedef struct {
@@ -279,7 +318,8 @@ int tj_balance_plan(const tj_balance_in *in, tj_balance_out *out);
 
 /* Optional phase timing for benchmarks.  `hip_events` is a host array of
  * hipEvent_t (created by the caller with timing enabled, passed as void*), or
- * NULL / n == 0 to switch timing off.  While set, every tj_sample records
+ * NULL / n == 0 to switch timing off.  While set, every tj_sample (and
+ * tj_frame_sample of a frame ring) records
  *   [0] start, [1] after mask + scan + select, [2] after the row gather
  * (n must be 3), and every tj_learner_step records
  *   [0] after the input cast, [1] after the forward GEMMs (before the fused
@@ -289,6 +329,7 @@ int tj_balance_plan(const tj_balance_in *in, tj_balance_out *out);
  *   for the next step follow it) (n must be 5),
  * on the call's stream.  The caller reads them after synchronising. */
 int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n);
+int tj_frame_buffer_set_phase_events(tj_frame_buffer *buf, void *const *hip_events, uint32_t n);
 int tj_learner_set_phase_events(tj_learner *lrn, void *const *hip_events, uint32_t n);
 
 const char *tj_strerror(int status);

@@ -26,7 +26,9 @@ TJ_MAX_LAYERS = 8
  TJ_STATE_ASTAR) = range(7)
 
 EXPORTS = [
-    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_actor_act", "tj_balance_plan",
+    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_actor_act", "tj_balance_plan", "tj_frame_buffer_arena_bytes", "tj_frame_buffer_create",
+    "tj_frame_buffer_destroy", "tj_frame_buffer_insert", "tj_frame_sample", "tj_frame_buffer_status",
+    "tj_frame_buffer_field_ptr", "tj_frame_buffer_set_phase_events",
     "tj_buffer_status", "tj_buffer_field_ptr", "tj_learner_num_params", "tj_learner_arena_bytes",
     "tj_learner_create", "tj_learner_destroy", "tj_learner_step", "tj_learner_get_state",
     "tj_learner_set_state", "tj_learner_get_step", "tj_learner_set_step", "tj_strerror",
@@ -138,6 +140,8 @@ def lib():
         L.tj_learner_set_step.argtypes = [vp, u64]
         L.tj_buffer_set_phase_events.restype = i32
         L.tj_buffer_set_phase_events.argtypes = [vp, C.POINTER(vp), u32]
+        L.tj_frame_buffer_set_phase_events.restype = i32
+        L.tj_frame_buffer_set_phase_events.argtypes = [vp, C.POINTER(vp), u32]
         L.tj_learner_set_phase_events.restype = i32
         L.tj_learner_set_phase_events.argtypes = [vp, C.POINTER(vp), u32]
         L.tj_strerror.restype = C.c_char_p
@@ -206,6 +210,83 @@ class Minibatch:
         out = {k: getattr(self, k).cpu().numpy() for k in ("obs", "next_obs", "action", "reward", "done")}
         out["idx"] = self.idx.cpu().numpy().view(np.uint32)
         return out
+
+
+class tj_frame_buffer_desc(C.Structure):
+    _fields_ = [("capacity", C.c_uint64), ("frame_elems", C.c_uint32), ("stack", C.c_uint32)]
+
+
+class FrameBuffer:
+    """tj_frame_buffer_* (one u8 frame per slot) over a torch-allocated arena."""
+
+    def __init__(self, capacity: int, frame_elems: int, stack: int, device="cuda:0", stream=None):
+        import torch
+
+        _require_gpu()
+        L = lib()
+        vp, u32, u64, i64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int64, C.c_int
+        L.tj_frame_buffer_arena_bytes.restype = C.c_size_t
+        L.tj_frame_buffer_arena_bytes.argtypes = [vp]
+        L.tj_frame_buffer_create.restype = i32
+        L.tj_frame_buffer_create.argtypes = [vp, vp, C.c_size_t, vp, vp]
+        L.tj_frame_buffer_destroy.argtypes = [vp]
+        L.tj_frame_buffer_insert.restype = i32
+        L.tj_frame_buffer_insert.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp]
+        L.tj_frame_sample.restype = i32
+        L.tj_frame_sample.argtypes = [vp, u32, i64, i64, u64, vp, vp]
+        L.tj_frame_buffer_status.restype = i32
+        L.tj_frame_buffer_status.argtypes = [vp, vp, vp]
+        L.tj_frame_buffer_field_ptr.restype = vp
+        L.tj_frame_buffer_field_ptr.argtypes = [vp, i32]
+        self.capacity, self.frame_elems, self.stack, self.device = capacity, frame_elems, stack, device
+        self.obs_elems, self.obs_dtype = frame_elems * stack, "u8"
+        self.desc = tj_frame_buffer_desc(capacity, frame_elems, stack)
+        nbytes = L.tj_frame_buffer_arena_bytes(C.byref(self.desc))
+        if nbytes == 0:
+            raise TjError(TJ_ERR_INVALID_ARG, "tj_frame_buffer_arena_bytes")
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        self.arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
+        self.arena_bytes = nbytes
+        h = C.c_void_p()
+        _check(L.tj_frame_buffer_create(C.byref(self.desc), self.arena_ptr, nbytes, _stream_ptr(stream), C.byref(h)),
+               "tj_frame_buffer_create")
+        self.h = h
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().tj_frame_buffer_destroy(self.h)
+            self.h = None
+
+    def insert(self, frame, action, reward, done, version, stream=None) -> int:
+        """Device tensors; returns the status (TJ_ERR_CAPACITY for too many rows)."""
+        self._keep = (frame, action, reward, done, version)
+        return lib().tj_frame_buffer_insert(self.h, int(action.shape[0]), frame.data_ptr(), action.data_ptr(),
+                                            reward.data_ptr(), done.data_ptr(), version.data_ptr(),
+                                            _stream_ptr(stream))
+
+    def insert_host(self, frame, action, reward, done, version) -> int:
+        import torch
+
+        dev = [torch.from_numpy(np.ascontiguousarray(v)).to(self.device) for v in (frame, action, reward, done, version)]
+        st = self.insert(*dev)
+        torch.cuda.current_stream().synchronize()
+        return st
+
+    def sample(self, mb: Minibatch, current_version: int, max_staleness: int, seed: int, stream=None) -> int:
+        return lib().tj_frame_sample(self.h, mb.batch, current_version, max_staleness, seed & (2**64 - 1),
+                                     C.byref(mb.c), _stream_ptr(stream))
+
+    def status(self, stream=None):
+        info = tj_buffer_info()
+        st = lib().tj_frame_buffer_status(self.h, C.byref(info), _stream_ptr(stream))
+        return st, info
+
+    def ages(self) -> np.ndarray:
+        import torch
+
+        ptr = lib().tj_frame_buffer_field_ptr(self.h, 1)
+        off = ptr - self.arena.data_ptr()
+        return self.arena[off:off + self.capacity].cpu().numpy()
 
 
 class Buffer:

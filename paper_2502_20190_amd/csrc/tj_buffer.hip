@@ -301,21 +301,21 @@ __global__ void zero_words(uint32_t *p, uint32_t n)
 template <typename V>
 int launch_copy_rows(const void *s0, void *d0, const void *s1, void *d1, uint32_t row_bytes,
                      uint32_t rows, const uint32_t *idx, int mode, uint64_t head, uint64_t cap,
-                     hipStream_t st)
+                     hipStream_t st, uint32_t nz)
 {
     const uint32_t vpr = row_bytes / sizeof(V);
     if (vpr >= 256) {
         // U vectors per thread: one block covers up to 256*U vectors of a row
         if (vpr <= 256 * 2) {
-            dim3 g2(rows, (vpr + 511) / 512, 2);
+            dim3 g2(rows, (vpr + 511) / 512, nz);
             copy_rows_wide<V, 2><<<g2, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
                                                      idx, mode, head, cap);
         } else if (vpr <= 256 * 4) {
-            dim3 g4(rows, (vpr + 1023) / 1024, 2);
+            dim3 g4(rows, (vpr + 1023) / 1024, nz);
             copy_rows_wide<V, 4><<<g4, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
                                                      idx, mode, head, cap);
         } else {
-            dim3 g8(rows, (vpr + 2047) / 2048, 2);
+            dim3 g8(rows, (vpr + 2047) / 2048, nz);
             copy_rows_wide<V, 8><<<g8, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
                                                      idx, mode, head, cap);
         }
@@ -323,23 +323,24 @@ int launch_copy_rows(const void *s0, void *d0, const void *s1, void *d1, uint32_
         constexpr int U = 2;
         // rows * vpr must fit 32 bits: callers split larger jobs
         uint64_t total = (uint64_t)rows * vpr;
-        dim3 grid((uint32_t)((total + 256 * U - 1) / (256 * U)), 1, 2);
+        dim3 grid((uint32_t)((total + 256 * U - 1) / (256 * U)), 1, nz);
         copy_rows_narrow<V, U><<<grid, 256, 0, st>>>((const V *)s0, (V *)d0, (const V *)s1, (V *)d1, vpr,
                                                      rows, idx, mode, head, cap);
     }
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 
+// nz = 2: both tensor pairs (s0 -> d0, s1 -> d1); nz = 1: only the first
 int copy_rows(const void *s0, void *d0, const void *s1, void *d1, uint32_t row_bytes, uint32_t rows,
-              const uint32_t *idx, int mode, uint64_t head, uint64_t cap, hipStream_t st)
+              const uint32_t *idx, int mode, uint64_t head, uint64_t cap, hipStream_t st, uint32_t nz = 2)
 {
     if (rows == 0) return TJ_OK;
     auto aligned = [&](size_t a) {
         return row_bytes % a == 0 && ((uintptr_t)s0 | (uintptr_t)d0 | (uintptr_t)s1 | (uintptr_t)d1) % a == 0;
     };
-    if (aligned(16)) return launch_copy_rows<uint4>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st);
-    if (aligned(4)) return launch_copy_rows<uint32_t>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st);
-    return launch_copy_rows<uint8_t>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st);
+    if (aligned(16)) return launch_copy_rows<uint4>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st, nz);
+    if (aligned(4)) return launch_copy_rows<uint32_t>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st, nz);
+    return launch_copy_rows<uint8_t>(s0, d0, s1, d1, row_bytes, rows, idx, mode, head, cap, st, nz);
 }
 
 size_t layout(const tj_buffer_desc *d, TjArena &a, RingPtrs *ring, unsigned long long **mask,
@@ -373,6 +374,165 @@ bool desc_ok(const tj_buffer_desc *d)
            (d->obs_dtype == TJ_OBS_F32 || d->obs_dtype == TJ_OBS_U8);
 }
 
+
+// ---------------------------------------------------------------- frame ring
+//
+// One u8 frame per slot; an observation is the stack of the last k frames of its episode (early in
+// an episode the first frame is repeated), rebuilt when a minibatch is gathered.  age[t] = rows
+// since the start of row t's episode, capped at k-1.
+
+// Ages of the n rows being inserted (row i goes to slot head + i).  A row starts an episode if it is
+// the first row ever or follows a row with done = 1; the look-back of at most k-1 rows reads the
+// incoming done flags and, before the chunk, the ring's (written by earlier inserts).
+__global__ __launch_bounds__(256) void frame_ages(uint8_t *__restrict__ age, const uint8_t *__restrict__ ring_done,
+                                                  const uint8_t *__restrict__ done_in, uint32_t n, uint64_t head,
+                                                  uint64_t cap, uint64_t rows_before, uint32_t k)
+{
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    uint32_t a = k - 1;
+    for (uint32_t d = 0; d + 1 < k; ++d) {
+        const int64_t r = (int64_t)i - d;                       // row of this chunk, may be negative
+        const uint64_t g = rows_before + i - d;                  // the same row counted from the first ever
+        bool start;
+        if (g == 0) {
+            start = true;
+        } else if (r >= 1) {
+            start = done_in[r - 1] != 0;
+        } else {
+            const uint64_t back = (uint64_t)(1 - r);             // slots before head
+            start = ring_done[(head + cap - back % cap) % cap] != 0;
+        }
+        if (start) { a = d; break; }
+        if (g == 0) break;
+    }
+    uint64_t s = head + i;
+    if (s >= cap) s -= cap;
+    age[s] = (uint8_t)a;
+}
+
+// As stale_mask_count, plus the frame ring's usability rule: not the newest row (no successor),
+// and once the ring has wrapped the look-back must not reach past the oldest slot (at head).
+__global__ __launch_bounds__(256) void frame_mask_count(const int32_t *__restrict__ version,
+                                                        const uint8_t *__restrict__ age, uint32_t count,
+                                                        uint32_t head, uint32_t cap, int64_t cur, int64_t max_st,
+                                                        unsigned long long *__restrict__ mask,
+                                                        uint32_t *__restrict__ tile_count)
+{
+    __shared__ uint32_t wave_cnt[4];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t base = blockIdx.x * kTile + wave * 256;
+    const uint32_t newest = head == 0 ? cap - 1 : head - 1;
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t s = base + r * 64 + lane;
+        bool e = s < count && s != newest;
+        if (e) {
+            const int64_t st = cur - (int64_t)version[s];
+            e = st >= 0 && st <= max_st;
+            if (e && count == cap) {
+                const uint32_t from_oldest = s >= head ? s - head : s + (cap - head);
+                e = from_oldest >= age[s];
+            }
+        }
+        const unsigned long long b = __ballot(e);
+        if (lane == 0) mask[(base >> 6) + r] = b;
+        cnt += __popcll(b);
+    }
+    if (lane == 0) wave_cnt[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) tile_count[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+}
+
+// Minibatch row r, plane q of 2k: q < k is position q of the stack of slot idx[r], q >= k position
+// q - k of the stack of its successor.  Position p of the stack of slot t is the frame in slot
+// t - min(k-1-p, age[t]).  U vectors of V per thread, streaming accesses.
+template <typename V, int U>
+__global__ __launch_bounds__(256) void gather_stacks(const V *__restrict__ frame, const uint8_t *__restrict__ age,
+                                                     const uint32_t *__restrict__ idx, V *__restrict__ obs,
+                                                     V *__restrict__ next_obs, uint32_t vpf, uint32_t k,
+                                                     uint32_t cap)
+{
+    const uint32_t r = blockIdx.x, q = blockIdx.z;
+    uint32_t t = idx[r];
+    if (t == kInvalid) return;
+    const uint32_t p = q < k ? q : q - k;
+    if (q >= k) t = t + 1 == cap ? 0 : t + 1;
+    uint32_t back = k - 1 - p;
+    const uint32_t a = age[t];
+    if (back > a) back = a;
+    const uint32_t src = t >= back ? t - back : t + cap - back;
+    const V *sp = frame + (size_t)src * vpf;
+    V *dp = (q < k ? obs : next_obs) + ((size_t)r * k + p) * vpf;
+    const uint32_t c0 = blockIdx.y * (256 * U) + threadIdx.x;
+    V tmp[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t c = c0 + u * 256;
+        if (c < vpf) tmp[u] = sp[c];        // up to 8 planes of neighbouring rows read the same frame: cached
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t c = c0 + u * 256;
+        if (c < vpf) st_stream(dp + c, tmp[u]);
+    }
+}
+
+template <typename V>
+int launch_gather_stacks(const void *frame, const uint8_t *age, const uint32_t *idx, void *obs, void *next_obs,
+                         uint32_t frame_bytes, uint32_t k, uint32_t cap, uint32_t batch, hipStream_t st)
+{
+    const uint32_t vpf = frame_bytes / sizeof(V);
+    constexpr int U = 2;
+    dim3 grid(batch, (vpf + 256 * U - 1) / (256 * U), 2 * k);
+    gather_stacks<V, U><<<grid, 256, 0, st>>>((const V *)frame, age, idx, (V *)obs, (V *)next_obs, vpf, k, cap);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+bool frame_desc_ok(const tj_frame_buffer_desc *d)
+{
+    return d && d->stack >= 1 && d->stack <= 16 && d->frame_elems >= 1 && d->capacity >= 2ull * d->stack &&
+           d->capacity < 0xFFFFFFFFull;
+}
+
+struct FrameLayout {
+    uint8_t *frame, *age;
+    RingPtrs ring;
+    unsigned long long *mask;
+    uint32_t *tile_count, *tile_off, *state;
+};
+
+size_t frame_layout(const tj_frame_buffer_desc *d, TjArena &a, FrameLayout *out)
+{
+    const uint64_t n = d->capacity, n_tiles = (n + kTile - 1) / kTile;
+    FrameLayout l;
+    l.frame = (uint8_t *)a.take(n * d->frame_elems);
+    l.age = (uint8_t *)a.take(n);
+    l.ring.obs = l.ring.next_obs = nullptr;
+    l.ring.action = (int32_t *)a.take(n * 4);
+    l.ring.reward = (float *)a.take(n * 4);
+    l.ring.done = (uint8_t *)a.take(n);
+    l.ring.version = (int32_t *)a.take(n * 4);
+    l.mask = (unsigned long long *)a.take(n_tiles * kWordsPerTile * 8);
+    l.tile_count = (uint32_t *)a.take(n_tiles * 4);
+    l.tile_off = (uint32_t *)a.take(n_tiles * 4);
+    l.state = (uint32_t *)a.take(32);
+    if (out) *out = l;
+    return a.off;
+}
+
+}  // namespace
+
+struct tj_frame_buffer {
+    tj_frame_buffer_desc desc;
+    FrameLayout l;
+    uint64_t head = 0, count = 0, rows_total = 0;
+    hipEvent_t ev[3];
+    bool timed = false;
+};
+
+namespace {
 }  // namespace
 
 struct tj_buffer {
@@ -580,6 +740,158 @@ void *tj_buffer_field_ptr(tj_buffer *buf, int field)
     case 3: return buf->ring.reward;
     case 4: return buf->ring.done;
     case 5: return buf->ring.version;
+    default: return nullptr;
+    }
+}
+
+size_t tj_frame_buffer_arena_bytes(const tj_frame_buffer_desc *desc)
+{
+    if (!frame_desc_ok(desc)) return 0;
+    TjArena a(nullptr);
+    return frame_layout(desc, a, nullptr);
+}
+
+int tj_frame_buffer_create(const tj_frame_buffer_desc *desc, void *dev_arena, size_t arena_bytes, void *hip_stream,
+                           tj_frame_buffer **out)
+{
+    if (!out) return TJ_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!frame_desc_ok(desc) || !dev_arena || ((uintptr_t)dev_arena & 255)) return TJ_ERR_INVALID_ARG;
+    if (arena_bytes < tj_frame_buffer_arena_bytes(desc)) return TJ_ERR_ARENA_TOO_SMALL;
+    tj_frame_buffer *b = new tj_frame_buffer();
+    b->desc = *desc;
+    TjArena a(dev_arena);
+    frame_layout(desc, a, &b->l);
+    zero_words<<<1, 64, 0, (hipStream_t)hip_stream>>>(b->l.state, 8);
+    if (hipGetLastError() != hipSuccess) {
+        delete b;
+        return TJ_ERR_DEVICE;
+    }
+    *out = b;
+    return TJ_OK;
+}
+
+int tj_frame_buffer_destroy(tj_frame_buffer *buf)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    delete buf;
+    return TJ_OK;
+}
+
+int tj_frame_buffer_insert(tj_frame_buffer *buf, uint32_t n, const uint8_t *d_frame, const int32_t *d_action,
+                           const float *d_reward, const uint8_t *d_done, const int32_t *d_version, void *hip_stream)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    if (n == 0) return TJ_OK;
+    if (!d_frame || !d_action || !d_reward || !d_done || !d_version) return TJ_ERR_INVALID_ARG;
+    const uint64_t cap = buf->desc.capacity;
+    if ((uint64_t)n > cap) return TJ_ERR_CAPACITY;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // ages first: they read the ring's done flags of earlier rows, which the scalar copy below may overwrite
+    frame_ages<<<(n + 255) / 256, 256, 0, st>>>(buf->l.age, buf->l.ring.done, d_done, n, buf->head, cap,
+                                                buf->rows_total, buf->desc.stack);
+    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+    const uint32_t max_rows = 1u << 20;
+    for (uint32_t done_rows = 0; done_rows < n; done_rows += max_rows) {
+        const uint32_t rows = n - done_rows < max_rows ? n - done_rows : max_rows;
+        const uint64_t head = (buf->head + done_rows) % cap;
+        const uint8_t *src = d_frame + (size_t)done_rows * buf->desc.frame_elems;
+        int rc = copy_rows(src, buf->l.frame, src, buf->l.frame, buf->desc.frame_elems, rows, nullptr, 1, head, cap,
+                           st, 1);
+        if (rc != TJ_OK) return rc;
+    }
+    insert_scalars<<<(n + 255) / 256, 256, 0, st>>>(buf->l.ring, n, d_action, d_reward, d_done, d_version, buf->head,
+                                                    cap);
+    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+    buf->rows_total += n;
+    buf->head = (buf->head + n) % cap;
+    buf->count = buf->count + n < cap ? buf->count + n : cap;
+    return TJ_OK;
+}
+
+int tj_frame_sample(tj_frame_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+                    uint64_t seed, const tj_minibatch *out, void *hip_stream)
+{
+    if (!buf || !out || batch == 0 || out->batch != batch) return TJ_ERR_INVALID_ARG;
+    if (!out->obs || !out->next_obs || !out->action || !out->reward || !out->done || !out->idx)
+        return TJ_ERR_INVALID_ARG;
+    if (batch > (1u << 20)) return TJ_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint32_t count = (uint32_t)buf->count, cap = (uint32_t)buf->desc.capacity;
+    uint32_t n_tiles = (count + kTile - 1) / kTile;
+    if (n_tiles == 0) n_tiles = 1;
+    if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[0], st));
+    frame_mask_count<<<n_tiles, 256, 0, st>>>(buf->l.ring.version, buf->l.age, count, (uint32_t)buf->head, cap,
+                                              current_version, max_staleness, buf->l.mask, buf->l.tile_count);
+    tile_scan<<<1, 1024, 0, st>>>(buf->l.tile_count, n_tiles, buf->l.tile_off, buf->l.state);
+    select_slots<<<(batch + 63) / 64, 64, 0, st>>>(buf->l.mask, buf->l.tile_off, n_tiles, buf->l.state, seed, batch,
+                                                   buf->l.ring, out->idx, out->action, out->reward, out->done);
+    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+    if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[1], st));
+    const uint32_t fb = buf->desc.frame_elems, k = buf->desc.stack;
+    auto aligned = [&](size_t a) {
+        return fb % a == 0 && ((uintptr_t)buf->l.frame | (uintptr_t)out->obs | (uintptr_t)out->next_obs) % a == 0;
+    };
+    int rc;
+    if (aligned(16))
+        rc = launch_gather_stacks<uint4>(buf->l.frame, buf->l.age, out->idx, out->obs, out->next_obs, fb, k, cap,
+                                         batch, st);
+    else if (aligned(4))
+        rc = launch_gather_stacks<uint32_t>(buf->l.frame, buf->l.age, out->idx, out->obs, out->next_obs, fb, k, cap,
+                                            batch, st);
+    else
+        rc = launch_gather_stacks<uint8_t>(buf->l.frame, buf->l.age, out->idx, out->obs, out->next_obs, fb, k, cap,
+                                           batch, st);
+    if (rc == TJ_OK && buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[2], st));
+    return rc;
+}
+
+int tj_frame_buffer_set_phase_events(tj_frame_buffer *buf, void *const *hip_events, uint32_t n)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    if (!hip_events || n == 0) {
+        buf->timed = false;
+        return TJ_OK;
+    }
+    if (n != 3) return TJ_ERR_INVALID_ARG;
+    for (int i = 0; i < 3; ++i) {
+        if (!hip_events[i]) return TJ_ERR_INVALID_ARG;
+        buf->ev[i] = (hipEvent_t)hip_events[i];
+    }
+    buf->timed = true;
+    return TJ_OK;
+}
+
+int tj_frame_buffer_status(tj_frame_buffer *buf, tj_buffer_info *h_out, void *hip_stream)
+{
+    if (!buf || !h_out) return TJ_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint32_t h[4] = {0, 0, 0, 0};
+    TJ_HIP_TRY(hipMemcpyAsync(h, buf->l.state, sizeof(h), hipMemcpyDeviceToHost, st));
+    TJ_HIP_TRY(hipStreamSynchronize(st));
+    h_out->capacity = buf->desc.capacity;
+    h_out->head = buf->head;
+    h_out->count = buf->count;
+    h_out->last_n_eligible = h[1];
+    h_out->sticky_error = (int32_t)h[0];
+    h_out->last_excluded_begin = h_out->last_excluded_len = 0;
+    if (h[0] != 0) {
+        zero_words<<<1, 64, 0, st>>>(buf->l.state, 1);
+        TJ_HIP_TRY(hipStreamSynchronize(st));
+    }
+    return (int32_t)h[0];
+}
+
+void *tj_frame_buffer_field_ptr(tj_frame_buffer *buf, int field)
+{
+    if (!buf) return nullptr;
+    switch (field) {
+    case 0: return buf->l.frame;
+    case 1: return buf->l.age;
+    case 2: return buf->l.ring.action;
+    case 3: return buf->l.ring.reward;
+    case 4: return buf->l.ring.done;
+    case 5: return buf->l.ring.version;
     default: return nullptr;
     }
 }

@@ -191,6 +191,25 @@ def make_chunk_device(wl: Workload, seed: int, chunk: int, n: int, device="cuda:
             "version": version}
 
 
+def make_frame_stream_device(wl: Workload, seed: int, chunk: int, n: int, t0: int, device="cuda:0"):
+    """Rows t0 .. t0+n of one environment stream for the frame ring (one u8 frame per row): frames
+    uniform, actions / rewards / done as make_chunk_device, and version tags that rise with time so
+    that a ring of wl.capacity rows spans the tags 0 .. wl.version_max."""
+    import torch
+
+    g = torch.Generator(device=device)
+    g.manual_seed((seed * 1_000_003 + 7_000_000 + chunk) & 0x7FFFFFFFFFFFFFFF)
+    fe = wl.obs_shape[1] * wl.obs_shape[2]
+    frame = torch.randint(0, 256, (n, fe), generator=g, device=device, dtype=torch.uint8)
+    action = torch.randint(0, wl.n_actions, (n,), generator=g, device=device, dtype=torch.int32)
+    reward = torch.rand((n,), generator=g, device=device, dtype=torch.float32) * 2.0 - 1.0
+    done = (torch.rand((n,), generator=g, device=device) < wl.done_p).to(torch.uint8)
+    per_version = max(1, wl.capacity // (wl.version_max + 1))
+    t = torch.arange(t0, t0 + n, device=device, dtype=torch.int64)
+    version = torch.clamp(t // per_version, max=wl.version_max).to(torch.int32)
+    return {"frame": frame, "action": action, "reward": reward, "done": done, "version": version}
+
+
 def small_variant(wl: Workload, capacity: int, batch: Optional[int] = None) -> Workload:
     """The same workload on a smaller ring (and batch), for cases the oracle
     finishes in seconds."""

@@ -332,3 +332,66 @@ def test_insert_stream_races_sampling_stream(tj, orc):
             np.testing.assert_array_equal(got[f], want[f], err_msg=f"{f} at iteration {it}")
     side.synchronize()
     assert arcs_seen > 0, "no sample ever overlapped an unfinished insert"
+
+
+# ---------------------------------------------------------------- frame ring (one frame per slot)
+
+def _frame_stream(rng, n, frame_elems, done_p, t0=0):
+    frames = rng.integers(0, 256, (n, frame_elems)).astype(np.uint8)
+    done = (rng.random(n) < done_p).astype(np.uint8)
+    return (frames, rng.integers(0, 18, n).astype(np.int32), rng.uniform(-1, 1, n).astype(np.float32), done,
+            ((t0 + np.arange(n)) // 50).astype(np.int32))
+
+
+@pytest.mark.parametrize("frame_elems,cap,total,k", [(7056, 3000, 2200, 4), (7056, 1500, 5300, 4), (100, 4096, 9000, 4),
+                                                      (37, 700, 2500, 3), (64, 64, 64, 2)])
+def test_frame_ring_against_the_oracle(tj, orc, frame_elems, cap, total, k):
+    """Inserts in ragged chunks (wrapping), ages, eligibility, indices and rebuilt stacks: bit-exact."""
+    rng = np.random.default_rng(frame_elems + cap)
+    g = tj.FrameBuffer(cap, frame_elems, k)
+    o = orc.FrameBuffer(cap, frame_elems, k)
+    pos = 0
+    while pos < total:
+        n = int(min(total - pos, rng.integers(1, min(900, cap) + 1)))
+        rows = _frame_stream(rng, n, frame_elems, 0.02, pos)
+        assert g.insert_host(*rows) == tj.TJ_OK and o.insert(*rows) == 0
+        pos += n
+    st, info = g.status()
+    assert (info.head, info.count) == (o.head, o.count)
+    np.testing.assert_array_equal(g.ages()[:o.count], o.ages()[:o.count])
+    cur = (total - 1) // 50
+    for seed, max_st, batch in ((1, 3, 64), (2, 0, 17), (3, 1000, 256)):
+        mb = tj.Minibatch(batch, frame_elems * k, "u8")
+        assert g.sample(mb, cur, max_st, seed) == tj.TJ_OK
+        st, info = g.status()
+        ost, oidx, oK = o.sample(batch, cur, max_st, seed)
+        assert st == ost and info.last_n_eligible == oK
+        got = mb.host()
+        np.testing.assert_array_equal(got["idx"], oidx)
+        if ost == 0:
+            want = o.gather(oidx)
+            for f in FIELDS:
+                np.testing.assert_array_equal(got[f], want[f], err_msg=f)
+    # too many rows at once: refused, nothing changes
+    rows = _frame_stream(rng, cap + 1, frame_elems, 0.0)
+    assert g.insert_host(*rows) == tj.TJ_ERR_CAPACITY and o.insert(*rows) == -5
+    _, info = g.status()
+    assert (info.head, info.count) == (o.head, o.count)
+
+
+def test_frame_ring_edge_cases(tj, orc):
+    g = tj.FrameBuffer(16, 8, 4)
+    mb = tj.Minibatch(4, 32, "u8")
+    assert g.sample(mb, 0, 10, 0) == tj.TJ_OK
+    assert g.status()[0] == tj.TJ_ERR_NO_ELIGIBLE                 # empty
+    rng = np.random.default_rng(0)
+    g.insert_host(*_frame_stream(rng, 1, 8, 0.0))
+    assert g.sample(mb, 0, 10, 0) == tj.TJ_OK
+    assert g.status()[0] == tj.TJ_ERR_NO_ELIGIBLE                 # one row: no successor
+    g.insert_host(*_frame_stream(rng, 1, 8, 0.0))
+    assert g.sample(mb, 0, 10, 0) == tj.TJ_OK
+    st, info = g.status()
+    assert st == tj.TJ_OK and info.last_n_eligible == 1 and (mb.host()["idx"] == 0).all()
+    L = tj.lib()
+    bad = tj.tj_frame_buffer_desc(4, 8, 4)                        # capacity below two stacks
+    assert L.tj_frame_buffer_arena_bytes(ctypes.byref(bad)) == 0
