@@ -193,6 +193,43 @@ __global__ __launch_bounds__(256) void col2im_mask_v8(const tj_bf16 *__restrict_
     *(uint4 *)(dz + p * g.C + c0) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// Copy of a channels-last tensor [n][OH][OW][O] into the interior of a zero-bordered one
+// [n][OH + 2 pad][OW + 2 pad][O] (the border is never written).  16 bytes per thread; O % 8 == 0.
+__global__ __launch_bounds__(256) void pad_halo(const tj_bf16 *__restrict__ src, tj_bf16 *__restrict__ dst, size_t n,
+                                                int OH, int OW, int O, int pad)
+{
+    const int O8 = O / 8;
+    const size_t total = n * OH * OW * O8;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int c = (int)(t % O8);
+    const size_t p = t / O8;
+    const int x = (int)(p % OW), y = (int)((p / OW) % OH);
+    const size_t img = p / ((size_t)OW * OH);
+    const size_t d = ((img * (OH + 2 * pad) + y + pad) * (OW + 2 * pad) + x + pad) * O + c * 8;
+    *(uint4 *)(dst + d) = *(const uint4 *)(src + p * O + c * 8);
+}
+
+// Weights of the input-gradient GEMM of a convolution (kernel k, stride s, A = ceil(k / s) taps per
+// dimension): row j = (py, px, c) over the s x s pixel block and the input channels, column
+// (a, b, o) over the taps and the output channels:
+//   Wd[j][(a*A + b)*O + o] = W[o][kh][kw][c],  kh = py + (A-1-a) s,  kw = px + (A-1-b) s   (0 if kh or kw >= k)
+// with W the fp32 master weights in the kernels' order [o][(kh*k + kw)*C + c].
+__global__ __launch_bounds__(256) void dgrad_weights(const float *__restrict__ w, tj_bf16 *__restrict__ wd, int O,
+                                                     int C, int k, int s, int A)
+{
+    const int Kd = A * A * O, N = s * s * C;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (size_t)N * Kd) return;
+    const int col = (int)(t % Kd), j = (int)(t / Kd);
+    const int o = col % O, b = (col / O) % A, a = col / (O * A);
+    const int c = j % C, px = (j / C) % s, py = j / (C * s);
+    const int kh = py + (A - 1 - a) * s, kw = px + (A - 1 - b) * s;
+    float v = 0.f;
+    if (kh < k && kw < k) v = w[(size_t)o * (k * k * C) + (kh * k + kw) * C + c];
+    wd[t] = tj_f32_to_bf16(v);
+}
+
 // Sums n_part partial gradient slices of n elements each into dst.  A block owns 32 consecutive
 // elements; its 8 thread rows each add every 8th slice (128-byte coalesced reads), then the 8 sums
 // are added in a fixed order: deterministic for a given n_part.

@@ -122,8 +122,12 @@ template <typename T> struct TjGemmArgs {
     int n_split;         // gridDim.z
     float *qsum;         // optional: qsum[z*qsum_zstride + j] = sum over this z's k of Q[j][k]
     size_t qsum_zstride;
-    TjGather gather;     // gather.on: P rows are patches of seg[0].P (bf16, one segment of at most 64
+    TjGather gather;     // gather.on: P rows are patches of seg[0].P (bf16, one segment of at most 128
                          // columns, whole 64-k stages, no split); ldp is ignored
+    TjGather out_map;    // with gather.on and out_map.on: D(i,j) -> Cj[origin(out_map, i) + koff(out_map, j)]
+                         // (ldcj ignored): row i is a coarse output position, column j a (pixel, channel) of
+                         // the s x s pixel block it owns.  The only output of such a launch; no bias / ReLU.
+    const T *mask_cj;    // optional with out_map: the result is zeroed where mask_cj[same offset] <= 0
 };
 
 template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st);

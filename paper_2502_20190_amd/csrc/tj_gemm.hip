@@ -979,6 +979,63 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
         }
     }
 
+    if constexpr (GATHER) {
+        if (a.out_map.on) {
+            // Mapped output (input gradient of a convolution): each 32 x 32 tile is staged in the wave's LDS
+            // scratch as bf16 rows of 32 columns; a lane then owns 8 consecutive columns (channels of one
+            // pixel) of a row: one 16-byte mask load and one 16-byte store at the mapped address.
+            constexpr int WPBm = SZA / (32 * kScratchPitch) >= 4 ? 4 : SZA / (32 * kScratchPitch);
+            static_assert(WPBm >= 2 && 7 / WPBm < NSTAGE, "epilogue scratch does not fit the P buffers");
+            const int sbm = wave / WPBm;
+            uint8_t *scrm = (sbm == 0 ? sA0 : sbm == 1 ? sA1 : sbm == 2 ? sA2 : sA3) + (wave % WPBm) * (32 * kScratchPitch);
+#pragma unroll
+            for (int fi = 0; fi < 2; ++fi) {
+                const int ibase = i0 + wi * 64 + fi * 32;
+                int64_t org[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    org[t] = tj_gather_origin(a.out_map, (uint32_t)min(ibase + (lane >> 2) + 16 * t, a.I - 1));
+#pragma unroll
+                for (int fj = 0; fj < NFJ; ++fj) {
+                    const int jbase = j0 + wj * 32 * NFJ + fj * 32;
+                    const f32x16 &v = acc[fi][fj];
+                    wave_sync();
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const uint32_t p01 = pack_bf16(v[rq * 4], v[rq * 4 + 1]), p23 = pack_bf16(v[rq * 4 + 2], v[rq * 4 + 3]);
+                        uint8_t *wp = scrm + (rq * 8 + lg * 4) * kScratchPitch + l32 * 2;
+                        *(T *)(wp) = (T)(p01 & 0xFFFFu);
+                        *(T *)(wp + kScratchPitch) = (T)(p01 >> 16);
+                        *(T *)(wp + 2 * kScratchPitch) = (T)(p23 & 0xFFFFu);
+                        *(T *)(wp + 3 * kScratchPitch) = (T)(p23 >> 16);
+                    }
+                    wave_sync();
+                    const int jv = jbase + (lane & 3) * 8;
+                    if (jv >= j_end) continue;
+                    const int64_t col = tj_gather_koff(a.out_map, jv);
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        if (ibase + (lane >> 2) + 16 * t >= a.I) continue;
+                        u32x4 d = *(const u32x4 *)(scrm + ((lane >> 2) + 16 * t) * kScratchPitch + (lane & 3) * 16);
+                        const int64_t off = org[t] + col;
+                        if (a.mask_cj) {
+                            const u32x4 m = *(const u32x4 *)(a.mask_cj + off);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {   // keep where the bf16 mask value is > 0
+                                const uint32_t lo = m[e] & 0xFFFFu, hi = m[e] >> 16;
+                                const uint32_t keep = ((lo & 0x7FFFu) != 0 && !(lo & 0x8000u) ? 0x0000FFFFu : 0u) |
+                                                      ((hi & 0x7FFFu) != 0 && !(hi & 0x8000u) ? 0xFFFF0000u : 0u);
+                                d[e] &= keep;
+                            }
+                        }
+                        *(u32x4 *)(a.Cj + off) = d;
+                    }
+                }
+            }
+            return;
+        }
+    }
+
     // ---- epilogue (as in gemm_bf16): math on every tile first, then the stores
 #pragma unroll
     for (int fi = 0; fi < 2; ++fi)
@@ -1098,9 +1155,13 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
     int jtot = 0;
     for (int s = 0; s < a.n_seg; ++s) jtot += a.seg[s].j_end - a.seg[s].j_begin;
     if (a.gather.on) {
-        if (a.n_seg != 1 || jtot > 64 || a.K % 64 || a.n_split != 1 || a.qsum || a.I < 1) return TJ_ERR_SHAPE;
-        return launch_dlds<1, 64, 3, true>(a, st);   // short contractions: two blocks per CU overlap their phases
+        if (a.n_seg != 1 || jtot > 128 || a.K % 64 || a.n_split != 1 || a.qsum || a.I < 1) return TJ_ERR_SHAPE;
+        if (a.out_map.on && (!a.Cj || a.Ci || a.Cf || a.relu || a.bias_j || a.seg[0].bias || a.mask))
+            return TJ_ERR_SHAPE;
+        // short contractions: two blocks per CU overlap their phases
+        return jtot > 64 ? launch_dlds<2, 64, 3, true>(a, st) : launch_dlds<1, 64, 3, true>(a, st);
     }
+    if (a.out_map.on) return TJ_ERR_SHAPE;
     if (uses_dlds(a)) {
         // pick the j extent of the tile (128 / 192 / 256) that needs the fewest rounds of 256 blocks,
         // weighted by the tile's work; ties go to the larger tile

@@ -965,6 +965,11 @@ template <typename T> struct ConvLearner : tj_learner {
         size_t part_stride;
         bool implicit;                  // conv without patch matrices: operand gathers (bf16, 32/64 channels)
         TjGather gth;
+        // input gradient as one gathered GEMM over the zero-bordered output gradient (see backward)
+        bool dgrad_gather;
+        TjGather dg_in, dg_out;
+        int A, Kd, Nd, pad;             // taps per dimension, A*A*O, s*s*C, A-1
+        T *dZh, *Wd;
         T *Wc_on, *WcT_on, *Wc_tg, *patches, *patchesT, *XT, *dZ, *dZT, *dpatch;
         float *part;
     };
@@ -1015,10 +1020,22 @@ template <typename T> struct ConvLearner : tj_learner {
                 if (sizeof(T) == 2 && (y.O == 32 || y.O == 64) && y.K % 64 == 0)
                     y.implicit = tj_gather_make(y.gth, g.C, g.H, g.W, g.k, g.s, g.OH, g.OW,
                                                 3 * (size_t)Bmax * y.OHW);
+                y.dgrad_gather = false;
+                if (l > 0 && y.implicit && g.k % g.s == 0 && g.H % g.s == 0 && g.W % g.s == 0 && g.C % 8 == 0) {
+                    y.A = g.k / g.s; y.pad = y.A - 1;
+                    y.Kd = y.A * y.A * y.O; y.Nd = g.s * g.s * g.C;
+                    const int Hc = g.H / g.s, Wc = g.W / g.s;
+                    if (y.Kd % 64 == 0 && y.Nd <= 128)
+                        y.dgrad_gather =
+                            tj_gather_make(y.dg_in, y.O, g.OH + 2 * y.pad, g.OW + 2 * y.pad, y.A, 1, Hc, Wc,
+                                           (size_t)Bmax * Hc * Wc) &&
+                            tj_gather_make(y.dg_out, g.C, g.H, g.W, g.s, g.s, Hc, Wc, (size_t)Bmax * Hc * Wc);
+                }
                 c = g.OC; h = g.OH; w = g.OW;
                 prev_conv = true;
             } else {
                 y.implicit = false;
+                y.dgrad_gather = false;
                 seen_linear = true;
                 y.O = (int)d.layers[l].out;
                 if (prev_conv) { y.C = c; y.S = h * w; } else { y.C = c * h * w; y.S = 1; }
@@ -1070,6 +1087,8 @@ template <typename T> struct ConvLearner : tj_learner {
         wc_tg_begin = lay[0].Wc_tg;
         for (int l = 0; l < L; ++l) lay[l].WcT_on = (T *)a.take((size_t)lay[l].K * lay[l].ldO * sizeof(T));
         for (int l = 0; l < L; ++l) lay[l].part = (float *)a.take((size_t)lay[l].n_split * lay[l].part_stride * 4);
+        for (int l = 0; l < L; ++l)
+            lay[l].Wd = lay[l].dgrad_gather ? (T *)a.take((size_t)lay[l].Nd * lay[l].Kd * sizeof(T)) : nullptr;
         size_t act0 = a.off;
         act_begin = base ? (uint8_t *)base + act0 : nullptr;
         const size_t B = (size_t)Bmax;
@@ -1088,7 +1107,9 @@ template <typename T> struct ConvLearner : tj_learner {
                     y.dZ = (T *)a.take(B * y.OHW * y.O * sizeof(T));
                     y.dZT = (T *)a.take((size_t)y.O * round_up((int)(B * y.OHW), VE) * sizeof(T));
                 }
-                y.dpatch = l > 0 ? (T *)a.take(B * y.OHW * y.ldK * sizeof(T)) : nullptr;
+                y.dpatch = (l > 0 && !y.dgrad_gather) ? (T *)a.take(B * y.OHW * y.ldK * sizeof(T)) : nullptr;
+                y.dZh = y.dgrad_gather ? (T *)a.take(B * (y.g.OH + 2 * y.pad) * (y.g.OW + 2 * y.pad) * y.O * sizeof(T))
+                                       : nullptr;
             } else {
                 act[l] = (T *)a.take(3 * B * y.ldK * sizeof(T));
                 y.patches = y.patchesT = y.dpatch = nullptr;
@@ -1140,6 +1161,18 @@ template <typename T> struct ConvLearner : tj_learner {
             j.dstT = (online && l > 0) ? y.WcT_on : nullptr;   // the first layer has no input gradient
             j.R = y.O; j.C = y.K; j.ldd = y.ldK; j.lddT = y.ldO;
             if (j.dst || j.dstT) jobs.job[n++] = j;
+        }
+        if constexpr (sizeof(T) == 2) {
+            if (online) {
+                for (int l = 0; l < L; ++l) {
+                    NLayer &y = lay[l];
+                    if (!y.dgrad_gather) continue;
+                    const size_t tot = (size_t)y.Nd * y.Kd;
+                    tjconv::dgrad_weights<<<(unsigned)((tot + 255) / 256), 256, 0, st>>>(theta_on + y.w_off, y.Wd, y.O,
+                                                                                       y.g.C, y.g.k, y.g.s, y.A);
+                }
+                if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+            }
         }
         return launch_cast<T>(jobs, n, st);
     }
@@ -1347,6 +1380,28 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.Ci = below.dZ; gm.ldci = y.ldK;
                 if (below.kind == TJ_LAYER_LINEAR) { gm.Cj = below.dZT; gm.ldcj = ldB; gm.cj_jmax = B; }
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+            } else if (y.dgrad_gather) {
+                // dX[img, s yy + py, s xx + px, c] = sum_{a,b,o} dZ0[img, yy + a, xx + b, o] * Wd[(py,px,c)][(a,b,o)],
+                // dZ0 = the output gradient with a zero border of A-1: a stride-1 gathered GEMM whose row is a
+                // coarse position (yy, xx) and whose columns are the s x s pixel block times the channels
+                if constexpr (sizeof(T) == 2) {
+                    const tjconv::ConvGeom &g = y.g;
+                    const size_t np = (size_t)B * g.OH * g.OW * (y.O / 8);
+                    tjconv::pad_halo<<<grid1(np), 256, 0, st>>>(y.dZ, y.dZh, (size_t)B, g.OH, g.OW, y.O, y.pad);
+                    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                    TjGemmArgs<T> gm;
+                    memset(&gm, 0, sizeof(gm));
+                    gm.n_seg = 1;
+                    gm.seg[0] = {0, y.Nd, y.dZh, nullptr, 0};
+                    gm.gather = y.dg_in;
+                    gm.Q = y.Wd;
+                    gm.ldp = y.Kd; gm.ldq = y.Kd;
+                    gm.I = B * (g.H / g.s) * (g.W / g.s); gm.K = y.Kd; gm.k_chunk = gm.K; gm.n_split = 1;
+                    gm.out_map = y.dg_out;
+                    gm.Cj = below.dZ; gm.cj_jmax = y.Nd;
+                    gm.mask_cj = act[l];
+                    if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                }
             } else {       // patch gradients, then the gather back onto the input pixels with the ReLU mask
                 TjGemmArgs<T> gm;
                 memset(&gm, 0, sizeof(gm));
