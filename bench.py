@@ -24,7 +24,9 @@ sys.path.insert(0, ROOT)
 # (FETCH_SIZE, WRITE_SIZE; see profiles/c3_gemm_counters.md), scaled by what the same counters read
 # for the streaming kernels of known size in the same runs (reduce_slices, adam_update: FETCH_SIZE
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the GEMM source it was taken with.
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 886.3e6, "gemm_source_sha256_16": "7beb0e67975fe575"}}
+GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip")
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 884.9e6, "gemm_source_sha256_16": "f0ddb074bc802018"},
+                "c5": {"bytes_per_step": 1565.0e6, "gemm_source_sha256_16": "f0ddb074bc802018"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
@@ -49,17 +51,19 @@ def gemm_flops_per_step(wl, synth, head_in_td_phase):
 
 def gemm_traffic(cfg, n_launch):
     """Counter-measured HBM bytes per GEMM launch, or None when there is no measurement for this
-    workload or the GEMM source has changed since it was taken."""
+    workload or a source of the contraction kernels has changed since it was taken."""
     import hashlib
 
     rec = GEMM_TRAFFIC.get(cfg)
     if rec is None:
         return None
-    src = os.path.join(ROOT, "paper_2502_20190_amd", "csrc", "tj_gemm.hip")
+    h = hashlib.sha256()
     try:
-        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        for name in GEMM_SOURCES:
+            h.update(open(os.path.join(ROOT, "paper_2502_20190_amd", "csrc", name), "rb").read())
     except OSError:
         return None
+    sha = h.hexdigest()[:16]
     return rec["bytes_per_step"] / n_launch if sha == rec["gemm_source_sha256_16"] else None
 
 
@@ -229,7 +233,18 @@ def main():
         n_gemm_launch = (n_layers - (1 if fused_head else 0)) + n_layers
     else:
         n_gemm_launch = (n_layers + n_conv - (1 if fused_head else 0)) + n_layers + (n_layers - 1)
+        first = wl.layers[0]
+        if wl.precision == "bf16" and wl.in_chw[0] == 4 and first[1] == 32 and first[2] in (4, 8) and first[3] % 2 == 0:
+            n_gemm_launch -= 1   # the fused first convolution multiplies with both networks' weights
+
     flops = gemm_flops_per_step(wl, synth, fused_head)
+    # the kernels behind the forward and backward phases (their launches share the MFMA roofline)
+    if wl.precision != "bf16":
+        gemm_kernel_name = "gemm_pq<float>"
+    elif n_conv == 0:
+        gemm_kernel_name = "gemm_bf16_dlds + gemm_bf16_dlds_pair"
+    else:
+        gemm_kernel_name = "gemm_bf16_dlds (gathered operands) + conv_first_u8c4 + conv_wgrad_bf16"
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
     achieved = flops / (gemm_ms * 1e-3) / 1e12
     peak = PEAK_TFLOPS[wl.precision]
@@ -249,7 +264,7 @@ def main():
                    "layers": [l[1] for l in wl.layers], "params": P},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": gemm_traffic(wl.name.split("-")[0], n_gemm_launch),
-                     "kernel": "gemm_pq", "launches_per_step": n_gemm_launch,
+                     "kernel": gemm_kernel_name, "launches_per_step": n_gemm_launch,
                      "flops_per_launch": flops / n_gemm_launch, "avg_launch_ms": gemm_ms / n_gemm_launch},
         "phases_ms": ph, "phase_events_on_steps": len(sampled),
         "gather": {"bound": "hbm", "achieved": gather_bytes / (ph["gather_ms"] * 1e-3) / 1e9,
