@@ -75,6 +75,12 @@ def lib():
         L.orc_learner_last_astar.restype = _i32
         L.orc_learner_last_astar.argtypes = [_vp, _vp]
         L.orc_num_threads.restype = _i32
+        L.orc_gae.restype = None
+        L.orc_gae.argtypes = [_u32, _u32, _vp, _vp, _vp, _dbl, _dbl, _vp, _vp]
+        L.orc_ppo_loss.restype = None
+        L.orc_ppo_loss.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _vp, _dbl, _dbl, _dbl, _vp]
+        L.orc_ppo_step.restype = None
+        L.orc_ppo_step.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _vp, _dbl, _dbl, _dbl, _vp]
         _lib = L
     return _lib
 
@@ -127,6 +133,17 @@ def balance_plan(tr_learner, tr_actor, batch, serial_batch, serial_buffer, capac
     st = f(tr_learner, tr_actor, batch, serial_batch, serial_buffer, capacity, _p(out))
     keys = ("max_staleness", "rows_per_version", "window", "ratio", "target_ratio", "throughput", "cut")
     return st, dict(zip(keys, out))
+
+
+def gae(reward, value, done, gamma: float, lam: float):
+    """Advantages and returns of rollouts stored environment-major: reward, done [n_env][T],
+    value [n_env][T + 1] (the last column bootstraps).  Returns (adv, ret), float64 [n_env][T]."""
+    reward, value, done = _c(reward, np.float32), _c(value, np.float32), _c(done, np.uint8)
+    n_env, T = reward.shape
+    assert value.shape == (n_env, T + 1) and done.shape == (n_env, T)
+    adv, ret = np.empty((n_env, T), np.float64), np.empty((n_env, T), np.float64)
+    lib().orc_gae(n_env, T, _p(reward), _p(value), _p(done), gamma, lam, _p(adv), _p(ret))
+    return adv, ret
 
 
 class Buffer:
@@ -327,4 +344,29 @@ class Learner:
     def last_astar(self) -> np.ndarray:
         out = np.empty(self.last_batch, np.int32)
         lib().orc_learner_last_astar(self.h, _p(out))
+        return out
+
+    def _ppo_args(self, obs, action, old_logp, adv, ret):
+        obs = _c(obs, self.np_dtype)
+        action, old_logp = _c(action, np.int32), _c(old_logp, np.float32)
+        adv, ret = _c(adv, np.float32), _c(ret, np.float32)
+        b = len(action)
+        assert obs.shape[0] == b and len(old_logp) == b and len(adv) == b and len(ret) == b
+        assert action.min() >= 0 and action.max() < self.n_actions - 1
+        return b, obs, action, old_logp, adv, ret
+
+    def ppo_loss(self, obs, action, old_logp, adv, ret, clip=0.2, c_v=0.5, c_e=0.01) -> np.ndarray:
+        """Actor-critic objective (the head's last output is the value): [L_pi, L_v, H, loss]."""
+        b, obs, action, old_logp, adv, ret = self._ppo_args(obs, action, old_logp, adv, ret)
+        out = np.empty(4, np.float64)
+        lib().orc_ppo_loss(self.h, b, _p(obs), _p(action), _p(old_logp), _p(adv), _p(ret), clip, c_v, c_e,
+                           _p(out))
+        return out
+
+    def ppo_step(self, obs, action, old_logp, adv, ret, clip=0.2, c_v=0.5, c_e=0.01) -> np.ndarray:
+        """One update on the whole batch; returns [L_pi, L_v, H, loss] before the update."""
+        b, obs, action, old_logp, adv, ret = self._ppo_args(obs, action, old_logp, adv, ret)
+        out = np.empty(4, np.float64)
+        lib().orc_ppo_step(self.h, b, _p(obs), _p(action), _p(old_logp), _p(adv), _p(ret), clip, c_v, c_e,
+                           _p(out))
         return out

@@ -657,6 +657,60 @@ double orc_learner_min_abs_preactivation(orc_learner *l, const void *obs, uint32
     return m;
 }
 
+/* Backward pass from dz = dLoss/d(head output) [batch][head width] (consumed) through the
+ * network whose layer inputs are acts[i] (freed here), leaving the gradient in l->grad, then one
+ * Adam update of l->theta (bias-corrected, eps outside the square root, t counts from 1). */
+static void backward_and_adam(orc_learner *l, uint32_t batch, double **acts, double *dz)
+{
+    const int nl = l->n_layers;
+    double *Wr = NULL;
+    const double *P = l->theta;
+    if (l->emulate_bf16) {
+        Wr = (double *)malloc(l->n_params * sizeof(double));
+        memcpy(Wr, l->theta, l->n_params * sizeof(double));
+        for (int i = 0; i < nl; ++i)
+            for (size_t e = 0; e < l->L[i].w_size; ++e)
+                Wr[l->L[i].w_off + e] = bf16_round(Wr[l->L[i].w_off + e]);
+        P = Wr;
+    }
+    for (int i = nl - 1; i >= 0; --i) {
+        const orc_layer *L = &l->L[i];
+        if (l->emulate_bf16)
+            for (size_t e = 0; e < (size_t)batch * L->out_size; ++e) dz[e] = bf16_round(dz[e]);
+#pragma omp parallel for schedule(static)
+        for (int o = 0; o < L->out_c; ++o)
+            layer_backward_params(L, o, batch, acts[i], dz, l->grad + L->w_off, l->grad + L->b_off);
+        if (i == 0) break;
+        double *dx = (double *)malloc((size_t)batch * L->in_size * sizeof(double));
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < (int64_t)batch; ++j) {
+            double *dxj = dx + (size_t)j * L->in_size;
+            layer_backward_input(L, P + L->w_off, dz + (size_t)j * L->out_size, dxj);
+            /* ReLU of the previous layer: derivative 0 where its output is <= 0 */
+            const double *h = acts[i] + (size_t)j * L->in_size;
+            for (size_t e = 0; e < L->in_size; ++e)
+                if (!(h[e] > 0.0)) dxj[e] = 0.0;
+        }
+        free(dz);
+        dz = dx;
+    }
+    free(dz);
+    free(Wr);
+    for (int i = 0; i < nl; ++i) free(acts[i]);
+    free(acts);
+
+    l->t += 1;
+    double c1 = 1.0 - pow(l->beta1, (double)l->t);
+    double c2 = 1.0 - pow(l->beta2, (double)l->t);
+    for (size_t p = 0; p < l->n_params; ++p) {
+        double g = l->grad[p];
+        l->m[p] = l->beta1 * l->m[p] + (1.0 - l->beta1) * g;
+        l->v[p] = l->beta2 * l->v[p] + (1.0 - l->beta2) * g * g;
+        double mhat = l->m[p] / c1, vhat = l->v[p] / c2;
+        l->theta[p] -= l->lr * mhat / (sqrt(vhat) + l->eps);
+    }
+}
+
 /* One learner step on a minibatch.  Returns the loss.
  * astar_override is NULL in normal use.  CPU-only tests that compare the two
  * rounding modes of this file pass one mode's greedy actions to the other, so
@@ -708,57 +762,119 @@ double orc_learner_step(orc_learner *l, uint32_t batch, const void *obs, const v
     double loss = loss_sum / (double)batch;
 
     /* backward through Q_online(s) only: y is a constant */
-    double *Wr = NULL;
-    const double *P = l->theta;
-    if (l->emulate_bf16) {
-        Wr = (double *)malloc(l->n_params * sizeof(double));
-        memcpy(Wr, l->theta, l->n_params * sizeof(double));
-        for (int i = 0; i < nl; ++i)
-            for (size_t e = 0; e < l->L[i].w_size; ++e)
-                Wr[l->L[i].w_off + e] = bf16_round(Wr[l->L[i].w_off + e]);
-        P = Wr;
-    }
-    for (int i = nl - 1; i >= 0; --i) {
-        const orc_layer *L = &l->L[i];
-        if (l->emulate_bf16)
-            for (size_t e = 0; e < (size_t)batch * L->out_size; ++e) dz[e] = bf16_round(dz[e]);
-#pragma omp parallel for schedule(static)
-        for (int o = 0; o < L->out_c; ++o)
-            layer_backward_params(L, o, batch, acts[i], dz, l->grad + L->w_off, l->grad + L->b_off);
-        if (i == 0) break;
-        double *dx = (double *)malloc((size_t)batch * L->in_size * sizeof(double));
-#pragma omp parallel for schedule(static)
-        for (int64_t j = 0; j < (int64_t)batch; ++j) {
-            double *dxj = dx + (size_t)j * L->in_size;
-            layer_backward_input(L, P + L->w_off, dz + (size_t)j * L->out_size, dxj);
-            /* ReLU of the previous layer: derivative 0 where its output is <= 0 */
-            const double *h = acts[i] + (size_t)j * L->in_size;
-            for (size_t e = 0; e < L->in_size; ++e)
-                if (!(h[e] > 0.0)) dxj[e] = 0.0;
-        }
-        free(dz);
-        dz = dx;
-    }
-    free(dz);
-    free(Wr);
-    for (int i = 0; i < nl; ++i) free(acts[i]);
-    free(acts);
-
-    /* Adam (bias-corrected, eps outside the square root), t counts from 1 */
-    l->t += 1;
-    double c1 = 1.0 - pow(l->beta1, (double)l->t);
-    double c2 = 1.0 - pow(l->beta2, (double)l->t);
-    for (size_t p = 0; p < l->n_params; ++p) {
-        double g = l->grad[p];
-        l->m[p] = l->beta1 * l->m[p] + (1.0 - l->beta1) * g;
-        l->v[p] = l->beta2 * l->v[p] + (1.0 - l->beta2) * g * g;
-        double mhat = l->m[p] / c1, vhat = l->v[p] / c2;
-        l->theta[p] -= l->lr * mhat / (sqrt(vhat) + l->eps);
-    }
+    backward_and_adam(l, batch, acts, dz);
     /* periodic hard target update */
     if (l->target_interval > 0 && l->t % l->target_interval == 0)
         memcpy(l->target, l->theta, l->n_params * sizeof(double));
     return loss;
+}
+
+/* ------------------------------------------------------------------ */
+/* On-policy workload (the PPO column of the appendix hyperparameter    */
+/* table: gamma 0.99, GAE 0.95, rollout 512, Adam eps 1e-5).  The paper */
+/* names the algorithm only; the estimator is Schulman et al. 2016      */
+/* (GAE, Eq. 16) and the objective Schulman et al. 2017 (Eq. 7 and 9).  */
+/* ------------------------------------------------------------------ */
+
+/* Generalised advantage estimates of n_env rollouts of T steps each, stored environment-major:
+ * reward[e][t], done[e][t], value[e][0..T] (value[e][T] bootstraps the step after the rollout).
+ *   delta_t = r_t + gamma * V_{t+1} * (1 - done_t) - V_t
+ *   A_t     = delta_t + gamma * lambda * (1 - done_t) * A_{t+1},   A_T = 0
+ *   ret_t   = A_t + V_t
+ * done_t = 1 means the episode ended with the transition at t: nothing after it leaks back. */
+void orc_gae(uint32_t n_env, uint32_t T, const float *reward, const float *value, const uint8_t *done,
+             double gamma, double lambda, double *adv, double *ret)
+{
+    for (uint32_t e = 0; e < n_env; ++e) {
+        const float *r = reward + (size_t)e * T, *v = value + (size_t)e * (T + 1);
+        const uint8_t *d = done + (size_t)e * T;
+        double next = 0.0;
+        for (int64_t t = (int64_t)T - 1; t >= 0; --t) {
+            double nd = d[t] ? 0.0 : 1.0;
+            double delta = (double)r[t] + gamma * (double)v[t + 1] * nd - (double)v[t];
+            next = delta + gamma * lambda * nd * next;
+            adv[(size_t)e * T + t] = next;
+            ret[(size_t)e * T + t] = next + (double)v[t];
+        }
+    }
+}
+
+/* Actor-critic head: the network's last layer has A + 1 outputs, policy logits z_0..z_{A-1} and
+ * the state value.  Per sample, with p = softmax(z), rho = p[a] / exp(old_logp):
+ *   L_pi = -min(rho * Adv, clip(rho, 1 - c, 1 + c) * Adv)       (clipped surrogate)
+ *   L_v  = (V - ret)^2
+ *   H    = -sum_a p_a log p_a
+ *   loss = mean_j (L_pi + c_v * L_v - c_e * H)
+ * out = {mean L_pi, mean L_v, mean H, loss}.  dz (optional) receives dloss/d(head output). */
+static void ppo_head(const double *z_all, uint32_t batch, int A, const int32_t *action,
+                     const float *old_logp, const float *adv, const float *ret, double clip,
+                     double c_v, double c_e, double out[4], double *dz_all)
+{
+    double s_pi = 0.0, s_v = 0.0, s_h = 0.0;
+    for (uint32_t j = 0; j < batch; ++j) {
+        const double *z = z_all + (size_t)j * (A + 1);
+        double mx = z[0];
+        for (int a = 1; a < A; ++a)
+            if (z[a] > mx) mx = z[a];
+        double se = 0.0;
+        for (int a = 0; a < A; ++a) se += exp(z[a] - mx);
+        double lse = mx + log(se);
+        double H = 0.0;
+        for (int a = 0; a < A; ++a) H -= exp(z[a] - lse) * (z[a] - lse);
+        double logp = z[action[j]] - lse;
+        double rho = exp(logp - (double)old_logp[j]);
+        double rc = rho < 1.0 - clip ? 1.0 - clip : (rho > 1.0 + clip ? 1.0 + clip : rho);
+        double s1 = rho * (double)adv[j], s2 = rc * (double)adv[j];
+        int unclipped = s1 <= s2; /* the minimum is the unclipped term: it carries the gradient */
+        double verr = z[A] - (double)ret[j];
+        s_pi += -(unclipped ? s1 : s2);
+        s_v += verr * verr;
+        s_h += H;
+        if (dz_all) {
+            double *dz = dz_all + (size_t)j * (A + 1);
+            for (int a = 0; a < A; ++a) {
+                double pa = exp(z[a] - lse);
+                double g = 0.0;
+                if (unclipped) g += -(double)adv[j] * rho * ((a == action[j] ? 1.0 : 0.0) - pa);
+                g += c_e * pa * ((z[a] - lse) + H); /* d(-H)/dz_a = p_a (log p_a + H) */
+                dz[a] = g / (double)batch;
+            }
+            dz[A] = 2.0 * c_v * verr / (double)batch;
+        }
+    }
+    out[0] = s_pi / (double)batch;
+    out[1] = s_v / (double)batch;
+    out[2] = s_h / (double)batch;
+    out[3] = out[0] + c_v * out[1] - c_e * out[2];
+}
+
+/* The objective on a batch under the current parameters, nothing updated. */
+void orc_ppo_loss(orc_learner *l, uint32_t batch, const void *obs, const int32_t *action,
+                  const float *old_logp, const float *adv, const float *ret, double clip, double c_v,
+                  double c_e, double out[4])
+{
+    const int A = l->n_actions - 1;
+    double *z = (double *)malloc((size_t)batch * (A + 1) * sizeof(double));
+    forward_batch(l, l->theta, obs, batch, NULL, z, NULL);
+    ppo_head(z, batch, A, action, old_logp, adv, ret, clip, c_v, c_e, out, NULL);
+    free(z);
+}
+
+/* One update on the whole batch: forward, objective, backward, Adam. */
+void orc_ppo_step(orc_learner *l, uint32_t batch, const void *obs, const int32_t *action,
+                  const float *old_logp, const float *adv, const float *ret, double clip, double c_v,
+                  double c_e, double out[4])
+{
+    const int nl = l->n_layers, A = l->n_actions - 1;
+    double **acts = (double **)malloc((size_t)nl * sizeof(double *));
+    for (int i = 0; i < nl; ++i)
+        acts[i] = (double *)malloc((size_t)batch * l->L[i].in_size * sizeof(double));
+    double *z = (double *)malloc((size_t)batch * (A + 1) * sizeof(double));
+    double *dz = (double *)malloc((size_t)batch * (A + 1) * sizeof(double));
+    forward_batch(l, l->theta, obs, batch, acts, z, NULL);
+    ppo_head(z, batch, A, action, old_logp, adv, ret, clip, c_v, c_e, out, dz);
+    free(z);
+    backward_and_adam(l, batch, acts, dz);
 }
 
 /* Per-row outputs of the last step: which = 0 Q_online(s) [B*A], 1 Q_online(s')

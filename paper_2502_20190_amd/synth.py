@@ -216,3 +216,39 @@ def small_variant(wl: Workload, capacity: int, batch: Optional[int] = None) -> W
     from dataclasses import replace
 
     return replace(wl, capacity=capacity, batch=batch or wl.batch)
+
+
+# ---------------------------------------------------------------- on-policy rollouts
+#
+# The PPO column of the paper's hyperparameter table: rollouts of 512 steps, the learner's batch
+# is the whole buffer (n_env * 512 fresh transitions), hidden width 256.  Inputs only: the
+# estimator and the objective live in the library and, separately, in the oracle.
+
+PPO_WORKLOADS = {
+    # name: (obs_dim, hidden widths, actions, n_env, rollout, precision)
+    "p1": ("p1-ppo-classic-control", 4, (256, 256), 2, 8, 512, "fp32"),
+    "p2": ("p2-ppo-vector-large-batch", 256, (1024, 1024, 1024), 31, 64, 512, "bf16"),
+}
+
+
+def ppo_layers(hidden, n_actions):
+    """Actor-critic MLP: shared trunk, head of n_actions logits + 1 state value."""
+    return _mlp(*hidden, n_actions + 1)
+
+
+def make_rollouts(obs_dim: int, n_actions: int, n_env: int, T: int, seed: int, done_p: float = 0.01):
+    """Seeded stand-in for what n_env actors send after T steps each (environment-major):
+    observations, actions, rewards, episode ends, and what the behaviour policy recorded when it
+    acted (state values incl. the bootstrap column, log-probability of the action taken; the
+    latter scattered around the uniform policy's so that probability ratios land on both sides
+    of the clipping interval)."""
+    rng = np.random.default_rng([MASTER_SEED, 77, seed])
+    n = n_env * T
+    return {
+        "obs": rng.standard_normal((n, obs_dim)).astype(np.float32),
+        "action": rng.integers(0, n_actions, n).astype(np.int32),
+        "reward": rng.uniform(-1.0, 1.0, (n_env, T)).astype(np.float32),
+        "done": (rng.random((n_env, T)) < done_p).astype(np.uint8),
+        "value": rng.standard_normal((n_env, T + 1)).astype(np.float32),
+        "old_logp": (-np.log(n_actions) + 0.25 * rng.standard_normal(n)).astype(np.float32),
+    }

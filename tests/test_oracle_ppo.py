@@ -1,0 +1,233 @@
+"""Pins for the oracle's on-policy functions (CPU only): the advantage estimator against its
+defining sum, closed forms and special cases; the clipped objective against hand-computed
+regimes, torch autograd / torch.optim.Adam in fp64 on whole steps, and finite differences."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_20190_amd import synth
+from paper_2502_20190_amd.synth import LIN
+
+
+# ---------------------------------------------------------------- advantage estimator
+
+def _gae_by_definition(reward, value, done, gamma, lam):
+    """A_t = sum_k (gamma lam)^k delta_{t+k}, the sum stopping at the end of the episode or of
+    the rollout; delta_t = r_t + gamma V_{t+1} (1 - done_t) - V_t.  Written as the explicit
+    double sum, not as the recursion."""
+    n_env, T = reward.shape
+    adv = np.zeros((n_env, T))
+    for e in range(n_env):
+        for t in range(T):
+            acc, w = 0.0, 1.0
+            for k in range(t, T):
+                nd = 0.0 if done[e, k] else 1.0
+                delta = float(reward[e, k]) + gamma * float(value[e, k + 1]) * nd - float(value[e, k])
+                acc += w * delta
+                if done[e, k]:
+                    break
+                w *= gamma * lam
+            adv[e, t] = acc
+    return adv
+
+
+def test_gae_matches_defining_sum(orc):
+    rng = np.random.default_rng(1)
+    for n_env, T, done_p in ((3, 17, 0.2), (2, 64, 0.05), (1, 1, 0.0), (4, 9, 1.0)):
+        reward = rng.uniform(-1, 1, (n_env, T)).astype(np.float32)
+        value = rng.standard_normal((n_env, T + 1)).astype(np.float32)
+        done = (rng.random((n_env, T)) < done_p).astype(np.uint8)
+        adv, ret = orc.gae(reward, value, done, 0.99, 0.95)
+        np.testing.assert_allclose(adv, _gae_by_definition(reward, value, done, 0.99, 0.95), atol=1e-12)
+        np.testing.assert_allclose(ret, adv + value[:, :T], atol=1e-15)
+
+
+def test_gae_special_cases(orc):
+    rng = np.random.default_rng(2)
+    n_env, T, g = 2, 40, 0.9
+    reward = rng.uniform(-1, 1, (n_env, T)).astype(np.float32)
+    value = rng.standard_normal((n_env, T + 1)).astype(np.float32)
+    none = np.zeros((n_env, T), np.uint8)
+    # lambda = 1: discounted Monte-Carlo return with a bootstrapped tail, minus the baseline
+    adv, ret = orc.gae(reward, value, none, g, 1.0)
+    for e in range(n_env):
+        for t in (0, 7, T - 1):
+            mc = sum(g ** (k - t) * float(reward[e, k]) for k in range(t, T)) + g ** (T - t) * float(value[e, T])
+            assert adv[e, t] == pytest.approx(mc - float(value[e, t]), abs=1e-12)
+            assert ret[e, t] == pytest.approx(mc, abs=1e-12)
+    # lambda = 0: the one-step TD error
+    adv, _ = orc.gae(reward, value, none, g, 0.0)
+    delta = reward.astype(np.float64) + g * value[:, 1:].astype(np.float64) - value[:, :T]
+    np.testing.assert_allclose(adv, delta, atol=1e-15)
+    # every step terminal: no bootstrap, no carry-over
+    adv, ret = orc.gae(reward, value, np.ones((n_env, T), np.uint8), g, 0.95)
+    np.testing.assert_allclose(adv, reward.astype(np.float64) - value[:, :T], atol=1e-15)
+    np.testing.assert_allclose(ret, reward.astype(np.float64), atol=1e-15)
+    # constant reward 1, zero values: a geometric series in gamma * lambda
+    T2, lam = 512, 0.95
+    adv, _ = orc.gae(np.ones((1, T2), np.float32), np.zeros((1, T2 + 1), np.float32),
+                     np.zeros((1, T2), np.uint8), 0.99, lam)
+    x = 0.99 * lam
+    np.testing.assert_allclose(adv[0], (1 - x ** (T2 - np.arange(T2))) / (1 - x), rtol=1e-12)
+    # an episode end cuts the series: the step before the end sees exactly two rewards
+    done = np.zeros((1, T2), np.uint8); done[0, 100] = 1
+    adv, _ = orc.gae(np.ones((1, T2), np.float32), np.zeros((1, T2 + 1), np.float32), done, 0.99, lam)
+    assert adv[0, 100] == pytest.approx(1.0, abs=1e-15)
+    assert adv[0, 99] == pytest.approx(1.0 + x, abs=1e-15)
+    assert adv[0, 101] == pytest.approx((1 - x ** (T2 - 101)) / (1 - x), rel=1e-12)
+
+
+# ---------------------------------------------------------------- clipped objective
+
+def _net(orc, hidden, obs_dim, A, seed, **kw):
+    layers = synth.ppo_layers(hidden, A)
+    l = orc.Learner(layers, (obs_dim, 1, 1), **kw)
+    theta = synth.xavier_init(layers, (obs_dim, 1, 1), seed).astype(np.float64)
+    theta += 0.05 * np.random.default_rng(seed + 5).standard_normal(theta.size)
+    l.set_state(orc.PARAMS, theta)
+    return l, layers, theta
+
+
+def test_ppo_hand_computed_regimes(orc):
+    """A head with zero weights: uniform policy (p = 1/A, H = log A), V = the value bias.  The
+    behaviour log-probability then sets the ratio directly."""
+    A, D, b = 4, 3, 6
+    layers = [(LIN, A + 1, 0, 0)]
+    l = orc.Learner(layers, (D, 1, 1), lr=0.1, eps=1e-5)
+    theta = np.zeros((A + 1) * D + A + 1)
+    theta[-1] = 0.75                                   # value bias
+    rng = np.random.default_rng(0)
+    obs = rng.standard_normal((b, D)).astype(np.float32)
+    action = rng.integers(0, A, b).astype(np.int32)
+    ret = rng.standard_normal(b).astype(np.float32)
+    adv_pos = rng.uniform(0.5, 1.5, b).astype(np.float32)
+    logA = np.log(A)
+
+    def run(old_logp, adv, **kw):
+        l.set_state(orc.PARAMS, theta); l.set_state(orc.ADAM_M, 0 * theta); l.set_state(orc.ADAM_V, 0 * theta)
+        l.t = 0
+        out = l.ppo_step(obs, action, np.full(b, old_logp, np.float32), adv, ret, clip=0.2, **kw)
+        return out, l.get_state(orc.GRADS), l.get_state(orc.PARAMS)
+
+    vloss = np.mean((0.75 - ret.astype(np.float64)) ** 2)
+    # ratio 1: the surrogate is the plain policy-gradient objective
+    out, g, _ = run(-logA, adv_pos, c_v=0.5, c_e=0.01)
+    np.testing.assert_allclose(out[:3], [-adv_pos.astype(np.float64).mean(), vloss, logA], rtol=1e-6)
+    assert out[3] == pytest.approx(out[0] + 0.5 * out[1] - 0.01 * out[2], abs=1e-15)
+    # its gradient wrt the logit biases: -(1/b) sum_j Adv_j (1[a = a_j] - 1/A); the entropy of a
+    # uniform policy is stationary, so c_e adds nothing
+    gb = g[(A + 1) * D:(A + 1) * D + A]
+    expect = -np.array([np.sum(adv_pos * ((action == a) - 1.0 / A)) for a in range(A)]) / b
+    np.testing.assert_allclose(gb, expect, rtol=1e-6, atol=1e-9)
+    assert g[-1] == pytest.approx(2 * 0.5 * np.mean(0.75 - ret.astype(np.float64)), rel=1e-7)
+    # ratio 2 (old_logp = log(1/A) - log 2; rounding old_logp to fp32 moves the ratio by 1e-7)
+    # with positive advantages: clipped at 1.2, no policy gradient; nothing else switched on ->
+    # the gradient is exactly zero and Adam leaves the parameters alone
+    out, g, th = run(-logA - np.log(2.0), adv_pos, c_v=0.0, c_e=0.0)
+    assert out[0] == pytest.approx(-1.2 * adv_pos.astype(np.float64).mean(), rel=1e-12)
+    assert not g.any() and np.array_equal(th, theta)
+    # ratio 2 with negative advantages: the unclipped term is the smaller one and keeps its gradient
+    out, g, _ = run(-logA - np.log(2.0), -adv_pos, c_v=0.0, c_e=0.0)
+    assert out[0] == pytest.approx(2.0 * adv_pos.astype(np.float64).mean(), rel=1e-6)
+    assert np.abs(g[(A + 1) * D:(A + 1) * D + A]).max() > 1e-3
+    # ratio 1/2 with negative advantages: clipped at 0.8, no gradient
+    out, g, _ = run(-logA + np.log(2.0), -adv_pos, c_v=0.0, c_e=0.0)
+    assert out[0] == pytest.approx(0.8 * adv_pos.astype(np.float64).mean(), rel=1e-12)
+    assert not g.any()
+    # ratio 1/2 with positive advantages: unclipped
+    out, g, _ = run(-logA + np.log(2.0), adv_pos, c_v=0.0, c_e=0.0)
+    assert out[0] == pytest.approx(-0.5 * adv_pos.astype(np.float64).mean(), rel=1e-6)
+    assert g.any()
+
+
+def _torch_net(layers, D, theta):
+    ws, off, i = [], 0, D
+    for (_, o, _, _) in layers:
+        W = torch.tensor(theta[off:off + o * i].reshape(o, i), dtype=torch.float64, requires_grad=True); off += o * i
+        bb = torch.tensor(theta[off:off + o], dtype=torch.float64, requires_grad=True); off += o
+        ws += [W, bb]
+        i = o
+    return ws
+
+
+def _torch_ppo(ws, obs, action, old_logp, adv, ret, clip, c_v, c_e):
+    x = torch.tensor(obs, dtype=torch.float64)
+    n = len(ws) // 2
+    for k in range(n):
+        x = torch.nn.functional.linear(x, ws[2 * k], ws[2 * k + 1])
+        if k + 1 < n:
+            x = torch.relu(x)
+    dist = torch.distributions.Categorical(logits=x[:, :-1])
+    ratio = torch.exp(dist.log_prob(torch.tensor(action, dtype=torch.int64)) - torch.tensor(old_logp, dtype=torch.float64))
+    a = torch.tensor(adv, dtype=torch.float64)
+    l_pi = -torch.minimum(ratio * a, torch.clamp(ratio, 1 - clip, 1 + clip) * a).mean()
+    l_v = torch.nn.functional.mse_loss(x[:, -1], torch.tensor(ret, dtype=torch.float64))
+    ent = dist.entropy().mean()
+    clipped = ((ratio > 1 + clip) & (a > 0)) | ((ratio < 1 - clip) & (a < 0))
+    return l_pi, l_v, ent, l_pi + c_v * l_v - c_e * ent, int(clipped.sum())
+
+
+@pytest.mark.parametrize("hidden,D,A,n_env,T", [((16, 12), 5, 3, 2, 24), ((32,), 7, 6, 3, 16), ((), 4, 2, 1, 20)])
+def test_ppo_steps_match_torch_autograd_and_adam(orc, hidden, D, A, n_env, T):
+    """Three successive updates on the same batch (the probability ratio moves away from what
+    the behaviour policy recorded, so later steps clip more) against torch in fp64."""
+    l, layers, theta = _net(orc, hidden, D, A, seed=11, lr=3e-3, eps=1e-5)
+    ro = synth.make_rollouts(D, A, n_env, T, seed=4)
+    adv64, ret64 = orc.gae(ro["reward"], ro["value"], ro["done"], 0.99, 0.95)
+    adv, ret = adv64.ravel().astype(np.float32), ret64.ravel().astype(np.float32)
+    ws = _torch_net(layers, D, theta)
+    opt = torch.optim.Adam(ws, lr=3e-3, betas=(0.9, 0.999), eps=1e-5)
+    n_clipped = []
+    for it in range(3):
+        opt.zero_grad()
+        parts = _torch_ppo(ws, ro["obs"], ro["action"], ro["old_logp"], adv, ret, 0.2, 0.5, 0.01)
+        parts[3].backward()
+        out = l.ppo_step(ro["obs"], ro["action"], ro["old_logp"], adv, ret, clip=0.2, c_v=0.5, c_e=0.01)
+        np.testing.assert_allclose(out, [float(p.detach()) for p in parts[:4]], rtol=1e-11, atol=1e-12)
+        n_clipped.append(parts[4])
+        g_t = np.concatenate([w.grad.numpy().ravel() for w in ws])
+        np.testing.assert_allclose(l.get_state(orc.GRADS), g_t, rtol=1e-9, atol=1e-12)
+        opt.step()
+        th_t = np.concatenate([w.detach().numpy().ravel() for w in ws])
+        np.testing.assert_allclose(l.get_state(orc.PARAMS), th_t, rtol=1e-9, atol=1e-11)
+    # both branches of the minimum are exercised
+    assert l.t == 3 and all(0 < c < n_env * T for c in n_clipped)
+    # the loss-only entry point agrees with the step's report at the same parameters
+    l2, _, _ = _net(orc, hidden, D, A, seed=11)
+    first = l2.ppo_loss(ro["obs"], ro["action"], ro["old_logp"], adv, ret)
+    l3, _, _ = _net(orc, hidden, D, A, seed=11, lr=0.0)
+    np.testing.assert_array_equal(first, l3.ppo_step(ro["obs"], ro["action"], ro["old_logp"], adv, ret))
+
+
+def test_ppo_gradient_by_finite_differences(orc):
+    D, A = 4, 3
+    l, layers, theta = _net(orc, (8,), D, A, seed=21, lr=0.0)
+    ro = synth.make_rollouts(D, A, 2, 10, seed=9)
+    adv64, ret64 = orc.gae(ro["reward"], ro["value"], ro["done"], 0.99, 0.95)
+    args = (ro["obs"], ro["action"], ro["old_logp"], adv64.ravel(), ret64.ravel())
+    l.ppo_step(*args, clip=0.2, c_v=0.5, c_e=0.01)
+    g = l.get_state(orc.GRADS)
+    assert np.array_equal(l.get_state(orc.PARAMS), theta)       # lr = 0
+    h = 1e-6
+    rng = np.random.default_rng(3)
+    for p in rng.choice(theta.size, 25, replace=False):
+        tp = theta.copy(); tp[p] += h; l.set_state(orc.PARAMS, tp)
+        up = l.ppo_loss(*args, clip=0.2, c_v=0.5, c_e=0.01)[3]
+        tp[p] -= 2 * h; l.set_state(orc.PARAMS, tp)
+        dn = l.ppo_loss(*args, clip=0.2, c_v=0.5, c_e=0.01)[3]
+        assert g[p] == pytest.approx((up - dn) / (2 * h), abs=2e-8)
+
+
+def test_ppo_bf16_emulation_stays_close(orc):
+    """The bf16 rounding mode (weights, activations, gradients at layer boundaries rounded)
+    moves a step's outputs by what bf16 resolution allows, no more."""
+    D, A = 16, 5
+    ro = synth.make_rollouts(D, A, 2, 32, seed=1)
+    adv64, ret64 = orc.gae(ro["reward"], ro["value"], ro["done"], 0.99, 0.95)
+    args = (ro["obs"], ro["action"], ro["old_logp"], adv64.ravel(), ret64.ravel())
+    a, _, _ = _net(orc, (32, 32), D, A, seed=2, lr=0.0)
+    b, _, _ = _net(orc, (32, 32), D, A, seed=2, lr=0.0, emulate_bf16=True)
+    oa, ob = a.ppo_step(*args), b.ppo_step(*args)
+    np.testing.assert_allclose(ob, oa, rtol=0.03, atol=0.02)
+    ga, gb = a.get_state(orc.GRADS), b.get_state(orc.GRADS)
+    assert np.linalg.norm(ga - gb) < 0.1 * np.linalg.norm(ga)
