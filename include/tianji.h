@@ -282,6 +282,85 @@ int tj_learner_set_state(tj_learner *lrn, int which, const float *h_in, size_t n
 int tj_learner_get_step(tj_learner *lrn, uint64_t *h_t);
 int tj_learner_set_step(tj_learner *lrn, uint64_t t);
 
+/* ---------------------------------------------------------------- on-policy */
+
+/* The paper's on-policy workload (Section 4 and the PPO column of the appendix
+ * hyperparameter table: gamma 0.99, GAE 0.95, rollout length 512, buffer size =
+ * batch size, Adam eps 1e-5, lr 1e-4, hidden width 256).  The paper names the
+ * algorithm only; the estimator is generalised advantage estimation (Schulman
+ * et al. 2016, Eq. 16), the objective PPO's clipped surrogate with value and
+ * entropy terms (Schulman et al. 2017, Eq. 7 and 9). */
+
+/* Advantages and returns of n_env rollouts of T steps, environment-major device
+ * arrays: d_reward, d_done [n_env][T]; d_value [n_env][T + 1] (what the
+ * behaviour policy's critic said at every step, last column = the state after
+ * the rollout); outputs d_adv, d_ret float [n_env][T]:
+ *   delta_t = r_t + gamma V_{t+1} (1 - done_t) - V_t
+ *   A_t     = delta_t + gamma lambda (1 - done_t) A_{t+1},  A_T = 0
+ *   ret_t   = A_t + V_t
+ * fp32; the recursion is evaluated as a scan of affine maps, so its rounding
+ * order differs from the serial one.  n_env == 0 or T == 0: nothing is done. */
+int tj_gae(uint32_t n_env, uint32_t T, const float *d_reward, const float *d_value,
+           const uint8_t *d_done, float gamma, float lambda, float *d_adv, float *d_ret,
+           void *hip_stream);
+
+typedef struct {
+    uint32_t obs_dim;                  /* fp32 vector observations                  */
+    uint32_t n_hidden;                 /* shared trunk: ReLU layers                 */
+    uint32_t hidden[TJ_MAX_LAYERS - 1];
+    uint32_t n_actions;                /* 1..63; the head has n_actions + 1 outputs:
+                                          logits, then the state value              */
+    uint32_t precision;                /* TJ_PRECISION_FP32 / _BF16                 */
+    uint32_t max_batch;
+    float lr, beta1, beta2, eps;       /* Adam                                      */
+    float clip, c_v, c_e;              /* clipping range, value and entropy weights */
+} tj_ppo_desc;
+
+/* Device pointers of one batch (the whole buffer: rollouts flattened). */
+typedef struct {
+    uint32_t batch;
+    const float *obs;        /* [batch][obs_dim]                                   */
+    const int32_t *action;   /* [batch], in [0, n_actions)                         */
+    const float *old_logp;   /* [batch] log-probability under the behaviour policy */
+    const float *adv, *ret;  /* [batch] from tj_gae                                */
+} tj_ppo_batch;
+
+typedef struct {
+    float loss_pi;   /* mean of -min(rho Adv, clip(rho, 1-c, 1+c) Adv)             */
+    float loss_v;    /* mean of (V - ret)^2                                        */
+    float entropy;   /* mean policy entropy                                        */
+    float loss;      /* loss_pi + c_v loss_v - c_e entropy (before the update)     */
+    uint32_t step;   /* t after this step                                          */
+} tj_ppo_stats;
+
+/* Parameters of the actor-critic network, flat order as tj_learner_num_params. */
+size_t tj_ppo_num_params(const tj_ppo_desc *desc);
+size_t tj_ppo_arena_bytes(const tj_ppo_desc *desc);
+
+/* An on-policy learner.  The handle is a tj_learner: tj_learner_destroy,
+ * tj_learner_get_state / set_state (PARAMS, GRADS, ADAM_M, ADAM_V),
+ * tj_learner_get_step / set_step and tj_learner_set_phase_events apply;
+ * tj_learner_step and tj_actor_act return TJ_ERR_INVALID_ARG for it.
+ * h_init: host pointer to tj_ppo_num_params floats. */
+int tj_ppo_create(const tj_ppo_desc *desc, void *dev_arena, size_t arena_bytes, const float *h_init,
+                  void *hip_stream, tj_learner **out);
+
+/* One update on the whole batch: with p = softmax(logits(s_j)), rho_j =
+ * p[a_j] / exp(old_logp_j) and H_j the entropy of p,
+ *   loss = mean_j ( -min(rho_j Adv_j, clip(rho_j, 1-c, 1+c) Adv_j)
+ *                   + c_v (V(s_j) - ret_j)^2 - c_e H_j )
+ * (where both terms of the minimum are equal the unclipped one carries the
+ * gradient), backward through the shared network, Adam as in tj_learner_step.
+ * batch->batch <= max_batch; d_stats: optional device pointer. */
+int tj_ppo_step(tj_learner *lrn, const tj_ppo_batch *batch, tj_ppo_stats *d_stats, void *hip_stream);
+
+/* Forward pass only, n <= max_batch observations: d_logits float [n][n_actions]
+ * and d_value float [n] (either may be NULL).  What an actor needs to act and
+ * to fill old_logp and the value columns of tj_gae.  Uses the learner's
+ * activation buffers: never concurrently with tj_ppo_step of the same handle. */
+int tj_ppo_evaluate(tj_learner *lrn, uint32_t n, const float *d_obs, float *d_logits, float *d_value,
+                    void *hip_stream);
+
 /* ---------------------------------------------------------------- timing */
 
 /* ---------------------------------------------------------------- balance */

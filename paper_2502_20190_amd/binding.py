@@ -33,6 +33,7 @@ EXPORTS = [
     "tj_learner_create", "tj_learner_destroy", "tj_learner_step", "tj_learner_get_state",
     "tj_learner_set_state", "tj_learner_get_step", "tj_learner_set_step", "tj_strerror",
     "tj_buffer_set_phase_events", "tj_learner_set_phase_events",
+    "tj_gae", "tj_ppo_num_params", "tj_ppo_arena_bytes", "tj_ppo_create", "tj_ppo_step", "tj_ppo_evaluate",
 ]
 
 
@@ -83,6 +84,18 @@ class tj_learner_desc(C.Structure):
                 ("precision", C.c_uint32), ("max_batch", C.c_uint32), ("gamma", C.c_float),
                 ("huber_delta", C.c_float), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("eps", C.c_float), ("target_interval", C.c_uint32)]
+
+
+class tj_ppo_desc(C.Structure):
+    _fields_ = [("obs_dim", C.c_uint32), ("n_hidden", C.c_uint32), ("hidden", C.c_uint32 * (TJ_MAX_LAYERS - 1)),
+                ("n_actions", C.c_uint32), ("precision", C.c_uint32), ("max_batch", C.c_uint32),
+                ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("clip", C.c_float), ("c_v", C.c_float), ("c_e", C.c_float)]
+
+
+class tj_ppo_batch(C.Structure):
+    _fields_ = [("batch", C.c_uint32), ("obs", C.c_void_p), ("action", C.c_void_p), ("old_logp", C.c_void_p),
+                ("adv", C.c_void_p), ("ret", C.c_void_p)]
 
 
 class tj_step_stats(C.Structure):
@@ -146,6 +159,18 @@ def lib():
         L.tj_learner_set_phase_events.argtypes = [vp, C.POINTER(vp), u32]
         L.tj_strerror.restype = C.c_char_p
         L.tj_strerror.argtypes = [i32]
+        L.tj_gae.restype = i32
+        L.tj_gae.argtypes = [u32, u32, vp, vp, vp, C.c_float, C.c_float, vp, vp, vp]
+        L.tj_ppo_num_params.restype = sz
+        L.tj_ppo_num_params.argtypes = [C.POINTER(tj_ppo_desc)]
+        L.tj_ppo_arena_bytes.restype = sz
+        L.tj_ppo_arena_bytes.argtypes = [C.POINTER(tj_ppo_desc)]
+        L.tj_ppo_create.restype = i32
+        L.tj_ppo_create.argtypes = [C.POINTER(tj_ppo_desc), vp, sz, vp, vp, C.POINTER(vp)]
+        L.tj_ppo_step.restype = i32
+        L.tj_ppo_step.argtypes = [vp, C.POINTER(tj_ppo_batch), vp, vp]
+        L.tj_ppo_evaluate.restype = i32
+        L.tj_ppo_evaluate.argtypes = [vp, u32, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -460,6 +485,93 @@ class Learner:
     @t.setter
     def t(self, value: int) -> None:
         _check(lib().tj_learner_set_step(self.h, value), "tj_learner_set_step")
+
+
+def gae(reward, value, done, gamma: float, lam: float, stream=None):
+    """tj_gae on device tensors: reward f32 [n_env, T], value f32 [n_env, T + 1], done u8 [n_env, T];
+    returns (adv, ret) f32 [n_env, T]."""
+    import torch
+
+    n_env, T = int(reward.shape[0]), int(reward.shape[1])
+    assert tuple(value.shape) == (n_env, T + 1) and tuple(done.shape) == (n_env, T)
+    assert reward.dtype == torch.float32 and value.dtype == torch.float32 and done.dtype == torch.uint8
+    assert reward.is_contiguous() and value.is_contiguous() and done.is_contiguous()
+    adv, ret = torch.empty_like(reward), torch.empty_like(reward)
+    _check(lib().tj_gae(n_env, T, reward.data_ptr(), value.data_ptr(), done.data_ptr(), gamma, lam,
+                        adv.data_ptr(), ret.data_ptr(), _stream_ptr(stream)), "tj_gae")
+    return adv, ret
+
+
+class PpoLearner:
+    """tj_ppo_* over a torch-allocated arena (state access through tj_learner_*)."""
+
+    def __init__(self, obs_dim: int, hidden, n_actions: int, precision: str, max_batch: int, init: np.ndarray,
+                 lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-5, clip=0.2, c_v=0.5, c_e=0.01, device="cuda:0",
+                 stream=None):
+        import torch
+
+        _require_gpu()
+        d = tj_ppo_desc()
+        d.obs_dim, d.n_hidden, d.n_actions = obs_dim, len(hidden), n_actions
+        for i, h in enumerate(hidden):
+            d.hidden[i] = h
+        d.precision = TJ_PRECISION_BF16 if precision == "bf16" else TJ_PRECISION_FP32
+        d.max_batch = max_batch
+        d.lr, d.beta1, d.beta2, d.eps, d.clip, d.c_v, d.c_e = lr, beta1, beta2, eps, clip, c_v, c_e
+        self.desc = d
+        self.n_actions = n_actions
+        self.n_params = lib().tj_ppo_num_params(C.byref(d))
+        nbytes = lib().tj_ppo_arena_bytes(C.byref(d))
+        if nbytes == 0 or self.n_params == 0:
+            raise TjError(TJ_ERR_SHAPE, "tj_ppo_arena_bytes")
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        self.arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
+        th = np.ascontiguousarray(init, np.float32)
+        assert th.size == self.n_params
+        h = C.c_void_p()
+        _check(lib().tj_ppo_create(C.byref(d), self.arena_ptr, nbytes, th.ctypes.data, _stream_ptr(stream),
+                                   C.byref(h)), "tj_ppo_create")
+        self.h = h
+        self.stats = torch.zeros(5, dtype=torch.int32, device=device)   # tj_ppo_stats {4 x f32, u32}
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().tj_learner_destroy(self.h)
+            self.h = None
+
+    def step(self, obs, action, old_logp, adv, ret, stream=None) -> int:
+        """One update on device tensors: obs f32 [B, obs_dim], action i32 [B], old_logp / adv / ret f32 [B]."""
+        b = tj_ppo_batch(int(action.shape[0]), obs.data_ptr(), action.data_ptr(), old_logp.data_ptr(),
+                         adv.data_ptr(), ret.data_ptr())
+        return lib().tj_ppo_step(self.h, C.byref(b), self.stats.data_ptr(), _stream_ptr(stream))
+
+    def evaluate(self, obs, stream=None):
+        """(logits f32 [n, A], value f32 [n]) of device observations under the current weights."""
+        import torch
+
+        n = int(obs.shape[0])
+        logits = torch.empty((n, self.n_actions), dtype=torch.float32, device=obs.device)
+        value = torch.empty(n, dtype=torch.float32, device=obs.device)
+        _check(lib().tj_ppo_evaluate(self.h, n, obs.data_ptr(), logits.data_ptr(), value.data_ptr(),
+                                     _stream_ptr(stream)), "tj_ppo_evaluate")
+        return logits, value
+
+    def read_stats(self):
+        """(loss_pi, loss_v, entropy, loss, t) of the last step."""
+        raw = self.stats.cpu().numpy()
+        f = raw.view(np.float32)
+        return float(f[0]), float(f[1]), float(f[2]), float(f[3]), int(raw.view(np.uint32)[4])
+
+    def get_state(self, which: int, stream=None) -> np.ndarray:
+        out = np.empty(self.n_params, np.float32)
+        _check(lib().tj_learner_get_state(self.h, which, out.ctypes.data, out.size, _stream_ptr(stream)),
+               "tj_learner_get_state")
+        return out
+
+    def set_state(self, which: int, values, stream=None) -> None:
+        v = np.ascontiguousarray(values, np.float32)
+        _check(lib().tj_learner_set_state(self.h, which, v.ctypes.data, v.size, _stream_ptr(stream)),
+               "tj_learner_set_state")
 
 
 def learner_for_workload(wl, init_online, init_target, device="cuda:0", max_batch: Optional[int] = None):

@@ -515,6 +515,164 @@ __global__ __launch_bounds__(256) void reduce_slices(float *__restrict__ g, size
     }
 }
 
+// ---------------------------------------------------------------- on-policy workload
+//
+// The PPO column of the paper's hyperparameter table (gamma 0.99, GAE 0.95, rollouts of 512
+// steps, batch = buffer, Adam eps 1e-5).  The estimator is GAE (Schulman et al. 2016, Eq. 16),
+// the objective the clipped surrogate with value and entropy terms (Schulman et al. 2017,
+// Eq. 7 and 9).
+
+// Advantages of one rollout per wave.  A_t = delta_t + c_t A_{t+1} is a chain of affine maps
+// x -> D + C x, which compose associatively: a lane folds its 8 consecutive steps into one map,
+// a suffix scan over the lanes (shuffles) gives every lane the advantage that enters its run, and
+// the lane then replays its 8 steps.  Chunks of 512 steps, last chunk first, carry A across.
+__global__ __launch_bounds__(256) void gae_scan(uint32_t n_env, uint32_t T, const float *__restrict__ reward,
+                                                const float *__restrict__ value,
+                                                const uint8_t *__restrict__ done, float gamma, float lam,
+                                                float *__restrict__ adv, float *__restrict__ ret)
+{
+    const uint32_t env = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (env >= n_env) return;
+    const float *r = reward + (size_t)env * T, *v = value + (size_t)env * ((size_t)T + 1);
+    const uint8_t *dn = done + (size_t)env * T;
+    float *ao = adv + (size_t)env * T, *ro = ret + (size_t)env * T;
+    float carry = 0.f;   // A at the first step of the chunk after this one (A_T = 0)
+    for (int64_t end = T; end > 0; end -= 512) {
+        const int64_t t0 = end - 512 + 8 * lane;
+        float dl[8], c[8], v0[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t t = t0 + e;
+            if (t >= 0) {
+                const float nd = dn[t] ? 0.f : 1.f;
+                v0[e] = v[t];
+                dl[e] = r[t] + gamma * v[t + 1] * nd - v0[e];
+                c[e] = gamma * lam * nd;
+            } else {   // before the rollout: the identity map
+                v0[e] = 0.f; dl[e] = 0.f; c[e] = 1.f;
+            }
+        }
+        float C = 1.f, D = 0.f;
+#pragma unroll
+        for (int e = 7; e >= 0; --e) { D = dl[e] + c[e] * D; C = c[e] * C; }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {   // (C, D) of lanes [lane, lane + 2 off)
+            const float C2 = __shfl_down(C, off, 64), D2 = __shfl_down(D, off, 64);
+            if (lane + off < 64) { D = D + C * D2; C = C * C2; }
+        }
+        const float a_first = D + C * carry;       // A at this lane's first step
+        float a = __shfl_down(a_first, 1, 64);     // A entering from the lane above
+        if (lane == 63) a = carry;
+#pragma unroll
+        for (int e = 7; e >= 0; --e) {
+            a = dl[e] + c[e] * a;
+            const int64_t t = t0 + e;
+            if (t >= 0) { ao[t] = a; ro[t] = a + v0[e]; }
+        }
+        carry = __shfl(a_first, 0, 64);
+    }
+}
+
+// Clipped actor-critic objective on the head's output Z[j] = (logits z_0..z_{A-1}, value):
+//   p = softmax(z), rho = p[a_j] / exp(old_logp_j), H = -sum p log p
+//   loss_j = -min(rho Adv, clip(rho, 1-c, 1+c) Adv) + c_v (V - ret)^2 - c_e H
+// Writes d(mean loss)/dZ in compute type, row-major and transposed (the two operand layouts of
+// the backward GEMMs), and per-block sums of the three terms.  One thread per sample.
+template <typename T> struct PpoHeadArgs {
+    const float *Z; int ldz; int B, A;
+    const int32_t *action; const float *old_logp, *adv, *ret;
+    float clip, c_v, c_e;
+    T *dZ; int lddz; T *dZT; int lddzt;
+    float *part;   // [blocks][4]: sum L_pi, sum L_v, sum H, unused
+};
+
+template <typename T> __global__ __launch_bounds__(256) void ppo_head(const PpoHeadArgs<T> a)
+{
+    __shared__ float red[4][3];
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    float l_pi = 0.f, l_v = 0.f, H = 0.f;
+    if (j < a.B) {
+        const float *z = a.Z + (size_t)j * a.ldz;
+        float mx = z[0];
+        for (int k = 1; k < a.A; ++k) mx = fmaxf(mx, z[k]);
+        float se = 0.f;
+        for (int k = 0; k < a.A; ++k) se += expf(z[k] - mx);
+        const float lse = mx + logf(se);
+        for (int k = 0; k < a.A; ++k) H -= expf(z[k] - lse) * (z[k] - lse);
+        const int act = min(max(a.action[j], 0), a.A - 1);
+        const float adv = a.adv[j];
+        const float rho = expf(z[act] - lse - a.old_logp[j]);
+        const float rc = fminf(fmaxf(rho, 1.f - a.clip), 1.f + a.clip);
+        const float s1 = rho * adv, s2 = rc * adv;
+        const bool unclipped = s1 <= s2;   // the minimum is the unclipped term: it carries the gradient
+        const float verr = z[a.A] - a.ret[j];
+        l_pi = -(unclipped ? s1 : s2);
+        l_v = verr * verr;
+        const float inv_b = 1.f / (float)a.B;
+        T *dz = a.dZ + (size_t)j * a.lddz;
+        for (int k = 0; k < a.A; ++k) {
+            const float lp = z[k] - lse, pk = expf(lp);
+            float g = a.c_e * pk * (lp + H);
+            if (unclipped) g -= adv * rho * ((k == act ? 1.f : 0.f) - pk);
+            const T gt = TjElem<T>::from_f32(g * inv_b);
+            dz[k] = gt;
+            a.dZT[(size_t)k * a.lddzt + j] = gt;
+        }
+        const T gv = TjElem<T>::from_f32(2.f * a.c_v * verr * inv_b);
+        dz[a.A] = gv;
+        a.dZT[(size_t)a.A * a.lddzt + j] = gv;
+    }
+    // block sums in a fixed order: shuffle tree per wave, then the four waves in turn
+    float s[3] = {l_pi, l_v, H};
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s[q] += __shfl_down(s[q], off, 64);
+    if ((threadIdx.x & 63) == 0)
+        for (int q = 0; q < 3; ++q) red[threadIdx.x >> 6][q] = s[q];
+    __syncthreads();
+    if (threadIdx.x < 3)
+        a.part[(size_t)blockIdx.x * 4 + threadIdx.x] =
+            red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+}
+
+// Means of the three terms and the objective, from the per-block sums (fixed order).
+__global__ __launch_bounds__(64) void ppo_stats_final(const float *__restrict__ part, int n_part, int B, float c_v,
+                                                      float c_e, uint32_t t_next, tj_ppo_stats *out,
+                                                      tj_ppo_stats *internal)
+{
+    float s[3] = {0.f, 0.f, 0.f};
+    for (int b = threadIdx.x; b < n_part; b += 64)
+        for (int q = 0; q < 3; ++q) s[q] += part[(size_t)b * 4 + q];
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s[q] += __shfl_down(s[q], off, 64);
+    if (threadIdx.x == 0) {
+        tj_ppo_stats o;
+        o.loss_pi = s[0] / (float)B;
+        o.loss_v = s[1] / (float)B;
+        o.entropy = s[2] / (float)B;
+        o.loss = o.loss_pi + c_v * o.loss_v - c_e * o.entropy;
+        o.step = t_next;
+        *internal = o;
+        if (out) *out = o;
+    }
+}
+
+// Splits head rows [n][ldz] into logits [n][A] and values [n].
+__global__ __launch_bounds__(256) void split_head(const float *__restrict__ Z, int ldz, uint32_t n, int A,
+                                                  float *__restrict__ logits, float *__restrict__ value)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float *z = Z + (size_t)j * ldz;
+    if (logits)
+        for (int k = 0; k < A; ++k) logits[(size_t)j * A + k] = z[k];
+    if (value) value[j] = z[A];
+}
+
 struct LayerPlan {
     int in, out;           // features
     int ld_in, ld_out;     // padded pitches (elements of T)
@@ -553,6 +711,9 @@ struct tj_learner {
     virtual int set_state(int which, const float *h_in, size_t n, hipStream_t st) = 0;
     virtual int infer(uint32_t n, const void *d_obs, float epsilon, uint64_t seed, int32_t *d_action,
                     int32_t *d_version, float *d_q, hipStream_t st) = 0;
+    // on-policy learners only
+    virtual int ppo_step(const tj_ppo_batch *, tj_ppo_stats *, hipStream_t) { return TJ_ERR_INVALID_ARG; }
+    virtual int ppo_evaluate(uint32_t, const float *, float *, float *, hipStream_t) { return TJ_ERR_INVALID_ARG; }
     uint64_t t = 0;
     hipEvent_t ev[5];
     bool timed = false;
@@ -627,6 +788,7 @@ template <typename T> struct MlpLearner : tj_learner {
     static constexpr int VE = TjElem<T>::kVec;
     tj_learner_desc d;
     int L = 0, A = 0, Bmax = 0, ldB = 0, ldA = 0, S = 1;
+    int n_pass = 3;                        // stacked forward passes: s, s' (online), s' (target); 1 = on-policy
     size_t P = 0, Ppad = 0;
     std::vector<LayerPlan> lay;
     float *theta_on = nullptr, *theta_tg = nullptr, *m = nullptr, *v = nullptr, *gpart = nullptr;
@@ -683,7 +845,7 @@ template <typename T> struct MlpLearner : tj_learner {
         size_t act0 = a.off;
         act_begin = base ? (uint8_t *)base + act0 : nullptr;
         for (int l = 0; l < L; ++l) {
-            const size_t rows = l == 0 ? 2 * (size_t)Bmax : 3 * (size_t)Bmax;
+            const size_t rows = (size_t)(n_pass == 1 ? 1 : (l == 0 ? 2 : 3)) * Bmax;
             X[l] = (T *)a.take(rows * lay[l].ld_in * sizeof(T));
             XT[l] = (T *)a.take((size_t)lay[l].in * ldB * sizeof(T));
         }
@@ -692,12 +854,15 @@ template <typename T> struct MlpLearner : tj_learner {
             dZT[l] = (T *)a.take((size_t)lay[l - 1].out * ldB * sizeof(T));
         }
         act_bytes = a.off - act0;
-        Qout = (float *)a.take(3 * (size_t)Bmax * ldA * 4);
+        Qout = (float *)a.take((size_t)n_pass * Bmax * ldA * 4);
         astar = (int32_t *)a.take((size_t)Bmax * 4);
         loss_part = (float *)a.take((size_t)((Bmax + kHeadRows - 1) / kHeadRows) * 4);
         stats_internal = (tj_step_stats *)a.take(sizeof(tj_step_stats));
+        plan_more(a);
         return a.off;
     }
+
+    virtual void plan_more(TjArena &) {}   // further pieces of a derived learner
 
     // fp32 master -> compute-type copies (and transposes for the online net)
     // Adam writes the straight copy of every weight block whose rows need no padding
@@ -730,7 +895,6 @@ template <typename T> struct MlpLearner : tj_learner {
             if (last_batch > B) TJ_HIP_TRY(hipMemsetAsync(act_begin, 0, act_bytes, st));
             last_batch = B;
         }
-        const int Kb = round_up(B, VE);
 
         // network input: [s ; s'] in compute type, and the transpose of s
         {
@@ -772,8 +936,17 @@ template <typename T> struct MlpLearner : tj_learner {
             if ((rc = run_head_td<T>(this, h, mb, d.gamma, d.huber_delta, st)) != TJ_OK) return rc;
         }
         if ((rc = mark(2, st)) != TJ_OK) return rc;
+        return backward_update(B, td_blocks<T>(B, A), d_stats, st);
+    }
 
-        // backward through Q_online(s).  The weight gradient and the input gradient of a layer both
+    // From dZ[L] / dZT[L] (gradient wrt the head's output, and its transpose) to the updated
+    // parameters: backward GEMMs, slice reduction, Adam, refreshed weight copies, target sync.
+    // n_loss_part per-block loss sums in loss_part are folded into the step's statistics.
+    int backward_update(int B, int n_loss_part, tj_step_stats *d_stats, hipStream_t st)
+    {
+        int rc;
+        const int Kb = round_up(B, VE);
+        // backward through the online network on s.  The weight gradient and the input gradient of a layer both
         // start from dZ_l and are independent: one paired launch where the kernels allow it.
         for (int l = L; l >= 1; --l) {
             const LayerPlan &lp = lay[l - 1];
@@ -831,7 +1004,7 @@ template <typename T> struct MlpLearner : tj_learner {
             tab.end[tab.n] = lay[l].w_off + (size_t)lay[l].in * lay[l].out;
             tab.dst[tab.n++] = Wc_on[l];
         }
-        const LossFinal lf = {loss_part, td_blocks<T>(B, A), B, (uint32_t)t, d_stats, stats_internal};
+        const LossFinal lf = {loss_part, n_loss_part, B, (uint32_t)t, d_stats, stats_internal};
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, 1, Ppad, P, d.lr,
                                                                       d.beta1, d.beta2, d.eps, c1, c2, tab, lf);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
@@ -850,7 +1023,7 @@ template <typename T> struct MlpLearner : tj_learner {
             float *d_q, hipStream_t st) override
     {
         const int n = (int)n_;
-        if (n < 1 || n > 2 * Bmax) return TJ_ERR_SHAPE;
+        if (n < 1 || n > (n_pass == 1 ? 1 : 2) * Bmax) return TJ_ERR_SHAPE;
         if (!d_obs || !d_action || !d_version || !(epsilon >= 0.f && epsilon <= 1.f)) return TJ_ERR_INVALID_ARG;
         int rc;
         CastJobs<T> jobs;
@@ -937,6 +1110,100 @@ template <typename T> struct MlpLearner : tj_learner {
         if (which == TJ_STATE_TARGET) rc = recast(false, st);
         TJ_HIP_TRY(hipStreamSynchronize(st));
         return rc;
+    }
+};
+
+// Actor-critic MLP (shared trunk; head = A logits + 1 value) updated with the clipped objective on
+// the whole batch.  One forward pass (no target network, no s'), so the activation buffers hold
+// max_batch rows; backward, slice reduction, Adam and the weight copies are the Q-learner's.
+template <typename T> struct PpoLearner : MlpLearner<T> {
+    using Base = MlpLearner<T>;
+    tj_ppo_desc pd;
+    float *ppo_part = nullptr;
+    tj_ppo_stats *ppo_stats = nullptr;
+
+    void plan_more(TjArena &a) override
+    {
+        ppo_part = (float *)a.take((size_t)((this->Bmax + 255) / 256) * 4 * 4);
+        ppo_stats = (tj_ppo_stats *)a.take(sizeof(tj_ppo_stats));
+    }
+
+    int step(const tj_minibatch *, tj_step_stats *, hipStream_t) override { return TJ_ERR_INVALID_ARG; }
+    int infer(uint32_t, const void *, float, uint64_t, int32_t *, int32_t *, float *, hipStream_t) override
+    {
+        return TJ_ERR_INVALID_ARG;
+    }
+
+    // forward of n rows of fp32 observations through the trunk and the head; head rows in Qout
+    int forward(int n, const float *d_obs, bool keep_transposes, hipStream_t st)
+    {
+        int rc;
+        const auto &lay = this->lay;
+        CastJobs<T> jobs;
+        jobs.job[0] = {d_obs, this->X[0], keep_transposes ? this->XT[0] : nullptr, n, lay[0].in, lay[0].ld_in,
+                       this->ldB};
+        if ((rc = launch_cast<T>(jobs, 1, st)) != TJ_OK) return rc;
+        if (keep_transposes && (rc = this->mark(0, st)) != TJ_OK) return rc;
+        for (int l = 0; l < this->L; ++l) {
+            TjGemmArgs<T> g;
+            memset(&g, 0, sizeof(g));
+            g.n_seg = 1;
+            g.seg[0] = {0, n, this->Wc_on[l], this->theta_on + lay[l].b_off, 0};
+            g.Q = this->X[l];
+            g.ldp = lay[l].ld_in; g.ldq = lay[l].ld_in;
+            g.I = lay[l].out; g.K = lay[l].ld_in;
+            g.k_chunk = g.K; g.n_split = 1;
+            if (l + 1 < this->L) {
+                g.relu = 1;
+                g.Ci = this->X[l + 1]; g.ldci = lay[l].ld_out;
+                if (keep_transposes) { g.Cj = this->XT[l + 1]; g.ldcj = this->ldB; g.cj_jmax = n; }
+            } else {
+                g.Cf = this->Qout; g.ldcf = this->ldA;
+            }
+            if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
+        }
+        return TJ_OK;
+    }
+
+    int ppo_step(const tj_ppo_batch *pb, tj_ppo_stats *d_stats, hipStream_t st) override
+    {
+        const int B = (int)pb->batch;
+        if (B < 1 || B > this->Bmax) return TJ_ERR_SHAPE;
+        if (!pb->obs || !pb->action || !pb->old_logp || !pb->adv || !pb->ret) return TJ_ERR_INVALID_ARG;
+        int rc;
+        if (this->last_batch != B) {
+            // pad columns beyond the batch must read as zero in the batch contraction
+            if (this->last_batch > B) TJ_HIP_TRY(hipMemsetAsync(this->act_begin, 0, this->act_bytes, st));
+            this->last_batch = B;
+        }
+        if ((rc = forward(B, pb->obs, true, st)) != TJ_OK) return rc;
+        if ((rc = this->mark(1, st)) != TJ_OK) return rc;
+        const auto &lh = this->lay[this->L - 1];
+        PpoHeadArgs<T> a;
+        a.Z = this->Qout; a.ldz = this->ldA; a.B = B; a.A = this->A - 1;
+        a.action = pb->action; a.old_logp = pb->old_logp; a.adv = pb->adv; a.ret = pb->ret;
+        a.clip = pd.clip; a.c_v = pd.c_v; a.c_e = pd.c_e;
+        a.dZ = this->dZ[this->L]; a.lddz = lh.ld_out; a.dZT = this->dZT[this->L]; a.lddzt = this->ldB;
+        a.part = ppo_part;
+        const int nblk = (B + 255) / 256;
+        ppo_head<T><<<nblk, 256, 0, st>>>(a);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        ppo_stats_final<<<1, 64, 0, st>>>(ppo_part, nblk, B, pd.c_v, pd.c_e, (uint32_t)(this->t + 1), d_stats,
+                                          ppo_stats);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        if ((rc = this->mark(2, st)) != TJ_OK) return rc;
+        return this->backward_update(B, 0, nullptr, st);
+    }
+
+    int ppo_evaluate(uint32_t n_, const float *d_obs, float *d_logits, float *d_value, hipStream_t st) override
+    {
+        const int n = (int)n_;
+        if (n < 1 || n > this->Bmax) return TJ_ERR_SHAPE;
+        if (!d_obs || (!d_logits && !d_value)) return TJ_ERR_INVALID_ARG;
+        int rc;
+        if ((rc = forward(n, d_obs, false, st)) != TJ_OK) return rc;
+        split_head<<<(n + 255) / 256, 256, 0, st>>>(this->Qout, this->ldA, n_, this->A - 1, d_logits, d_value);
+        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
     }
 };
 
@@ -1752,6 +2019,116 @@ int tj_learner_set_step(tj_learner *l, uint64_t t)
     if (!l) return TJ_ERR_INVALID_ARG;
     l->t = t;
     return TJ_OK;
+}
+
+}  // extern "C"
+
+// ---- on-policy workload
+
+namespace {
+
+bool ppo_desc_ok(const tj_ppo_desc *d)
+{
+    if (!d || !d->obs_dim || !d->max_batch || d->n_actions < 1 || d->n_actions > 63) return false;
+    if (d->n_hidden + 1 > TJ_MAX_LAYERS) return false;
+    if (d->precision != TJ_PRECISION_FP32 && d->precision != TJ_PRECISION_BF16) return false;
+    for (uint32_t i = 0; i < d->n_hidden; ++i)
+        if (!d->hidden[i]) return false;
+    return d->clip > 0.f && d->clip < 1.f && d->c_v >= 0.f && d->c_e >= 0.f;
+}
+
+// the network as a layer chain: hidden layers, then n_actions logits + 1 value
+tj_learner_desc ppo_network(const tj_ppo_desc *d)
+{
+    tj_learner_desc n;
+    memset(&n, 0, sizeof(n));
+    n.n_layers = d->n_hidden + 1;
+    for (uint32_t i = 0; i < d->n_hidden; ++i) n.layers[i] = {TJ_LAYER_LINEAR, d->hidden[i], 0, 0};
+    n.layers[d->n_hidden] = {TJ_LAYER_LINEAR, d->n_actions + 1, 0, 0};
+    n.in_c = d->obs_dim; n.in_h = 1; n.in_w = 1;
+    n.obs_dtype = TJ_OBS_F32;
+    n.precision = d->precision;
+    n.max_batch = d->max_batch;
+    n.lr = d->lr; n.beta1 = d->beta1; n.beta2 = d->beta2; n.eps = d->eps;
+    n.target_interval = 0;
+    return n;
+}
+
+template <typename T> size_t measure_ppo(const tj_ppo_desc *d)
+{
+    PpoLearner<T> l;
+    l.d = ppo_network(d);
+    l.n_pass = 1;
+    return l.plan(nullptr);
+}
+
+template <typename T>
+int create_ppo(const tj_ppo_desc *d, void *arena, size_t bytes, const float *h_theta, hipStream_t st, tj_learner **out)
+{
+    PpoLearner<T> *l = new PpoLearner<T>();
+    l->pd = *d;
+    l->d = ppo_network(d);
+    l->n_pass = 1;
+    const size_t need = l->plan(nullptr);
+    if (bytes < need) { delete l; return TJ_ERR_ARENA_TOO_SMALL; }
+    l->plan(arena);
+    int rc = TJ_OK;
+    if (hipMemsetAsync(arena, 0, need, st) != hipSuccess) rc = TJ_ERR_DEVICE;
+    if (rc == TJ_OK) rc = l->set_state(TJ_STATE_PARAMS, h_theta, l->P, st);
+    if (rc != TJ_OK) { delete l; return rc; }
+    *out = l;
+    return TJ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tj_gae(uint32_t n_env, uint32_t T, const float *d_reward, const float *d_value, const uint8_t *d_done, float gamma,
+           float lambda, float *d_adv, float *d_ret, void *hip_stream)
+{
+    if (!d_reward || !d_value || !d_done || !d_adv || !d_ret) return TJ_ERR_INVALID_ARG;
+    if (!(gamma >= 0.f && gamma <= 1.f) || !(lambda >= 0.f && lambda <= 1.f)) return TJ_ERR_INVALID_ARG;
+    if (n_env == 0 || T == 0) return TJ_OK;
+    gae_scan<<<(n_env + 3) / 4, 256, 0, (hipStream_t)hip_stream>>>(n_env, T, d_reward, d_value, d_done, gamma, lambda,
+                                                                    d_adv, d_ret);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+size_t tj_ppo_num_params(const tj_ppo_desc *d)
+{
+    if (!ppo_desc_ok(d)) return 0;
+    const tj_learner_desc n = ppo_network(d);
+    return tj_learner_num_params(&n);
+}
+
+size_t tj_ppo_arena_bytes(const tj_ppo_desc *d)
+{
+    if (!ppo_desc_ok(d)) return 0;
+    return d->precision == TJ_PRECISION_BF16 ? measure_ppo<tj_bf16>(d) : measure_ppo<float>(d);
+}
+
+int tj_ppo_create(const tj_ppo_desc *d, void *dev_arena, size_t arena_bytes, const float *h_init, void *hip_stream,
+                  tj_learner **out)
+{
+    if (!out) return TJ_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!ppo_desc_ok(d) || !dev_arena || ((uintptr_t)dev_arena & 255) || !h_init) return TJ_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    return d->precision == TJ_PRECISION_BF16 ? create_ppo<tj_bf16>(d, dev_arena, arena_bytes, h_init, st, out)
+                                             : create_ppo<float>(d, dev_arena, arena_bytes, h_init, st, out);
+}
+
+int tj_ppo_step(tj_learner *l, const tj_ppo_batch *batch, tj_ppo_stats *d_stats, void *hip_stream)
+{
+    if (!l || !batch) return TJ_ERR_INVALID_ARG;
+    return l->ppo_step(batch, d_stats, (hipStream_t)hip_stream);
+}
+
+int tj_ppo_evaluate(tj_learner *l, uint32_t n, const float *d_obs, float *d_logits, float *d_value, void *hip_stream)
+{
+    if (!l) return TJ_ERR_INVALID_ARG;
+    return l->ppo_evaluate(n, d_obs, d_logits, d_value, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

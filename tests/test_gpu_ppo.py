@@ -1,0 +1,247 @@
+"""GPU parity of the on-policy workload (advantage estimation, clipped actor-critic update)
+against the CPU oracle, through the C ABI.
+
+Tolerances (relative, per tensor: max|a-b| / max|b|): 1e-5 for the fp32 advantage scan, 1e-4 for
+fp32 updates, 2e-2 for bf16 GEMM operands with fp32 accumulation.  Inputs come from the seeded
+generators; the oracle never receives anything from the GPU."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from paper_2502_20190_amd import synth
+from parity_util import rel_max, rel_scalar
+
+pytestmark = pytest.mark.gpu
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def tj():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2502_20190_amd import binding
+
+    binding.lib()
+    return binding
+
+
+def _dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# ---------------------------------------------------------------- advantage estimation
+
+@pytest.mark.parametrize("n_env,T,done_p", [(8, 512, 0.01), (3, 17, 0.3), (5, 513, 0.02), (64, 512, 0.01),
+                                            (1, 1, 0.0), (2, 1030, 0.005), (7, 8, 0.5), (6, 511, 0.0),
+                                            (4, 64, 1.0)])
+def test_gae_matches_oracle(tj, orc, n_env, T, done_p):
+    import torch
+
+    ro = synth.make_rollouts(4, 2, n_env, T, seed=n_env * 1000 + T, done_p=done_p)
+    adv, ret = tj.gae(_dev(ro["reward"]), _dev(ro["value"]), _dev(ro["done"]), 0.99, 0.95)
+    torch.cuda.synchronize()
+    oadv, oret = orc.gae(ro["reward"], ro["value"], ro["done"], float(np.float32(0.99)), float(np.float32(0.95)))
+    assert rel_max(adv.cpu().numpy(), oadv) < 1e-5
+    assert rel_max(ret.cpu().numpy(), oret) < 1e-5
+
+
+def test_gae_full_size_and_degenerate_calls(tj, orc):
+    """The benchmark's rollout shape (64 environments x 512 steps), other discount settings, and
+    the calls that do nothing or are refused."""
+    import torch
+
+    ro = synth.make_rollouts(4, 2, 64, 512, seed=5)
+    r, v, d = _dev(ro["reward"]), _dev(ro["value"]), _dev(ro["done"])
+    for gamma, lam in ((1.0, 1.0), (0.9, 0.0), (0.0, 0.5)):
+        adv, ret = tj.gae(r, v, d, gamma, lam)
+        oadv, oret = orc.gae(ro["reward"], ro["value"], ro["done"], gamma, lam)
+        assert rel_max(adv.cpu().numpy(), oadv) < 1e-5 and rel_max(ret.cpu().numpy(), oret) < 1e-5
+    L = tj.lib()
+    out = torch.zeros(4, device="cuda")
+    assert L.tj_gae(0, 512, r.data_ptr(), v.data_ptr(), d.data_ptr(), 0.99, 0.95, out.data_ptr(), out.data_ptr(),
+                    None) == tj.TJ_OK
+    assert L.tj_gae(4, 0, r.data_ptr(), v.data_ptr(), d.data_ptr(), 0.99, 0.95, out.data_ptr(), out.data_ptr(),
+                    None) == tj.TJ_OK
+    assert L.tj_gae(4, 8, None, v.data_ptr(), d.data_ptr(), 0.99, 0.95, out.data_ptr(), out.data_ptr(),
+                    None) == tj.TJ_ERR_INVALID_ARG
+    assert L.tj_gae(4, 8, r.data_ptr(), v.data_ptr(), d.data_ptr(), 1.5, 0.95, out.data_ptr(), out.data_ptr(),
+                    None) == tj.TJ_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert not out.any()
+
+
+# ---------------------------------------------------------------- clipped update
+
+HYPER = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-5)      # the PPO column of the hyperparameter table
+COEF = dict(clip=0.2, c_v=0.5, c_e=0.01)
+
+
+def _pair(tj, orc, obs_dim, hidden, A, precision, max_batch, seed=0, lr=None):
+    layers = synth.ppo_layers(hidden, A)
+    theta = synth.xavier_init(layers, (obs_dim, 1, 1), seed)
+    theta = (theta + 0.02 * np.random.default_rng(seed + 50).standard_normal(theta.size)).astype(np.float32)
+    hyper = dict(HYPER)
+    if lr is not None:
+        hyper["lr"] = lr
+    g = tj.PpoLearner(obs_dim, hidden, A, precision, max_batch, theta, **hyper, **COEF)
+    o = orc.Learner(layers, (obs_dim, 1, 1), emulate_bf16=(precision == "bf16"), **hyper)
+    o.set_state(orc.PARAMS, theta.astype(np.float64))
+    return g, o
+
+
+def _batch(orc, o, obs_dim, A, n_env, T, seed, precision, n=None):
+    """Rollouts -> flat batch with oracle-side advantages.  For fp32 comparisons at 1e-4, rows
+    within float noise of a ReLU kink or of the clipping boundary (where the gradient jumps by
+    O(1/B) in single rows) are re-drawn from another seed; the selection uses the oracle's own
+    forward pass."""
+    def draw(s):
+        ro = synth.make_rollouts(obs_dim, A, n_env, T, seed=s)
+        adv, ret = orc.gae(ro["reward"], ro["value"], ro["done"], 0.99, 0.95)
+        return dict(obs=ro["obs"], action=ro["action"], old_logp=ro["old_logp"],
+                    adv=adv.ravel().astype(np.float32), ret=ret.ravel().astype(np.float32))
+
+    rows = draw(seed)
+    if n is not None:
+        rows = {k: v[:n] for k, v in rows.items()}
+    if precision == "bf16":
+        return rows
+    for it in range(20):
+        z = o.forward(0, rows["obs"])[:, :A]
+        logp = z[np.arange(len(z)), rows["action"]] - np.log(np.exp(z - z.max(1, keepdims=True)).sum(1)) - z.max(1)
+        rho = np.exp(logp - rows["old_logp"])
+        bad = (o.min_abs_preactivation(rows["obs"]) <= 5e-6) | (np.abs(rho - 0.8) < 1e-4) | (np.abs(rho - 1.2) < 1e-4)
+        if not bad.any():
+            return rows
+        repl = draw(seed + 7919 * (it + 1))
+        for f in rows:
+            rows[f][bad] = repl[f][: len(bad)][bad]
+    raise AssertionError("no batch clear of the kinks found")
+
+
+def _sync(tj, orc, g, o):
+    """The GPU learner takes the oracle's state (never the other way round)."""
+    g.set_state(tj.TJ_STATE_PARAMS, o.get_state(orc.PARAMS))
+    g.set_state(tj.TJ_STATE_ADAM_M, o.get_state(orc.ADAM_M))
+    g.set_state(tj.TJ_STATE_ADAM_V, o.get_state(orc.ADAM_V))
+    assert tj.lib().tj_learner_set_step(g.h, o.t) == tj.TJ_OK
+
+
+def _step_both(tj, orc, g, o, rows, tol, sync=False):
+    if sync:
+        _sync(tj, orc, g, o)
+    dev = {k: _dev(v) for k, v in rows.items()}
+    assert g.step(dev["obs"], dev["action"], dev["old_logp"], dev["adv"], dev["ret"]) == tj.TJ_OK
+    ostats = o.ppo_step(rows["obs"], rows["action"], rows["old_logp"], rows["adv"], rows["ret"], **COEF)
+    gs = g.read_stats()
+    assert gs[4] == o.t
+    worst = {name: rel_scalar(gs[i], ostats[i]) for i, name in enumerate(("loss_pi", "loss_v", "entropy", "loss"))}
+    # the policy term averages signed numbers and may sit near zero: measure it against the
+    # scale of its summands
+    scale = float(np.abs(rows["adv"]).mean())
+    worst["loss_pi"] = abs(gs[0] - ostats[0]) / max(abs(ostats[0]), scale)
+    worst["loss"] = abs(gs[3] - ostats[3]) / max(abs(ostats[3]), scale)
+    worst["grad"] = rel_max(g.get_state(tj.TJ_STATE_GRADS), o.get_state(orc.GRADS))
+    worst["theta"] = rel_max(g.get_state(tj.TJ_STATE_PARAMS), o.get_state(orc.PARAMS))
+    worst["m"] = rel_max(g.get_state(tj.TJ_STATE_ADAM_M), o.get_state(orc.ADAM_M))
+    worst["v"] = rel_max(g.get_state(tj.TJ_STATE_ADAM_V), o.get_state(orc.ADAM_V))
+    bad = {k: v for k, v in worst.items() if not v < tol}
+    assert not bad, f"beyond {tol}: {bad} (all: {worst})"
+    return worst
+
+
+def test_p1_classic_control_free_running(tj, orc):
+    """The small on-policy configuration (4 observations, 256-256 trunk, 2 actions, 8 rollouts
+    of 512 steps = batch 4096, fp32): five successive updates on the same batch, as the epochs
+    of one PPO iteration; the ratio drifts from the behaviour policy's, clipping sets in."""
+    _, D, hidden, A, n_env, T, prec = synth.PPO_WORKLOADS["p1"]
+    g, o = _pair(tj, orc, D, hidden, A, prec, n_env * T, seed=1, lr=1e-3)
+    rows = _batch(orc, o, D, A, n_env, T, 10, prec)
+    theta0 = o.get_state(orc.PARAMS)
+    for it in range(5):
+        worst = _step_both(tj, orc, g, o, rows, TOL[prec], sync=it > 0)
+    # the update itself, not just the weights
+    du_g = g.get_state(tj.TJ_STATE_PARAMS).astype(np.float64) - theta0
+    du_o = o.get_state(orc.PARAMS) - theta0
+    assert rel_max(du_g, du_o) < 1e-3
+    print("p1 worst relative errors at the fifth step:", worst)
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_ragged_shapes_and_batch_changes(tj, orc, precision):
+    """Widths and batches that are multiples of nothing, a batch that shrinks and grows again
+    (pad columns of the transposed activations must read as zero), 63 actions (the most the
+    head kernel accepts)."""
+    for (D, hidden, A) in ((19, (70, 33), 5), (130, (200,), 63), (7, (), 3)):
+        g, o = _pair(tj, orc, D, hidden, A, precision, 700, seed=3, lr=1e-3)
+        for i, n in enumerate((700, 100, 257)):
+            rows = _batch(orc, o, D, A, 2, 350, 20 + i, precision, n=n)
+            _step_both(tj, orc, g, o, rows, TOL[precision], sync=True)
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_multi_tile_trunk(tj, orc, precision):
+    D, hidden, A = 96, (384, 320), 17
+    g, o = _pair(tj, orc, D, hidden, A, precision, 1536, seed=4, lr=1e-3)
+    rows = _batch(orc, o, D, A, 3, 512, 30, precision)
+    _step_both(tj, orc, g, o, rows, TOL[precision])
+    _step_both(tj, orc, g, o, rows, TOL[precision], sync=True)
+
+
+def test_p2_full_size_step(tj, orc):
+    """The large on-policy configuration at full size (256 observations, 1024-1024-1024 trunk,
+    31 actions + value, 64 rollouts of 512 steps = batch 32768, bf16), the launch configuration
+    the benchmark times, against the bf16-rounding oracle."""
+    _, D, hidden, A, n_env, T, prec = synth.PPO_WORKLOADS["p2"]
+    g, o = _pair(tj, orc, D, hidden, A, prec, n_env * T, seed=7)
+    rows = _batch(orc, o, D, A, n_env, T, 40, prec)
+    print("p2 full-size worst relative errors:", _step_both(tj, orc, g, o, rows, TOL[prec]))
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_evaluate_matches_oracle_forward(tj, orc, precision):
+    import torch
+
+    D, hidden, A = 24, (128, 64), 6
+    g, o = _pair(tj, orc, D, hidden, A, precision, 512, seed=8)
+    obs = synth.make_rollouts(D, A, 1, 300, seed=2)["obs"]
+    logits, value = g.evaluate(_dev(obs))
+    torch.cuda.synchronize()
+    z = o.forward(0, obs)
+    assert rel_max(logits.cpu().numpy(), z[:, :A]) < TOL[precision]
+    assert rel_max(value.cpu().numpy(), z[:, A]) < TOL[precision]
+
+
+def test_argument_errors(tj, orc):
+    import torch
+
+    g, o = _pair(tj, orc, 8, (32,), 4, "fp32", 64, seed=9)
+    rows = _batch(orc, o, 8, 4, 1, 128, 3, "fp32")
+    dev = {k: _dev(v) for k, v in rows.items()}
+    # more rows than max_batch
+    assert g.step(dev["obs"], dev["action"], dev["old_logp"], dev["adv"], dev["ret"]) == tj.TJ_ERR_SHAPE
+    L = tj.lib()
+    b = tj.tj_ppo_batch(64, dev["obs"].data_ptr(), None, dev["old_logp"].data_ptr(), dev["adv"].data_ptr(),
+                        dev["ret"].data_ptr())
+    assert L.tj_ppo_step(g.h, C.byref(b), None, None) == tj.TJ_ERR_INVALID_ARG
+    # a Q-learning step or epsilon-greedy inference on an on-policy handle is refused
+    mb = tj.Minibatch(16, 8, "f32")
+    assert L.tj_learner_step(g.h, C.byref(mb.c), None, None) == tj.TJ_ERR_INVALID_ARG
+    # and the other way round
+    wl = synth.WORKLOADS["c1"]
+    q = tj.learner_for_workload(wl, synth.xavier_init(wl.layers, wl.in_chw, 1), synth.xavier_init(wl.layers, wl.in_chw, 2))
+    b.action = dev["action"].data_ptr()
+    assert L.tj_ppo_step(q.h, C.byref(b), None, None) == tj.TJ_ERR_INVALID_ARG
+    # descriptors the library refuses
+    d = tj.tj_ppo_desc()
+    d.obs_dim, d.n_hidden, d.n_actions, d.max_batch = 8, 1, 64, 32
+    d.hidden[0] = 16
+    d.clip, d.c_v, d.c_e = 0.2, 0.5, 0.01
+    assert L.tj_ppo_arena_bytes(C.byref(d)) == 0           # 64 actions: one too many
+    d.n_actions, d.clip = 4, 0.0
+    assert L.tj_ppo_arena_bytes(C.byref(d)) == 0           # no clipping range
+    torch.cuda.synchronize()
+    assert g.read_stats()[4] == 0                           # nothing ran
