@@ -129,12 +129,120 @@ def cpu_baseline(wl, synth, buf, versions, theta, target, budget_rows):
     }
 
 
+def bench_ppo(args):
+    """On-policy workload: a step is advantage estimation over the whole rollout buffer (tj_gae)
+    plus one clipped actor-critic update on it (tj_ppo_step), batch = buffer."""
+    import numpy as np
+    import torch
+
+    from paper_2502_20190_amd import binding as tj, synth
+
+    name, D, hidden, A, n_env, T, precision = synth.PPO_WORKLOADS[args.config]
+    torch.cuda.set_device(0)
+    B = n_env * T
+    layers = synth.ppo_layers(hidden, A)
+    theta = synth.xavier_init(layers, (D, 1, 1), 1)
+    hyper = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-5, clip=0.2, c_v=0.5, c_e=0.01)
+    lrn = tj.PpoLearner(D, hidden, A, precision, B, theta, **hyper)
+    ro = synth.make_rollouts(D, A, n_env, T, seed=1)
+    dev = {k: torch.from_numpy(v).cuda() for k, v in ro.items()}
+    L = tj.lib()
+
+    def one_step():
+        adv, ret = tj.gae(dev["reward"], dev["value"], dev["done"], 0.99, 0.95)
+        rc = lrn.step(dev["obs"], dev["action"], dev["old_logp"], adv.view(-1), ret.view(-1))
+        if rc != tj.TJ_OK:
+            raise tj.TjError(rc, "bench step")
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    K = args.steps
+    every = max(1, args.event_every)
+    sampled = list(range(0, K, every))
+    lev = [tj.HipEvents(5) for _ in sampled]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        if i % every == 0:
+            L.tj_learner_set_phase_events(lrn.h, lev[i // every].ev, 5)
+        elif i % every == 1:
+            L.tj_learner_set_phase_events(lrn.h, None, 0)
+        one_step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    L.tj_learner_set_phase_events(lrn.h, None, 0)
+    stats = lrn.read_stats()
+    assert stats[4] == args.warmup + K and np.isfinite(stats[3])
+
+    # advantage estimation alone (the learner's events start after its input cast)
+    t1 = time.perf_counter()
+    for _ in range(200):
+        tj.gae(dev["reward"], dev["value"], dev["done"], 0.99, 0.95)
+    torch.cuda.synchronize()
+    gae_ms = (time.perf_counter() - t1) / 200 * 1e3
+
+    ms = lambda evs, a, b: sum(e.elapsed_ms(a, b) for e in evs) / len(evs)
+    ph = {"gae_ms_standalone": gae_ms, "forward_gemm_ms": ms(lev, 0, 1), "objective_ms": ms(lev, 1, 2),
+          "backward_gemm_ms": ms(lev, 2, 3), "adam_ms": ms(lev, 3, 4)}
+    shapes = synth.layer_shapes(layers, (D, 1, 1))
+    per_sample = [2 * int(np.prod(ws)) for _, ws, _, _, _ in shapes]
+    flops = B * (2 * sum(per_sample) + sum(per_sample[1:]))     # forward, weight and input gradients
+    n_layers = len(layers)
+    n_launch = n_layers + (n_layers if precision == "bf16" else 2 * n_layers - 1)
+    gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
+    achieved = flops / (gemm_ms * 1e-3) / 1e12
+    P = synth.num_params(layers, (D, 1, 1))
+    adam_bytes = (30 if precision == "bf16" else 28) * P
+    gae_bytes = n_env * T * (4 + 4 + 1 + 4 + 4) + n_env * 4      # reward, value, done in; adv, ret out
+    out = {
+        "metric": "learner transitions consumed/sec at 1 MI355X",
+        "value": B * K / wall, "unit": "transitions/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": precision, "data": "synthetic",
+        "config": {"workload": name, "n_env": n_env, "rollout": T, "batch": B, "obs_elems": D,
+                   "layers": [l[1] for l in layers], "params": P},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[precision], "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_TFLOPS[precision], "traffic": None,
+                     "kernel": "gemm_bf16_dlds + gemm_bf16_dlds_pair" if precision == "bf16" else "gemm_pq<float>",
+                     "launches_per_step": n_launch, "flops_per_launch": flops / n_launch,
+                     "avg_launch_ms": gemm_ms / n_launch},
+        "phases_ms": ph, "phase_events_on_steps": len(sampled),
+        "gae": {"bound": "hbm", "achieved": gae_bytes / (gae_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "bytes": gae_bytes, "frac": gae_bytes / (gae_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                 "unit": "GB/s", "bytes": adam_bytes,
+                 "frac": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "loss": stats[3],
+    }
+    if not args.no_cpu_baseline:
+        from oracle import orc
+
+        rows = args.cpu_rows or max(8, min(B, int(3e11 / (flops / B))))
+        t1 = time.perf_counter()
+        adv, ret = orc.gae(ro["reward"], ro["value"], ro["done"], 0.99, 0.95)
+        t_gae = time.perf_counter() - t1
+        o = orc.Learner(layers, (D, 1, 1), lr=1e-4, eps=1e-5)
+        o.set_state(orc.PARAMS, theta.astype(np.float64))
+        t1 = time.perf_counter()
+        o.ppo_step(ro["obs"][:rows], ro["action"][:rows], ro["old_logp"][:rows], adv.ravel()[:rows],
+                   ret.ravel()[:rows])
+        t_learn = time.perf_counter() - t1
+        out["cpu_baseline"] = {
+            "value": B / (t_gae + t_learn * B / rows), "unit": "transitions/s", "cores": orc.num_threads(),
+            "kind": "oracle",
+            "sample": (f"advantage estimation over all {n_env} x {T} steps ({t_gae * 1e3:.1f} ms) + one fp64 "
+                       f"update on {rows} of the {B} rows ({t_learn:.2f} s), update time scaled by {B}/{rows}"),
+        }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="c3", help="workload: c1 ... c5")
+    ap.add_argument("--config", default="c3", help="workload: c1 ... c5 (replay + double-DQN), p1, p2 (on-policy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's learner step (0 = auto)")
     ap.add_argument("--insert-rows", type=int, default=0,
@@ -154,6 +262,12 @@ def main():
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no collectives are part of it)",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.config.startswith("p"):
+        if args.insert_rows or args.frame_ring or args.actor_rows:
+            print("bench.py: the on-policy workloads take none of the replay-ring options", file=sys.stderr)
+            sys.exit(2)
+        return bench_ppo(args)
 
     import numpy as np
     import torch
