@@ -254,6 +254,10 @@ def main():
     ap.add_argument("--actor-rows", type=int, default=0,
                     help="after the learner loop, also time epsilon-greedy policy inference (tj_actor_act) "
                          "on this many observations per call (at most twice the batch)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the sample of step i+1 on a second stream while step i learns (double-buffered "
+                         "minibatches) instead of one stream, strictly one after the other; measured: no "
+                         "gain, the GEMM kernels leave no registers for a second kernel's waves")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record the per-phase HIP events on every n-th timed step (each event costs "
                          "about 5 us of stream time, so recording them on every step slows the loop)")
@@ -287,18 +291,38 @@ def main():
     theta = synth.xavier_init(wl.layers, wl.in_chw, 1)
     target = synth.xavier_init(wl.layers, wl.in_chw, 2)
     lrn = tj.learner_for_workload(wl, theta, target)
-    mb = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype)
     L = tj.lib()
+    overlap = args.overlap
+    # Buffer loop and learner loop run asynchronously (Section 3.1): the sampler fills minibatch
+    # i % 2 on its own stream while the learner consumes the other one.  Two events per minibatch
+    # order the hand-over in both directions; every step still samples and learns once.
+    mbs = [tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype) for _ in range(2 if overlap else 1)]
+    s_sample = torch.cuda.Stream() if overlap else None
+    s_learn = torch.cuda.Stream() if overlap else None
+    filled = [torch.cuda.Event() for _ in mbs]
+    consumed = [torch.cuda.Event() for _ in mbs]
 
     side = torch.cuda.Stream() if args.insert_rows else None
     fresh = synth.make_chunk_device(wl, synth.MASTER_SEED, 10_000, args.insert_rows) if args.insert_rows else None
+    n_issued = [0]
 
     def one_step(i):
         if fresh is not None:
             buf.insert_concurrent(fresh["obs"], fresh["next_obs"], fresh["action"], fresh["reward"],
                                   fresh["done"], fresh["version"], side)
-        rc = buf.sample(mb, wl.current_version, wl.max_staleness, i)
-        rc = rc or lrn.step(mb)
+        k = n_issued[0] % len(mbs)
+        if overlap:
+            if n_issued[0] >= len(mbs):
+                s_sample.wait_event(consumed[k])
+            rc = buf.sample(mbs[k], wl.current_version, wl.max_staleness, i, stream=s_sample)
+            filled[k].record(s_sample)
+            s_learn.wait_event(filled[k])
+            rc = rc or lrn.step(mbs[k], stream=s_learn)
+            consumed[k].record(s_learn)
+        else:
+            rc = buf.sample(mbs[k], wl.current_version, wl.max_staleness, i)
+            rc = rc or lrn.step(mbs[k])
+        n_issued[0] += 1
         if rc != tj.TJ_OK:
             raise tj.TjError(rc, "bench step")
 
@@ -381,6 +405,7 @@ def main():
                      "kernel": gemm_kernel_name, "launches_per_step": n_gemm_launch,
                      "flops_per_launch": flops / n_gemm_launch, "avg_launch_ms": gemm_ms / n_gemm_launch},
         "phases_ms": ph, "phase_events_on_steps": len(sampled),
+        "sample_learn_overlap": overlap,
         "gather": {"bound": "hbm", "achieved": gather_bytes / (ph["gather_ms"] * 1e-3) / 1e9,
                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": gather_bytes},
         "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9,
