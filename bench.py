@@ -193,7 +193,8 @@ def bench_ppo(args):
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
     achieved = flops / (gemm_ms * 1e-3) / 1e12
     P = synth.num_params(layers, (D, 1, 1))
-    adam_bytes = (30 if precision == "bf16" else 28) * P
+    S = max(1, min(8, B // (1024 if precision == "bf16" else 64)))
+    adam_bytes = ((30 if precision == "bf16" else 28) + (4 * S if S > 1 else 0)) * P
     gae_bytes = n_env * T * (4 + 4 + 1 + 4 + 4) + n_env * 4      # reward, value, done in; adv, ret out
     out = {
         "metric": "learner transitions consumed/sec at 1 MI355X",
@@ -388,6 +389,12 @@ def main():
     peak = PEAK_TFLOPS[wl.precision]
     P = synth.num_params(wl.layers, wl.in_chw)
     adam_bytes = (30 if wl.precision == "bf16" else 28) * P
+    if n_conv == 0:
+        # MLPs: the Adam kernel also sums the S slices of the split weight-gradient contraction
+        # (S more gradient reads, one gradient write)
+        S = max(1, min(8, wl.batch // (1024 if wl.precision == "bf16" else 64)))
+        if S > 1:
+            adam_bytes += 4 * S * P
     gather_bytes = 2 * wl.batch * wl.record_bytes
     if args.frame_ring:   # k + 1 distinct frames read, 2k planes written, plus the scalars
         k, fe = wl.obs_shape[0], wl.obs_shape[1] * wl.obs_shape[2]

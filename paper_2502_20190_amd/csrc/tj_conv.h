@@ -230,24 +230,44 @@ __global__ __launch_bounds__(256) void dgrad_weights(const float *__restrict__ w
     wd[t] = tj_f32_to_bf16(v);
 }
 
-// Sums n_part partial gradient slices of n elements each into dst.  A block owns 32 consecutive
-// elements; its 8 thread rows each add every 8th slice (128-byte coalesced reads), then the 8 sums
-// are added in a fixed order: deterministic for a given n_part.
+// Sums n_part partial gradient slices of n elements each into dst.  A block owns 128 consecutive
+// elements (32 lanes x 16 bytes); its 8 thread rows each add every 8th slice, four loads in flight
+// at a time, then the 8 sums are added in a fixed order: deterministic for a given n_part.
+// Slices start 16-byte aligned and are padded to a multiple of 4 elements (zstride % 4 == 0).
 __global__ __launch_bounds__(256) void reduce_parts(const float *__restrict__ part, size_t zstride, int n_part,
                                                     float *__restrict__ dst, size_t n)
 {
-    __shared__ float sh[8][33];
+    __shared__ float4 sh[8][32];
     const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
-    const size_t e = (size_t)blockIdx.x * 32 + col;
-    float sum = 0.f;
-    if (e < n)
-        for (int z = grp; z < n_part; z += 8) sum += part[(size_t)z * zstride + e];
+    const size_t e = ((size_t)blockIdx.x * 32 + col) * 4;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (e < n) {
+        const float *src = part + e;
+        int z = grp;
+        for (; z + 24 < n_part; z += 32) {
+            float4 p[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[u] = *(const float4 *)(src + (size_t)(z + 8 * u) * zstride);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { sum.x += p[u].x; sum.y += p[u].y; sum.z += p[u].z; sum.w += p[u].w; }
+        }
+        for (; z < n_part; z += 8) {
+            const float4 p = *(const float4 *)(src + (size_t)z * zstride);
+            sum.x += p.x; sum.y += p.y; sum.z += p.z; sum.w += p.w;
+        }
+    }
     sh[grp][col] = sum;
     __syncthreads();
     if (grp != 0 || e >= n) return;
 #pragma unroll
-    for (int g = 1; g < 8; ++g) sum += sh[g][col];
-    dst[e] = sum;
+    for (int g = 1; g < 8; ++g) {
+        const float4 p = sh[g][col];
+        sum.x += p.x; sum.y += p.y; sum.z += p.z; sum.w += p.w;
+    }
+    const float out[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (e + q < n) dst[e + q] = out[q];
 }
 
 }  // namespace tjconv

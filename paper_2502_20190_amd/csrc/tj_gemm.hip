@@ -1184,7 +1184,9 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
             long t = 0;
             for (int s = 0; s < a.n_seg; ++s) t += (a.seg[s].j_end - a.seg[s].j_begin + 127) / 128;
             t *= (long)((a.I + 255) / 256) * a.n_split;
-            return t > 256 ? launch_dlds<2, 64, 3>(a, st) : launch_dlds<2, TJ_CFG2>(a, st);
+            if (t > 256) return launch_dlds<2, 64, 3>(a, st);
+            // at most half the CUs would get a 128-wide tile: 64-wide tiles give twice the blocks
+            return t <= 128 ? launch_dlds<1, 128, 3>(a, st) : launch_dlds<2, TJ_CFG2>(a, st);
         }
         if (best == 3) return launch_dlds<3, TJ_CFG3>(a, st);
         return launch_dlds<4, TJ_CFG4>(a, st);

@@ -421,11 +421,12 @@ struct LossFinal {
 };
 
 // Adam on the flat fp32 master state (bias-corrected, eps outside the square root); the gradient
-// is the sum of S slices (S = 1 when the weight-gradient GEMMs reduced their own split).  Also
-// emits the compute-type copy of the weights: 16 B read and 12 B + sizeof(T) written per parameter.
+// is the sum of S slices (split batch contraction of the weight-gradient GEMMs), added in slice
+// order and written back to slice 0.  Also emits the compute-type copy of the weights: with one
+// slice 16 B read and 12 B + sizeof(T) written per parameter.
 template <typename T>
 __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, float *__restrict__ m,
-                                                   float *__restrict__ v, const float *__restrict__ gpart,
+                                                   float *__restrict__ v, float *__restrict__ gpart,
                                                    int S, size_t gstride, size_t P, float lr, float b1,
                                                    float b2, float eps, float c1, float c2,
                                                    const EmitTable<T> tab, const LossFinal lf)
@@ -447,11 +448,19 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
     if (i >= P) return;
     if (i + 4 <= P) {
         float4 g = ld4_stream(gpart + i);
-        for (int s = 1; s < S; ++s) {
-            const float4 p = ld4_stream(gpart + (size_t)s * gstride + i);
-            g.x += p.x; g.y += p.y; g.z += p.z; g.w += p.w;
-        }
         float4 mm = ld4_stream(m + i), vv = ld4_stream(v + i), th = ld4_stream(theta + i);
+        if (S > 1) {   // slices are added in slice order, eight loads in flight at a time
+            float4 p[8];
+            for (int s0 = 1; s0 < S; s0 += 8) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < S) p[u] = ld4_stream(gpart + (size_t)(s0 + u) * gstride + i);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < S) { g.x += p[u].x; g.y += p[u].y; g.z += p[u].z; g.w += p[u].w; }
+            }
+            *(float4 *)(gpart + i) = g;   // slice 0 keeps the step's gradient
+        }
         float ga[4] = {g.x, g.y, g.z, g.w}, ma[4] = {mm.x, mm.y, mm.z, mm.w};
         float va[4] = {vv.x, vv.y, vv.z, vv.w}, ta[4] = {th.x, th.y, th.z, th.w};
 #pragma unroll
@@ -477,6 +486,7 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
         for (size_t e = i; e < P; ++e) {
             float g = gpart[e];
             for (int s = 1; s < S; ++s) g += gpart[(size_t)s * gstride + e];
+            if (S > 1) gpart[e] = g;
             const float mm = b1 * m[e] + (1.f - b1) * g;
             const float vv = b2 * v[e] + (1.f - b2) * g * g;
             m[e] = mm;
@@ -485,32 +495,6 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
             theta[e] = th;
             for (int k = 0; k < tab.n; ++k)
                 if (e >= tab.begin[k] && e < tab.end[k]) tab.dst[k][e - tab.begin[k]] = TjElem<T>::from_f32(th);
-        }
-    }
-}
-
-// Adds the split slices 1..S-1 of the flat gradient into slice 0 (fixed order: deterministic).
-__global__ __launch_bounds__(256) void reduce_slices(float *__restrict__ g, size_t gstride, int S, size_t n)
-{
-    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (i >= n) return;
-    if (i + 4 <= n) {
-        float4 p[8];
-        float4 sum = ld4_stream(g + i);
-        for (int s0 = 1; s0 < S; s0 += 8) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (s0 + u < S) p[u] = ld4_stream(g + (size_t)(s0 + u) * gstride + i);
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (s0 + u < S) { sum.x += p[u].x; sum.y += p[u].y; sum.z += p[u].z; sum.w += p[u].w; }
-        }
-        *(float4 *)(g + i) = sum;
-    } else {
-        for (size_t e = i; e < n; ++e) {
-            float sum = g[e];
-            for (int s = 1; s < S; ++s) sum += g[(size_t)s * gstride + e];
-            g[e] = sum;
         }
     }
 }
@@ -988,11 +972,7 @@ template <typename T> struct MlpLearner : tj_learner {
             if (l >= 2 && (rc = tj_gemm<T>(gd, st)) != TJ_OK) return rc;
         }
 
-        if (S > 1) {   // the split slices of every weight gradient are summed, in slice order, into slice 0
-            reduce_slices<<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(gpart, Ppad, S, P);
-            if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
-        }
-        if ((rc = mark(3, st)) != TJ_OK) return rc;
+        if ((rc = mark(3, st)) != TJ_OK) return rc;   // the S slices of the gradient are summed by the Adam kernel
         t += 1;
         const float c1 = (float)(1.0 - pow((double)d.beta1, (double)t));
         const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
@@ -1005,7 +985,7 @@ template <typename T> struct MlpLearner : tj_learner {
             tab.dst[tab.n++] = Wc_on[l];
         }
         const LossFinal lf = {loss_part, n_loss_part, B, (uint32_t)t, d_stats, stats_internal};
-        adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, 1, Ppad, P, d.lr,
+        adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S, Ppad, P, d.lr,
                                                                       d.beta1, d.beta2, d.eps, c1, c2, tab, lf);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
@@ -1606,7 +1586,7 @@ template <typename T> struct ConvLearner : tj_learner {
                     wa.m_chunk = round_up((int)((Ms + y.n_split - 1) / y.n_split), 32);
                     if ((rc = tj_conv_wgrad(wa, st)) != TJ_OK) return rc;
                     const size_t n = (size_t)y.O * y.K + y.O;   // weights, then bias: one block of the gradient
-                    tjconv::reduce_parts<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride,
+                    tjconv::reduce_parts<<<dim3((unsigned)((n + 127) / 128)), 256, 0, st>>>(y.part, y.part_stride,
                                                                                          y.n_split, grad + y.w_off, n);
                     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
                     wgrad_done = true;
@@ -1629,7 +1609,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.qsum = y.part + (size_t)y.O * y.K; gm.qsum_zstride = y.part_stride;
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
                 const size_t n = (size_t)y.O * y.K + y.O;
-                tjconv::reduce_parts<<<dim3((unsigned)((n + 31) / 32)), 256, 0, st>>>(y.part, y.part_stride, ns,
+                tjconv::reduce_parts<<<dim3((unsigned)((n + 127) / 128)), 256, 0, st>>>(y.part, y.part_stride, ns,
                                                                                      grad + y.w_off, n);
                 if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
             }

@@ -293,6 +293,29 @@ def test_gathered_conv_operands_with_ragged_batches(tj, orc):
         _step_both(tj, orc, g, o, wl, _batch(wl, 360 + step, b), TOL["bf16"], sync=step > 0)
 
 
+@pytest.mark.parametrize("hw,batch", [(36, 300), (100, 140)])
+def test_first_conv_kernel_loops_over_images(tj, orc, hw, batch):
+    """More images (2 x batch) than the fused first-convolution kernel has blocks (one per CU), so
+    every block walks several images: register prefetch of the next frame stack, hand-over between
+    the image buffers.  36 x 36 frames fit two image buffers in LDS, 100 x 100 frames only one (the
+    variant with two barriers per image)."""
+    from paper_2502_20190_amd.synth import CONV
+
+    wl = _conv_workload("bf16", batch=batch, in_chw=(4, hw, hw),
+                        layers=((CONV, 32, 8, 4), (CONV, 64, 4, 2), (LIN, 24, 0, 0), (LIN, 6, 0, 0)), n_actions=6)
+    g, o = _pair(tj, orc, wl, seed=15)
+    _step_both(tj, orc, g, o, wl, _batch(wl, 380), TOL["bf16"])
+
+
+def test_c5_full_batch_step(tj, orc):
+    """Config 5's learner step at full size (Nature-DQN network, batch 2048, bf16), the launch
+    configuration the benchmark times for the pixel workloads, against the bf16-rounding oracle."""
+    wl = synth.WORKLOADS["c5"]
+    g, o = _pair(tj, orc, wl, seed=16)
+    worst, _ = _step_both(tj, orc, g, o, wl, _batch(wl, 390), TOL["bf16"])
+    print("c5 full-batch worst relative errors:", worst)
+
+
 def test_c4_nature_dqn_shape_small_batch(tj, orc):
     """Config 4's network (4x84x84 u8 frames, conv 8x8/4x32, 4x4/2x64, 3x3/1x64, FC 3136-512-18, bf16)
     at batch 16, against the bf16-rounding oracle."""
