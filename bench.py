@@ -25,8 +25,8 @@ sys.path.insert(0, ROOT)
 # for the streaming kernels of known size in the same runs (reduce_slices, adam_update: FETCH_SIZE
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the GEMM source it was taken with.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 884.9e6, "gemm_source_sha256_16": "f0ddb074bc802018"},
-                "c5": {"bytes_per_step": 1565.0e6, "gemm_source_sha256_16": "f0ddb074bc802018"}}
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 885.5e6, "gemm_source_sha256_16": "f0312061636ba798"},
+                "c5": {"bytes_per_step": 1564.0e6, "gemm_source_sha256_16": "f0312061636ba798"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
@@ -129,6 +129,30 @@ def cpu_baseline(wl, synth, buf, versions, theta, target, budget_rows):
     }
 
 
+def library_gemm_reference(batch_cols, width, batch):
+    """torch.matmul (vendor GEMM) in bf16 on the three shapes of a width x width layer: forward over
+    batch_cols stacked rows, input gradient and weight gradient over batch rows.  Events on torch's
+    current stream, 50 calls each."""
+    import torch
+
+    out = {}
+    for name, (M, N, K) in {"forward": (batch_cols, width, width), "input_gradient": (batch, width, width),
+                            "weight_gradient": (width, width, batch)}.items():
+        a = torch.randn(M, K, device="cuda", dtype=torch.bfloat16)
+        b = torch.randn(N, K, device="cuda", dtype=torch.bfloat16)
+        for _ in range(5):
+            a @ b.t()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(50):
+            a @ b.t()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 50 * 1e3
+        out[name] = {"M": M, "N": N, "K": K, "us": us, "TFLOP/s": 2.0 * M * N * K / us / 1e6}
+    return out
+
+
 def bench_ppo(args):
     """On-policy workload: a step is advantage estimation over the whole rollout buffer (tj_gae)
     plus one clipped actor-critic update on it (tj_ppo_step), batch = buffer."""
@@ -216,6 +240,8 @@ def bench_ppo(args):
                  "frac": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "loss": stats[3],
     }
+    if args.library_gemm and precision == "bf16":
+        out["library_gemm_reference"] = library_gemm_reference(B, max(hidden), B)
     if not args.no_cpu_baseline:
         from oracle import orc
 
@@ -259,6 +285,10 @@ def main():
                     help="run the sample of step i+1 on a second stream while step i learns (double-buffered "
                          "minibatches) instead of one stream, strictly one after the other; measured: no "
                          "gain, the GEMM kernels leave no registers for a second kernel's waves")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the vendor GEMM behind torch.matmul on this workload's largest forward, "
+                         "input-gradient and weight-gradient shapes (plain products, no fused epilogue): a "
+                         "reference point for the roofline figures, not part of the step")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record the per-phase HIP events on every n-th timed step (each event costs "
                          "about 5 us of stream time, so recording them on every step slows the loop)")
@@ -438,6 +468,9 @@ def main():
         dt = (time.perf_counter() - t0) / 50
         out["actor_inference"] = {"rows_per_call": args.actor_rows, "ms_per_call": dt * 1e3,
                                   "actions_per_s": args.actor_rows / dt, "epsilon": 0.05}
+    if args.library_gemm and wl.precision == "bf16" and n_conv == 0:
+        width = max(l[1] for l in wl.layers)
+        out["library_gemm_reference"] = library_gemm_reference(3 * wl.batch, width, wl.batch)
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or max(8, min(wl.batch, int(3e11 / (gemm_flops_per_step(wl, synth, False) / wl.batch))))
         out["cpu_baseline"] = cpu_baseline(wl, synth, buf, versions, theta, target, rows)
