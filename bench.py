@@ -166,14 +166,15 @@ def bench_ppo(args):
     B = n_env * T
     layers = synth.ppo_layers(hidden, A)
     theta = synth.xavier_init(layers, (D, 1, 1), 1)
-    hyper = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-5, clip=0.2, c_v=0.5, c_e=0.01)
-    lrn = tj.PpoLearner(D, hidden, A, precision, B, theta, **hyper)
+    H = synth.PPO_HYPER
+    lrn = tj.PpoLearner(D, hidden, A, precision, B, theta, lr=H["lr"], beta1=H["beta1"], beta2=H["beta2"],
+                        eps=H["eps"], clip=0.2, c_v=0.5, c_e=0.01)
     ro = synth.make_rollouts(D, A, n_env, T, seed=1)
     dev = {k: torch.from_numpy(v).cuda() for k, v in ro.items()}
     L = tj.lib()
 
     def one_step():
-        adv, ret = tj.gae(dev["reward"], dev["value"], dev["done"], 0.99, 0.95)
+        adv, ret = tj.gae(dev["reward"], dev["value"], dev["done"], H["gamma"], H["lam"])
         rc = lrn.step(dev["obs"], dev["action"], dev["old_logp"], adv.view(-1), ret.view(-1))
         if rc != tj.TJ_OK:
             raise tj.TjError(rc, "bench step")
@@ -202,7 +203,7 @@ def bench_ppo(args):
     # advantage estimation alone (the learner's events start after its input cast)
     t1 = time.perf_counter()
     for _ in range(200):
-        tj.gae(dev["reward"], dev["value"], dev["done"], 0.99, 0.95)
+        tj.gae(dev["reward"], dev["value"], dev["done"], H["gamma"], H["lam"])
     torch.cuda.synchronize()
     gae_ms = (time.perf_counter() - t1) / 200 * 1e3
 
@@ -247,9 +248,9 @@ def bench_ppo(args):
 
         rows = args.cpu_rows or max(8, min(B, int(3e11 / (flops / B))))
         t1 = time.perf_counter()
-        adv, ret = orc.gae(ro["reward"], ro["value"], ro["done"], 0.99, 0.95)
+        adv, ret = orc.gae(ro["reward"], ro["value"], ro["done"], H["gamma"], H["lam"])
         t_gae = time.perf_counter() - t1
-        o = orc.Learner(layers, (D, 1, 1), lr=1e-4, eps=1e-5)
+        o = orc.Learner(layers, (D, 1, 1), lr=H["lr"], eps=H["eps"])
         o.set_state(orc.PARAMS, theta.astype(np.float64))
         t1 = time.perf_counter()
         o.ppo_step(ro["obs"][:rows], ro["action"][:rows], ro["old_logp"][:rows], adv.ravel()[:rows],

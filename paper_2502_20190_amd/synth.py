@@ -231,6 +231,10 @@ PPO_WORKLOADS = {
 }
 
 
+# Appendix E, Table 2, PPO column (Adam's betas are the usual defaults; the table gives eps and lr)
+PPO_HYPER = {"gamma": 0.99, "lam": 0.95, "lr": 1e-4, "beta1": 0.9, "beta2": 0.999, "eps": 1e-5}
+
+
 def ppo_layers(hidden, n_actions):
     """Actor-critic MLP: shared trunk, head of n_actions logits + 1 state value."""
     return _mlp(*hidden, n_actions + 1)

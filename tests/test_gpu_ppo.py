@@ -76,7 +76,7 @@ def test_gae_full_size_and_degenerate_calls(tj, orc):
 
 # ---------------------------------------------------------------- clipped update
 
-HYPER = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-5)      # the PPO column of the hyperparameter table
+HYPER = {k: synth.PPO_HYPER[k] for k in ("lr", "beta1", "beta2", "eps")}   # the PPO column of the hyperparameter table
 COEF = dict(clip=0.2, c_v=0.5, c_e=0.01)
 
 
