@@ -272,6 +272,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c3", help="workload: c1 ... c5 (replay + double-DQN), p1, p2 (on-policy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--max-staleness", type=int, default=None,
+                    help="override the workload's staleness gate (config 5 names a sweep over 1, 4, 16, 64)")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle's learner step (0 = auto)")
     ap.add_argument("--insert-rows", type=int, default=0,
                     help="also push this many new transitions per step into the ring on a second stream "
@@ -311,6 +313,10 @@ def main():
     from paper_2502_20190_amd import binding as tj, synth
 
     wl = synth.WORKLOADS[args.config]
+    if args.max_staleness is not None:
+        from dataclasses import replace
+
+        wl = replace(wl, max_staleness=args.max_staleness)
     torch.cuda.set_device(0)
     if args.frame_ring:
         if wl.obs_dtype != "u8" or args.insert_rows:
