@@ -316,6 +316,37 @@ def test_c5_full_batch_step(tj, orc):
     print("c5 full-batch worst relative errors:", worst)
 
 
+@pytest.mark.parametrize("kind", ["mlp-bf16", "mlp-fp32", "conv-bf16"])
+def test_steps_are_reproducible_bit_for_bit(tj, kind):
+    """Every reduction on the path has a fixed order (no atomics on floating point): two learners
+    built from the same state and fed the same minibatches end in identical parameters and
+    optimizer moments."""
+    from paper_2502_20190_amd.synth import CONV
+
+    if kind == "conv-bf16":
+        wl = _conv_workload("bf16", batch=48, in_chw=(4, 36, 36),
+                            layers=((CONV, 32, 8, 4), (CONV, 64, 4, 2), (LIN, 64, 0, 0), (LIN, 6, 0, 0)), n_actions=6)
+    else:
+        wl = replace(synth.WORKLOADS["c3"], obs_shape=(96,), n_actions=12, batch=2048, lr=1e-3,
+                     precision=kind.split("-")[1],
+                     layers=((LIN, 320, 0, 0), (LIN, 256, 0, 0), (LIN, 12, 0, 0)))
+    theta = synth.xavier_init(wl.layers, wl.in_chw, 3)
+    target = synth.xavier_init(wl.layers, wl.in_chw, 4)
+    finals = []
+    for run in range(2):
+        g = tj.learner_for_workload(wl, theta, target)
+        mb = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype)
+        for step in range(4):
+            mb.load(**_batch(wl, 900 + step))
+            assert g.step(mb) == tj.TJ_OK
+        finals.append([g.get_state(w) for w in (tj.TJ_STATE_PARAMS, tj.TJ_STATE_ADAM_M, tj.TJ_STATE_ADAM_V,
+                                                 tj.TJ_STATE_GRADS)] + [g.read_stats()])
+    for a, b in zip(finals[0][:4], finals[1][:4]):
+        assert np.array_equal(a, b)
+    assert finals[0][4] == finals[1][4]
+    assert not np.array_equal(finals[0][0], theta)
+
+
 def test_c4_nature_dqn_shape_small_batch(tj, orc):
     """Config 4's network (4x84x84 u8 frames, conv 8x8/4x32, 4x4/2x64, 3x3/1x64, FC 3136-512-18, bf16)
     at batch 16, against the bf16-rounding oracle."""

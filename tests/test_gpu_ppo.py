@@ -245,3 +245,26 @@ def test_argument_errors(tj, orc):
     assert L.tj_ppo_arena_bytes(C.byref(d)) == 0           # no clipping range
     torch.cuda.synchronize()
     assert g.read_stats()[4] == 0                           # nothing ran
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_updates_are_reproducible_bit_for_bit(tj, orc, precision):
+    """Fixed reduction orders: two learners from the same state, the same batch, identical results;
+    the advantage scan as well."""
+    import torch
+
+    D, hidden, A, n_env, steps = 48, (192, 160), 9, 6, 512
+    ro = synth.make_rollouts(D, A, n_env, steps, seed=12)
+    dev = {k: _dev(v) for k, v in ro.items()}
+    outs = []
+    for run in range(2):
+        g, _ = _pair(tj, orc, D, hidden, A, precision, n_env * steps, seed=21, lr=1e-3)
+        adv, ret = tj.gae(dev["reward"], dev["value"], dev["done"], 0.99, 0.95)
+        for it in range(3):
+            assert g.step(dev["obs"], dev["action"], dev["old_logp"], adv.view(-1), ret.view(-1)) == tj.TJ_OK
+        torch.cuda.synchronize()
+        outs.append((adv.cpu().numpy(), ret.cpu().numpy(), g.get_state(tj.TJ_STATE_PARAMS),
+                     g.get_state(tj.TJ_STATE_ADAM_V), g.read_stats()))
+    for a, b in zip(outs[0][:4], outs[1][:4]):
+        assert np.array_equal(a, b)
+    assert outs[0][4] == outs[1][4] and outs[0][4][4] == 3
