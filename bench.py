@@ -25,8 +25,8 @@ sys.path.insert(0, ROOT)
 # for the streaming kernels of known size in the same runs (reduce_slices, adam_update: FETCH_SIZE
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the GEMM source it was taken with.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 885.5e6, "gemm_source_sha256_16": "f0312061636ba798"},
-                "c5": {"bytes_per_step": 1564.0e6, "gemm_source_sha256_16": "f0312061636ba798"}}
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 885.5e6, "gemm_source_sha256_16": "f422a59c9a51514f"},
+                "c5": {"bytes_per_step": 1564.0e6, "gemm_source_sha256_16": "f422a59c9a51514f"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
