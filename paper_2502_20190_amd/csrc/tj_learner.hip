@@ -562,7 +562,9 @@ __global__ __launch_bounds__(256) void gae_scan(uint32_t n_env, uint32_t T, cons
 //   p = softmax(z), rho = p[a_j] / exp(old_logp_j), H = -sum p log p
 //   loss_j = -min(rho Adv, clip(rho, 1-c, 1+c) Adv) + c_v (V - ret)^2 - c_e H
 // Writes d(mean loss)/dZ in compute type, row-major and transposed (the two operand layouts of
-// the backward GEMMs), and per-block sums of the three terms.  One thread per sample.
+// the backward GEMMs), and per-block sums of the three terms.  Eight lanes per sample; both
+// copies of the gradient leave through an LDS tile (whole 16-byte vectors row-major, 32
+// consecutive samples per head output transposed).
 template <typename T> struct PpoHeadArgs {
     const float *Z; int ldz; int B, A;
     const int32_t *action; const float *old_logp, *adv, *ret;
@@ -571,19 +573,49 @@ template <typename T> struct PpoHeadArgs {
     float *part;   // [blocks][4]: sum L_pi, sum L_v, sum H, unused
 };
 
-template <typename T> __global__ __launch_bounds__(256) void ppo_head(const PpoHeadArgs<T> a)
+constexpr int kPpoRows = 32;    // samples per block of ppo_head
+constexpr int kPpoLanes = 8;    // lanes per sample: lane g owns head outputs g, g + 8, ...
+
+template <typename T>
+__global__ __launch_bounds__(kPpoRows * kPpoLanes) void ppo_head(const PpoHeadArgs<T> a)
 {
-    __shared__ float red[4][3];
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    constexpr int VEC = 16 / (int)sizeof(T);
+    constexpr int kMaxCols = 64 + VEC;               // A + 1 <= 64, rounded up to whole vectors, plus one
+    constexpr int NI = 64 / kPpoLanes;               // head outputs per lane, at most
+    __shared__ __align__(16) T tile[kPpoRows * kMaxCols];
+    __shared__ float red[kPpoRows * kPpoLanes / 64][3];
+    const int cols = (a.A + 1 + VEC - 1) / VEC * VEC;  // row-major columns written per sample (<= lddz)
+    const int pitch = cols + VEC;                      // odd number of vectors: rows spread over the banks
+    const int row0 = blockIdx.x * kPpoRows;
+    const int r = threadIdx.x / kPpoLanes, g = threadIdx.x % kPpoLanes;
+    const int j = row0 + r;
+    // sums over the lanes of one sample (8 consecutive lanes of a wave)
+    auto group_sum = [](float v) {
+        v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); v += __shfl_xor(v, 4, 64);
+        return v;
+    };
     float l_pi = 0.f, l_v = 0.f, H = 0.f;
-    if (j < a.B) {
+    if (j < a.B) {   // uniform over a sample's lanes
         const float *z = a.Z + (size_t)j * a.ldz;
-        float mx = z[0];
-        for (int k = 1; k < a.A; ++k) mx = fmaxf(mx, z[k]);
+        float zv[NI];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int k = g + kPpoLanes * i;
+            zv[i] = k < a.A ? z[k] : -INFINITY;
+            mx = fmaxf(mx, zv[i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 1, 64)); mx = fmaxf(mx, __shfl_xor(mx, 2, 64)); mx = fmaxf(mx, __shfl_xor(mx, 4, 64));
         float se = 0.f;
-        for (int k = 0; k < a.A; ++k) se += expf(z[k] - mx);
-        const float lse = mx + logf(se);
-        for (int k = 0; k < a.A; ++k) H -= expf(z[k] - lse) * (z[k] - lse);
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            if (g + kPpoLanes * i < a.A) se += expf(zv[i] - mx);
+        const float lse = mx + logf(group_sum(se));
+        float h = 0.f;
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            if (g + kPpoLanes * i < a.A) h -= expf(zv[i] - lse) * (zv[i] - lse);
+        H = group_sum(h);
         const int act = min(max(a.action[j], 0), a.A - 1);
         const float adv = a.adv[j];
         const float rho = expf(z[act] - lse - a.old_logp[j]);
@@ -594,20 +626,24 @@ template <typename T> __global__ __launch_bounds__(256) void ppo_head(const PpoH
         l_pi = -(unclipped ? s1 : s2);
         l_v = verr * verr;
         const float inv_b = 1.f / (float)a.B;
-        T *dz = a.dZ + (size_t)j * a.lddz;
-        for (int k = 0; k < a.A; ++k) {
-            const float lp = z[k] - lse, pk = expf(lp);
-            float g = a.c_e * pk * (lp + H);
-            if (unclipped) g -= adv * rho * ((k == act ? 1.f : 0.f) - pk);
-            const T gt = TjElem<T>::from_f32(g * inv_b);
-            dz[k] = gt;
-            a.dZT[(size_t)k * a.lddzt + j] = gt;
+        T *row = tile + r * pitch;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int k = g + kPpoLanes * i;
+            if (k < a.A) {
+                const float lp = zv[i] - lse, pk = expf(lp);
+                float gr = a.c_e * pk * (lp + H);
+                if (unclipped) gr -= adv * rho * ((k == act ? 1.f : 0.f) - pk);
+                row[k] = TjElem<T>::from_f32(gr * inv_b);
+            } else if (k == a.A) {
+                row[k] = TjElem<T>::from_f32(2.f * a.c_v * verr * inv_b);
+            } else if (k < cols) {
+                row[k] = TjElem<T>::from_f32(0.f);
+            }
         }
-        const T gv = TjElem<T>::from_f32(2.f * a.c_v * verr * inv_b);
-        dz[a.A] = gv;
-        a.dZT[(size_t)a.A * a.lddzt + j] = gv;
+        if (g != 0) { l_pi = 0.f; l_v = 0.f; H = 0.f; }   // one lane per sample carries its terms
     }
-    // block sums in a fixed order: shuffle tree per wave, then the four waves in turn
+    // block sums in a fixed order: shuffle tree per wave, then the waves in turn
     float s[3] = {l_pi, l_v, H};
 #pragma unroll
     for (int q = 0; q < 3; ++q)
@@ -616,9 +652,23 @@ template <typename T> __global__ __launch_bounds__(256) void ppo_head(const PpoH
     if ((threadIdx.x & 63) == 0)
         for (int q = 0; q < 3; ++q) red[threadIdx.x >> 6][q] = s[q];
     __syncthreads();
-    if (threadIdx.x < 3)
-        a.part[(size_t)blockIdx.x * 4 + threadIdx.x] =
-            red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+    if (threadIdx.x < 3) {
+        float t = red[0][threadIdx.x];
+        for (int w = 1; w < kPpoRows * kPpoLanes / 64; ++w) t += red[w][threadIdx.x];
+        a.part[(size_t)blockIdx.x * 4 + threadIdx.x] = t;
+    }
+    const int n_rows = min(kPpoRows, a.B - row0);
+    // row-major gradient: whole 16-byte vectors, consecutive lanes on consecutive vectors of a row
+    const int vpr = cols / VEC;
+    for (int v = threadIdx.x; v < n_rows * vpr; v += kPpoRows * kPpoLanes) {
+        const int rr = v / vpr, c = v - rr * vpr;
+        *(uint4 *)(a.dZ + (size_t)(row0 + rr) * a.lddz + c * VEC) = *(const uint4 *)(tile + rr * pitch + c * VEC);
+    }
+    // transposed gradient: 32 consecutive samples of one head output per 32 lanes
+    for (int e = threadIdx.x; e < (a.A + 1) * kPpoRows; e += kPpoRows * kPpoLanes) {
+        const int k = e / kPpoRows, rr = e % kPpoRows;
+        if (rr < n_rows) a.dZT[(size_t)k * a.lddzt + row0 + rr] = tile[rr * pitch + k];
+    }
 }
 
 // Means of the three terms and the objective, from the per-block sums (fixed order).
@@ -1104,7 +1154,7 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
 
     void plan_more(TjArena &a) override
     {
-        ppo_part = (float *)a.take((size_t)((this->Bmax + 255) / 256) * 4 * 4);
+        ppo_part = (float *)a.take((size_t)((this->Bmax + kPpoRows - 1) / kPpoRows) * 4 * 4);
         ppo_stats = (tj_ppo_stats *)a.take(sizeof(tj_ppo_stats));
     }
 
@@ -1165,8 +1215,8 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
         a.clip = pd.clip; a.c_v = pd.c_v; a.c_e = pd.c_e;
         a.dZ = this->dZ[this->L]; a.lddz = lh.ld_out; a.dZT = this->dZT[this->L]; a.lddzt = this->ldB;
         a.part = ppo_part;
-        const int nblk = (B + 255) / 256;
-        ppo_head<T><<<nblk, 256, 0, st>>>(a);
+        const int nblk = (B + kPpoRows - 1) / kPpoRows;
+        ppo_head<T><<<nblk, kPpoRows * kPpoLanes, 0, st>>>(a);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         ppo_stats_final<<<1, 64, 0, st>>>(ppo_part, nblk, B, pd.c_v, pd.c_e, (uint32_t)(this->t + 1), d_stats,
                                           ppo_stats);
