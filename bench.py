@@ -20,10 +20,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM traffic of the GEMM launches of one c3 step, from two rocprofv3 --pmc runs of this script
-# (FETCH_SIZE, WRITE_SIZE; see profiles/c3_gemm_counters.md), scaled by what the same counters read
-# for the streaming kernels of known size in the same runs (reduce_slices, adam_update: FETCH_SIZE
-# reads half the bytes, WRITE_SIZE all of them).  Valid for the GEMM source it was taken with.
+# HBM traffic of the contraction launches of one step (c3, c5), from two rocprofv3 --pmc runs of
+# this script each (FETCH_SIZE, WRITE_SIZE; see profiles/c3_gemm_counters.md), scaled by what the
+# same counters read for a streaming kernel of known size in the same runs (adam_update: FETCH_SIZE
+# reads half the bytes, WRITE_SIZE all of them).  Valid for the kernel sources it was taken with.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip")
 GEMM_TRAFFIC = {"c3": {"bytes_per_step": 885.5e6, "gemm_source_sha256_16": "f422a59c9a51514f"},
                 "c5": {"bytes_per_step": 1564.0e6, "gemm_source_sha256_16": "f422a59c9a51514f"}}
