@@ -81,6 +81,8 @@ def lib():
         L.orc_ppo_loss.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _vp, _dbl, _dbl, _dbl, _vp]
         L.orc_ppo_step.restype = None
         L.orc_ppo_step.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _vp, _dbl, _dbl, _dbl, _vp]
+        L.orc_ppo_act.restype = None
+        L.orc_ppo_act.argtypes = [_vp, _vp, _u32, _u64, _vp, _vp, _vp, _vp]
         _lib = L
     return _lib
 
@@ -370,3 +372,13 @@ class Learner:
         lib().orc_ppo_step(self.h, b, _p(obs), _p(action), _p(old_logp), _p(adv), _p(ret), clip, c_v, c_e,
                            _p(out))
         return out
+
+    def ppo_act(self, obs, seed: int):
+        """Sampled actions under the stochastic policy: (action, logp, value, margin), where margin is
+        the distance of the uniform draw from the nearest cumulative probability."""
+        obs = _c(obs, self.np_dtype)
+        n = obs.shape[0]
+        action = np.empty(n, np.int32)
+        logp, value, margin = np.empty(n), np.empty(n), np.empty(n)
+        lib().orc_ppo_act(self.h, _p(obs), n, seed, _p(action), _p(logp), _p(value), _p(margin))
+        return action, logp, value, margin

@@ -877,6 +877,42 @@ void orc_ppo_step(orc_learner *l, uint32_t batch, const void *obs, const int32_t
     backward_and_adam(l, batch, acts, dz);
 }
 
+/* Acting under the stochastic policy (what an actor does between updates): for observation j,
+ * p = softmax(logits(s_j)), u_j = (top 24 bits of rng64(seed, j)) / 2^24, the action is the
+ * smallest a whose cumulative probability p_0 + ... + p_a exceeds u_j (the last action if rounding
+ * leaves none), logp its log-probability, value the head's last output.  margin (optional)
+ * receives the distance from u_j to the nearest cumulative probability: a comparison in another
+ * precision may legitimately pick a neighbouring action when it is within rounding of zero. */
+void orc_ppo_act(orc_learner *l, const void *obs, uint32_t n, uint64_t seed, int32_t *action,
+                 double *logp, double *value, double *margin)
+{
+    const int A = l->n_actions - 1;
+    double *z = (double *)malloc((size_t)n * (A + 1) * sizeof(double));
+    forward_batch(l, l->theta, obs, n, NULL, z, NULL);
+    for (uint32_t j = 0; j < n; ++j) {
+        const double *zj = z + (size_t)j * (A + 1);
+        double mx = zj[0];
+        for (int a = 1; a < A; ++a)
+            if (zj[a] > mx) mx = zj[a];
+        double se = 0.0;
+        for (int a = 0; a < A; ++a) se += exp(zj[a] - mx);
+        double lse = mx + log(se);
+        double u = (double)(orc_rng64(seed, j) >> 40) / 16777216.0;
+        double cdf = 0.0, best = INFINITY;
+        int pick = A - 1, found = 0;
+        for (int a = 0; a < A; ++a) {
+            cdf += exp(zj[a] - lse);
+            if (a + 1 < A && fabs(cdf - u) < best) best = fabs(cdf - u);
+            if (!found && cdf > u) { pick = a; found = 1; }
+        }
+        action[j] = pick;
+        logp[j] = zj[pick] - lse;
+        value[j] = zj[A];
+        if (margin) margin[j] = best;
+    }
+    free(z);
+}
+
 /* Per-row outputs of the last step: which = 0 Q_online(s) [B*A], 1 Q_online(s')
  * [B*A], 2 Q_target(s') [B*A], 3 y [B], 4 delta [B]. */
 int orc_learner_last(orc_learner *l, int which, double *out)

@@ -231,3 +231,53 @@ def test_ppo_bf16_emulation_stays_close(orc):
     np.testing.assert_allclose(ob, oa, rtol=0.03, atol=0.02)
     ga, gb = a.get_state(orc.GRADS), b.get_state(orc.GRADS)
     assert np.linalg.norm(ga - gb) < 0.1 * np.linalg.norm(ga)
+
+
+# ---------------------------------------------------------------- acting under the policy
+
+def test_ppo_act_uses_the_generator_and_the_cumulative_rule(orc):
+    """A head with zero weights and hand-set logit biases: p is known in closed form, the uniform
+    draw comes from the generator's own 64-bit outputs, and the action follows from the cumulative
+    sums written out here (numpy cumsum and searchsorted, not the oracle's loop)."""
+    A, D, n, seed = 5, 3, 4000, 77
+    layers = [(LIN, A + 1, 0, 0)]
+    l = orc.Learner(layers, (D, 1, 1))
+    bias = np.array([0.3, -1.2, 0.0, 2.0, 0.7])
+    theta = np.zeros((A + 1) * D + A + 1)
+    theta[(A + 1) * D:(A + 1) * D + A] = bias
+    theta[-1] = -0.5
+    l.set_state(orc.PARAMS, theta)
+    obs = np.random.default_rng(0).standard_normal((n, D)).astype(np.float32)
+    action, logp, value, margin = l.ppo_act(obs, seed)
+    p = np.exp(bias) / np.exp(bias).sum()
+    u = np.array([(orc.rng64(seed, j) >> 40) / 2.0 ** 24 for j in range(n)])
+    expect = np.minimum(np.searchsorted(np.cumsum(p), u, side="right"), A - 1)
+    assert np.array_equal(action, expect)
+    np.testing.assert_allclose(logp, np.log(p)[action], atol=1e-13)
+    np.testing.assert_allclose(value, -0.5, atol=1e-15)
+    np.testing.assert_allclose(margin, np.abs(np.cumsum(p)[None, :A - 1] - u[:, None]).min(1), atol=1e-13)
+    # the sampled frequencies are the policy's probabilities (chi-square, 4 degrees of freedom)
+    counts = np.bincount(action, minlength=A)
+    chi2 = ((counts - n * p) ** 2 / (n * p)).sum()
+    assert chi2 < 18.5            # 99.9 % quantile
+    # same seed, same draws; another seed, other draws; a prefix of the batch gives a prefix
+    assert np.array_equal(l.ppo_act(obs, seed)[0], action)
+    assert not np.array_equal(l.ppo_act(obs, seed + 1)[0], action)
+    assert np.array_equal(l.ppo_act(obs[:100], seed)[0], action[:100])
+
+
+def test_ppo_act_degenerate_policies(orc):
+    D = 2
+    # one action: always chosen, log-probability 0
+    l = orc.Learner([(LIN, 2, 0, 0)], (D, 1, 1))
+    l.set_state(orc.PARAMS, np.array([0.4, -0.3, 0.1, 0.2, 1.5, 0.25]))
+    obs = np.random.default_rng(1).standard_normal((50, D)).astype(np.float32)
+    action, logp, value, _ = l.ppo_act(obs, 3)
+    assert not action.any() and np.allclose(logp, 0.0, atol=1e-15)
+    np.testing.assert_allclose(value, obs.astype(np.float64) @ np.array([0.1, 0.2]) + 0.25, atol=1e-14)
+    # a policy that puts (numerically) all mass on one action
+    l = orc.Learner([(LIN, 4, 0, 0)], (D, 1, 1))
+    th = np.zeros(4 * D + 4); th[4 * D + 1] = 800.0
+    l.set_state(orc.PARAMS, th)
+    action, logp, _, _ = l.ppo_act(obs, 5)
+    assert (action == 1).all() and np.allclose(logp, 0.0, atol=1e-15)
