@@ -361,6 +361,17 @@ int tj_ppo_step(tj_learner *lrn, const tj_ppo_batch *batch, tj_ppo_stats *d_stat
 int tj_ppo_evaluate(tj_learner *lrn, uint32_t n, const float *d_obs, float *d_logits, float *d_value,
                     void *hip_stream);
 
+/* Acting under the stochastic policy, n <= max_batch observations: with p =
+ * softmax(logits(s_j)) and u_j = (top 24 bits of SplitMix64(seed, j)) / 2^24
+ * (tj_sample's generator), the action is the first a whose cumulative
+ * probability p_0 + ... + p_a exceeds u_j (the last action if rounding leaves
+ * none).  d_action int32[n]; d_logp float[n] = log p[action], what
+ * tj_ppo_batch.old_logp expects; d_value float[n] (may be NULL) = V(s_j), the
+ * value columns of tj_gae.  Same buffers and the same rule about overlapping
+ * calls as tj_ppo_evaluate. */
+int tj_ppo_act(tj_learner *lrn, uint32_t n, const float *d_obs, uint64_t seed, int32_t *d_action,
+               float *d_logp, float *d_value, void *hip_stream);
+
 /* ---------------------------------------------------------------- timing */
 
 /* ---------------------------------------------------------------- balance */

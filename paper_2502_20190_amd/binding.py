@@ -33,7 +33,7 @@ EXPORTS = [
     "tj_learner_create", "tj_learner_destroy", "tj_learner_step", "tj_learner_get_state",
     "tj_learner_set_state", "tj_learner_get_step", "tj_learner_set_step", "tj_strerror",
     "tj_buffer_set_phase_events", "tj_learner_set_phase_events",
-    "tj_gae", "tj_ppo_num_params", "tj_ppo_arena_bytes", "tj_ppo_create", "tj_ppo_step", "tj_ppo_evaluate",
+    "tj_gae", "tj_ppo_num_params", "tj_ppo_arena_bytes", "tj_ppo_create", "tj_ppo_step", "tj_ppo_evaluate", "tj_ppo_act",
 ]
 
 
@@ -171,6 +171,8 @@ def lib():
         L.tj_ppo_step.argtypes = [vp, C.POINTER(tj_ppo_batch), vp, vp]
         L.tj_ppo_evaluate.restype = i32
         L.tj_ppo_evaluate.argtypes = [vp, u32, vp, vp, vp, vp]
+        L.tj_ppo_act.restype = i32
+        L.tj_ppo_act.argtypes = [vp, u32, vp, u64, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -555,6 +557,18 @@ class PpoLearner:
         _check(lib().tj_ppo_evaluate(self.h, n, obs.data_ptr(), logits.data_ptr(), value.data_ptr(),
                                      _stream_ptr(stream)), "tj_ppo_evaluate")
         return logits, value
+
+    def act(self, obs, seed: int, stream=None):
+        """Sampled (action i32 [n], logp f32 [n], value f32 [n]) for device observations."""
+        import torch
+
+        n = int(obs.shape[0])
+        action = torch.empty(n, dtype=torch.int32, device=obs.device)
+        logp = torch.empty(n, dtype=torch.float32, device=obs.device)
+        value = torch.empty(n, dtype=torch.float32, device=obs.device)
+        _check(lib().tj_ppo_act(self.h, n, obs.data_ptr(), seed & (2**64 - 1), action.data_ptr(), logp.data_ptr(),
+                                value.data_ptr(), _stream_ptr(stream)), "tj_ppo_act")
+        return action, logp, value
 
     def read_stats(self):
         """(loss_pi, loss_v, entropy, loss, t) of the last step."""

@@ -707,6 +707,33 @@ __global__ __launch_bounds__(256) void split_head(const float *__restrict__ Z, i
     if (value) value[j] = z[A];
 }
 
+// Acting under the stochastic policy: row j of Z = (logits, value); u_j = top 24 bits of
+// SplitMix64(seed, j) / 2^24; the action is the first whose cumulative softmax probability exceeds
+// u_j (the last action if rounding leaves none).  One thread per observation.
+__global__ __launch_bounds__(256) void ppo_sample(const float *__restrict__ Z, int ldz, uint32_t n, int A,
+                                                  uint64_t seed, int32_t *__restrict__ action,
+                                                  float *__restrict__ logp, float *__restrict__ value)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float *z = Z + (size_t)j * ldz;
+    float mx = z[0];
+    for (int k = 1; k < A; ++k) mx = fmaxf(mx, z[k]);
+    float se = 0.f;
+    for (int k = 0; k < A; ++k) se += expf(z[k] - mx);
+    const float lse = mx + logf(se);
+    const float u = (float)(tj_splitmix64(seed, j) >> 40) * (1.f / 16777216.f);   // exact: 24 bits
+    float cdf = 0.f;
+    int pick = A - 1;
+    for (int k = 0; k < A; ++k) {
+        cdf += expf(z[k] - lse);
+        if (cdf > u) { pick = k; break; }
+    }
+    action[j] = pick;
+    logp[j] = z[pick] - lse;
+    if (value) value[j] = z[A];
+}
+
 struct LayerPlan {
     int in, out;           // features
     int ld_in, ld_out;     // padded pitches (elements of T)
@@ -748,6 +775,10 @@ struct tj_learner {
     // on-policy learners only
     virtual int ppo_step(const tj_ppo_batch *, tj_ppo_stats *, hipStream_t) { return TJ_ERR_INVALID_ARG; }
     virtual int ppo_evaluate(uint32_t, const float *, float *, float *, hipStream_t) { return TJ_ERR_INVALID_ARG; }
+    virtual int ppo_act(uint32_t, const float *, uint64_t, int32_t *, float *, float *, hipStream_t)
+    {
+        return TJ_ERR_INVALID_ARG;
+    }
     uint64_t t = 0;
     hipEvent_t ev[5];
     bool timed = false;
@@ -1233,6 +1264,19 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
         int rc;
         if ((rc = forward(n, d_obs, false, st)) != TJ_OK) return rc;
         split_head<<<(n + 255) / 256, 256, 0, st>>>(this->Qout, this->ldA, n_, this->A - 1, d_logits, d_value);
+        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+    }
+
+    int ppo_act(uint32_t n_, const float *d_obs, uint64_t seed, int32_t *d_action, float *d_logp, float *d_value,
+                hipStream_t st) override
+    {
+        const int n = (int)n_;
+        if (n < 1 || n > this->Bmax) return TJ_ERR_SHAPE;
+        if (!d_obs || !d_action || !d_logp) return TJ_ERR_INVALID_ARG;
+        int rc;
+        if ((rc = forward(n, d_obs, false, st)) != TJ_OK) return rc;
+        ppo_sample<<<(n + 255) / 256, 256, 0, st>>>(this->Qout, this->ldA, n_, this->A - 1, seed, d_action, d_logp,
+                                                     d_value);
         return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
     }
 };
@@ -2159,6 +2203,13 @@ int tj_ppo_evaluate(tj_learner *l, uint32_t n, const float *d_obs, float *d_logi
 {
     if (!l) return TJ_ERR_INVALID_ARG;
     return l->ppo_evaluate(n, d_obs, d_logits, d_value, (hipStream_t)hip_stream);
+}
+
+int tj_ppo_act(tj_learner *l, uint32_t n, const float *d_obs, uint64_t seed, int32_t *d_action, float *d_logp,
+               float *d_value, void *hip_stream)
+{
+    if (!l) return TJ_ERR_INVALID_ARG;
+    return l->ppo_act(n, d_obs, seed, d_action, d_logp, d_value, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

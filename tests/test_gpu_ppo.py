@@ -268,3 +268,38 @@ def test_updates_are_reproducible_bit_for_bit(tj, orc, precision):
     for a, b in zip(outs[0][:4], outs[1][:4]):
         assert np.array_equal(a, b)
     assert outs[0][4] == outs[1][4] and outs[0][4][4] == 3
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_acting_under_the_policy(tj, orc, precision):
+    """Sampled actions equal the oracle's except where the uniform draw sits within float rounding
+    of a cumulative probability (there a neighbouring action is the other valid answer);
+    log-probabilities and values within tolerance on the rows that agree."""
+    import torch
+
+    D, hidden, A, n = 24, (128, 64), 7, 3000
+    g, o = _pair(tj, orc, D, hidden, A, precision, 3072, seed=31)
+    obs = synth.make_rollouts(D, A, 1, n, seed=6)["obs"]
+    for seed in (1, 2**63 + 5):
+        action, logp, value = g.act(_dev(obs), seed)
+        torch.cuda.synchronize()
+        oa, ologp, ovalue, margin = o.ppo_act(obs, seed)
+        ga = action.cpu().numpy()
+        mism = ga != oa
+        tol_u = 1e-5 if precision == "fp32" else 2e-2
+        assert (margin[mism] < tol_u).all() and (np.abs(ga[mism] - oa[mism]) <= 1).all()
+        assert mism.mean() < (0.001 if precision == "fp32" else 0.05)
+        same = ~mism
+        assert np.abs(logp.cpu().numpy()[same] - ologp[same]).max() < TOL[precision] * max(1.0, np.abs(ologp).max())
+        assert rel_max(value.cpu().numpy(), ovalue) < TOL[precision]
+        assert ga.min() >= 0 and ga.max() < A
+    # the draws depend on the seed and on nothing else
+    a1, _, _ = g.act(_dev(obs), 9)
+    a2, _, _ = g.act(_dev(obs), 9)
+    a3, _, _ = g.act(_dev(obs), 10)
+    assert torch.equal(a1, a2) and not torch.equal(a1, a3)
+    # more observations than the learner was sized for
+    big = torch.zeros((3073, D), device="cuda")
+    out = torch.zeros(3073, dtype=torch.int32, device="cuda")
+    f = torch.zeros(3073, device="cuda")
+    assert tj.lib().tj_ppo_act(g.h, 3073, big.data_ptr(), 1, out.data_ptr(), f.data_ptr(), None, None) == tj.TJ_ERR_SHAPE
