@@ -56,6 +56,75 @@ template <> __device__ __forceinline__ float vec_sum<tj_bf16>(const u32x4 &v)
     return s;
 }
 
+// Epilogue of one 32 x 32 accumulator tile in the MFMA layout (i = ibase + 8*(r/4) + 4*(lane/32) + r%4,
+// j = jbase + lane%32): bias, ReLU, mask, then the stores into whichever outputs are set.
+template <typename T>
+__device__ __forceinline__ void pq_epilogue(const TjGemmArgs<T> &a, const TjGemmSeg<T> &seg, const f32x16 &acc,
+                                            const int ibase, const int jbase, const int j_end, const int z,
+                                            const int lane)
+{
+    const int l32 = lane & 31, lg = lane >> 5;
+    const int j = jbase + l32;
+    if (j >= j_end) return;
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+        const int ib = ibase + rq * 8 + lg * 4;
+        if (ib >= a.I) continue;
+        const int nvalid = min(4, a.I - ib);
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[rq * 4 + e];
+        if (seg.bias) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid) v[e] += seg.bias[ib + e];
+        }
+        if (a.bias_j) {
+            const float bj = a.bias_j[j];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += bj;
+        }
+        if (a.relu) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+        }
+        if (a.mask) {
+            const T *mp = a.mask + (size_t)j * a.ldmask + ib;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid && !(TjElem<T>::to_f32(mp[e]) > 0.f)) v[e] = 0.f;
+        }
+        if (a.Ci) {
+            T *cp = a.Ci + (size_t)j * a.ldci + ib;
+            if (nvalid == 4) {
+                if constexpr (sizeof(T) == 2) {
+                    uint2 o;
+                    o.x = (uint32_t)tj_f32_to_bf16(v[0]) | ((uint32_t)tj_f32_to_bf16(v[1]) << 16);
+                    o.y = (uint32_t)tj_f32_to_bf16(v[2]) | ((uint32_t)tj_f32_to_bf16(v[3]) << 16);
+                    *(uint2 *)cp = o;
+                } else {
+                    *(float4 *)cp = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            } else {
+                for (int e = 0; e < nvalid; ++e) cp[e] = TjElem<T>::from_f32(v[e]);
+            }
+        }
+        if (a.Cj && j < a.cj_jmax) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid) a.Cj[(size_t)(ib + e) * a.ldcj + j] = TjElem<T>::from_f32(v[e]);
+        }
+        if (a.Cf) {
+            float *fp = a.Cf + (size_t)z * a.cf_zstride + (size_t)j * a.ldcf + ib;
+            if (nvalid == 4 && ((uintptr_t)fp & 15) == 0) {
+                *(float4 *)fp = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+                for (int e = 0; e < nvalid; ++e) fp[e] = v[e];
+            }
+        }
+    }
+}
+
 // NF = 32-wide fragments per wave and dimension: block tile 64*NF square (four waves, 2 x 2).  NF = 1 gives
 // small problems four times as many blocks to spread over the CUs.
 template <typename T, int NF>
@@ -166,70 +235,81 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
     }
 
 #pragma unroll
-    for (int fi = 0; fi < NF; ++fi) {
+    for (int fi = 0; fi < NF; ++fi)
 #pragma unroll
-        for (int fj = 0; fj < NF; ++fj) {
-            const int j = j0 + wj * 32 * NF + fj * 32 + l32;
-            if (j >= j_end) continue;
+        for (int fj = 0; fj < NF; ++fj)
+            pq_epilogue<T>(a, seg, acc[fi][fj], i0 + wi * 32 * NF + fi * 32, j0 + wj * 32 * NF + fj * 32, j_end, z, lane);
+}
+
+// Small fp32 problems: a 32 x 32 output tile per block, and the block's four waves split the
+// contraction among them (operand fragments straight from global memory in the MFMA layout, eight
+// 16-byte loads in flight per lane), so a launch has 16 times the waves of the 64 x 64 tiling and
+// each wave a quarter of the dependent MFMA chain.  Waves 1..3 leave their accumulators in LDS,
+// wave 0 adds them in wave order (deterministic) and runs the epilogue.
+__global__ __launch_bounds__(256) void gemm_f32_ksplit4(const TjGemmArgs<float> a, const int tiles_seg0)
+{
+    typedef float T;
+    __shared__ float red[3][17][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lg = lane >> 5;
+    const int sidx = (a.n_seg > 1 && (int)blockIdx.y >= tiles_seg0) ? 1 : 0;
+    const TjGemmSeg<T> seg = a.seg[sidx];
+    const int j0 = seg.j_begin + ((int)blockIdx.y - (sidx ? tiles_seg0 : 0)) * 32;
+    const int j_end = seg.j_end;
+    const int i0 = blockIdx.x * 32;
+    const int z = blockIdx.z;
+    const int k_begin = z * a.k_chunk;
+    const int k_end = min(a.K, k_begin + a.k_chunk);
+
+    // k steps of 8 (lane half lg takes k .. k+3 of each step); this wave's share of them
+    const int n_step = k_end > k_begin ? (k_end - k_begin + 7) / 8 : 0;
+    const int per = (n_step + 3) / 4;
+    const int s_begin = min(n_step, wave * per), s_end = min(n_step, s_begin + per);
+    const int i = i0 + l32, j = j0 + l32;
+    const bool okP = i < a.I, okQ = j < j_end;
+    const T *pP = seg.P + (size_t)(okP ? i : 0) * a.ldp + k_begin + lg * 4;
+    const T *pQ = a.Q + (size_t)(okQ ? j - seg.q_shift : 0) * a.ldq + k_begin + lg * 4;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    f32x16 acc;
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const int ib = i0 + wi * 32 * NF + fi * 32 + rq * 8 + lg * 4;
-                if (ib >= a.I) continue;
-                const int nvalid = min(4, a.I - ib);
-                float v[4];
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const bool do_qsum = a.qsum != nullptr && blockIdx.x == 0;
+    float qs = 0.f;
+    for (int s0 = s_begin; s0 < s_end; s0 += 4) {
+        u32x4 p[4], q[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[fi][fj][rq * 4 + e];
-                if (seg.bias) {
+        for (int u = 0; u < 4; ++u) {
+            const int st = s0 + u;
+            const bool kin = st < s_end && k_begin + st * 8 + lg * 4 < k_end;   // K and the chunks are multiples of 4
+            p[u] = (kin && okP) ? *(const u32x4 *)(pP + st * 8) : zero4;
+            q[u] = (kin && okQ) ? *(const u32x4 *)(pQ + st * 8) : zero4;
+        }
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (e < nvalid) v[e] += seg.bias[ib + e];
-                }
-                if (a.bias_j) {
-                    const float bj = a.bias_j[j];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += bj;
-                }
-                if (a.relu) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-                }
-                if (a.mask) {
-                    const T *mp = a.mask + (size_t)j * a.ldmask + ib;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (e < nvalid && !(TjElem<T>::to_f32(mp[e]) > 0.f)) v[e] = 0.f;
-                }
-                if (a.Ci) {
-                    T *cp = a.Ci + (size_t)j * a.ldci + ib;
-                    if (nvalid == 4) {
-                        if constexpr (sizeof(T) == 2) {
-                            uint2 o;
-                            o.x = (uint32_t)tj_f32_to_bf16(v[0]) | ((uint32_t)tj_f32_to_bf16(v[1]) << 16);
-                            o.y = (uint32_t)tj_f32_to_bf16(v[2]) | ((uint32_t)tj_f32_to_bf16(v[3]) << 16);
-                            *(uint2 *)cp = o;
-                        } else {
-                            *(float4 *)cp = make_float4(v[0], v[1], v[2], v[3]);
-                        }
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) cp[e] = TjElem<T>::from_f32(v[e]);
-                    }
-                }
-                if (a.Cj && j < a.cj_jmax) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (e < nvalid) a.Cj[(size_t)(ib + e) * a.ldcj + j] = TjElem<T>::from_f32(v[e]);
-                }
-                if (a.Cf) {
-                    float *fp = a.Cf + (size_t)z * a.cf_zstride + (size_t)j * a.ldcf + ib;
-                    if (nvalid == 4 && ((uintptr_t)fp & 15) == 0) {
-                        *(float4 *)fp = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-                        for (int e = 0; e < nvalid; ++e) fp[e] = v[e];
-                    }
-                }
-            }
+        for (int u = 0; u < 4; ++u) {
+            if (s0 + u >= s_end) break;
+            mma<T>(acc, p[u], q[u]);
+            if (do_qsum) qs += vec_sum<T>(q[u]);
         }
     }
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[wave - 1][r][lane] = acc[r];
+        red[wave - 1][16][lane] = qs;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int w = 0; w < 3; ++w) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] += red[w][r][lane];
+        qs += red[w][16][lane];
+    }
+    if (do_qsum) {
+        const float sum = qs + __shfl_xor(qs, 32, 64);
+        if (lg == 0 && j < j_end) a.qsum[(size_t)z * a.qsum_zstride + j] = sum;
+    }
+    pq_epilogue<T>(a, seg, acc, i0, j0, j_end, z, lane);
 }
 
 
@@ -1263,6 +1343,15 @@ template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st)
         int t64[2] = {0, 0};
         for (int s = 0; s < a.n_seg; ++s) t64[s] = (a.seg[s].j_end - a.seg[s].j_begin + 63) / 64;
         dim3 g64((a.I + 63) / 64, t64[0] + t64[1], a.n_split);
+        if constexpr (sizeof(T) == 4) {
+            if ((long)g64.x * g64.y * g64.z < 256) {   // and too few of those: 32 x 32 tiles, waves split k
+                int t32[2] = {0, 0};
+                for (int s = 0; s < a.n_seg; ++s) t32[s] = (a.seg[s].j_end - a.seg[s].j_begin + 31) / 32;
+                dim3 g32((a.I + 31) / 32, t32[0] + t32[1], a.n_split);
+                gemm_f32_ksplit4<<<g32, 256, 0, st>>>(a, t32[0]);
+                return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+            }
+        }
         gemm_pq<T, 1><<<g64, 256, 0, st>>>(a, t64[0]);
     } else {
         gemm_pq<T, 2><<<grid, 256, 0, st>>>(a, tiles[0]);
