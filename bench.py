@@ -407,6 +407,17 @@ def main():
     if wl.precision == "bf16" and n_conv == 0:
         # forward: hidden layers; backward: weight and input gradient of a layer share one launch
         n_gemm_launch = (n_layers - (1 if fused_head else 0)) + n_layers
+    elif n_conv == 0:
+        # fp32 MLP: the two gradients of a layer share a launch where both problems are small (the
+        # library's thresholds: fewer than 128 tiles of 128 x 128 and fewer than 256 of 64 x 64)
+        S = max(1, min(8, wl.batch // 64))
+        cdiv = lambda a, b: -(-a // b)
+        small = lambda I, J, z: cdiv(I, 128) * cdiv(J, 128) * z < 128 and cdiv(I, 64) * cdiv(J, 64) * z < 256
+        widths = [wl.obs_elems] + [l[1] for l in wl.layers]
+        n_gemm_launch = n_layers + n_layers + (n_layers - 1)
+        for l in range(1, n_layers):       # layer l + 1 of the network: its weight and input gradient
+            if small(widths[l], widths[l + 1], S) and small(widths[l], wl.batch, 1):
+                n_gemm_launch -= 1
     else:
         n_gemm_launch = (n_layers + n_conv - (1 if fused_head else 0)) + n_layers + (n_layers - 1)
         first = wl.layers[0]

@@ -246,18 +246,19 @@ __global__ __launch_bounds__(256) void gemm_pq(const TjGemmArgs<T> a, const int 
 // 16-byte loads in flight per lane), so a launch has 16 times the waves of the 64 x 64 tiling and
 // each wave a quarter of the dependent MFMA chain.  Waves 1..3 leave their accumulators in LDS,
 // wave 0 adds them in wave order (deterministic) and runs the epilogue.
-__global__ __launch_bounds__(256) void gemm_f32_ksplit4(const TjGemmArgs<float> a, const int tiles_seg0)
+__device__ __forceinline__ void ksplit4_body(const TjGemmArgs<float> &a, const int tiles_seg0, const int bx,
+                                             const int by, const int bz)
 {
     typedef float T;
     __shared__ float red[3][17][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
-    const int sidx = (a.n_seg > 1 && (int)blockIdx.y >= tiles_seg0) ? 1 : 0;
+    const int sidx = (a.n_seg > 1 && by >= tiles_seg0) ? 1 : 0;
     const TjGemmSeg<T> seg = a.seg[sidx];
-    const int j0 = seg.j_begin + ((int)blockIdx.y - (sidx ? tiles_seg0 : 0)) * 32;
+    const int j0 = seg.j_begin + (by - (sidx ? tiles_seg0 : 0)) * 32;
     const int j_end = seg.j_end;
-    const int i0 = blockIdx.x * 32;
-    const int z = blockIdx.z;
+    const int i0 = bx * 32;
+    const int z = bz;
     const int k_begin = z * a.k_chunk;
     const int k_end = min(a.K, k_begin + a.k_chunk);
 
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(256) void gemm_f32_ksplit4(const TjGemmArgs<float> 
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    const bool do_qsum = a.qsum != nullptr && blockIdx.x == 0;
+    const bool do_qsum = a.qsum != nullptr && bx == 0;
     float qs = 0.f;
     for (int s0 = s_begin; s0 < s_end; s0 += 4) {
         u32x4 p[4], q[4];
@@ -310,6 +311,28 @@ __global__ __launch_bounds__(256) void gemm_f32_ksplit4(const TjGemmArgs<float> 
         if (lg == 0 && j < j_end) a.qsum[(size_t)z * a.qsum_zstride + j] = sum;
     }
     pq_epilogue<T>(a, seg, acc, i0, j0, j_end, z, lane);
+}
+
+__global__ __launch_bounds__(256) void gemm_f32_ksplit4(const TjGemmArgs<float> a, const int tiles_seg0)
+{
+    ksplit4_body(a, tiles_seg0, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+}
+
+// Two independent small problems in one launch (a layer's weight gradient and input gradient):
+// blocks [0, nblk0) work on the first, the rest on the second.
+struct PairF32 {
+    TjGemmArgs<float> a[2];
+    int tiles_seg0[2];
+    int gx[2], gy[2];     // tile counts in i and j (the split slices follow)
+    int nblk0;
+};
+
+__global__ __launch_bounds__(256) void gemm_f32_ksplit4_pair(const PairF32 p)
+{
+    const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
+    const int id = (int)blockIdx.x - which * p.nblk0;
+    const int bx = id % p.gx[which], by = (id / p.gx[which]) % p.gy[which], bz = id / (p.gx[which] * p.gy[which]);
+    ksplit4_body(p.a[which], p.tiles_seg0[which], bx, by, bz);
 }
 
 
@@ -1330,6 +1353,42 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
     p.tiles_seg0[1] = tiles[0];
     p.nblk0 = (int)n0;
     gemm_bf16_dlds_pair<2, 64, 3><<<n0 + n1, 512, 0, st>>>(p);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+// Tile counts of the 32 x 32 tiling, and whether the problem is small enough for it
+static bool ksplit4_plan(const TjGemmArgs<float> &a, int t32[2], long &blocks)
+{
+    long t64 = 0, t128 = 0;
+    t32[0] = t32[1] = 0;
+    for (int s = 0; s < a.n_seg; ++s) {
+        const int len = a.seg[s].j_end - a.seg[s].j_begin;
+        t128 += (len + BJ - 1) / BJ;
+        t64 += (len + 63) / 64;
+        t32[s] = (len + 31) / 32;
+    }
+    blocks = (long)((a.I + 31) / 32) * (t32[0] + t32[1]) * a.n_split;
+    // the same thresholds as tj_gemm<float>
+    return (long)((a.I + BI - 1) / BI) * t128 * a.n_split < 128 && (long)((a.I + 63) / 64) * t64 * a.n_split < 256;
+}
+
+int tj_gemm_pair_f32(const TjGemmArgs<float> &a0, const TjGemmArgs<float> &a1, hipStream_t st)
+{
+    int tiles[2], rc;
+    if ((rc = check_args(a0, tiles)) != TJ_OK || (rc = check_args(a1, tiles)) != TJ_OK) return rc;
+    PairF32 p;
+    long n0 = 0, n1 = 0;
+    int t0[2], t1[2];
+    if (!ksplit4_plan(a0, t0, n0) || !ksplit4_plan(a1, t1, n1) || n0 + n1 > 0x7fffffff) {   // one after the other
+        if ((rc = tj_gemm<float>(a0, st)) != TJ_OK) return rc;
+        return tj_gemm<float>(a1, st);
+    }
+    p.a[0] = a0; p.a[1] = a1;
+    p.tiles_seg0[0] = t0[0]; p.tiles_seg0[1] = t1[0];
+    p.gx[0] = (a0.I + 31) / 32; p.gy[0] = t0[0] + t0[1];
+    p.gx[1] = (a1.I + 31) / 32; p.gy[1] = t1[0] + t1[1];
+    p.nblk0 = (int)n0;
+    gemm_f32_ksplit4_pair<<<(unsigned)(n0 + n1), 256, 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 

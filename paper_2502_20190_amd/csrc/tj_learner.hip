@@ -1043,11 +1043,11 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.Ci = dZ[l - 1]; g.ldci = lp.ld_in;
                 g.Cj = dZT[l - 1]; g.ldcj = ldB; g.cj_jmax = B;
             }
-            if constexpr (sizeof(T) == 2) {
-                if (l >= 2) {
-                    if ((rc = tj_gemm_pair(gw, gd, st)) != TJ_OK) return rc;
-                    continue;
-                }
+            if (l >= 2) {
+                if constexpr (sizeof(T) == 2) rc = tj_gemm_pair(gw, gd, st);
+                else rc = tj_gemm_pair_f32(gw, gd, st);
+                if (rc != TJ_OK) return rc;
+                continue;
             }
             if ((rc = tj_gemm<T>(gw, st)) != TJ_OK) return rc;
             if (l >= 2 && (rc = tj_gemm<T>(gd, st)) != TJ_OK) return rc;
