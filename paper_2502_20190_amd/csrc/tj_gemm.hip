@@ -1246,11 +1246,17 @@ int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
 }
 
 // The direct-to-LDS kernel needs whole 64-k stages in every split slice and enough rows to fill
-// its 256-row tiles; everything else takes the register-staged kernel.
+// its 256-row tiles; everything else takes the register-staged kernel.  A skinny product (a head
+// layer: 32 rows or more) over many columns still streams its column operand faster through the
+// direct-to-LDS ring, even though most of a tile's rows repeat the last valid row.
 bool uses_dlds(const TjGemmArgs<tj_bf16> &a)
 {
     const bool whole_stages = a.K % 64 == 0 && (a.n_split == 1 || a.k_chunk % 64 == 0);
-    return whole_stages && a.I >= 128;
+    if (!whole_stages) return false;
+    if (a.I >= 128) return true;
+    long jtot = 0;
+    for (int s = 0; s < a.n_seg; ++s) jtot += a.seg[s].j_end - a.seg[s].j_begin;
+    return a.I >= 32 && jtot * (long)a.K >= (1L << 24);
 }
 
 int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st)
