@@ -423,6 +423,16 @@ def main():
         first = wl.layers[0]
         if wl.precision == "bf16" and wl.in_chw[0] == 4 and first[1] == 32 and first[2] in (4, 8) and first[3] % 2 == 0:
             n_gemm_launch -= 1   # the fused first convolution multiplies with both networks' weights
+        if wl.precision == "bf16":
+            # later convolutions on the gathered-operand kernel (32 / 64 channels, patch length a multiple
+            # of 64): the online and the target pass share one launch
+            c_in = first[1]
+            for kind, out, k, _ in wl.layers[1:]:
+                if kind != synth.CONV:
+                    break
+                if out in (32, 64) and (k * k * c_in) % 64 == 0:
+                    n_gemm_launch -= 1
+                c_in = out
 
     flops = gemm_flops_per_step(wl, synth, fused_head)
     # the kernels behind the forward and backward phases (their launches share the MFMA roofline)

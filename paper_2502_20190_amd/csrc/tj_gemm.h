@@ -135,6 +135,8 @@ template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st);
 // Two independent bf16 GEMMs as one launch where both fit the direct-to-LDS kernel (they share
 // one ramp-up and tail); otherwise the same as two tj_gemm calls.
 int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, hipStream_t st);
+// bf16 with gathered operands: the same for two convolutions of equal shape class
+int tj_gemm_gather_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, hipStream_t st);
 // fp32: the same for two small problems (falls back to two launches otherwise)
 int tj_gemm_pair_f32(const TjGemmArgs<float> &a0, const TjGemmArgs<float> &a1, hipStream_t st);
 

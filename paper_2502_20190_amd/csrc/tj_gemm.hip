@@ -1218,6 +1218,16 @@ __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPa
                                       (int)blockIdx.x - which * p.nblk0);
 }
 
+// The same for two gathered-operand problems (a convolution under the online and under the target
+// weights).
+template <int NFJ>
+__global__ TJ_DLDS_ATTRS(NFJ, 64, 3) void gemm_bf16_dlds_gpair(const GemmPair p)
+{
+    const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
+    dlds_body<NFJ, 64, 3, false, true>(p.a[which], p.tiles_seg0[which], p.tm[which],
+                                       (int)blockIdx.x - which * p.nblk0);
+}
+
 // Tile map and grid size of one problem for the 256 x 64*NFJ tiles.
 template <int NFJ> unsigned plan_dlds(const TjGemmArgs<tj_bf16> &a, TileMap &tm, int tiles[2])
 {
@@ -1359,6 +1369,40 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
     p.tiles_seg0[1] = tiles[0];
     p.nblk0 = (int)n0;
     gemm_bf16_dlds_pair<2, 64, 3><<<n0 + n1, 512, 0, st>>>(p);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
+int tj_gemm_gather_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, hipStream_t st)
+{
+    int tiles[2], rc;
+    if ((rc = check_args(a0, tiles)) != TJ_OK || (rc = check_args(a1, tiles)) != TJ_OK) return rc;
+    auto fits = [](const TjGemmArgs<tj_bf16> &a, int &jtot) {   // what the gathered launch of launch_bf16 takes
+        jtot = a.n_seg == 1 ? a.seg[0].j_end - a.seg[0].j_begin : 0;
+        return a.gather.on && !a.out_map.on && a.n_seg == 1 && jtot <= 128 && a.K % 64 == 0 && a.n_split == 1 &&
+               !a.qsum && a.I >= 1;
+    };
+    int j0 = 0, j1 = 0;
+    if (!fits(a0, j0) || !fits(a1, j1) || (j0 > 64) != (j1 > 64)) {   // no common kernel: one after the other
+        if ((rc = tj_gemm<tj_bf16>(a0, st)) != TJ_OK) return rc;
+        return tj_gemm<tj_bf16>(a1, st);
+    }
+    GemmPair p;
+    p.a[0] = a0; p.a[1] = a1;
+    if (j0 > 64) {
+        const unsigned n0 = plan_dlds<2>(a0, p.tm[0], tiles);
+        p.tiles_seg0[0] = tiles[0];
+        const unsigned n1 = plan_dlds<2>(a1, p.tm[1], tiles);
+        p.tiles_seg0[1] = tiles[0];
+        p.nblk0 = (int)n0;
+        gemm_bf16_dlds_gpair<2><<<n0 + n1, 512, 0, st>>>(p);
+    } else {
+        const unsigned n0 = plan_dlds<1>(a0, p.tm[0], tiles);
+        p.tiles_seg0[0] = tiles[0];
+        const unsigned n1 = plan_dlds<1>(a1, p.tm[1], tiles);
+        p.tiles_seg0[1] = tiles[0];
+        p.nblk0 = (int)n0;
+        gemm_bf16_dlds_gpair<1><<<n0 + n1, 512, 0, st>>>(p);
+    }
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 

@@ -1608,10 +1608,11 @@ template <typename T> struct ConvLearner : tj_learner {
                                                               round_up((int)((size_t)Bmax * y.OHW), VE));
                     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
                 }
+                TjGemmArgs<T> both[2];
                 for (int net = 0; net < 2; ++net) {   // online on s and s', target on s'
                     const size_t row0 = net == 0 ? 0 : (l == 0 ? Ms : 2 * Ms);
                     const size_t nrow = net == 0 ? 2 * Ms : Ms;
-                    TjGemmArgs<T> gm;
+                    TjGemmArgs<T> &gm = both[net];
                     memset(&gm, 0, sizeof(gm));
                     gm.n_seg = 1;
                     if (y.implicit) {   // patches gathered from the images themselves
@@ -1627,8 +1628,17 @@ template <typename T> struct ConvLearner : tj_learner {
                     gm.bias_j = (net == 0 ? theta_on : theta_tg) + y.b_off;
                     gm.relu = 1;
                     gm.Cj = act[l + 1] + (net == 0 ? 0 : 2 * Ms * y.O); gm.ldcj = y.O; gm.cj_jmax = y.O;
-                    if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
                 }
+                bool paired = false;
+                if constexpr (sizeof(T) == 2) {
+                    if (y.implicit) {   // the two networks' passes share one launch
+                        if ((rc = tj_gemm_gather_pair(both[0], both[1], st)) != TJ_OK) return rc;
+                        paired = true;
+                    }
+                }
+                if (!paired)
+                    for (int net = 0; net < 2; ++net)
+                        if ((rc = tj_gemm<T>(both[net], st)) != TJ_OK) return rc;
             } else {
                 if (l > 0 && lay[l - 1].kind == TJ_LAYER_CONV2D)   // transposed input of the s rows
                     if ((rc = transpose(act[l], y.ldK, y.XT, ldB, B, y.K, st)) != TJ_OK) return rc;
