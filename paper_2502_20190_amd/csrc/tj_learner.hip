@@ -734,6 +734,37 @@ __global__ __launch_bounds__(256) void ppo_sample(const float *__restrict__ Z, i
     if (value) value[j] = z[A];
 }
 
+// Sum of S fp32 partial outputs [j][i] of a split forward contraction (slice order), plus the bias
+// of row j's network (rows >= j_target use the second), ReLU, cast; writes the activation rows
+// Y[j][i] and, for j < jt_max, the transposed copy YT[i][j].  Four consecutive i per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void sum_bias_relu(const float *__restrict__ part, size_t zstride, int S, int J,
+                                                     int I, const float *__restrict__ bias0,
+                                                     const float *__restrict__ bias1, int j_target,
+                                                     T *__restrict__ Y, int ldy, T *__restrict__ YT, int ldyt,
+                                                     int jt_max)
+{
+    const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int vpr = I / 4;
+    if (v >= (size_t)J * vpr) return;
+    const int j = (int)(v / vpr), i = (int)(v - (size_t)j * vpr) * 4;
+    const float *src = part + (size_t)j * I + i;
+    float4 acc = *(const float4 *)src;
+    for (int z = 1; z < S; ++z) {
+        const float4 p = *(const float4 *)(src + (size_t)z * zstride);
+        acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w;
+    }
+    const float *b = (j >= j_target ? bias1 : bias0) + i;
+    const float o[4] = {fmaxf(acc.x + b[0], 0.f), fmaxf(acc.y + b[1], 0.f), fmaxf(acc.z + b[2], 0.f),
+                        fmaxf(acc.w + b[3], 0.f)};
+    T *y = Y + (size_t)j * ldy + i;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = TjElem<T>::from_f32(o[e]);
+    if (j < jt_max)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) YT[(size_t)(i + e) * ldyt + j] = TjElem<T>::from_f32(o[e]);
+}
+
 struct LayerPlan {
     int in, out;           // features
     int ld_in, ld_out;     // padded pitches (elements of T)
@@ -1313,6 +1344,10 @@ template <typename T> struct ConvLearner : tj_learner {
         T *dZh, *Wd;
         T *Wc_on, *WcT_on, *Wc_tg, *patches, *patchesT, *XT, *dZ, *dZT, *dpatch;
         float *part;
+        // linear layer whose forward fills too few tiles: the contraction is split f_split ways into
+        // fp32 partial outputs, summed with bias and ReLU by sum_bias_relu
+        int f_split, f_chunk;
+        float *f_part;
     };
     tj_learner_desc d;
     int L = 0, A = 0, Bmax = 0, ldB = 0, ldA = 0;
@@ -1448,12 +1483,26 @@ template <typename T> struct ConvLearner : tj_learner {
                     y.dZ = (T *)a.take(B * y.OHW * y.O * sizeof(T));
                     y.dZT = (T *)a.take((size_t)y.O * round_up((int)(B * y.OHW), VE) * sizeof(T));
                 }
+                y.f_split = 1; y.f_chunk = 0; y.f_part = nullptr;
                 y.dpatch = (l > 0 && !y.dgrad_gather) ? (T *)a.take(B * y.OHW * y.ldK * sizeof(T)) : nullptr;
                 y.dZh = y.dgrad_gather ? (T *)a.take(B * (y.g.OH + 2 * y.pad) * (y.g.OW + 2 * y.pad) * y.O * sizeof(T))
                                        : nullptr;
             } else {
                 act[l] = (T *)a.take(3 * B * y.ldK * sizeof(T));
                 y.patches = y.patchesT = y.dpatch = nullptr;
+                y.f_split = 1; y.f_chunk = y.ldK; y.f_part = nullptr;
+                if (sizeof(T) == 2 && l + 1 < L && y.ldK % 64 == 0 && y.O >= 128 && y.O % 4 == 0) {
+                    const long tiles = (long)((y.O + 255) / 256) * ((3 * B + 63) / 64);
+                    const int stages = y.ldK / 64;
+                    if (tiles < 64 && stages >= 16) {   // a long contraction on a few blocks
+                        int fs = (int)(256 / tiles);
+                        if (fs > 8) fs = 8;
+                        if (fs > stages / 4) fs = stages / 4;
+                        y.f_chunk = (stages + fs - 1) / fs * 64;
+                        y.f_split = (y.ldK + y.f_chunk - 1) / y.f_chunk;
+                        y.f_part = (float *)a.take((size_t)y.f_split * 3 * B * y.O * 4);
+                    }
+                }
                 y.XT = (T *)a.take((size_t)y.K * ldB * sizeof(T));
                 y.dZ = (T *)a.take(B * y.ldO * sizeof(T));
                 y.dZT = (T *)a.take((size_t)y.O * ldB * sizeof(T));
@@ -1651,6 +1700,18 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.ldp = y.ldK; gm.ldq = y.ldK;
                 gm.I = y.O; gm.K = y.ldK; gm.k_chunk = gm.K; gm.n_split = 1;
                 if (l + 1 == L) break;   // the head layer runs with the TD step below
+                if (y.f_split > 1) {   // split contraction: partial sums, then bias + ReLU + both layouts
+                    gm.seg[0].bias = nullptr; gm.seg[1].bias = nullptr;
+                    gm.n_split = y.f_split; gm.k_chunk = y.f_chunk;
+                    gm.Cf = y.f_part; gm.ldcf = y.O; gm.cf_zstride = (size_t)3 * B * y.O;
+                    if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                    const size_t nvec = (size_t)3 * B * (y.O / 4);
+                    sum_bias_relu<T><<<grid1(nvec), 256, 0, st>>>(y.f_part, gm.cf_zstride, y.f_split, 3 * B, y.O,
+                                                               theta_on + y.b_off, theta_tg + y.b_off, 2 * B,
+                                                               act[l + 1], lay[l + 1].ldK, lay[l + 1].XT, ldB, B);
+                    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                    continue;
+                }
                 gm.relu = 1;
                 gm.Ci = act[l + 1]; gm.ldci = lay[l + 1].ldK;
                 gm.Cj = lay[l + 1].XT; gm.ldcj = ldB; gm.cj_jmax = B;
