@@ -230,16 +230,33 @@ __global__ __launch_bounds__(256) void dgrad_weights(const float *__restrict__ w
     wd[t] = tj_f32_to_bf16(v);
 }
 
-// Sums n_part partial gradient slices of n elements each into dst.  A block owns 128 consecutive
-// elements (32 lanes x 16 bytes); its 8 thread rows each add every 8th slice, four loads in flight
-// at a time, then the 8 sums are added in a fixed order: deterministic for a given n_part.
-// Slices start 16-byte aligned and are padded to a multiple of 4 elements (zstride % 4 == 0).
-__global__ __launch_bounds__(256) void reduce_parts(const float *__restrict__ part, size_t zstride, int n_part,
-                                                    float *__restrict__ dst, size_t n)
+// Sums the partial gradient slices of every layer into the flat gradient, all layers in one launch.
+// Job q: n_part slices of n elements each (slice z at part + z * zstride) -> dst[0, n); blocks
+// [block_begin[q], block_begin[q + 1]) work on it.  A block owns 128 consecutive elements (32 lanes
+// x 16 bytes); its 8 thread rows each add every 8th slice, four loads in flight at a time, then the
+// 8 sums are added in a fixed order: deterministic for a given n_part.  Slices start 16-byte aligned
+// and are padded to a multiple of 4 elements (zstride % 4 == 0).
+struct ReduceJobs {
+    int n_job;
+    const float *part[TJ_MAX_LAYERS];
+    size_t zstride[TJ_MAX_LAYERS];
+    int n_part[TJ_MAX_LAYERS];
+    float *dst[TJ_MAX_LAYERS];
+    size_t n[TJ_MAX_LAYERS];
+    unsigned block_begin[TJ_MAX_LAYERS + 1];
+};
+
+__global__ __launch_bounds__(256) void reduce_parts(const ReduceJobs jobs)
 {
     __shared__ float4 sh[8][32];
+    int q = 0;
+    while (q + 1 < jobs.n_job && blockIdx.x >= jobs.block_begin[q + 1]) ++q;
+    const float *__restrict__ part = jobs.part[q];
+    const size_t zstride = jobs.zstride[q], n = jobs.n[q];
+    const int n_part = jobs.n_part[q];
+    float *__restrict__ dst = jobs.dst[q];
     const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
-    const size_t e = ((size_t)blockIdx.x * 32 + col) * 4;
+    const size_t e = ((size_t)(blockIdx.x - jobs.block_begin[q]) * 32 + col) * 4;
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
     if (e < n) {
         const float *src = part + e;
@@ -266,8 +283,8 @@ __global__ __launch_bounds__(256) void reduce_parts(const float *__restrict__ pa
     }
     const float out[4] = {sum.x, sum.y, sum.z, sum.w};
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (e + q < n) dst[e + q] = out[q];
+    for (int k = 0; k < 4; ++k)
+        if (e + k < n) dst[e + k] = out[k];
 }
 
 }  // namespace tjconv

@@ -1734,6 +1734,15 @@ template <typename T> struct ConvLearner : tj_learner {
         if ((rc = mark(2, st)) != TJ_OK) return rc;
 
         // ---- backward through Q_online(s)
+        // the partial weight gradients of all layers are summed by one launch after the loop
+        tjconv::ReduceJobs jobs;
+        jobs.n_job = 0;
+        jobs.block_begin[0] = 0;
+        auto add_reduce_job = [&](const float *part, size_t zstride, int n_part, float *dst, size_t n) {
+            const int q = jobs.n_job++;
+            jobs.part[q] = part; jobs.zstride[q] = zstride; jobs.n_part[q] = n_part; jobs.dst[q] = dst; jobs.n[q] = n;
+            jobs.block_begin[q + 1] = jobs.block_begin[q] + (unsigned)((n + 127) / 128);
+        };
         for (int l = L - 1; l >= 0; --l) {
             NLayer &y = lay[l];
             const bool conv = y.kind == TJ_LAYER_CONV2D;
@@ -1750,10 +1759,7 @@ template <typename T> struct ConvLearner : tj_learner {
                     wa.n_split = y.n_split;
                     wa.m_chunk = round_up((int)((Ms + y.n_split - 1) / y.n_split), 32);
                     if ((rc = tj_conv_wgrad(wa, st)) != TJ_OK) return rc;
-                    const size_t n = (size_t)y.O * y.K + y.O;   // weights, then bias: one block of the gradient
-                    tjconv::reduce_parts<<<dim3((unsigned)((n + 127) / 128)), 256, 0, st>>>(y.part, y.part_stride,
-                                                                                         y.n_split, grad + y.w_off, n);
-                    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                    add_reduce_job(y.part, y.part_stride, y.n_split, grad + y.w_off, (size_t)y.O * y.K + y.O);
                     wgrad_done = true;
                 }
             }
@@ -1773,10 +1779,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.Cf = y.part; gm.ldcf = y.K; gm.cf_zstride = y.part_stride;
                 gm.qsum = y.part + (size_t)y.O * y.K; gm.qsum_zstride = y.part_stride;
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
-                const size_t n = (size_t)y.O * y.K + y.O;
-                tjconv::reduce_parts<<<dim3((unsigned)((n + 127) / 128)), 256, 0, st>>>(y.part, y.part_stride, ns,
-                                                                                     grad + y.w_off, n);
-                if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                add_reduce_job(y.part, y.part_stride, ns, grad + y.w_off, (size_t)y.O * y.K + y.O);
             }
             if (l == 0) break;
             NLayer &below = lay[l - 1];
@@ -1843,6 +1846,8 @@ template <typename T> struct ConvLearner : tj_learner {
                     return rc;
             }
         }
+        tjconv::reduce_parts<<<jobs.block_begin[jobs.n_job], 256, 0, st>>>(jobs);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(3, st)) != TJ_OK) return rc;
 
         t += 1;
