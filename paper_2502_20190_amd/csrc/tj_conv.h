@@ -215,11 +215,24 @@ __global__ __launch_bounds__(256) void pad_halo(const tj_bf16 *__restrict__ src,
 // (a, b, o) over the taps and the output channels:
 //   Wd[j][(a*A + b)*O + o] = W[o][kh][kw][c],  kh = py + (A-1-a) s,  kw = px + (A-1-b) s   (0 if kh or kw >= k)
 // with W the fp32 master weights in the kernels' order [o][(kh*k + kw)*C + c].
-__global__ __launch_bounds__(256) void dgrad_weights(const float *__restrict__ w, tj_bf16 *__restrict__ wd, int O,
-                                                     int C, int k, int s, int A)
+// All layers in one launch: blocks [block_begin[q], block_begin[q + 1]) build the matrix of job q.
+struct DgradWeightJobs {
+    int n_job;
+    const float *w[TJ_MAX_LAYERS];
+    tj_bf16 *wd[TJ_MAX_LAYERS];
+    int O[TJ_MAX_LAYERS], C[TJ_MAX_LAYERS], k[TJ_MAX_LAYERS], s[TJ_MAX_LAYERS], A[TJ_MAX_LAYERS];
+    unsigned block_begin[TJ_MAX_LAYERS + 1];
+};
+
+__global__ __launch_bounds__(256) void dgrad_weights(const DgradWeightJobs jobs)
 {
+    int q = 0;
+    while (q + 1 < jobs.n_job && blockIdx.x >= jobs.block_begin[q + 1]) ++q;
+    const float *__restrict__ w = jobs.w[q];
+    tj_bf16 *__restrict__ wd = jobs.wd[q];
+    const int O = jobs.O[q], C = jobs.C[q], k = jobs.k[q], s = jobs.s[q], A = jobs.A[q];
     const int Kd = A * A * O, N = s * s * C;
-    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t t = (size_t)(blockIdx.x - jobs.block_begin[q]) * 256 + threadIdx.x;
     if (t >= (size_t)N * Kd) return;
     const int col = (int)(t % Kd), j = (int)(t / Kd);
     const int o = col % O, b = (col / O) % A, a = col / (O * A);

@@ -1554,14 +1554,21 @@ template <typename T> struct ConvLearner : tj_learner {
         }
         if constexpr (sizeof(T) == 2) {
             if (online) {
+                tjconv::DgradWeightJobs dj;
+                dj.n_job = 0;
+                dj.block_begin[0] = 0;
                 for (int l = 0; l < L; ++l) {
                     NLayer &y = lay[l];
                     if (!y.dgrad_gather) continue;
-                    const size_t tot = (size_t)y.Nd * y.Kd;
-                    tjconv::dgrad_weights<<<(unsigned)((tot + 255) / 256), 256, 0, st>>>(theta_on + y.w_off, y.Wd, y.O,
-                                                                                       y.g.C, y.g.k, y.g.s, y.A);
+                    const int q = dj.n_job++;
+                    dj.w[q] = theta_on + y.w_off; dj.wd[q] = y.Wd;
+                    dj.O[q] = y.O; dj.C[q] = y.g.C; dj.k[q] = y.g.k; dj.s[q] = y.g.s; dj.A[q] = y.A;
+                    dj.block_begin[q + 1] = dj.block_begin[q] + (unsigned)(((size_t)y.Nd * y.Kd + 255) / 256);
                 }
-                if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                if (dj.n_job > 0) {
+                    tjconv::dgrad_weights<<<dj.block_begin[dj.n_job], 256, 0, st>>>(dj);
+                    if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+                }
             }
         }
         return launch_cast<T>(jobs, n, st);
