@@ -433,6 +433,11 @@ def main():
                 if out in (32, 64) and (k * k * c_in) % 64 == 0:
                     n_gemm_launch -= 1
                 c_in = out
+            # a linear layer's weight and input gradient share a launch where both fit the direct-to-LDS
+            # kernel (the input gradient contracts over the layer's padded width: whole 64-element stages)
+            for li, (kind, out, _, _) in enumerate(wl.layers):
+                if kind == synth.LIN and li > 0 and (-(-out // 8) * 8) % 64 == 0 and wl.batch % 64 == 0:
+                    n_gemm_launch -= 1
 
     flops = gemm_flops_per_step(wl, synth, fused_head)
     # the kernels behind the forward and backward phases (their launches share the MFMA roofline)

@@ -1770,8 +1770,10 @@ template <typename T> struct ConvLearner : tj_learner {
                     wgrad_done = true;
                 }
             }
+            TjGemmArgs<T> gw;            // a linear layer's weight gradient waits for its input gradient:
+            bool gw_pending = false;     // the two share one launch (bf16)
             if (!wgrad_done) {   // dW[o][k] = sum_m dZ[m][o] X[m][k] (k in kernel order), db[o] = sum_m dZ[m][o]
-                TjGemmArgs<T> gm;
+                TjGemmArgs<T> &gm = gw;
                 memset(&gm, 0, sizeof(gm));
                 gm.n_seg = 1;
                 gm.seg[0] = {0, y.O, conv ? y.patchesT : y.XT, nullptr, 0};
@@ -1785,7 +1787,8 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.n_split = ns;
                 gm.Cf = y.part; gm.ldcf = y.K; gm.cf_zstride = y.part_stride;
                 gm.qsum = y.part + (size_t)y.O * y.K; gm.qsum_zstride = y.part_stride;
-                if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                gw_pending = sizeof(T) == 2 && !conv && l > 0;
+                if (!gw_pending && (rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
                 add_reduce_job(y.part, y.part_stride, ns, grad + y.w_off, (size_t)y.O * y.K + y.O);
             }
             if (l == 0) break;
@@ -1801,7 +1804,16 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.mask = act[l]; gm.ldmask = y.ldK;
                 gm.Ci = below.dZ; gm.ldci = y.ldK;
                 if (below.kind == TJ_LAYER_LINEAR) { gm.Cj = below.dZT; gm.ldcj = ldB; gm.cj_jmax = B; }
-                if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                if constexpr (sizeof(T) == 2) {
+                    if (gw_pending) {
+                        if ((rc = tj_gemm_pair(gw, gm, st)) != TJ_OK) return rc;
+                        gw_pending = false;
+                    } else if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) {
+                        return rc;
+                    }
+                } else {
+                    if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
+                }
             } else if (y.dgrad_gather) {
                 // dX[img, s yy + py, s xx + px, c] = sum_{a,b,o} dZ0[img, yy + a, xx + b, o] * Wd[(py,px,c)][(a,b,o)],
                 // dZ0 = the output gradient with a zero border of A-1: a stride-1 gathered GEMM whose row is a
