@@ -116,6 +116,40 @@ __global__ __launch_bounds__(256) void transpose2d(const T *__restrict__ src, in
     }
 }
 
+// The same for 2-byte elements with 16-byte accesses on both sides: a 64 x 64 tile per block, eight
+// elements per load and per store.  lds, ldd and Cc are multiples of 8, both bases 16-byte aligned,
+// ldd >= R rounded up to 8; rows past R read as zero (so the pad columns of dst are written as zeros).
+__global__ __launch_bounds__(256) void transpose2d_v8(const uint16_t *__restrict__ src, int lds,
+                                                      uint16_t *__restrict__ dst, int ldd, int R, int Cc)
+{
+    __shared__ uint16_t tile[64][66];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int v = threadIdx.x + 256 * i;          // 512 vectors of the tile: row v / 8, columns 8 (v % 8) ..
+        const int r = v >> 3, cv = (v & 7) * 8;
+        uint4 d = make_uint4(0u, 0u, 0u, 0u);
+        if (r0 + r < R && c0 + cv < Cc) d = *(const uint4 *)(src + (size_t)(r0 + r) * lds + c0 + cv);
+        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            tile[r][cv + 2 * e] = (uint16_t)(w[e] & 0xFFFFu);
+            tile[r][cv + 2 * e + 1] = (uint16_t)(w[e] >> 16);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int v = threadIdx.x + 256 * i;          // output row (source column) v / 8, source rows 8 (v % 8) ..
+        const int c = v >> 3, rv = (v & 7) * 8;
+        if (c0 + c >= Cc || r0 + rv >= (R + 7) / 8 * 8) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[rv + 2 * e][c] | ((uint32_t)tile[rv + 2 * e + 1][c] << 16);
+        *(uint4 *)(dst + (size_t)(c0 + c) * ldd + r0 + rv) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 // Input gradient of a convolution from the patch-gradient matrix (gather form, no atomics):
 // dA[img,y,x,c] = sum over the patches (oh, ow) and kernel offsets (kh, kw) with
 // oh*s + kh = y, ow*s + kw = x of dpatch[(img,oh,ow)][(kh,kw,c)], then the ReLU derivative of

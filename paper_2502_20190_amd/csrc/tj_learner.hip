@@ -1578,6 +1578,14 @@ template <typename T> struct ConvLearner : tj_learner {
 
     int transpose(const T *src, int lds, T *dst, int ldd, int R, int Cc, hipStream_t st)
     {
+        if constexpr (sizeof(T) == 2) {
+            if (lds % 8 == 0 && ldd % 8 == 0 && Cc % 8 == 0 && ldd >= round_up(R, 8) &&
+                (((uintptr_t)src | (uintptr_t)dst) & 15) == 0) {
+                dim3 g64((Cc + 63) / 64, (R + 63) / 64);
+                tjconv::transpose2d_v8<<<g64, 256, 0, st>>>((const uint16_t *)src, lds, (uint16_t *)dst, ldd, R, Cc);
+                return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+            }
+        }
         dim3 grid((Cc + 31) / 32, (R + 31) / 32);
         tjconv::transpose2d<T><<<grid, 256, 0, st>>>(src, lds, dst, ldd, R, Cc);
         return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
