@@ -175,7 +175,7 @@ def test_ragged_shapes_and_batch_changes(tj, orc, precision):
     """Widths and batches that are multiples of nothing, a batch that shrinks and grows again
     (pad columns of the transposed activations must read as zero), 63 actions (the most the
     head kernel accepts)."""
-    for (D, hidden, A) in ((19, (70, 33), 5), (130, (200,), 63), (7, (), 3)):
+    for (D, hidden, A) in ((19, (70, 33), 5), (130, (200,), 63), (7, (), 3), (6, (40,), 1)):
         g, o = _pair(tj, orc, D, hidden, A, precision, 700, seed=3, lr=1e-3)
         for i, n in enumerate((700, 100, 257)):
             rows = _batch(orc, o, D, A, 2, 350, 20 + i, precision, n=n)
