@@ -222,8 +222,17 @@ enum {
     TJ_STATE_ADAM_V = 4,  /* second moment [P]                                    */
     TJ_STATE_QVALS = 5,   /* last step: Q_online(s), Q_online(s'), Q_target(s'),
                              each [batch][A], concatenated (get only)             */
-    TJ_STATE_ASTAR = 6    /* last step: greedy next actions as floats [batch]
+    TJ_STATE_ASTAR = 6,   /* last step: greedy next actions as floats [batch]
                              (get only)                                           */
+    /* The weights as the contraction kernels read them (get only, [P], flat
+     * order of TJ_STATE_PARAMS): every weight is the compute-type copy converted
+     * back to float (bf16 precision: the round-to-nearest-even image of the
+     * master weight; fp32: the master weight itself), biases are the master's.
+     * _T reads the transposed copies the input-gradient kernels contract over
+     * (layers that keep none read as the straight copy). */
+    TJ_STATE_WEIGHTS_COMPUTE = 7,        /* online network                        */
+    TJ_STATE_WEIGHTS_COMPUTE_T = 8,      /* online network, transposed copies     */
+    TJ_STATE_WEIGHTS_COMPUTE_TARGET = 9  /* target network                        */
 };
 
 /* Number of parameters P of the network in `desc` (0 if desc is bad).  Flat
@@ -252,6 +261,8 @@ int tj_learner_destroy(tj_learner *lrn);
  * outside the square root) with t = 1, 2, ...; then, if t is a multiple of
  * target_interval, the target parameters become a copy of the online ones.
  * `mb` holds device pointers (idx is not read); mb->batch <= max_batch.
+ * Actions are expected in [0, A); the kernels cannot report a bad one, so an
+ * action outside that range is read as the nearest valid one (0 or A - 1).
  * d_stats (device pointer, may be NULL) receives loss and t. */
 int tj_learner_step(tj_learner *lrn, const tj_minibatch *mb, tj_step_stats *d_stats,
                     void *hip_stream);

@@ -23,7 +23,7 @@ TJ_PRECISION_FP32, TJ_PRECISION_BF16 = 0, 1
 TJ_LAYER_LINEAR, TJ_LAYER_CONV2D = 0, 1
 TJ_MAX_LAYERS = 8
 (TJ_STATE_PARAMS, TJ_STATE_TARGET, TJ_STATE_GRADS, TJ_STATE_ADAM_M, TJ_STATE_ADAM_V, TJ_STATE_QVALS,
- TJ_STATE_ASTAR) = range(7)
+ TJ_STATE_ASTAR, TJ_STATE_WEIGHTS_COMPUTE, TJ_STATE_WEIGHTS_COMPUTE_T, TJ_STATE_WEIGHTS_COMPUTE_TARGET) = range(10)
 
 EXPORTS = [
     "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_actor_act", "tj_balance_plan", "tj_frame_buffer_arena_bytes", "tj_frame_buffer_create",
@@ -521,7 +521,7 @@ class PpoLearner:
         d.max_batch = max_batch
         d.lr, d.beta1, d.beta2, d.eps, d.clip, d.c_v, d.c_e = lr, beta1, beta2, eps, clip, c_v, c_e
         self.desc = d
-        self.n_actions = n_actions
+        self.obs_dim, self.hidden, self.n_actions = obs_dim, tuple(hidden), n_actions
         self.n_params = lib().tj_ppo_num_params(C.byref(d))
         nbytes = lib().tj_ppo_arena_bytes(C.byref(d))
         if nbytes == 0 or self.n_params == 0:

@@ -855,17 +855,6 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16(const TjGemmArgs<tj_bf16> a,
 // and also says that every wave is done reading the buffer about to be refilled.
 template <int N> struct IntC { static constexpr int value = N; };
 
-// (bytes of k per row per stage, ring depth) for the 128-, 192- and 256-wide j tiles
-#ifndef TJ_CFG2
-#define TJ_CFG2 128, 3
-#endif
-#ifndef TJ_CFG3
-#define TJ_CFG3 128, 2
-#endif
-#ifndef TJ_CFG4
-#define TJ_CFG4 128, 2
-#endif
-
 template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false>
 __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const int tiles_seg0, const TileMap &tm,
                                           const int block_id)
@@ -1294,9 +1283,6 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
             const long cost = ((t + 255) / 256) * nfj;
             if (best_cost < 0 || cost <= best_cost) { best = nfj; best_cost = cost; }
         }
-#ifdef TJ_FORCE_NFJ
-        best = TJ_FORCE_NFJ;   // tuning builds only
-#endif
         if (best == 2) {
             // more tiles than CUs: the shallow-stage variant fits two blocks per CU, so one block's
             // epilogue overlaps the other's main loop; otherwise one block per CU with deep stages
@@ -1305,10 +1291,10 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
             t *= (long)((a.I + 255) / 256) * a.n_split;
             if (t > 256) return launch_dlds<2, 64, 3>(a, st);
             // at most half the CUs would get a 128-wide tile: 64-wide tiles give twice the blocks
-            return t <= 128 ? launch_dlds<1, 128, 3>(a, st) : launch_dlds<2, TJ_CFG2>(a, st);
+            return t <= 128 ? launch_dlds<1, 128, 3>(a, st) : launch_dlds<2, 128, 3>(a, st);
         }
-        if (best == 3) return launch_dlds<3, TJ_CFG3>(a, st);
-        return launch_dlds<4, TJ_CFG4>(a, st);
+        if (best == 3) return launch_dlds<3, 128, 2>(a, st);
+        return launch_dlds<4, 128, 2>(a, st);
     }
     TileMap tm;
     tm.tiles_i = (a.I + B2I - 1) / B2I;
@@ -1359,7 +1345,7 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
         p.tiles_seg0[1] = tiles[0];
         if (m0 + m1 >= 512) {
             p.nblk0 = (int)m0;
-            gemm_bf16_dlds_pair<4, TJ_CFG4><<<m0 + m1, 512, 0, st>>>(p);
+            gemm_bf16_dlds_pair<4, 128, 2><<<m0 + m1, 512, 0, st>>>(p);
             return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
         }
     }

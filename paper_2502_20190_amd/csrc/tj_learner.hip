@@ -794,6 +794,20 @@ bool all_linear(const tj_learner_desc *d)
     return d->obs_dtype == TJ_OBS_F32;
 }
 
+// Reads n elements of compute type from the device and widens them to float (host side).
+template <typename T> int fetch_as_float(const T *d_src, size_t n, std::vector<float> &out, hipStream_t st)
+{
+    std::vector<T> raw(n);
+    out.resize(n);
+    if (hipMemcpyAsync(raw.data(), d_src, n * sizeof(T), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        (void)hipGetLastError();
+        return TJ_ERR_DEVICE;
+    }
+    for (size_t i = 0; i < n; ++i) out[i] = TjElem<T>::to_f32(raw[i]);
+    return TJ_OK;
+}
+
 }  // namespace
 
 struct tj_learner {
@@ -1163,6 +1177,30 @@ template <typename T> struct MlpLearner : tj_learner {
             if (n != P) return TJ_ERR_INVALID_ARG;
             TJ_HIP_TRY(hipMemcpyAsync(h_out, gpart, P * 4, hipMemcpyDeviceToHost, st));
             TJ_HIP_TRY(hipStreamSynchronize(st));
+            return TJ_OK;
+        }
+        if (which == TJ_STATE_WEIGHTS_COMPUTE || which == TJ_STATE_WEIGHTS_COMPUTE_T ||
+            which == TJ_STATE_WEIGHTS_COMPUTE_TARGET) {
+            if (n != P) return TJ_ERR_INVALID_ARG;
+            const bool tg = which == TJ_STATE_WEIGHTS_COMPUTE_TARGET, tr = which == TJ_STATE_WEIGHTS_COMPUTE_T;
+            TJ_HIP_TRY(hipMemcpyAsync(h_out, tg ? theta_tg : theta_on, P * 4, hipMemcpyDeviceToHost, st));   // biases
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            std::vector<float> w;
+            for (int l = 0; l < L; ++l) {
+                const LayerPlan &lp = lay[l];
+                float *dst = h_out + lp.w_off;
+                int rc;
+                if (tr) {
+                    if ((rc = fetch_as_float<T>(WcT_on[l], (size_t)lp.in * lp.ld_out, w, st)) != TJ_OK) return rc;
+                    for (int o = 0; o < lp.out; ++o)
+                        for (int k = 0; k < lp.in; ++k) dst[(size_t)o * lp.in + k] = w[(size_t)k * lp.ld_out + o];
+                } else {
+                    if ((rc = fetch_as_float<T>(tg ? Wc_tg[l] : Wc_on[l], (size_t)lp.out * lp.ld_in, w, st)) != TJ_OK)
+                        return rc;
+                    for (int o = 0; o < lp.out; ++o)
+                        for (int k = 0; k < lp.in; ++k) dst[(size_t)o * lp.in + k] = w[(size_t)o * lp.ld_in + k];
+                }
+            }
             return TJ_OK;
         }
         if (which == TJ_STATE_QVALS) {
@@ -1992,6 +2030,30 @@ template <typename T> struct ConvLearner : tj_learner {
             std::vector<float> tmp(P);
             TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), src, P * 4, hipMemcpyDeviceToHost, st));
             TJ_HIP_TRY(hipStreamSynchronize(st));
+            permute_host(tmp.data(), h_out, false);
+            return TJ_OK;
+        }
+        if (which == TJ_STATE_WEIGHTS_COMPUTE || which == TJ_STATE_WEIGHTS_COMPUTE_T ||
+            which == TJ_STATE_WEIGHTS_COMPUTE_TARGET) {
+            if (n != P) return TJ_ERR_INVALID_ARG;
+            const bool tg = which == TJ_STATE_WEIGHTS_COMPUTE_TARGET, tr = which == TJ_STATE_WEIGHTS_COMPUTE_T;
+            std::vector<float> tmp(P), w;
+            TJ_HIP_TRY(hipMemcpyAsync(tmp.data(), tg ? theta_tg : theta_on, P * 4, hipMemcpyDeviceToHost, st));   // biases
+            TJ_HIP_TRY(hipStreamSynchronize(st));
+            for (int l = 0; l < L; ++l) {
+                const NLayer &y = lay[l];
+                float *dst = tmp.data() + y.w_off;   // the kernels' order [O][k]
+                int rc;
+                if (tr && l > 0) {                   // the first layer keeps no transposed copy
+                    if ((rc = fetch_as_float<T>(y.WcT_on, (size_t)y.K * y.ldO, w, st)) != TJ_OK) return rc;
+                    for (int o = 0; o < y.O; ++o)
+                        for (int k = 0; k < y.K; ++k) dst[(size_t)o * y.K + k] = w[(size_t)k * y.ldO + o];
+                } else {
+                    if ((rc = fetch_as_float<T>(tg ? y.Wc_tg : y.Wc_on, (size_t)y.O * y.ldK, w, st)) != TJ_OK) return rc;
+                    for (int o = 0; o < y.O; ++o)
+                        for (int k = 0; k < y.K; ++k) dst[(size_t)o * y.K + k] = w[(size_t)o * y.ldK + k];
+                }
+            }
             permute_host(tmp.data(), h_out, false);
             return TJ_OK;
         }

@@ -53,6 +53,16 @@ def test_plan_against_a_simulated_ring(orc, tr_l, tr_a, batch, k):
 
 
 def test_library_routine_equals_the_oracle(orc):
+    _library_routine_equals_the_oracle(orc)
+
+
+@pytest.mark.gpu
+def test_library_routine_equals_the_oracle_on_the_gpu_box(orc):
+    """The same comparison in the GPU run (host arithmetic of the library, as loaded there)."""
+    _library_routine_equals_the_oracle(orc)
+
+
+def _library_routine_equals_the_oracle(orc):
     from paper_2502_20190_amd import binding as tj
 
     rng = np.random.default_rng(4)
