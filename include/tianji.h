@@ -42,7 +42,8 @@ typedef enum {
     TJ_ERR_ARENA_TOO_SMALL = -3, /* arena_bytes < tj_*_arena_bytes()             */
     TJ_ERR_NO_ELIGIBLE = -4,     /* a sample found no slot inside the gate       */
     TJ_ERR_CAPACITY = -5,        /* insert of more rows than the ring holds      */
-    TJ_ERR_DEVICE = -6           /* a HIP call failed                            */
+    TJ_ERR_DEVICE = -6,          /* a HIP call failed                            */
+    TJ_ERR_SCRATCH_LIMIT = -7    /* tj_sample_noalloc on a ring beyond its limit */
 } tj_status;
 
 enum { TJ_OBS_F32 = 0, TJ_OBS_U8 = 1 };
@@ -138,6 +139,27 @@ int tj_buffer_insert_concurrent(tj_buffer *buf, uint32_t n, const void *d_obs, c
  * status becomes TJ_ERR_NO_ELIGIBLE (see tj_buffer_status). */
 int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
               uint64_t seed, const tj_minibatch *out, void *hip_stream);
+
+/* tj_sample for callers that cannot allocate device memory or let a library do
+ * so on their behalf (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it).  Same arguments, same result, same reporting
+ * through tj_buffer_status as tj_sample, but the sampler's scratch (eligibility
+ * mask, per-tile counts and offsets) is not taken from the ring arena: it lives
+ * in a fixed array inside the library's device image, 557 056 bytes that every
+ * GPU the library runs on holds until the process ends.  The call allocates
+ * nothing, frees nothing and creates no HIP object.
+ *  - Rings of more than TJ_SAMPLE_NOALLOC_MAX_CAPACITY slots are refused with
+ *    TJ_ERR_SCRATCH_LIMIT.
+ *  - Once tj_buffer_insert_concurrent has been used on `buf`, the first sample
+ *    after it must be a tj_sample (it creates the event that orders later
+ *    inserts); before that, this call returns TJ_ERR_INVALID_ARG.
+ *  - All calls on one GPU share the one array, whatever the buffer or stream:
+ *    calls that overlap in time on the same GPU race.  Order them on one stream
+ *    or with events.  The array keeps the last call's contents; every word a
+ *    call reads it has written itself before. */
+#define TJ_SAMPLE_NOALLOC_MAX_CAPACITY 4194304ull
+int tj_sample_noalloc(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+                      uint64_t seed, const tj_minibatch *out, void *hip_stream);
 
 /* Synchronises `hip_stream`, then reports ring state, the last K and the sticky
  * status (which it clears).  Returns the sticky status. */

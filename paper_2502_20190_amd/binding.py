@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libtianji_hip.so")
 
 TJ_OK = 0
 TJ_ERR_INVALID_ARG, TJ_ERR_SHAPE, TJ_ERR_ARENA_TOO_SMALL = -1, -2, -3
-TJ_ERR_NO_ELIGIBLE, TJ_ERR_CAPACITY, TJ_ERR_DEVICE = -4, -5, -6
+TJ_ERR_NO_ELIGIBLE, TJ_ERR_CAPACITY, TJ_ERR_DEVICE, TJ_ERR_SCRATCH_LIMIT = -4, -5, -6, -7
 TJ_OBS_F32, TJ_OBS_U8 = 0, 1
 TJ_PRECISION_FP32, TJ_PRECISION_BF16 = 0, 1
 TJ_LAYER_LINEAR, TJ_LAYER_CONV2D = 0, 1
@@ -26,7 +26,7 @@ TJ_MAX_LAYERS = 8
  TJ_STATE_ASTAR, TJ_STATE_WEIGHTS_COMPUTE, TJ_STATE_WEIGHTS_COMPUTE_T, TJ_STATE_WEIGHTS_COMPUTE_TARGET) = range(10)
 
 EXPORTS = [
-    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_actor_act", "tj_balance_plan", "tj_frame_buffer_arena_bytes", "tj_frame_buffer_create",
+    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_sample_noalloc", "tj_actor_act", "tj_balance_plan", "tj_frame_buffer_arena_bytes", "tj_frame_buffer_create",
     "tj_frame_buffer_destroy", "tj_frame_buffer_insert", "tj_frame_sample", "tj_frame_buffer_status",
     "tj_frame_buffer_field_ptr", "tj_frame_buffer_set_phase_events",
     "tj_buffer_status", "tj_buffer_field_ptr", "tj_learner_num_params", "tj_learner_arena_bytes",
@@ -129,6 +129,8 @@ def lib():
         L.tj_buffer_insert_concurrent.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp, vp]
         L.tj_sample.restype = i32
         L.tj_sample.argtypes = [vp, u32, i64, i64, u64, C.POINTER(tj_minibatch), vp]
+        L.tj_sample_noalloc.restype = i32
+        L.tj_sample_noalloc.argtypes = [vp, u32, i64, i64, u64, C.POINTER(tj_minibatch), vp]
         L.tj_buffer_status.restype = i32
         L.tj_buffer_status.argtypes = [vp, C.POINTER(tj_buffer_info), vp]
         L.tj_buffer_field_ptr.restype = vp
@@ -369,6 +371,10 @@ class Buffer:
     def sample(self, mb: Minibatch, current_version: int, max_staleness: int, seed: int, stream=None) -> int:
         return lib().tj_sample(self.h, mb.batch, current_version, max_staleness, seed & (2**64 - 1),
                                C.byref(mb.c), _stream_ptr(stream))
+
+    def sample_noalloc(self, mb: Minibatch, current_version: int, max_staleness: int, seed: int, stream=None) -> int:
+        return lib().tj_sample_noalloc(self.h, mb.batch, current_version, max_staleness, seed & (2**64 - 1),
+                                       C.byref(mb.c), _stream_ptr(stream))
 
     def status(self, stream=None):
         info = tj_buffer_info()

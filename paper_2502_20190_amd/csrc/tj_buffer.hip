@@ -18,6 +18,7 @@
 //   4 copy_rows        : gathers obs / next_obs rows with 16-byte lanes
 //                        (HBM bound, 2*B*row_bytes read + written)
 #include "tj_common.h"
+#include <mutex>
 
 namespace {
 
@@ -653,14 +654,21 @@ int tj_buffer_insert_concurrent(tj_buffer *buf, uint32_t n, const void *d_obs, c
     return insert_rows(buf, n, d_obs, d_next_obs, d_action, d_reward, d_done, d_version, st);
 }
 
-int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
-              uint64_t seed, const tj_minibatch *out, void *hip_stream)
+// The sampler's kernels on `st`, with the eligibility mask, the tile counts and the tile offsets in
+// the given scratch (the ring arena's own, or the library's built-in one).
+static int sample_into(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+                       uint64_t seed, const tj_minibatch *out, hipStream_t st, unsigned long long *mask,
+                       uint32_t *tile_count, uint32_t *tile_off, bool may_create_event)
 {
     if (!buf || !out || batch == 0 || out->batch != batch) return TJ_ERR_INVALID_ARG;
     if (!out->obs || !out->next_obs || !out->action || !out->reward || !out->done || !out->idx)
         return TJ_ERR_INVALID_ARG;
     if (batch > (1u << 20)) return TJ_ERR_SHAPE;
-    hipStream_t st = (hipStream_t)hip_stream;
+    // later concurrent inserts wait for the end of this sample: the event must exist
+    if (buf->concurrent_used && !buf->sample_done) {
+        if (!may_create_event) return TJ_ERR_INVALID_ARG;
+        TJ_HIP_TRY(hipEventCreateWithFlags(&buf->sample_done, hipEventDisableTiming));
+    }
     const uint32_t count = (uint32_t)buf->count;
     // only the tiles that hold valid slots take part (at least one, so K is always written)
     uint32_t n_tiles = (count + kTile - 1) / kTile;
@@ -674,11 +682,10 @@ int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t m
     }
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[0], st));
     stale_mask_count<<<n_tiles, 256, 0, st>>>(buf->ring.version, count, current_version, max_staleness,
-                                              buf->mask, buf->tile_count, buf->state, (uint32_t)buf->desc.capacity);
-    tile_scan<<<1, 1024, 0, st>>>(buf->tile_count, n_tiles, buf->tile_off, buf->state);
-    select_slots<<<(batch + 63) / 64, 64, 0, st>>>(buf->mask, buf->tile_off, n_tiles, buf->state,
-                                                      seed, batch, buf->ring, out->idx, out->action,
-                                                      out->reward, out->done);
+                                              mask, tile_count, buf->state, (uint32_t)buf->desc.capacity);
+    tile_scan<<<1, 1024, 0, st>>>(tile_count, n_tiles, tile_off, buf->state);
+    select_slots<<<(batch + 63) / 64, 64, 0, st>>>(mask, tile_off, n_tiles, buf->state, seed, batch, buf->ring,
+                                                   out->idx, out->action, out->reward, out->done);
     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[1], st));
     int rc = copy_rows(buf->ring.obs, out->obs, buf->ring.next_obs, out->next_obs, buf->row_bytes, batch,
@@ -686,11 +693,65 @@ int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t m
     if (rc == TJ_OK && buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[2], st));
     buf->last_sample_stream = st;
     buf->sampled = true;
-    if (rc == TJ_OK && buf->concurrent_used) {   // later concurrent inserts wait for this point
-        if (!buf->sample_done) TJ_HIP_TRY(hipEventCreateWithFlags(&buf->sample_done, hipEventDisableTiming));
-        TJ_HIP_TRY(hipEventRecord(buf->sample_done, st));
-    }
+    if (rc == TJ_OK && buf->concurrent_used) TJ_HIP_TRY(hipEventRecord(buf->sample_done, st));
     return rc;
+}
+
+int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+              uint64_t seed, const tj_minibatch *out, void *hip_stream)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    return sample_into(buf, batch, current_version, max_staleness, seed, out, (hipStream_t)hip_stream, buf->mask,
+                       buf->tile_count, buf->tile_off, true);
+}
+
+// ---- the allocation-free variant: the sampler's scratch lives in the library's own image
+constexpr uint64_t kNoAllocMaxSlots = TJ_SAMPLE_NOALLOC_MAX_CAPACITY;
+constexpr size_t kNoAllocTiles = (size_t)(kNoAllocMaxSlots / kTile);
+constexpr size_t kNoAllocMaskBytes = kNoAllocTiles * kWordsPerTile * 8;
+constexpr size_t kNoAllocBytes = kNoAllocMaskBytes + 2 * kNoAllocTiles * 4;
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+
+// Device address of `scratch` on the current device (every device holds its own copy of the array
+// at its own address): looked up once per device, with that device current.
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_lock;
+
+static int scratch_on_current_device(unsigned char **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TJ_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return TJ_ERR_DEVICE;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (unsigned char *)g_scratch_ptr[dev];
+    return TJ_OK;
+}
+
+int tj_sample_noalloc(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
+                      uint64_t seed, const tj_minibatch *out, void *hip_stream)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    if (buf->desc.capacity > kNoAllocMaxSlots) return TJ_ERR_SCRATCH_LIMIT;
+    unsigned char *base = nullptr;
+    int rc = scratch_on_current_device(&base);
+    if (rc != TJ_OK) return rc;
+    // every tile the kernels read is written by this call first: nothing has to start at zero
+    unsigned long long *mask = (unsigned long long *)base;
+    uint32_t *tile_count = (uint32_t *)(base + kNoAllocMaskBytes);
+    uint32_t *tile_off = tile_count + kNoAllocTiles;
+    return sample_into(buf, batch, current_version, max_staleness, seed, out, (hipStream_t)hip_stream, mask,
+                       tile_count, tile_off, false);
 }
 
 int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n)
@@ -906,6 +967,7 @@ const char *tj_strerror(int status)
     case TJ_ERR_NO_ELIGIBLE: return "no eligible transition inside the staleness gate";
     case TJ_ERR_CAPACITY: return "more rows than the ring holds";
     case TJ_ERR_DEVICE: return "HIP call failed";
+    case TJ_ERR_SCRATCH_LIMIT: return "ring larger than the built-in scratch of the allocation-free call";
     default: return "unknown status";
     }
 }
