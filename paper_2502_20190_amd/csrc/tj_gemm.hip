@@ -855,11 +855,24 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16(const TjGemmArgs<tj_bf16> a,
 // and also says that every wave is done reading the buffer about to be refilled.
 template <int N> struct IntC { static constexpr int value = N; };
 
-template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false>
+// LDS bytes of one block: NSTAGE stage buffers of the P tile (256 rows) and of the Q tile.
+template <int NFJ, int BKB, int NSTAGE> constexpr int dlds_lds_bytes() { return NSTAGE * (256 + 64 * NFJ) * BKB; }
+
+// TRANS: both operands are stored with the contraction index as their SLOW index, P as [k][i] with
+// row pitch ldp and Q as [k][j] with row pitch ldq (the weight gradient dW[j][i] = sum_m dZ[m][j] X[m][i]
+// straight from the row-major activations and gradients).  A stage then holds 32 contraction rows
+// of 256 (P) and 64*NFJ (Q) columns, fetched as whole rows, and the MFMA operands (8 consecutive
+// contraction values per lane) come out of LDS through transposing reads (ds_read_b64_tr_b16:
+// lane i of a 16-lane group receives column i of four consecutive rows, whose 8-byte pieces the
+// group's lanes 4r .. 4r+3 point at).  The 16-byte vector v of row r is stored at position
+// v ^ ((r & 3) << 2), so that the rows one transposing read touches fall into distinct banks.
+// Needs BKB = 64, NFJ = 2, one segment, no q_shift, I and the segment's columns multiples of 8.
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, bool TRANS = false>
 __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const int tiles_seg0, const TileMap &tm,
-                                          const int block_id)
+                                          const int block_id, uint8_t *lds)
 {
     typedef tj_bf16 T;
+    static_assert(!TRANS || (BKB == 64 && NFJ == 2 && !GATHER), "transposed operands: 256 x 128 tiles, 32-row stages");
     constexpr int BJ3 = 64 * NFJ;
     constexpr int KE = BKB / 2;              // k elements per stage
     constexpr int VPR = BKB / 16;            // 16-byte vectors per row
@@ -870,30 +883,17 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     constexpr int KS = BKB / 32;             // MFMA k steps per stage
     constexpr int SZA = 256 * BKB, SZB = BJ3 * BKB;
     static_assert(NSTAGE >= 2 && NSTAGE <= 6 && (NSTAGE - 1) * LPS < 64, "ring depth");
-    __shared__ __align__(1024) uint8_t sA0[SZA];
-    __shared__ __align__(1024) uint8_t sA1[SZA];
-    __shared__ __align__(1024) uint8_t sA2[NSTAGE > 2 ? SZA : 16];
-    __shared__ __align__(1024) uint8_t sA3[NSTAGE > 3 ? SZA : 16];
-    __shared__ __align__(1024) uint8_t sA4[NSTAGE > 4 ? SZA : 16];
-    __shared__ __align__(1024) uint8_t sA5[NSTAGE > 5 ? SZA : 16];
-    __shared__ __align__(1024) uint8_t sB0[SZB];
-    __shared__ __align__(1024) uint8_t sB1[SZB];
-    __shared__ __align__(1024) uint8_t sB2[NSTAGE > 2 ? SZB : 16];
-    __shared__ __align__(1024) uint8_t sB3[NSTAGE > 3 ? SZB : 16];
-    __shared__ __align__(1024) uint8_t sB4[NSTAGE > 4 ? SZB : 16];
-    __shared__ __align__(1024) uint8_t sB5[NSTAGE > 5 ? SZB : 16];
-    auto bufA = [&](auto u) -> uint8_t * {
-        constexpr int U = decltype(u)::value;
-        if constexpr (U == 0) return sA0; else if constexpr (U == 1) return sA1;
-        else if constexpr (U == 2) return sA2; else if constexpr (U == 3) return sA3;
-        else if constexpr (U == 4) return sA4; else return sA5;
-    };
-    auto bufB = [&](auto u) -> uint8_t * {
-        constexpr int U = decltype(u)::value;
-        if constexpr (U == 0) return sB0; else if constexpr (U == 1) return sB1;
-        else if constexpr (U == 2) return sB2; else if constexpr (U == 3) return sB3;
-        else if constexpr (U == 4) return sB4; else return sB5;
-    };
+    uint8_t *const sA0 = lds;                // stage buffers: P tiles first, then Q tiles
+    uint8_t *const sA1 = lds + SZA;
+    uint8_t *const sA2 = lds + 2 * SZA;
+    uint8_t *const sA3 = lds + 3 * SZA;
+    uint8_t *const sB0 = lds + NSTAGE * SZA;
+    uint8_t *const sB1 = sB0 + SZB;
+    uint8_t *const sB2 = sB0 + 2 * SZB;
+    uint8_t *const sB3 = sB0 + 3 * SZB;
+    (void)sB0; (void)sB1; (void)sB2; (void)sB3;
+    auto bufA = [&](auto u) -> uint8_t * { return lds + decltype(u)::value * SZA; };
+    auto bufB = [&](auto u) -> uint8_t * { return lds + NSTAGE * SZA + decltype(u)::value * SZB; };
 
     int ti, tj, z;
     {
@@ -931,25 +931,41 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     auto swizzle = [](int row) { return VPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };
     const T *gsrcP[LP];
     const T *gsrcQ[LQ];
+    if constexpr (TRANS) {
+        // P: load instruction c = wave + 8 t fills rows 2c, 2c+1 (512 bytes each); Q: instruction c = wave
+        // fills rows 4c .. 4c+3 (256 bytes each).  Columns past the end repeat the last valid vector.
 #pragma unroll
-    for (int t = 0; t < LP; ++t) {
-        const int row = (wave + 8 * t) * RPI + lrow;
-        const int i = min(i0 + row, a.I - 1);
-        if constexpr (GATHER)
-            gsrcP[t] = seg.P + tj_gather_origin(a.gather, (uint32_t)i);
-        else
-            gsrcP[t] = seg.P + (size_t)i * a.ldp + (lpos ^ swizzle(row)) * 8 + k_begin;
+        for (int t = 0; t < LP; ++t) {
+            const int row = 2 * (wave + 8 * t) + (lane >> 5);
+            const int col = min(i0 + 8 * ((lane & 31) ^ ((row & 3) << 2)), a.I - 8);
+            gsrcP[t] = seg.P + (size_t)(k_begin + row) * a.ldp + col;
+        }
+        const int rowq = 4 * wave + (lane >> 4);
+        const int colq = min(j0 + 8 * ((lane & 15) ^ ((rowq & 3) << 2)), j_end - 8);
+        gsrcQ[0] = a.Q + (size_t)(k_begin + rowq) * a.ldq + colq;
+    } else {
+#pragma unroll
+        for (int t = 0; t < LP; ++t) {
+            const int row = (wave + 8 * t) * RPI + lrow;
+            const int i = min(i0 + row, a.I - 1);
+            if constexpr (GATHER)
+                gsrcP[t] = seg.P + tj_gather_origin(a.gather, (uint32_t)i);
+            else
+                gsrcP[t] = seg.P + (size_t)i * a.ldp + (lpos ^ swizzle(row)) * 8 + k_begin;
+        }
+#pragma unroll
+        for (int t = 0; t < LQ; ++t) {
+            const int c = (wave + 8 * t) % CHQ;
+            const int row = c * RPI + lrow;
+            const int j = min(j0 + row, j_end - 1);
+            gsrcQ[t] = a.Q + (size_t)(j - seg.q_shift) * a.ldq + (lpos ^ swizzle(row)) * 8 + k_begin;
+        }
     }
     // gather form: the k of this lane's vector is the same for all its P rows (the swizzle of a
     // lane's rows does not depend on t), so one offset per stage serves every P load
     const int kposP = (lpos ^ swizzle(wave * RPI + lrow)) * 8 + k_begin;
-#pragma unroll
-    for (int t = 0; t < LQ; ++t) {
-        const int c = (wave + 8 * t) % CHQ;
-        const int row = c * RPI + lrow;
-        const int j = min(j0 + row, j_end - 1);
-        gsrcQ[t] = a.Q + (size_t)(j - seg.q_shift) * a.ldq + (lpos ^ swizzle(row)) * 8 + k_begin;
-    }
+    // elements a stage advances the sources by
+    const size_t stepP = TRANS ? (size_t)KE * a.ldp : (size_t)KE, stepQ = TRANS ? (size_t)KE * a.ldq : (size_t)KE;
     // global_load_lds_dwordx4: lane l's 16 bytes go to LDS address M0 + 16 l.  Issued as inline
     // assembly so that the compiler's wait-count pass does not see these loads: it would otherwise
     // put a vmcnt(0) wait (all stages landed) in front of LDS reads it cannot tell apart from the
@@ -962,13 +978,13 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
                      : "memory");
     };
     auto issue = [&](uint8_t *sA, uint8_t *sB, int s) {
-        const int offP = GATHER ? tj_gather_koff(a.gather, kposP + s * KE) : s * KE;
+        const size_t offP = GATHER ? (size_t)tj_gather_koff(a.gather, kposP + s * KE) : s * stepP;
 #pragma unroll
         for (int t = 0; t < LP; ++t) dma16(gsrcP[t] + offP, sA + (wave + 8 * t) * 1024);
 #pragma unroll
         for (int t = 0; t < LQ; ++t) {
             const int c = (wave + 8 * t) % CHQ;   // wave-uniform
-            dma16(gsrcQ[t] + s * KE, sB + c * 1024);
+            dma16(gsrcQ[t] + s * stepQ, sB + c * 1024);
         }
     };
 
@@ -989,14 +1005,36 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     const int pa_off = (wi * 64 + l32) * BKB, pb_off = (wj * 32 * NFJ + l32) * BKB;
     // Operand fetch runs one k step ahead of the MFMAs; the scheduling barriers keep the compiler
     // from hoisting every LDS read of a stage to its top (which costs > 256 registers).
+    // transposed operands: byte offset of this lane's 8-byte piece in row 8 (lane / 32) + (lane % 16) / 4 of a
+    // stage, for the 32 columns starting at the wave's first (fragment f adds 4 vectors before the swizzle)
+    const int i16 = lane & 15;
+    const int tr_row = 8 * lg + (i16 >> 2), tr_swz = ((i16 >> 2) & 3) << 2;
+    const int tr_vec = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1), tr_lo = (i16 & 1) * 8;
     auto compute = [&](const uint8_t *sA, const uint8_t *sB) {
         u32x4 pf[2][2], qf[2][NFJ];
         auto fetch = [&](int ks, int set) {
-            const int off = swz ^ (ks * 32);
+            if constexpr (TRANS) {
+                typedef short s16x4 __attribute__((ext_vector_type(4)));
+                typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+                auto rd = [&](const uint8_t *base, int pitch, int vec0) {
+                    const uint8_t *p0 = base + (16 * ks + tr_row) * pitch + (((vec0 + tr_vec) ^ tr_swz) << 4) + tr_lo;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p0);
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 4 * pitch));
+                    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+                    const u32x4 v = {l2.x, l2.y, h2.x, h2.y};
+                    return v;
+                };
 #pragma unroll
-            for (int f = 0; f < 2; ++f) pf[set][f] = *(const u32x4 *)(sA + pa_off + f * 32 * BKB + off);
+                for (int f = 0; f < 2; ++f) pf[set][f] = rd(sA, 512, 8 * wi + 4 * f);
 #pragma unroll
-            for (int f = 0; f < NFJ; ++f) qf[set][f] = *(const u32x4 *)(sB + pb_off + f * 32 * BKB + off);
+                for (int f = 0; f < NFJ; ++f) qf[set][f] = rd(sB, 2 * BJ3, 4 * NFJ * wj + 4 * f);
+            } else {
+                const int off = swz ^ (ks * 32);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) pf[set][f] = *(const u32x4 *)(sA + pa_off + f * 32 * BKB + off);
+#pragma unroll
+                for (int f = 0; f < NFJ; ++f) qf[set][f] = *(const u32x4 *)(sB + pb_off + f * 32 * BKB + off);
+            }
         };
         fetch(0, 0);
 #pragma unroll
@@ -1045,11 +1083,11 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
         compute(bufA(u), bufB(u));
     };
 
-    if (0 < n_stage) issue(sA0, sB0, 0);
-    if constexpr (NSTAGE > 2) { if (1 < n_stage) issue(sA1, sB1, 1); }
-    if constexpr (NSTAGE > 3) { if (2 < n_stage) issue(sA2, sB2, 2); }
-    if constexpr (NSTAGE > 4) { if (3 < n_stage) issue(sA3, sB3, 3); }
-    if constexpr (NSTAGE > 5) { if (4 < n_stage) issue(sA4, sB4, 4); }
+    if (0 < n_stage) issue(bufA(IntC<0>{}), bufB(IntC<0>{}), 0);
+    if constexpr (NSTAGE > 2) { if (1 < n_stage) issue(bufA(IntC<1>{}), bufB(IntC<1>{}), 1); }
+    if constexpr (NSTAGE > 3) { if (2 < n_stage) issue(bufA(IntC<2>{}), bufB(IntC<2>{}), 2); }
+    if constexpr (NSTAGE > 4) { if (3 < n_stage) issue(bufA(IntC<3>{}), bufB(IntC<3>{}), 3); }
+    if constexpr (NSTAGE > 5) { if (4 < n_stage) issue(bufA(IntC<4>{}), bufB(IntC<4>{}), 4); }
     for (int s = 0; s < n_stage; s += NSTAGE) {
         ring_step(IntC<0>{}, s);
         if (s + 1 < n_stage) ring_step(IntC<1>{}, s + 1);
@@ -1181,16 +1219,18 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2, \
                                                               ((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2)))
 
-template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false>
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, bool TRANS = false>
 __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
                                                               const TileMap tm)
 {
-    dlds_body<NFJ, BKB, NSTAGE, QSUM, GATHER>(a, tiles_seg0, tm, (int)blockIdx.x);
+    __shared__ __align__(1024) uint8_t lds[dlds_lds_bytes<NFJ, BKB, NSTAGE>()];
+    dlds_body<NFJ, BKB, NSTAGE, QSUM, GATHER, TRANS>(a, tiles_seg0, tm, (int)blockIdx.x, lds);
 }
 
 // Two independent GEMMs in one launch (e.g. the weight gradient and the input gradient of a layer,
 // which both start from the same dZ): blocks [0, nblk0) work on the first, the rest on the second,
-// so the two share one ramp-up and one tail instead of running back to back.
+// so the two share one ramp-up and one tail instead of running back to back.  Either may have
+// transposed operands (TjGemmArgs::trans); both forms of the body share the stage buffers.
 struct GemmPair {
     TjGemmArgs<tj_bf16> a[2];
     int tiles_seg0[2];
@@ -1201,10 +1241,16 @@ struct GemmPair {
 template <int NFJ, int BKB, int NSTAGE>
 __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPair p)
 {
-    // one call site: the body's LDS buffers must exist once
+    __shared__ __align__(1024) uint8_t lds[dlds_lds_bytes<NFJ, BKB, NSTAGE>()];
     const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
-    dlds_body<NFJ, BKB, NSTAGE, true>(p.a[which], p.tiles_seg0[which], p.tm[which],
-                                      (int)blockIdx.x - which * p.nblk0);
+    const int id = (int)blockIdx.x - which * p.nblk0;
+    if constexpr (BKB == 64 && NFJ == 2) {
+        if (p.a[which].trans) {   // block-uniform
+            dlds_body<NFJ, BKB, NSTAGE, true, false, true>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
+            return;
+        }
+    }
+    dlds_body<NFJ, BKB, NSTAGE, true>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
 }
 
 // The same for two gathered-operand problems (a convolution under the online and under the target
@@ -1212,9 +1258,10 @@ __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPa
 template <int NFJ>
 __global__ TJ_DLDS_ATTRS(NFJ, 64, 3) void gemm_bf16_dlds_gpair(const GemmPair p)
 {
+    __shared__ __align__(1024) uint8_t lds[dlds_lds_bytes<NFJ, 64, 3>()];
     const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
     dlds_body<NFJ, 64, 3, false, true>(p.a[which], p.tiles_seg0[which], p.tm[which],
-                                       (int)blockIdx.x - which * p.nblk0);
+                                       (int)blockIdx.x - which * p.nblk0, lds);
 }
 
 // Tile map and grid size of one problem for the 256 x 64*NFJ tiles.
@@ -1258,10 +1305,30 @@ bool uses_dlds(const TjGemmArgs<tj_bf16> &a)
     return a.I >= 32 && jtot * (long)a.K >= (1L << 24);
 }
 
+// What the transposed-operand form of the direct-to-LDS kernel assumes.
+bool trans_ok(const TjGemmArgs<tj_bf16> &a)
+{
+    if (!a.trans || a.gather.on || a.out_map.on || a.n_seg != 1 || a.seg[0].q_shift != 0) return false;
+    const int cols = a.seg[0].j_end - a.seg[0].j_begin;
+    if (a.I < 8 || a.I % 8 || cols < 8 || cols % 8 || a.seg[0].j_begin % 8) return false;
+    return a.K % 32 == 0 && (a.n_split == 1 || a.k_chunk % 32 == 0);
+}
+
 int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st)
 {
     int jtot = 0;
     for (int s = 0; s < a.n_seg; ++s) jtot += a.seg[s].j_end - a.seg[s].j_begin;
+    if (a.trans) {
+        if (!trans_ok(a)) return TJ_ERR_SHAPE;
+        TileMap tm;
+        int t2[2];
+        const unsigned nblk = plan_dlds<2>(a, tm, t2);
+        if (a.qsum)
+            gemm_bf16_dlds<2, 64, 3, true, false, true><<<nblk, 512, 0, st>>>(a, t2[0], tm);
+        else
+            gemm_bf16_dlds<2, 64, 3, false, false, true><<<nblk, 512, 0, st>>>(a, t2[0], tm);
+        return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+    }
     if (a.gather.on) {
         if (a.n_seg != 1 || jtot > 128 || a.K % 64 || a.n_split != 1 || a.qsum || a.I < 1) return TJ_ERR_SHAPE;
         if (a.out_map.on && (!a.Cj || a.Ci || a.Cf || a.relu || a.bias_j || a.seg[0].bias || a.mask))
@@ -1313,7 +1380,13 @@ template <typename T> int check_args(const TjGemmArgs<T> &a, int tiles[2])
     constexpr int KE = kRowBytes / (int)sizeof(T);
     if (a.n_seg < 1 || a.n_seg > 2 || a.I <= 0 || a.K <= 0 || a.n_split < 1) return TJ_ERR_SHAPE;
     if (a.gather.on && sizeof(T) != 2) return TJ_ERR_SHAPE;
-    if ((!a.gather.on && (a.ldp % VE || a.K > a.ldp)) || a.ldq % VE || a.K % VE || a.K > a.ldq) return TJ_ERR_SHAPE;
+    if (a.trans) {   // operands [k][i] and [k][j]: the pitches bound the columns, not the contraction
+        if (sizeof(T) != 2 || a.ldp % VE || a.ldq % VE || a.I > a.ldp || a.K % VE) return TJ_ERR_SHAPE;
+        for (int s = 0; s < a.n_seg; ++s)
+            if (a.seg[s].j_end > a.ldq) return TJ_ERR_SHAPE;
+    } else if ((!a.gather.on && (a.ldp % VE || a.K > a.ldp)) || a.ldq % VE || a.K % VE || a.K > a.ldq) {
+        return TJ_ERR_SHAPE;
+    }
     if (a.n_split > 1 && (a.k_chunk % KE || (size_t)a.k_chunk * a.n_split < (size_t)a.K)) return TJ_ERR_SHAPE;
     if (a.n_split == 1 && a.k_chunk < a.K) return TJ_ERR_SHAPE;
     if ((a.Ci && a.ldci % VE) || (a.mask && a.ldmask % 4)) return TJ_ERR_SHAPE;
@@ -1331,13 +1404,14 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
 {
     int tiles[2], rc;
     if ((rc = check_args(a0, tiles)) != TJ_OK || (rc = check_args(a1, tiles)) != TJ_OK) return rc;
-    if (a0.gather.on || a1.gather.on || !uses_dlds(a0) || !uses_dlds(a1)) {   // no common kernel: one after the other
+    auto fits = [](const TjGemmArgs<tj_bf16> &a) { return a.trans ? trans_ok(a) : uses_dlds(a); };
+    if (a0.gather.on || a1.gather.on || !fits(a0) || !fits(a1)) {   // no common kernel: one after the other
         if ((rc = tj_gemm<tj_bf16>(a0, st)) != TJ_OK) return rc;
         return tj_gemm<tj_bf16>(a1, st);
     }
     GemmPair p;
     p.a[0] = a0; p.a[1] = a1;
-    {   // two or more rounds of 256 x 256 tiles (one block per CU): a third less operand traffic
+    if (!a0.trans && !a1.trans) {   // two or more rounds of 256 x 256 tiles (one block per CU): a third less operand traffic
         // per flop than 256 x 128; with fewer tiles the two-blocks-per-CU variant below is as fast
         const unsigned m0 = plan_dlds<4>(a0, p.tm[0], tiles);
         p.tiles_seg0[0] = tiles[0];

@@ -242,6 +242,11 @@ struct HeadTdArgs {
     tj_bf16 *dZT; int lddzt;               // [A][lddzt]
     int32_t *astar;
     float *loss_part;                      // one per block
+    // optional: gradient wrt the head's input rows of s, dX[j][k] = relu'(X[j][k]) g_j W_on[a_j][k]
+    // (dL/dQ has one non-zero per row, so this product needs no contraction)
+    tj_bf16 *dX; int lddx;                 // [B][lddx]
+    tj_bf16 *dXT; int lddxt;               // [Kin][lddxt]
+    int Kin;                               // real (unpadded) width of the head's input
 };
 
 __device__ __forceinline__ void head_wave_sync()
@@ -372,6 +377,49 @@ __global__ __launch_bounds__(kHeadThreads) void head_td(const HeadTdArgs a)
         for (int u = 0; u < 8; ++u)
             if (s_aj[8 * vc + u] == arow) o[u >> 1] |= (uint32_t)tj_f32_to_bf16(s_g[8 * vc + u]) << (16 * (u & 1));
         *(headu32x4 *)(a.dZT + (size_t)arow * a.lddzt + j0 + 8 * vc) = o;
+    }
+    if (!a.dX) return;
+    // Input gradient of the head layer for the block's 32 transitions, in chunks of 256 columns:
+    // product of the bf16 gradient and the bf16 weight in fp32 (exact), ReLU mask from the
+    // activation, rounded to bf16: what the contraction over the actions would give.  Rows go out
+    // as 16-byte vectors; the transposed copy leaves through an LDS tile [column][transition].
+    constexpr int kChunk = 256, kPitch = kHeadRows + 8;   // 80-byte rows: 16-byte aligned, spread over the banks
+    tj_bf16 *tile = (tj_bf16 *)&stage[0][0][0];
+    static_assert(kChunk * kPitch * 2 <= (int)sizeof(stage), "transpose tile must fit the staging slabs");
+    const bool want_t = a.dXT != nullptr;   // block-uniform
+    for (int k0 = 0; k0 < a.K; k0 += kChunk) {
+        if (want_t) __syncthreads();   // the partial tiles (first pass) or the previous chunk's tile have been read
+        for (int e = threadIdx.x; e < kHeadRows * (kChunk / 8); e += kHeadThreads) {
+            const int j = e / (kChunk / 8), k = k0 + (e % (kChunk / 8)) * 8;
+            headu32x4 o = zero;
+            const int aj = s_aj[j];
+            if (k < a.K && aj >= 0) {
+                const headu32x4 x = *(const headu32x4 *)(a.X + ((size_t)a.row0[0] + j0 + j) * a.ldx + k);
+                const headu32x4 w = *(const headu32x4 *)(a.W_on + (size_t)aj * a.ldw + k);
+                const float g = tj_bf16_to_f32(tj_f32_to_bf16(s_g[j]));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t xl = x[u] & 0xFFFFu, xh = x[u] >> 16;
+                    const float pl = g * __uint_as_float(w[u] << 16), ph = g * __uint_as_float(w[u] & 0xFFFF0000u);
+                    const uint32_t lo = (int16_t)xl > 0 ? tj_f32_to_bf16(pl) : 0u;
+                    const uint32_t hi = (int16_t)xh > 0 ? tj_f32_to_bf16(ph) : 0u;
+                    o[u] = lo | (hi << 16);
+                }
+            }
+            if (k < a.K && j0 + j < a.B) *(headu32x4 *)(a.dX + (size_t)(j0 + j) * a.lddx + k) = o;
+            if (want_t) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    tile[(k - k0 + u) * kPitch + j] = (tj_bf16)((o[u >> 1] >> (16 * (u & 1))) & 0xFFFFu);
+            }
+        }
+        if (!want_t) continue;
+        __syncthreads();
+        for (int e = threadIdx.x; e < kChunk * (kHeadRows / 8); e += kHeadThreads) {
+            const int k = k0 + (e >> 2), vc = e & 3;
+            if (k >= a.Kin || j0 + 8 * vc >= a.lddxt) continue;   // columns past the batch, inside the pitch, are zero
+            *(headu32x4 *)(a.dXT + (size_t)k * a.lddxt + j0 + 8 * vc) = *(const headu32x4 *)(tile + (k - k0) * kPitch + 8 * vc);
+        }
     }
 }
 
@@ -847,6 +895,9 @@ template <typename T> struct HeadTd {
     float *Q; int ldq;
     T *dZ; int lddz; T *dZT; int lddzt;
     int32_t *astar; float *loss_part;
+    // where the fused kernel runs it also writes the gradient wrt the head's input (rows of s) and
+    // its transpose, if dX is set
+    T *dX; int lddx; T *dXT; int lddxt; int Kin;
 };
 
 template <typename T> constexpr bool head_fused(int A) { return sizeof(T) == 2 && A <= 32; }
@@ -872,6 +923,7 @@ int run_head_td(tj_learner *self, const HeadTd<T> &h, const tj_minibatch *mb, fl
             a.gamma = gamma; a.kappa = kappa;
             a.dZ = h.dZ; a.lddz = h.lddz; a.dZT = h.dZT; a.lddzt = h.lddzt;
             a.astar = h.astar; a.loss_part = h.loss_part;
+            a.dX = h.dX; a.lddx = h.lddx; a.dXT = h.dXT; a.lddxt = h.lddxt; a.Kin = h.Kin;
             head_td<<<td_blocks<T>(h.B, h.A), kHeadThreads, 0, st>>>(a);
             return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
         }
@@ -978,6 +1030,17 @@ template <typename T> struct MlpLearner : tj_learner {
     // Adam writes the straight copy of every weight block whose rows need no padding
     bool adam_emits(int l) const { return lay[l].ld_in == lay[l].in; }
 
+    // Weight gradient of layer l (1-based) straight from the row-major X_{l-1} and dZ_l (transposing LDS
+    // reads) instead of their transposed copies: bf16, whole 32-row stages of the batch, widths that are
+    // whole 16-byte vectors.  The first and the last layer keep the transposed operands: their narrow
+    // sides fill too few of the 256 x 128 tiles that form takes.  Where it applies, the transposed copy
+    // of X_{l-1} and of dZ_l is not written at all.
+    bool wgrad_trans(int l, int B) const
+    {
+        if (sizeof(T) != 2 || B % 32 != 0 || l < 2 || l > L - 1) return false;
+        return lay[l - 1].in % 8 == 0 && lay[l - 1].out % 8 == 0;
+    }
+
     int recast(bool online, hipStream_t st, bool after_adam = false)
     {
         CastJobs<T> jobs;
@@ -1029,7 +1092,7 @@ template <typename T> struct MlpLearner : tj_learner {
             g.k_chunk = g.K; g.n_split = 1;
             g.relu = 1;
             g.Ci = X[l + 1]; g.ldci = lay[l].ld_out;
-            g.Cj = XT[l + 1]; g.ldcj = ldB; g.cj_jmax = B;
+            if (!wgrad_trans(l + 2, B)) { g.Cj = XT[l + 1]; g.ldcj = ldB; g.cj_jmax = B; }
             if ((rc = tj_gemm<T>(g, st)) != TJ_OK) return rc;
         }
         {   // head layer and TD step
@@ -1043,21 +1106,30 @@ template <typename T> struct MlpLearner : tj_learner {
             h.Q = Qout; h.ldq = ldA;
             h.dZ = dZ[L]; h.lddz = lh.ld_out; h.dZT = dZT[L]; h.lddzt = ldB;
             h.astar = astar; h.loss_part = loss_part;
+            h.dX = nullptr; h.lddx = 0; h.dXT = nullptr; h.lddxt = 0; h.Kin = lh.in;
+            if (head_fused<T>(A) && L >= 2) {   // the fused kernel also writes the head's input gradient
+                h.dX = dZ[L - 1]; h.lddx = lh.ld_in;
+                if (!wgrad_trans(L - 1, B)) { h.dXT = dZT[L - 1]; h.lddxt = ldB; }
+            }
             if ((rc = run_head_td<T>(this, h, mb, d.gamma, d.huber_delta, st)) != TJ_OK) return rc;
         }
         if ((rc = mark(2, st)) != TJ_OK) return rc;
-        return backward_update(B, td_blocks<T>(B, A), d_stats, st);
+        return backward_update(B, td_blocks<T>(B, A), d_stats, st, head_fused<T>(A) && L >= 2);
     }
 
     // From dZ[L] / dZT[L] (gradient wrt the head's output, and its transpose) to the updated
     // parameters: backward GEMMs, slice reduction, Adam, refreshed weight copies, target sync.
     // n_loss_part per-block loss sums in loss_part are folded into the step's statistics.
-    int backward_update(int B, int n_loss_part, tj_step_stats *d_stats, hipStream_t st)
+    int backward_update(int B, int n_loss_part, tj_step_stats *d_stats, hipStream_t st, bool head_dx_done = false)
     {
         int rc;
         const int Kb = round_up(B, VE);
         // backward through the online network on s.  The weight gradient and the input gradient of a layer both
-        // start from dZ_l and are independent: one paired launch where the kernels allow it.
+        // start from dZ_l and are independent: one paired launch where the kernels allow it.  Where the TD kernel
+        // has already written the head's input gradient, the head's weight gradient waits and shares the launch
+        // of the first layer's weight gradient (neither has an input gradient beside it).
+        TjGemmArgs<T> gw_head;
+        bool head_pending = false;
         for (int l = L; l >= 1; --l) {
             const LayerPlan &lp = lay[l - 1];
             TjGemmArgs<T> gw, gd;
@@ -1065,15 +1137,27 @@ template <typename T> struct MlpLearner : tj_learner {
                 TjGemmArgs<T> &g = gw;
                 memset(&g, 0, sizeof(g));
                 g.n_seg = 1;
-                g.seg[0] = {0, lp.out, XT[l - 1], nullptr, 0};
-                g.Q = dZT[l];
-                g.ldp = ldB; g.ldq = ldB;
+                if (wgrad_trans(l, B)) {   // row-major operands, contraction over their rows
+                    g.seg[0] = {0, lp.out, X[l - 1], nullptr, 0};
+                    g.Q = dZ[l];
+                    g.ldp = lp.ld_in; g.ldq = lp.ld_out;
+                    g.trans = 1;
+                } else {
+                    g.seg[0] = {0, lp.out, XT[l - 1], nullptr, 0};
+                    g.Q = dZT[l];
+                    g.ldp = ldB; g.ldq = ldB;
+                }
                 g.I = lp.in; g.K = Kb;
                 g.n_split = S;
                 const int ke = 128 / (int)sizeof(T);
                 g.k_chunk = round_up((Kb + S - 1) / S, ke);
                 g.Cf = gpart + lp.w_off; g.ldcf = lp.in; g.cf_zstride = Ppad;
                 g.qsum = gpart + lp.b_off; g.qsum_zstride = Ppad;
+            }
+            if (l == L && head_dx_done) {
+                gw_head = gw;
+                head_pending = true;
+                continue;
             }
             if (l >= 2) {   // dX_{l-1}[m][k] = relu'(X_{l-1}) * sum_n dZ_l[m][n] W_l[n][k]
                 TjGemmArgs<T> &g = gd;
@@ -1086,7 +1170,7 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.k_chunk = g.K; g.n_split = 1;
                 g.mask = X[l - 1]; g.ldmask = lp.ld_in;
                 g.Ci = dZ[l - 1]; g.ldci = lp.ld_in;
-                g.Cj = dZT[l - 1]; g.ldcj = ldB; g.cj_jmax = B;
+                if (!wgrad_trans(l - 1, B)) { g.Cj = dZT[l - 1]; g.ldcj = ldB; g.cj_jmax = B; }
             }
             if (l >= 2) {
                 if constexpr (sizeof(T) == 2) rc = tj_gemm_pair(gw, gd, st);
@@ -1094,8 +1178,14 @@ template <typename T> struct MlpLearner : tj_learner {
                 if (rc != TJ_OK) return rc;
                 continue;
             }
+            if (head_pending) {   // l == 1
+                if constexpr (sizeof(T) == 2) rc = tj_gemm_pair(gw, gw_head, st);
+                else rc = TJ_ERR_SHAPE;   // the fused head kernel exists for bf16 only
+                if (rc != TJ_OK) return rc;
+                head_pending = false;
+                continue;
+            }
             if ((rc = tj_gemm<T>(gw, st)) != TJ_OK) return rc;
-            if (l >= 2 && (rc = tj_gemm<T>(gd, st)) != TJ_OK) return rc;
         }
 
         if ((rc = mark(3, st)) != TJ_OK) return rc;   // the S slices of the gradient are summed by the Adam kernel
@@ -1286,7 +1376,7 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
             if (l + 1 < this->L) {
                 g.relu = 1;
                 g.Ci = this->X[l + 1]; g.ldci = lay[l].ld_out;
-                if (keep_transposes) { g.Cj = this->XT[l + 1]; g.ldcj = this->ldB; g.cj_jmax = n; }
+                if (keep_transposes && !this->wgrad_trans(l + 2, n)) { g.Cj = this->XT[l + 1]; g.ldcj = this->ldB; g.cj_jmax = n; }
             } else {
                 g.Cf = this->Qout; g.ldcf = this->ldA;
             }
@@ -1771,6 +1861,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
             }
         }
+        bool head_dx_done = false;
         {   // head layer and TD step
             NLayer &y = lay[L - 1];
             HeadTd<T> h;
@@ -1782,6 +1873,11 @@ template <typename T> struct ConvLearner : tj_learner {
             h.Q = Qout; h.ldq = ldA;
             h.dZ = y.dZ; h.lddz = y.ldO; h.dZT = y.dZT; h.lddzt = ldB;
             h.astar = astar; h.loss_part = loss_part;
+            h.dX = nullptr; h.lddx = 0; h.dXT = nullptr; h.lddxt = 0; h.Kin = y.K;
+            head_dx_done = head_fused<T>(A) && L >= 2 && lay[L - 2].kind == TJ_LAYER_LINEAR;
+            if (head_dx_done) {   // the fused kernel also writes the head's input gradient
+                h.dX = lay[L - 2].dZ; h.lddx = y.ldK; h.dXT = lay[L - 2].dZT; h.lddxt = ldB;
+            }
             if ((rc = run_head_td<T>(this, h, mb, d.gamma, d.huber_delta, st)) != TJ_OK) return rc;
         }
         if ((rc = mark(2, st)) != TJ_OK) return rc;
@@ -1833,12 +1929,13 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.n_split = ns;
                 gm.Cf = y.part; gm.ldcf = y.K; gm.cf_zstride = y.part_stride;
                 gm.qsum = y.part + (size_t)y.O * y.K; gm.qsum_zstride = y.part_stride;
-                gw_pending = sizeof(T) == 2 && !conv && l > 0;
+                gw_pending = sizeof(T) == 2 && !conv && l > 0 && !(l == L - 1 && head_dx_done);
                 if (!gw_pending && (rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
                 add_reduce_job(y.part, y.part_stride, ns, grad + y.w_off, (size_t)y.O * y.K + y.O);
             }
             if (l == 0) break;
             NLayer &below = lay[l - 1];
+            if (l == L - 1 && head_dx_done) continue;   // written by the TD kernel
             if (!conv) {   // dX[m][k] = relu'(X) * sum_o dZ[m][o] W[o][k]
                 TjGemmArgs<T> gm;
                 memset(&gm, 0, sizeof(gm));
