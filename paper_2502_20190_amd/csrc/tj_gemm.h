@@ -128,9 +128,10 @@ template <typename T> struct TjGemmArgs {
                          // (ldcj ignored): row i is a coarse output position, column j a (pixel, channel) of
                          // the s x s pixel block it owns.  The only output of such a launch; no bias / ReLU.
     const T *mask_cj;    // optional with out_map: the result is zeroed where mask_cj[same offset] <= 0
-    int trans;           // bf16 only: both operands are stored contraction-major, P as [k][i] (row pitch ldp)
+    int trans;           // bf16 only.  1: both operands are stored contraction-major, P as [k][i] (row pitch ldp)
                          // and Q as [k][j] (row pitch ldq); rows k in [0, K) must exist (K a multiple of 32,
-                         // like every split chunk), I and the columns multiples of 8, one segment, no q_shift
+                         // like every split chunk), I and the columns multiples of 8, one segment, no q_shift.
+                         // 2: only P is stored that way, Q as usual (no qsum)
 };
 
 template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st);

@@ -867,12 +867,14 @@ template <int NFJ, int BKB, int NSTAGE> constexpr int dlds_lds_bytes() { return 
 // group's lanes 4r .. 4r+3 point at).  The 16-byte vector v of row r is stored at position
 // v ^ ((r & 3) << 2), so that the rows one transposing read touches fall into distinct banks.
 // Needs BKB = 64, NFJ = 2, one segment, no q_shift, I and the segment's columns multiples of 8.
-template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, bool TRANS = false>
+// TRANS = 2: only P is stored that way (the input gradient dX[j][i] = sum_n dZ[j][n] W[n][i] from
+// the row-major weights); Q keeps its contraction-contiguous rows, 32 elements of them per stage.
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, int TRANS = 0>
 __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const int tiles_seg0, const TileMap &tm,
                                           const int block_id, uint8_t *lds)
 {
     typedef tj_bf16 T;
-    static_assert(!TRANS || (BKB == 64 && NFJ == 2 && !GATHER), "transposed operands: 256 x 128 tiles, 32-row stages");
+    static_assert(TRANS == 0 || (BKB == 64 && NFJ == 2 && !GATHER), "transposed operands: 256 x 128 tiles, 32-row stages");
     constexpr int BJ3 = 64 * NFJ;
     constexpr int KE = BKB / 2;              // k elements per stage
     constexpr int VPR = BKB / 16;            // 16-byte vectors per row
@@ -931,18 +933,15 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     auto swizzle = [](int row) { return VPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };
     const T *gsrcP[LP];
     const T *gsrcQ[LQ];
-    if constexpr (TRANS) {
-        // P: load instruction c = wave + 8 t fills rows 2c, 2c+1 (512 bytes each); Q: instruction c = wave
-        // fills rows 4c .. 4c+3 (256 bytes each).  Columns past the end repeat the last valid vector.
+    if constexpr (TRANS != 0) {
+        // P: load instruction c = wave + 8 t fills rows 2c, 2c+1 (512 bytes each).  Columns past the end
+        // repeat the last valid vector.
 #pragma unroll
         for (int t = 0; t < LP; ++t) {
             const int row = 2 * (wave + 8 * t) + (lane >> 5);
             const int col = min(i0 + 8 * ((lane & 31) ^ ((row & 3) << 2)), a.I - 8);
             gsrcP[t] = seg.P + (size_t)(k_begin + row) * a.ldp + col;
         }
-        const int rowq = 4 * wave + (lane >> 4);
-        const int colq = min(j0 + 8 * ((lane & 15) ^ ((rowq & 3) << 2)), j_end - 8);
-        gsrcQ[0] = a.Q + (size_t)(k_begin + rowq) * a.ldq + colq;
     } else {
 #pragma unroll
         for (int t = 0; t < LP; ++t) {
@@ -953,6 +952,13 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
             else
                 gsrcP[t] = seg.P + (size_t)i * a.ldp + (lpos ^ swizzle(row)) * 8 + k_begin;
         }
+    }
+    if constexpr (TRANS == 1) {
+        // Q: instruction c = wave fills rows 4c .. 4c+3 (256 bytes each)
+        const int rowq = 4 * wave + (lane >> 4);
+        const int colq = min(j0 + 8 * ((lane & 15) ^ ((rowq & 3) << 2)), j_end - 8);
+        gsrcQ[0] = a.Q + (size_t)(k_begin + rowq) * a.ldq + colq;
+    } else {
 #pragma unroll
         for (int t = 0; t < LQ; ++t) {
             const int c = (wave + 8 * t) % CHQ;
@@ -965,7 +971,7 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     // lane's rows does not depend on t), so one offset per stage serves every P load
     const int kposP = (lpos ^ swizzle(wave * RPI + lrow)) * 8 + k_begin;
     // elements a stage advances the sources by
-    const size_t stepP = TRANS ? (size_t)KE * a.ldp : (size_t)KE, stepQ = TRANS ? (size_t)KE * a.ldq : (size_t)KE;
+    const size_t stepP = TRANS != 0 ? (size_t)KE * a.ldp : (size_t)KE, stepQ = TRANS == 1 ? (size_t)KE * a.ldq : (size_t)KE;
     // global_load_lds_dwordx4: lane l's 16 bytes go to LDS address M0 + 16 l.  Issued as inline
     // assembly so that the compiler's wait-count pass does not see these loads: it would otherwise
     // put a vmcnt(0) wait (all stages landed) in front of LDS reads it cannot tell apart from the
@@ -1013,25 +1019,28 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     auto compute = [&](const uint8_t *sA, const uint8_t *sB) {
         u32x4 pf[2][2], qf[2][NFJ];
         auto fetch = [&](int ks, int set) {
-            if constexpr (TRANS) {
-                typedef short s16x4 __attribute__((ext_vector_type(4)));
-                typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
-                auto rd = [&](const uint8_t *base, int pitch, int vec0) {
-                    const uint8_t *p0 = base + (16 * ks + tr_row) * pitch + (((vec0 + tr_vec) ^ tr_swz) << 4) + tr_lo;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p0);
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 4 * pitch));
-                    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
-                    const u32x4 v = {l2.x, l2.y, h2.x, h2.y};
-                    return v;
-                };
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+            auto rd = [&](const uint8_t *base, int pitch, int vec0) {
+                const uint8_t *p0 = base + (16 * ks + tr_row) * pitch + (((vec0 + tr_vec) ^ tr_swz) << 4) + tr_lo;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p0);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 4 * pitch));
+                const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+                const u32x4 v = {l2.x, l2.y, h2.x, h2.y};
+                return v;
+            };
+            const int off = swz ^ (ks * 32);
+            if constexpr (TRANS != 0) {
 #pragma unroll
                 for (int f = 0; f < 2; ++f) pf[set][f] = rd(sA, 512, 8 * wi + 4 * f);
+            } else {
+#pragma unroll
+                for (int f = 0; f < 2; ++f) pf[set][f] = *(const u32x4 *)(sA + pa_off + f * 32 * BKB + off);
+            }
+            if constexpr (TRANS == 1) {
 #pragma unroll
                 for (int f = 0; f < NFJ; ++f) qf[set][f] = rd(sB, 2 * BJ3, 4 * NFJ * wj + 4 * f);
             } else {
-                const int off = swz ^ (ks * 32);
-#pragma unroll
-                for (int f = 0; f < 2; ++f) pf[set][f] = *(const u32x4 *)(sA + pa_off + f * 32 * BKB + off);
 #pragma unroll
                 for (int f = 0; f < NFJ; ++f) qf[set][f] = *(const u32x4 *)(sB + pb_off + f * 32 * BKB + off);
             }
@@ -1219,7 +1228,7 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2, \
                                                               ((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2)))
 
-template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, bool TRANS = false>
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, int TRANS = 0>
 __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
                                                               const TileMap tm)
 {
@@ -1245,8 +1254,12 @@ __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPa
     const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
     const int id = (int)blockIdx.x - which * p.nblk0;
     if constexpr (BKB == 64 && NFJ == 2) {
-        if (p.a[which].trans) {   // block-uniform
-            dlds_body<NFJ, BKB, NSTAGE, true, false, true>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
+        if (p.a[which].trans == 1) {   // block-uniform
+            dlds_body<NFJ, BKB, NSTAGE, true, false, 1>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
+            return;
+        }
+        if (p.a[which].trans == 2) {
+            dlds_body<NFJ, BKB, NSTAGE, false, false, 2>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
             return;
         }
     }
@@ -1308,9 +1321,14 @@ bool uses_dlds(const TjGemmArgs<tj_bf16> &a)
 // What the transposed-operand form of the direct-to-LDS kernel assumes.
 bool trans_ok(const TjGemmArgs<tj_bf16> &a)
 {
-    if (!a.trans || a.gather.on || a.out_map.on || a.n_seg != 1 || a.seg[0].q_shift != 0) return false;
-    const int cols = a.seg[0].j_end - a.seg[0].j_begin;
-    if (a.I < 8 || a.I % 8 || cols < 8 || cols % 8 || a.seg[0].j_begin % 8) return false;
+    if (a.trans < 1 || a.trans > 2 || a.gather.on || a.out_map.on || a.n_seg != 1) return false;
+    if (a.I < 8 || a.I % 8) return false;
+    if (a.trans == 1) {
+        const int cols = a.seg[0].j_end - a.seg[0].j_begin;
+        if (a.seg[0].q_shift != 0 || cols < 8 || cols % 8 || a.seg[0].j_begin % 8) return false;
+    } else if (a.qsum) {
+        return false;
+    }
     return a.K % 32 == 0 && (a.n_split == 1 || a.k_chunk % 32 == 0);
 }
 
@@ -1323,10 +1341,12 @@ int launch_bf16(const TjGemmArgs<tj_bf16> &a, const int tiles[2], hipStream_t st
         TileMap tm;
         int t2[2];
         const unsigned nblk = plan_dlds<2>(a, tm, t2);
-        if (a.qsum)
-            gemm_bf16_dlds<2, 64, 3, true, false, true><<<nblk, 512, 0, st>>>(a, t2[0], tm);
+        if (a.trans == 2)
+            gemm_bf16_dlds<2, 64, 3, false, false, 2><<<nblk, 512, 0, st>>>(a, t2[0], tm);
+        else if (a.qsum)
+            gemm_bf16_dlds<2, 64, 3, true, false, 1><<<nblk, 512, 0, st>>>(a, t2[0], tm);
         else
-            gemm_bf16_dlds<2, 64, 3, false, false, true><<<nblk, 512, 0, st>>>(a, t2[0], tm);
+            gemm_bf16_dlds<2, 64, 3, false, false, 1><<<nblk, 512, 0, st>>>(a, t2[0], tm);
         return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
     }
     if (a.gather.on) {
@@ -1380,10 +1400,10 @@ template <typename T> int check_args(const TjGemmArgs<T> &a, int tiles[2])
     constexpr int KE = kRowBytes / (int)sizeof(T);
     if (a.n_seg < 1 || a.n_seg > 2 || a.I <= 0 || a.K <= 0 || a.n_split < 1) return TJ_ERR_SHAPE;
     if (a.gather.on && sizeof(T) != 2) return TJ_ERR_SHAPE;
-    if (a.trans) {   // operands [k][i] and [k][j]: the pitches bound the columns, not the contraction
+    if (a.trans) {   // P (and with trans == 1 also Q) as [k][columns]: the pitch bounds the columns, not the contraction
         if (sizeof(T) != 2 || a.ldp % VE || a.ldq % VE || a.I > a.ldp || a.K % VE) return TJ_ERR_SHAPE;
         for (int s = 0; s < a.n_seg; ++s)
-            if (a.seg[s].j_end > a.ldq) return TJ_ERR_SHAPE;
+            if (a.trans == 1 ? a.seg[s].j_end > a.ldq : a.K > a.ldq) return TJ_ERR_SHAPE;
     } else if ((!a.gather.on && (a.ldp % VE || a.K > a.ldp)) || a.ldq % VE || a.K % VE || a.K > a.ldq) {
         return TJ_ERR_SHAPE;
     }

@@ -1041,19 +1041,37 @@ template <typename T> struct MlpLearner : tj_learner {
         return lay[l - 1].in % 8 == 0 && lay[l - 1].out % 8 == 0;
     }
 
+    // Input gradient of layer l (1-based, l >= 2) with the row-major weight copy as its first operand
+    // (transposing LDS reads): bf16, a contraction over whole 32-row stages of the weight matrix.  Such a
+    // layer keeps no transposed weight copy.
+    bool dgrad_trans(int l) const
+    {
+        return sizeof(T) == 2 && lay[l - 1].in % 8 == 0 && lay[l - 1].out % 32 == 0;
+    }
+    // Layer index l (0-based) keeps a transposed weight copy: its input gradient exists, is a contraction
+    // (the head's is not where the TD kernel writes it) and does not read the straight copy.
+    bool keeps_wct(int l) const
+    {
+        if (l == 0) return false;
+        if (l == L - 1 && n_pass == 3 && head_fused<T>(A)) return false;
+        return !dgrad_trans(l + 1);
+    }
+
     int recast(bool online, hipStream_t st, bool after_adam = false)
     {
         CastJobs<T> jobs;
+        int n = 0;
         for (int l = 0; l < L; ++l) {
-            CastJob<T> &j = jobs.job[l];
+            CastJob<T> j;
             j.src = (online ? theta_on : theta_tg) + lay[l].w_off;
             j.dst = online ? Wc_on[l] : Wc_tg[l];
             if (after_adam && adam_emits(l)) j.dst = nullptr;
-            j.dstT = online ? WcT_on[l] : nullptr;
+            j.dstT = online && keeps_wct(l) ? WcT_on[l] : nullptr;
             j.R = lay[l].out; j.C = lay[l].in;
             j.ldd = lay[l].ld_in; j.lddT = lay[l].ld_out;
+            if (j.dst || j.dstT) jobs.job[n++] = j;
         }
-        return launch_cast<T>(jobs, L, st);
+        return launch_cast<T>(jobs, n, st);
     }
 
     int step(const tj_minibatch *mb, tj_step_stats *d_stats, hipStream_t st) override
@@ -1163,10 +1181,17 @@ template <typename T> struct MlpLearner : tj_learner {
                 TjGemmArgs<T> &g = gd;
                 memset(&g, 0, sizeof(g));
                 g.n_seg = 1;
-                g.seg[0] = {0, B, WcT_on[l - 1], nullptr, 0};
                 g.Q = dZ[l];
-                g.ldp = lp.ld_out; g.ldq = lp.ld_out;
-                g.I = lp.in; g.K = lp.ld_out;   // pad columns are zero in both operands
+                g.ldq = lp.ld_out;
+                g.I = lp.in;
+                if (dgrad_trans(l)) {   // the weights as stored, [n][k]: the contraction runs over their rows
+                    g.seg[0] = {0, B, Wc_on[l - 1], nullptr, 0};
+                    g.ldp = lp.ld_in; g.K = lp.out;
+                    g.trans = 2;
+                } else {
+                    g.seg[0] = {0, B, WcT_on[l - 1], nullptr, 0};
+                    g.ldp = lp.ld_out; g.K = lp.ld_out;   // pad columns are zero in both operands
+                }
                 g.k_chunk = g.K; g.n_split = 1;
                 g.mask = X[l - 1]; g.ldmask = lp.ld_in;
                 g.Ci = dZ[l - 1]; g.ldci = lp.ld_in;
@@ -1280,7 +1305,7 @@ template <typename T> struct MlpLearner : tj_learner {
                 const LayerPlan &lp = lay[l];
                 float *dst = h_out + lp.w_off;
                 int rc;
-                if (tr) {
+                if (tr && keeps_wct(l)) {
                     if ((rc = fetch_as_float<T>(WcT_on[l], (size_t)lp.in * lp.ld_out, w, st)) != TJ_OK) return rc;
                     for (int o = 0; o < lp.out; ++o)
                         for (int k = 0; k < lp.in; ++k) dst[(size_t)o * lp.in + k] = w[(size_t)k * lp.ld_out + o];
