@@ -8,15 +8,16 @@
 //   tile_count / tile_off u32 [ceil(N/1024)]
 //   state u32 [8] {sticky, K, arc begin, arc length, rows inserted so far (u64), -, -}
 //
-// tj_sample = four kernels on one stream:
-//   1 stale_mask_count : coalesced read of the tags, wave ballot -> mask words,
-//                        popcount -> per-tile counts            (HBM bound, 4N B)
-//   2 tile_scan        : exclusive prefix sum of tile counts, K (one block)
-//   3 select_slots     : per draw: SplitMix64, mul-high range reduction, binary
-//                        search over tile offsets, popcount walk over the tile's
-//                        mask words, k-th set bit; copies the scalar fields
-//   4 copy_rows        : gathers obs / next_obs rows with 16-byte lanes
-//                        (HBM bound, 2*B*row_bytes read + written)
+// tj_sample = three kernels on one stream:
+//   1 mask_count   : one wave per tile of 1024 slots reads the tags (16 bytes per lane), ballots ->
+//                    mask words, popcount -> per-tile counts              (HBM bound, 4N B)
+//   2 select_rows  : every block repeats the exclusive prefix sum of the tile counts in LDS, then
+//                    per draw: SplitMix64, mul-high range reduction, binary search over the tile
+//                    offsets, popcount walk over the tile's mask words, k-th set bit; copies the
+//                    scalar fields
+//   3 copy_rows    : gathers obs / next_obs rows with 16-byte lanes
+//                    (HBM bound, 2*B*row_bytes read + written)
+// Rings of more than 8192 tiles (8.4 M slots) scan in a kernel of their own (tile_scan, select_slots).
 #include "tj_common.h"
 #include <mutex>
 
@@ -36,43 +37,78 @@ struct RingPtrs {
 
 // ---------------------------------------------------------------- sampler
 
-// One block per tile of 1024 slots, four waves, each wave 4 x 64 slots: coalesced read of the
-// tags, wave ballot -> mask words, popcount -> tile count.
-// Slots of the arc [ex_begin, ex_begin + ex_len) (mod cap), which an unfinished concurrent insert
-// is overwriting, are not eligible.
-__global__ __launch_bounds__(256) void stale_mask_count(const int32_t *__restrict__ version,
-                                                        uint32_t count, int64_t cur, int64_t max_st,
-                                                        unsigned long long *__restrict__ mask,
-                                                        uint32_t *__restrict__ tile_count,
-                                                        const uint32_t *__restrict__ state, uint32_t cap)
+// Bit i of a 16-bit value to bit 4 i.
+__device__ __forceinline__ unsigned long long spread4(unsigned long long x)
 {
-    const uint32_t ex_begin = state[2], ex_len = state[3];
-    __shared__ uint32_t wave_cnt[4];
+    x = (x | (x << 24)) & 0x000000FF000000FFull;
+    x = (x | (x << 12)) & 0x000F000F000F000Full;
+    x = (x | (x << 6)) & 0x0303030303030303ull;
+    x = (x | (x << 3)) & 0x1111111111111111ull;
+    return x;
+}
+
+// One wave per tile of 1024 slots (four tiles per block): the wave reads the tile's tags as four
+// 1 KiB runs (16 bytes per lane, all four loads in flight), so lane l of run r holds slots
+// 256 r + 4 l .. + 3.  Sixteen ballots (one per run and element) give the eligibility bits; mask
+// word 4 r + q collects, for the lanes 16 q + i, bit e of lane i at position 4 i + e.  Lanes 0..15
+// write the tile's 16 mask words (one 128-byte line), lane 0 its count.
+// Slots of the arc [ex_begin, ex_begin + ex_len) (mod cap), which an unfinished concurrent insert
+// is overwriting, are not eligible.  FRAME adds the frame ring's rule: not the newest row (no
+// successor), and once the ring has wrapped the look-back (age) must not reach past the oldest slot.
+template <bool FRAME>
+__global__ __launch_bounds__(256) void mask_count(const int32_t *__restrict__ version,
+                                                  const uint8_t *__restrict__ age, uint32_t count, uint32_t head,
+                                                  uint32_t cap, int64_t cur, int64_t max_st,
+                                                  unsigned long long *__restrict__ mask,
+                                                  uint32_t *__restrict__ tile_count,
+                                                  const uint32_t *__restrict__ state, uint32_t n_tiles)
+{
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t base = blockIdx.x * kTile + wave * 256;
-    int32_t v[4];
-    bool ok[4];
+    const uint32_t tile = blockIdx.x * 4 + wave;
+    if (tile >= n_tiles) return;
+    const uint32_t ex_begin = FRAME ? 0u : state[2], ex_len = FRAME ? 0u : state[3];
+    const uint32_t newest = head == 0 ? cap - 1 : head - 1;
+    const uint32_t base = tile * kTile;
+    int4 v[4];
+    uint32_t ag[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        uint32_t s = base + r * 64 + lane;
-        const uint32_t d = s >= ex_begin ? s - ex_begin : s + (cap - ex_begin);
-        ok[r] = s < count && d >= ex_len;
-        v[r] = ok[r] ? version[s] : 0;
+    for (int r = 0; r < 4; ++r) {   // the tag array is padded to whole 256-byte pieces: a vector that starts inside it ends inside it
+        const uint32_t s0 = base + 256 * r + 4 * lane;
+        v[r] = s0 < count ? *(const int4 *)(version + s0) : make_int4(0, 0, 0, 0);
+        if (FRAME) ag[r] = (s0 < count && count == cap) ? *(const uint32_t *)(age + s0) : 0u;
     }
+    unsigned long long b[4][4];
     uint32_t cnt = 0;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        int64_t st = cur - (int64_t)v[r];
-        bool e = ok[r] && st >= 0 && st <= max_st;
-        unsigned long long b = __ballot(e);
-        uint32_t w = (base >> 6) + r;
-        if (lane == 0) mask[w] = b;   // the mask array is padded to whole tiles
-        cnt += __popcll(b);
+        const int32_t ve[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t s = base + 256 * r + 4 * lane + e;
+            const int64_t st = cur - (int64_t)ve[e];
+            bool ok = s < count && st >= 0 && st <= max_st;
+            if (FRAME) {
+                const uint32_t from_oldest = s >= head ? s - head : s + (cap - head);
+                ok = ok && s != newest && (count != cap || from_oldest >= ((ag[r] >> (8 * e)) & 0xFFu));
+            } else {
+                const uint32_t d = s >= ex_begin ? s - ex_begin : s + (cap - ex_begin);
+                ok = ok && d >= ex_len;
+            }
+            b[r][e] = __ballot(ok);
+            cnt += __popcll(b[r][e]);
+        }
     }
-    if (lane == 0) wave_cnt[wave] = cnt;
-    __syncthreads();
-    if (threadIdx.x == 0)
-        tile_count[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    const uint32_t q = lane & 3;
+    unsigned long long word = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        unsigned long long wr = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wr |= spread4((b[r][e] >> (16 * q)) & 0xFFFFull) << e;
+        if ((lane >> 2) == (uint32_t)r) word = wr;
+    }
+    if (lane < 16) mask[(size_t)tile * kWordsPerTile + lane] = word;   // the mask array is padded to whole tiles
+    if (lane == 0) tile_count[tile] = cnt;
 }
 
 // Exclusive scan of the tile counts by one block of 1024 threads, four counts per thread and
@@ -177,6 +213,96 @@ template <> __device__ __forceinline__ void st_stream<uint4>(uint4 *p, uint4 v)
     typedef uint32_t u4 __attribute__((ext_vector_type(4)));
     const u4 w = {v.x, v.y, v.z, v.w};
     __builtin_nontemporal_store(w, (u4 *)p);
+}
+
+// Scan and select in one kernel, R draws per block.  Every block first repeats the exclusive prefix
+// sum of the tile counts (at most kScanTiles of them, read from L2) and keeps it in LDS, which
+// replaces a scan launch of its own: thread t loads counts 32 t .. 32 t + 31 as eight 16-byte
+// vectors (all in flight), sums them, one shuffle scan over the wave and the wave totals give its
+// base, and it writes its 32 running sums back as vectors.  Block 0 publishes K.  Threads j < R then
+// take their draws as select_slots does, with the binary search in LDS and the tile's 16 mask words
+// fetched as one 128-byte line.
+constexpr int kScanTiles = 8192;
+constexpr int kMaxDrawsPerBlock = 64;
+
+__global__ __launch_bounds__(256) void select_rows(
+    const unsigned long long *__restrict__ mask, const uint32_t *__restrict__ tile_count, uint32_t n_tiles,
+    uint32_t *__restrict__ state, uint64_t seed, uint32_t batch, uint32_t R, RingPtrs ring,
+    uint32_t *__restrict__ idx, int32_t *__restrict__ action, float *__restrict__ reward,
+    uint8_t *__restrict__ done)
+{
+    constexpr int E = kScanTiles / 256;      // counts per thread
+    __shared__ __align__(16) uint32_t off[kScanTiles];
+    __shared__ uint32_t wave_sum[4];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t c[E];
+#pragma unroll
+    for (int v = 0; v < E / 4; ++v) {   // the array is padded to whole 256-byte pieces: a vector that starts inside it ends inside it
+        const uint32_t i = tid * E + 4 * v;
+        const uint4 x = i < n_tiles ? *(const uint4 *)(tile_count + i) : make_uint4(0u, 0u, 0u, 0u);
+        c[4 * v] = x.x; c[4 * v + 1] = i + 1 < n_tiles ? x.y : 0u;
+        c[4 * v + 2] = i + 2 < n_tiles ? x.z : 0u; c[4 * v + 3] = i + 3 < n_tiles ? x.w : 0u;
+    }
+    uint32_t mine = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) mine += c[e];
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(incl, d, 64);
+        if (lane >= (uint32_t)d) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    uint32_t run = incl - mine;
+    for (uint32_t w = 0; w < wave; ++w) run += wave_sum[w];
+    const uint32_t K = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+#pragma unroll
+    for (int v = 0; v < E / 4; ++v) {
+        uint4 o;
+        o.x = run; run += c[4 * v];
+        o.y = run; run += c[4 * v + 1];
+        o.z = run; run += c[4 * v + 2];
+        o.w = run; run += c[4 * v + 3];
+        *(uint4 *)(off + tid * E + 4 * v) = o;
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        state[1] = K;
+        if (K == 0) state[0] = (uint32_t)TJ_ERR_NO_ELIGIBLE;
+    }
+    __syncthreads();
+    const uint32_t j = blockIdx.x * R + tid;
+    if (tid >= R || j >= batch) return;
+    uint32_t slot = kInvalid;
+    if (K != 0) {
+        const uint32_t k = (uint32_t)__umul64hi(tj_splitmix64(seed, j), (uint64_t)K);
+        uint32_t a = 0, b = n_tiles;             // last tile t with off[t] <= k
+        while (b - a > 1) {
+            const uint32_t mid = (a + b) >> 1;
+            if (off[mid] <= k) a = mid; else b = mid;
+        }
+        uint32_t rem = k - off[a];
+        const ulonglong2 *mw = (const ulonglong2 *)(mask + (size_t)a * kWordsPerTile);
+        unsigned long long m[kWordsPerTile];
+#pragma unroll
+        for (int i = 0; i < kWordsPerTile / 2; ++i) {
+            const ulonglong2 t = mw[i];
+            m[2 * i] = t.x; m[2 * i + 1] = t.y;
+        }
+        uint32_t w = 0;
+        unsigned long long mm = m[0];
+#pragma unroll
+        for (int i = 0; i < kWordsPerTile - 1; ++i) {   // K > 0 guarantees the walk ends inside this tile
+            const uint32_t cw = __popcll(mm);
+            if (w == (uint32_t)i && rem >= cw) { rem -= cw; w = i + 1; mm = m[i + 1]; }
+        }
+        for (uint32_t i = 0; i < rem; ++i) mm &= mm - 1;   // drop the rem lowest set bits
+        slot = (a * kWordsPerTile + w) * 64 + (uint32_t)(__ffsll((long long)mm) - 1);
+        action[j] = ring.action[slot];
+        reward[j] = ring.reward[slot];
+        done[j] = ring.done[slot];
+    }
+    idx[j] = slot;
 }
 
 // mode 0 (gather): dst row r <- src row idx[r];  mode 1 (insert): dst row
@@ -410,40 +536,6 @@ __global__ __launch_bounds__(256) void frame_ages(uint8_t *__restrict__ age, con
     uint64_t s = head + i;
     if (s >= cap) s -= cap;
     age[s] = (uint8_t)a;
-}
-
-// As stale_mask_count, plus the frame ring's usability rule: not the newest row (no successor),
-// and once the ring has wrapped the look-back must not reach past the oldest slot (at head).
-__global__ __launch_bounds__(256) void frame_mask_count(const int32_t *__restrict__ version,
-                                                        const uint8_t *__restrict__ age, uint32_t count,
-                                                        uint32_t head, uint32_t cap, int64_t cur, int64_t max_st,
-                                                        unsigned long long *__restrict__ mask,
-                                                        uint32_t *__restrict__ tile_count)
-{
-    __shared__ uint32_t wave_cnt[4];
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t base = blockIdx.x * kTile + wave * 256;
-    const uint32_t newest = head == 0 ? cap - 1 : head - 1;
-    uint32_t cnt = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint32_t s = base + r * 64 + lane;
-        bool e = s < count && s != newest;
-        if (e) {
-            const int64_t st = cur - (int64_t)version[s];
-            e = st >= 0 && st <= max_st;
-            if (e && count == cap) {
-                const uint32_t from_oldest = s >= head ? s - head : s + (cap - head);
-                e = from_oldest >= age[s];
-            }
-        }
-        const unsigned long long b = __ballot(e);
-        if (lane == 0) mask[(base >> 6) + r] = b;
-        cnt += __popcll(b);
-    }
-    if (lane == 0) wave_cnt[wave] = cnt;
-    __syncthreads();
-    if (threadIdx.x == 0) tile_count[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
 }
 
 // Minibatch row r, plane q of 2k: q < k is position q of the stack of slot idx[r], q >= k position
@@ -681,11 +773,19 @@ static int sample_into(tj_buffer *buf, uint32_t batch, int64_t current_version, 
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
     }
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[0], st));
-    stale_mask_count<<<n_tiles, 256, 0, st>>>(buf->ring.version, count, current_version, max_staleness,
-                                              mask, tile_count, buf->state, (uint32_t)buf->desc.capacity);
-    tile_scan<<<1, 1024, 0, st>>>(tile_count, n_tiles, tile_off, buf->state);
-    select_slots<<<(batch + 63) / 64, 64, 0, st>>>(mask, tile_off, n_tiles, buf->state, seed, batch, buf->ring,
-                                                   out->idx, out->action, out->reward, out->done);
+    mask_count<false><<<(n_tiles + 3) / 4, 256, 0, st>>>(buf->ring.version, nullptr, count, 0u,
+                                                         (uint32_t)buf->desc.capacity, current_version, max_staleness,
+                                                         mask, tile_count, buf->state, n_tiles);
+    if (n_tiles <= (uint32_t)kScanTiles) {
+        uint32_t R = batch / 256;   // draws per block: a few hundred blocks at most repeat the prefix sum
+        R = R < 1 ? 1 : (R > (uint32_t)kMaxDrawsPerBlock ? (uint32_t)kMaxDrawsPerBlock : R);
+        select_rows<<<(batch + R - 1) / R, 256, 0, st>>>(mask, tile_count, n_tiles, buf->state, seed, batch, R, buf->ring,
+                                                         out->idx, out->action, out->reward, out->done);
+    } else {
+        tile_scan<<<1, 1024, 0, st>>>(tile_count, n_tiles, tile_off, buf->state);
+        select_slots<<<(batch + 63) / 64, 64, 0, st>>>(mask, tile_off, n_tiles, buf->state, seed, batch, buf->ring,
+                                                       out->idx, out->action, out->reward, out->done);
+    }
     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[1], st));
     int rc = copy_rows(buf->ring.obs, out->obs, buf->ring.next_obs, out->next_obs, buf->row_bytes, batch,
@@ -882,11 +982,20 @@ int tj_frame_sample(tj_frame_buffer *buf, uint32_t batch, int64_t current_versio
     uint32_t n_tiles = (count + kTile - 1) / kTile;
     if (n_tiles == 0) n_tiles = 1;
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[0], st));
-    frame_mask_count<<<n_tiles, 256, 0, st>>>(buf->l.ring.version, buf->l.age, count, (uint32_t)buf->head, cap,
-                                              current_version, max_staleness, buf->l.mask, buf->l.tile_count);
-    tile_scan<<<1, 1024, 0, st>>>(buf->l.tile_count, n_tiles, buf->l.tile_off, buf->l.state);
-    select_slots<<<(batch + 63) / 64, 64, 0, st>>>(buf->l.mask, buf->l.tile_off, n_tiles, buf->l.state, seed, batch,
-                                                   buf->l.ring, out->idx, out->action, out->reward, out->done);
+    mask_count<true><<<(n_tiles + 3) / 4, 256, 0, st>>>(buf->l.ring.version, buf->l.age, count, (uint32_t)buf->head, cap,
+                                                        current_version, max_staleness, buf->l.mask, buf->l.tile_count,
+                                                        buf->l.state, n_tiles);
+    if (n_tiles <= (uint32_t)kScanTiles) {
+        uint32_t R = batch / 256;
+        R = R < 1 ? 1 : (R > (uint32_t)kMaxDrawsPerBlock ? (uint32_t)kMaxDrawsPerBlock : R);
+        select_rows<<<(batch + R - 1) / R, 256, 0, st>>>(buf->l.mask, buf->l.tile_count, n_tiles, buf->l.state, seed,
+                                                         batch, R, buf->l.ring, out->idx, out->action, out->reward,
+                                                         out->done);
+    } else {
+        tile_scan<<<1, 1024, 0, st>>>(buf->l.tile_count, n_tiles, buf->l.tile_off, buf->l.state);
+        select_slots<<<(batch + 63) / 64, 64, 0, st>>>(buf->l.mask, buf->l.tile_off, n_tiles, buf->l.state, seed, batch,
+                                                       buf->l.ring, out->idx, out->action, out->reward, out->done);
+    }
     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[1], st));
     const uint32_t fb = buf->desc.frame_elems, k = buf->desc.stack;

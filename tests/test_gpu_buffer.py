@@ -395,3 +395,26 @@ def test_frame_ring_edge_cases(tj, orc):
     L = tj.lib()
     bad = tj.tj_frame_buffer_desc(4, 8, 4)                        # capacity below two stacks
     assert L.tj_frame_buffer_arena_bytes(ctypes.byref(bad)) == 0
+
+
+def test_ring_with_more_tiles_than_one_block_scans(tj, orc):
+    """9 M slots = 8790 tiles of 1024: beyond the 8192 tile counts that the select kernel's blocks
+    prefix-sum for themselves in LDS, so the scan runs as a kernel of its own.  Partly filled ring,
+    ragged last tile, batches on both sides of the draws-per-block steps."""
+    from dataclasses import replace
+
+    wl = replace(synth.WORKLOADS["c2"], capacity=9_000_000, obs_shape=(1,))
+    total = 8_800_000 + 321
+    gbuf = tj.Buffer(wl.capacity, wl.obs_elems, wl.obs_dtype)
+    rows = synth.make_chunk(wl, 77, 0, total)
+    gbuf.insert_host(rows)
+    for batch, cur, max_st, seed in ((1000, 999, 3, 1), (37, 500, 0, 2), (5000, 999, 999, 3)):
+        mb = tj.Minibatch(batch, wl.obs_elems, wl.obs_dtype)
+        assert gbuf.sample(mb, cur, max_st, seed) == tj.TJ_OK
+        st, info = gbuf.status()
+        ost, oidx, oK = orc.sample(rows["version"], total, cur, max_st, seed, batch)
+        assert st == ost == 0 and info.last_n_eligible == oK
+        got = mb.host()
+        np.testing.assert_array_equal(got["idx"], oidx)
+        for f in FIELDS:
+            np.testing.assert_array_equal(got[f], rows[f][oidx], err_msg=f)
