@@ -23,9 +23,10 @@ _vp, _u64, _i64, _u32, _i32, _dbl = C.c_void_p, C.c_uint64, C.c_int64, C.c_uint3
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB):
+        path = os.environ.get("ORC_LIB", LIB)   # e.g. the sanitizer build (see build_oracle.py)
+        if path == LIB and not os.path.exists(LIB):
             build_oracle()
-        L = C.CDLL(LIB)
+        L = C.CDLL(path)
         L.orc_rng64.restype = _u64
         L.orc_rng64.argtypes = [_u64, _u64]
         L.orc_mulhi64.restype = _u64
