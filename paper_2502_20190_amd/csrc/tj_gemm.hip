@@ -1443,6 +1443,17 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
             return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
         }
     }
+    if (!a0.trans && !a1.trans) {   // few tiles (skinny problems): 256 x 64 tiles with deep stages, one block per CU
+        const unsigned s0 = plan_dlds<1>(a0, p.tm[0], tiles);
+        p.tiles_seg0[0] = tiles[0];
+        const unsigned s1 = plan_dlds<1>(a1, p.tm[1], tiles);
+        p.tiles_seg0[1] = tiles[0];
+        if (s0 + s1 <= 256) {
+            p.nblk0 = (int)s0;
+            gemm_bf16_dlds_pair<1, 128, 3><<<s0 + s1, 512, 0, st>>>(p);
+            return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+        }
+    }
     const unsigned n0 = plan_dlds<2>(a0, p.tm[0], tiles);
     p.tiles_seg0[0] = tiles[0];
     const unsigned n1 = plan_dlds<2>(a1, p.tm[1], tiles);
