@@ -125,6 +125,23 @@ template <typename T> int launch_cast(const CastJobs<T> &jobs, int n_jobs, hipSt
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 
+// Zero fill of a 16-byte aligned region (a kernel rather than a memset node, so that a caller may
+// capture the step into a HIP graph).
+__global__ __launch_bounds__(256) void zero_fill16(uint4 *__restrict__ p, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+inline int launch_zero(void *p, size_t bytes, hipStream_t st)   // bytes: a multiple of 256 (arena pieces)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return TJ_OK;
+    const unsigned blocks = (unsigned)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+    zero_fill16<<<blocks, 256, 0, st>>>((uint4 *)p, n16);
+    return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
+}
+
 // TD target, Huber loss and its gradient, one thread per transition, one wave per block (many
 // small blocks: the kernel is latency bound).
 //   a* = argmax_a Q_on(s',a) (lowest index on ties); y = r + gamma (1-done) Q_tg(s',a*)
@@ -1083,7 +1100,7 @@ template <typename T> struct MlpLearner : tj_learner {
         if (last_batch != B) {
             // pad columns beyond the batch must read as zero in the batch contraction
             // (the arena starts zeroed; only a shrinking batch leaves stale columns behind)
-            if (last_batch > B) TJ_HIP_TRY(hipMemsetAsync(act_begin, 0, act_bytes, st));
+            if (last_batch > B && (rc = launch_zero(act_begin, act_bytes, st)) != TJ_OK) return rc;
             last_batch = B;
         }
 
@@ -1418,7 +1435,7 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
         int rc;
         if (this->last_batch != B) {
             // pad columns beyond the batch must read as zero in the batch contraction
-            if (this->last_batch > B) TJ_HIP_TRY(hipMemsetAsync(this->act_begin, 0, this->act_bytes, st));
+            if (this->last_batch > B && (rc = launch_zero(this->act_begin, this->act_bytes, st)) != TJ_OK) return rc;
             this->last_batch = B;
         }
         if ((rc = forward(B, pb->obs, true, st)) != TJ_OK) return rc;
@@ -1751,7 +1768,7 @@ template <typename T> struct ConvLearner : tj_learner {
         if (!mb->obs || !mb->next_obs || !mb->action || !mb->reward || !mb->done) return TJ_ERR_INVALID_ARG;
         int rc;
         if (last_batch != B) {
-            if (last_batch > B) TJ_HIP_TRY(hipMemsetAsync(act_begin, 0, act_bytes, st));
+            if (last_batch > B && (rc = launch_zero(act_begin, act_bytes, st)) != TJ_OK) return rc;
             last_batch = B;
         }
         const int Kb = round_up(B, VE);
