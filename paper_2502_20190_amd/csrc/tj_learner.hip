@@ -1160,9 +1160,9 @@ template <typename T> struct MlpLearner : tj_learner {
         int rc;
         const int Kb = round_up(B, VE);
         // backward through the online network on s.  The weight gradient and the input gradient of a layer both
-        // start from dZ_l and are independent: one paired launch where the kernels allow it.  Where the TD kernel
-        // has already written the head's input gradient, the head's weight gradient waits and shares the launch
-        // of the first layer's weight gradient (neither has an input gradient beside it).
+        // start from dZ_l and are independent: one paired launch where the kernels allow it.  The head's weight
+        // gradient shares the launch of the first layer's weight gradient instead (neither is a problem that
+        // fills the chip); its input gradient runs alone unless the TD kernel has already written it.
         TjGemmArgs<T> gw_head;
         bool head_pending = false;
         for (int l = L; l >= 1; --l) {
@@ -1189,7 +1189,10 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.Cf = gpart + lp.w_off; g.ldcf = lp.in; g.cf_zstride = Ppad;
                 g.qsum = gpart + lp.b_off; g.qsum_zstride = Ppad;
             }
-            if (l == L && head_dx_done) {
+            // the head's weight gradient waits for the first layer's (bf16, two layers or more): both are
+            // skinny split contractions that fill the chip only together
+            const bool defer_head = l == L && L >= 2 && sizeof(T) == 2;
+            if (defer_head && head_dx_done) {
                 gw_head = gw;
                 head_pending = true;
                 continue;
@@ -1213,6 +1216,12 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.mask = X[l - 1]; g.ldmask = lp.ld_in;
                 g.Ci = dZ[l - 1]; g.ldci = lp.ld_in;
                 if (!wgrad_trans(l - 1, B)) { g.Cj = dZT[l - 1]; g.ldcj = ldB; g.cj_jmax = B; }
+            }
+            if (defer_head) {   // the input gradient alone now
+                if ((rc = tj_gemm<T>(gd, st)) != TJ_OK) return rc;
+                gw_head = gw;
+                head_pending = true;
+                continue;
             }
             if (l >= 2) {
                 if constexpr (sizeof(T) == 2) rc = tj_gemm_pair(gw, gd, st);
