@@ -350,10 +350,13 @@ __device__ __forceinline__ void wave_sync()
 // hardware loads and stores share one counter (vmcnt), so a load issued after a tile's stores would
 // wait for those stores to finish.  The kernels run this on every tile first, then store.
 __device__ __forceinline__ f32x16 tile_math_edge(const TjGemmArgs<tj_bf16> &a, const TjGemmSeg<tj_bf16> &seg,
-                                              f32x16 v, const int ibase, const int jbase, const int j_end,
+                                              f32x16 v, int ibase, int jbase, const int j_end,
                                               const int lane)
 {
     typedef tj_bf16 T;
+    // Opaque to the optimiser: the per-element addresses and guards below are then formed inside the branch
+    // that leads here and do not occupy registers on the interior tiles' path.
+    asm volatile("" : "+v"(ibase), "+v"(jbase));
     const int l32 = lane & 31, lg = lane >> 5;
     const int jl = jbase + l32;
     if (seg.bias) {
@@ -403,10 +406,11 @@ __device__ __forceinline__ f32x16 tile_math_edge(const TjGemmArgs<tj_bf16> &a, c
 enum { kOutCi = 1, kOutCj = 2, kOutCf = 4, kOutAll = 7 };
 
 __device__ __forceinline__ void store_tile_edge(const TjGemmArgs<tj_bf16> &a, const f32x16 v, uint8_t *scr,
-                                           const int ibase, const int jbase, const int j_end, const int z,
+                                           int ibase, int jbase, const int j_end, const int z,
                                            const int lane, const int which)
 {
     typedef tj_bf16 T;
+    asm volatile("" : "+v"(ibase), "+v"(jbase));   // as in tile_math_edge
     const int l32 = lane & 31, lg = lane >> 5;
     if (a.Ci && (which & kOutCi)) {   // rows j, 32 consecutive i (64 bytes) each
         wave_sync();
@@ -617,6 +621,25 @@ __device__ __forceinline__ void store_pair_ci(const TjGemmArgs<tj_bf16> &a, cons
         o1.x = pack_bf16(v1[rq * 4], v1[rq * 4 + 1]); o1.y = pack_bf16(v1[rq * 4 + 2], v1[rq * 4 + 3]);
         *(uint2 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 2) = o0;
         *(uint2 *)(scr + l32 * kScratchPitch + 64 + (rq * 8 + lg * 4) * 2) = o1;
+    }
+    wave_sync();
+    tj_bf16 *cp = a.Ci + (size_t)(jbase + (lane >> 3)) * a.ldci + ibase + (lane & 7) * 8;
+    const uint8_t *sp = scr + (lane >> 3) * kScratchPitch + (lane & 7) * 16;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) *(u32x4 *)(cp + (size_t)(8 * t) * a.ldci) = *(const u32x4 *)(sp + 8 * t * kScratchPitch);
+}
+
+// The same from values already rounded and packed (p[q] = elements 2q, 2q + 1 of the tile's registers).
+__device__ __forceinline__ void store_pair_ci_packed(const TjGemmArgs<tj_bf16> &a, const uint32_t (&p0)[8],
+                                                     const uint32_t (&p1)[8], uint8_t *scr, const int ibase,
+                                                     const int jbase, const int lane)
+{
+    const int l32 = lane & 31, lg = lane >> 5;
+    wave_sync();
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+        *(uint2 *)(scr + l32 * kScratchPitch + (rq * 8 + lg * 4) * 2) = make_uint2(p0[2 * rq], p0[2 * rq + 1]);
+        *(uint2 *)(scr + l32 * kScratchPitch + 64 + (rq * 8 + lg * 4) * 2) = make_uint2(p1[2 * rq], p1[2 * rq + 1]);
     }
     wave_sync();
     tj_bf16 *cp = a.Ci + (size_t)(jbase + (lane >> 3)) * a.ldci + ibase + (lane & 7) * 8;
@@ -869,10 +892,18 @@ template <int NFJ, int BKB, int NSTAGE> constexpr int dlds_lds_bytes() { return 
 // Needs BKB = 64, NFJ = 2, one segment, no q_shift, I and the segment's columns multiples of 8.
 // TRANS = 2: only P is stored that way (the input gradient dX[j][i] = sum_n dZ[j][n] W[n][i] from
 // the row-major weights); Q keeps its contraction-contiguous rows, 32 elements of them per stage.
-template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, int TRANS = 0>
-__device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const int tiles_seg0, const TileMap &tm,
+// OUTS: 0, or the set of outputs (kOutCi | kOutCj | kOutCf) the launch can have: the epilogue of the others
+// is not compiled in (shorter code, fewer live registers after the main loop).
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, int TRANS = 0, int OUTS = 0>
+__device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a_in, const int tiles_seg0, const TileMap &tm,
                                           const int block_id, uint8_t *lds)
 {
+    TjGemmArgs<tj_bf16> a = a_in;
+    if constexpr (OUTS != 0) {
+        if (!(OUTS & kOutCi)) a.Ci = nullptr;
+        if (!(OUTS & kOutCj)) a.Cj = nullptr;
+        if (!(OUTS & kOutCf)) a.Cf = nullptr;
+    }
     typedef tj_bf16 T;
     static_assert(TRANS == 0 || (BKB == 64 && NFJ == 2 && !GATHER), "transposed operands: 256 x 128 tiles, 32-row stages");
     constexpr int BJ3 = 64 * NFJ;
@@ -1176,16 +1207,49 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     }
 
     // ---- epilogue (as in gemm_bf16): math on every tile first, then the stores
-#pragma unroll
-    for (int fi = 0; fi < 2; ++fi)
-#pragma unroll
-        for (int fj = 0; fj < NFJ; ++fj)
-            tile_math(a, seg, acc[fi][fj], i0 + wi * 64 + fi * 32, j0 + wj * 32 * NFJ + fj * 32, j_end, lane);
     constexpr int WPB = SZA / (32 * kScratchPitch) >= 4 ? 4 : SZA / (32 * kScratchPitch);   // waves per buffer
     static_assert(WPB >= 2 && 7 / WPB < NSTAGE, "epilogue scratch does not fit the P buffers");
     const int sb = wave / WPB;
     uint8_t *scr = (sb == 0 ? sA0 : sb == 1 ? sA1 : sb == 2 ? sA2 : sA3) + (wave % WPB) * (32 * kScratchPitch);
     const int ib0 = i0 + wi * 64, jb0 = j0 + wj * 32 * NFJ;
+    if constexpr (OUTS == kOutCi) {
+        // one bf16 output: every tile is rounded as soon as its math is done, so the stores start from half
+        // as many live registers
+        uint32_t pk[2][NFJ][8];
+#pragma unroll
+        for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+            for (int fj = 0; fj < NFJ; ++fj) {
+                tile_math(a, seg, acc[fi][fj], ib0 + fi * 32, jb0 + fj * 32, j_end, lane);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) pk[fi][fj][q] = pack_bf16(acc[fi][fj][2 * q], acc[fi][fj][2 * q + 1]);
+            }
+        if (!a.Ci) return;
+#pragma unroll
+        for (int fj = 0; fj < NFJ; ++fj) {
+            const int jb = jb0 + fj * 32;
+            if (ib0 + 64 <= a.I && jb + 32 <= j_end) {
+                store_pair_ci_packed(a, pk[0][fj], pk[1][fj], scr, ib0, jb, lane);
+            } else {   // edge tiles: the guarded stores round again, which leaves a bf16 value as it is
+#pragma unroll
+                for (int fi = 0; fi < 2; ++fi) {
+                    f32x16 v;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        v[2 * q] = __uint_as_float(pk[fi][fj][q] << 16);
+                        v[2 * q + 1] = __uint_as_float(pk[fi][fj][q] & 0xFFFF0000u);
+                    }
+                    store_tile(a, v, scr, ib0 + fi * 32, jb, j_end, z, lane, kOutCi);
+                }
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int fj = 0; fj < NFJ; ++fj)
+            tile_math(a, seg, acc[fi][fj], i0 + wi * 64 + fi * 32, j0 + wj * 32 * NFJ + fj * 32, j_end, lane);
     if (a.Ci) {
 #pragma unroll
         for (int fj = 0; fj < NFJ; ++fj) {
@@ -1228,12 +1292,12 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a, const in
     __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2, \
                                                               ((NFJ) <= 2 && (BKB) * (NSTAGE) <= 192) ? 4 : 2)))
 
-template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, int TRANS = 0>
+template <int NFJ, int BKB, int NSTAGE, bool QSUM, bool GATHER = false, int TRANS = 0, int OUTS = 0>
 __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds(const TjGemmArgs<tj_bf16> a, const int tiles_seg0,
                                                               const TileMap tm)
 {
     __shared__ __align__(1024) uint8_t lds[dlds_lds_bytes<NFJ, BKB, NSTAGE>()];
-    dlds_body<NFJ, BKB, NSTAGE, QSUM, GATHER, TRANS>(a, tiles_seg0, tm, (int)blockIdx.x, lds);
+    dlds_body<NFJ, BKB, NSTAGE, QSUM, GATHER, TRANS, OUTS>(a, tiles_seg0, tm, (int)blockIdx.x, lds);
 }
 
 // Two independent GEMMs in one launch (e.g. the weight gradient and the input gradient of a layer,
@@ -1247,12 +1311,22 @@ struct GemmPair {
     int nblk0;
 };
 
-template <int NFJ, int BKB, int NSTAGE>
+// HIDDEN: both members have transposed operands and the outputs of a hidden layer's backward pass (the
+// weight gradient only its fp32 slices, the input gradient only its row-major bf16 copy).
+template <int NFJ, int BKB, int NSTAGE, bool HIDDEN = false>
 __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPair p)
 {
     __shared__ __align__(1024) uint8_t lds[dlds_lds_bytes<NFJ, BKB, NSTAGE>()];
     const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
     const int id = (int)blockIdx.x - which * p.nblk0;
+    if constexpr (HIDDEN) {
+        static_assert(BKB == 64 && NFJ == 2, "transposed operands: 256 x 128 tiles");
+        if (p.a[which].trans == 1)   // block-uniform
+            dlds_body<NFJ, BKB, NSTAGE, true, false, 1, kOutCf>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
+        else
+            dlds_body<NFJ, BKB, NSTAGE, false, false, 2, kOutCi>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
+        return;
+    }
     if constexpr (BKB == 64 && NFJ == 2) {
         if (p.a[which].trans == 1) {   // block-uniform
             dlds_body<NFJ, BKB, NSTAGE, true, false, 1>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
@@ -1299,6 +1373,8 @@ int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else if (a.qsum)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
+    else if (NFJ == 2 && BKB == 64 && a.Ci && !a.Cj && !a.Cf)   // a hidden layer's forward: one bf16 output
+        gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, false, 0, kOutCi><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
@@ -1459,7 +1535,13 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
     const unsigned n1 = plan_dlds<2>(a1, p.tm[1], tiles);
     p.tiles_seg0[1] = tiles[0];
     p.nblk0 = (int)n0;
-    gemm_bf16_dlds_pair<2, 64, 3><<<n0 + n1, 512, 0, st>>>(p);
+    auto hidden = [](const TjGemmArgs<tj_bf16> &a) {
+        return a.trans == 1 ? (a.Cf && !a.Ci && !a.Cj) : (a.trans == 2 && a.Ci && !a.Cj && !a.Cf);
+    };
+    if (hidden(a0) && hidden(a1))
+        gemm_bf16_dlds_pair<2, 64, 3, true><<<n0 + n1, 512, 0, st>>>(p);
+    else
+        gemm_bf16_dlds_pair<2, 64, 3><<<n0 + n1, 512, 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
 }
 
