@@ -676,6 +676,33 @@ __device__ __forceinline__ void store_pair_cj(const TjGemmArgs<tj_bf16> &a, cons
     for (int t = 0; t < 4; ++t) *(u32x4 *)(cp + (size_t)(8 * t) * a.ldcj) = *(const u32x4 *)(sp + 8 * t * kScratchPitch);
 }
 
+// The same from values already rounded and packed.
+__device__ __forceinline__ void store_pair_cj_packed(const TjGemmArgs<tj_bf16> &a, const uint32_t (&p0)[8],
+                                                     const uint32_t (&p1)[8], uint8_t *scr, const int ibase,
+                                                     const int jbase, const int lane)
+{
+    typedef tj_bf16 T;
+    const int l32 = lane & 31, lg = lane >> 5;
+    wave_sync();
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+        uint8_t *wp = scr + (rq * 8 + lg * 4) * kScratchPitch + l32 * 2;
+        *(T *)(wp) = (T)(p0[2 * rq] & 0xFFFFu);
+        *(T *)(wp + kScratchPitch) = (T)(p0[2 * rq] >> 16);
+        *(T *)(wp + 2 * kScratchPitch) = (T)(p0[2 * rq + 1] & 0xFFFFu);
+        *(T *)(wp + 3 * kScratchPitch) = (T)(p0[2 * rq + 1] >> 16);
+        *(T *)(wp + 64) = (T)(p1[2 * rq] & 0xFFFFu);
+        *(T *)(wp + 64 + kScratchPitch) = (T)(p1[2 * rq] >> 16);
+        *(T *)(wp + 64 + 2 * kScratchPitch) = (T)(p1[2 * rq + 1] & 0xFFFFu);
+        *(T *)(wp + 64 + 3 * kScratchPitch) = (T)(p1[2 * rq + 1] >> 16);
+    }
+    wave_sync();
+    T *cp = a.Cj + (size_t)(ibase + (lane >> 3)) * a.ldcj + jbase + (lane & 7) * 8;
+    const uint8_t *sp = scr + (lane >> 3) * kScratchPitch + (lane & 7) * 16;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) *(u32x4 *)(cp + (size_t)(8 * t) * a.ldcj) = *(const u32x4 *)(sp + 8 * t * kScratchPitch);
+}
+
 // ---------------------------------------------------------------- bf16 kernel
 //
 // Block tile 256 (i) x 128 (j), four waves as 2 x 2, wave tile 128 x 64 = 4 x 2
@@ -1212,8 +1239,8 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a_in, const
     const int sb = wave / WPB;
     uint8_t *scr = (sb == 0 ? sA0 : sb == 1 ? sA1 : sb == 2 ? sA2 : sA3) + (wave % WPB) * (32 * kScratchPitch);
     const int ib0 = i0 + wi * 64, jb0 = j0 + wj * 32 * NFJ;
-    if constexpr (OUTS == kOutCi) {
-        // one bf16 output: every tile is rounded as soon as its math is done, so the stores start from half
+    if constexpr (OUTS == kOutCi || OUTS == (kOutCi | kOutCj)) {
+        // bf16 outputs only: every tile is rounded as soon as its math is done, so the stores start from half
         // as many live registers
         uint32_t pk[2][NFJ][8];
 #pragma unroll
@@ -1224,22 +1251,46 @@ __device__ __forceinline__ void dlds_body(const TjGemmArgs<tj_bf16> &a_in, const
 #pragma unroll
                 for (int q = 0; q < 8; ++q) pk[fi][fj][q] = pack_bf16(acc[fi][fj][2 * q], acc[fi][fj][2 * q + 1]);
             }
-        if (!a.Ci) return;
+        // edge tiles: the guarded stores round again, which leaves a bf16 value as it is
+        auto widen = [&](const uint32_t (&p)[8]) {
+            f32x16 v;
 #pragma unroll
-        for (int fj = 0; fj < NFJ; ++fj) {
-            const int jb = jb0 + fj * 32;
-            if (ib0 + 64 <= a.I && jb + 32 <= j_end) {
-                store_pair_ci_packed(a, pk[0][fj], pk[1][fj], scr, ib0, jb, lane);
-            } else {   // edge tiles: the guarded stores round again, which leaves a bf16 value as it is
+            for (int q = 0; q < 8; ++q) {
+                v[2 * q] = __uint_as_float(p[q] << 16);
+                v[2 * q + 1] = __uint_as_float(p[q] & 0xFFFF0000u);
+            }
+            return v;
+        };
+        if (a.Ci) {
+#pragma unroll
+            for (int fj = 0; fj < NFJ; ++fj) {
+                const int jb = jb0 + fj * 32;
+                if (ib0 + 64 <= a.I && jb + 32 <= j_end) {
+                    store_pair_ci_packed(a, pk[0][fj], pk[1][fj], scr, ib0, jb, lane);
+                } else {
+#pragma unroll
+                    for (int fi = 0; fi < 2; ++fi)
+                        store_tile(a, widen(pk[fi][fj]), scr, ib0 + fi * 32, jb, j_end, z, lane, kOutCi);
+                }
+            }
+        }
+        if constexpr ((OUTS & kOutCj) != 0) {
+            if (a.Cj) {
+                const int jmax = min(j_end, a.cj_jmax);
 #pragma unroll
                 for (int fi = 0; fi < 2; ++fi) {
-                    f32x16 v;
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        v[2 * q] = __uint_as_float(pk[fi][fj][q] << 16);
-                        v[2 * q + 1] = __uint_as_float(pk[fi][fj][q] & 0xFFFF0000u);
+                    for (int fj = 0; fj + 1 < NFJ; fj += 2) {
+                        const int jb = jb0 + fj * 32;
+                        if (ib0 + fi * 32 + 32 <= a.I && jb + 64 <= jmax && ((a.ldcj | jb) & 7) == 0) {
+                            store_pair_cj_packed(a, pk[fi][fj], pk[fi][fj + 1], scr, ib0 + fi * 32, jb, lane);
+                        } else {
+                            store_tile(a, widen(pk[fi][fj]), scr, ib0 + fi * 32, jb, j_end, z, lane, kOutCj);
+                            store_tile(a, widen(pk[fi][fj + 1]), scr, ib0 + fi * 32, jb + 32, j_end, z, lane, kOutCj);
+                        }
                     }
-                    store_tile(a, v, scr, ib0 + fi * 32, jb, j_end, z, lane, kOutCi);
+                    if (NFJ & 1)
+                        store_tile(a, widen(pk[fi][NFJ - 1]), scr, ib0 + fi * 32, jb0 + (NFJ - 1) * 32, j_end, z, lane, kOutCj);
                 }
             }
         }
@@ -1313,18 +1364,19 @@ struct GemmPair {
 
 // HIDDEN: both members have transposed operands and the outputs of a hidden layer's backward pass (the
 // weight gradient only its fp32 slices, the input gradient only its row-major bf16 copy).
-template <int NFJ, int BKB, int NSTAGE, bool HIDDEN = false>
+template <int NFJ, int BKB, int NSTAGE, int HIDDEN = 0>   // 2: the input gradient also in its transposed layout
 __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPair p)
 {
     __shared__ __align__(1024) uint8_t lds[dlds_lds_bytes<NFJ, BKB, NSTAGE>()];
     const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
     const int id = (int)blockIdx.x - which * p.nblk0;
-    if constexpr (HIDDEN) {
+    if constexpr (HIDDEN != 0) {
         static_assert(BKB == 64 && NFJ == 2, "transposed operands: 256 x 128 tiles");
         if (p.a[which].trans == 1)   // block-uniform
             dlds_body<NFJ, BKB, NSTAGE, true, false, 1, kOutCf>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
         else
-            dlds_body<NFJ, BKB, NSTAGE, false, false, 2, kOutCi>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
+            dlds_body<NFJ, BKB, NSTAGE, false, false, 2, HIDDEN == 2 ? (kOutCi | kOutCj) : kOutCi>(
+                p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
         return;
     }
     if constexpr (BKB == 64 && NFJ == 2) {
@@ -1375,6 +1427,8 @@ int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else if (NFJ == 2 && BKB == 64 && a.Ci && !a.Cj && !a.Cf)   // a hidden layer's forward: one bf16 output
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, false, 0, kOutCi><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
+    else if (NFJ == 2 && BKB == 64 && a.Ci && a.Cj && !a.Cf)   // ... in both layouts
+        gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, false, 0, kOutCi | kOutCj><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
@@ -1536,10 +1590,12 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
     p.tiles_seg0[1] = tiles[0];
     p.nblk0 = (int)n0;
     auto hidden = [](const TjGemmArgs<tj_bf16> &a) {
-        return a.trans == 1 ? (a.Cf && !a.Ci && !a.Cj) : (a.trans == 2 && a.Ci && !a.Cj && !a.Cf);
+        return a.trans == 1 ? (a.Cf && !a.Ci && !a.Cj) : (a.trans == 2 && a.Ci && !a.Cf);
     };
-    if (hidden(a0) && hidden(a1))
-        gemm_bf16_dlds_pair<2, 64, 3, true><<<n0 + n1, 512, 0, st>>>(p);
+    if (hidden(a0) && hidden(a1) && !(a0.trans == 2 && a0.Cj) && !(a1.trans == 2 && a1.Cj))
+        gemm_bf16_dlds_pair<2, 64, 3, 1><<<n0 + n1, 512, 0, st>>>(p);
+    else if (hidden(a0) && hidden(a1))
+        gemm_bf16_dlds_pair<2, 64, 3, 2><<<n0 + n1, 512, 0, st>>>(p);
     else
         gemm_bf16_dlds_pair<2, 64, 3><<<n0 + n1, 512, 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;

@@ -354,11 +354,13 @@ __global__ __launch_bounds__(kHeadThreads) void head_td(const HeadTdArgs a)
         const int j = j0 + lane;
         if (lane < kHeadRows && j < a.B) {
             int best = 0;
-            float bv = qs[1][lane][0];
-            for (int i = 1; i < a.A; ++i) {
-                const float x = qs[1][lane][i];
-                if (x > bv) { bv = x; best = i; }
-            }
+            float qrow[32];   // all 32 reads issue before the first comparison
+#pragma unroll
+            for (int i = 0; i < 32; ++i) qrow[i] = qs[1][lane][i];
+            float bv = qrow[0];
+#pragma unroll
+            for (int i = 1; i < 32; ++i)
+                if (i < a.A && qrow[i] > bv) { bv = qrow[i]; best = i; }
             a.astar[j] = best;
             aj = a.action[j];
             aj = aj < 0 ? 0 : (aj >= a.A ? a.A - 1 : aj);
@@ -404,6 +406,42 @@ __global__ __launch_bounds__(kHeadThreads) void head_td(const HeadTdArgs a)
     tj_bf16 *tile = (tj_bf16 *)&stage[0][0][0];
     static_assert(kChunk * kPitch * 2 <= (int)sizeof(stage), "transpose tile must fit the staging slabs");
     const bool want_t = a.dXT != nullptr;   // block-uniform
+    if (!want_t) {
+        // rows only: every thread takes up to kInFlight vectors of the 32 x K block and issues all their
+        // loads before the first product, so the block makes one round trip to memory per pass
+        constexpr int kInFlight = 6;
+        const int nvec = a.K / 8, total = kHeadRows * nvec;
+        for (int base = threadIdx.x; base < total; base += kInFlight * kHeadThreads) {
+            headu32x4 x[kInFlight], wv[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int e = base + u * kHeadThreads, j = e / nvec, k = (e % nvec) * 8;
+                const int aj = e < total ? s_aj[j] : -1;
+                x[u] = wv[u] = zero;
+                if (aj >= 0) {
+                    x[u] = *(const headu32x4 *)(a.X + ((size_t)a.row0[0] + j0 + j) * a.ldx + k);
+                    wv[u] = *(const headu32x4 *)(a.W_on + (size_t)aj * a.ldw + k);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int e = base + u * kHeadThreads, j = e / nvec, k = (e % nvec) * 8;
+                if (e >= total || j0 + j >= a.B) continue;
+                const float g = tj_bf16_to_f32(tj_f32_to_bf16(s_g[j]));
+                headu32x4 o;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t xl = x[u][c] & 0xFFFFu, xh = x[u][c] >> 16;
+                    const float pl = g * __uint_as_float(wv[u][c] << 16), ph = g * __uint_as_float(wv[u][c] & 0xFFFF0000u);
+                    const uint32_t lo = (int16_t)xl > 0 ? tj_f32_to_bf16(pl) : 0u;
+                    const uint32_t hi = (int16_t)xh > 0 ? tj_f32_to_bf16(ph) : 0u;
+                    o[c] = lo | (hi << 16);
+                }
+                *(headu32x4 *)(a.dX + (size_t)(j0 + j) * a.lddx + k) = o;
+            }
+        }
+        return;
+    }
     for (int k0 = 0; k0 < a.K; k0 += kChunk) {
         if (want_t) __syncthreads();   // the partial tiles (first pass) or the previous chunk's tile have been read
         for (int e = threadIdx.x; e < kHeadRows * (kChunk / 8); e += kHeadThreads) {
