@@ -1364,13 +1364,17 @@ struct GemmPair {
 
 // HIDDEN: both members have transposed operands and the outputs of a hidden layer's backward pass (the
 // weight gradient only its fp32 slices, the input gradient only its row-major bf16 copy).
-template <int NFJ, int BKB, int NSTAGE, int HIDDEN = 0>   // 2: the input gradient also in its transposed layout
+template <int NFJ, int BKB, int NSTAGE, int HIDDEN = 0>   // 2: the input gradient also in its transposed layout; 3: see below
 __global__ TJ_DLDS_ATTRS(NFJ, BKB, NSTAGE) void gemm_bf16_dlds_pair(const GemmPair p)
 {
     __shared__ __align__(1024) uint8_t lds[dlds_lds_bytes<NFJ, BKB, NSTAGE>()];
     const int which = (int)blockIdx.x >= p.nblk0 ? 1 : 0;
     const int id = (int)blockIdx.x - which * p.nblk0;
-    if constexpr (HIDDEN != 0) {
+    if constexpr (HIDDEN == 3) {   // two split weight gradients: fp32 slices only
+        dlds_body<NFJ, BKB, NSTAGE, true, false, 0, kOutCf>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
+        return;
+    }
+    if constexpr (HIDDEN == 1 || HIDDEN == 2) {
         static_assert(BKB == 64 && NFJ == 2, "transposed operands: 256 x 128 tiles");
         if (p.a[which].trans == 1)   // block-uniform
             dlds_body<NFJ, BKB, NSTAGE, true, false, 1, kOutCf>(p.a[which], p.tiles_seg0[which], p.tm[which], id, lds);
@@ -1425,9 +1429,9 @@ int launch_dlds(const TjGemmArgs<tj_bf16> &a, hipStream_t st)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else if (a.qsum)
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, true><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
-    else if (NFJ == 2 && BKB == 64 && a.Ci && !a.Cj && !a.Cf)   // a hidden layer's forward: one bf16 output
+    else if (a.Ci && !a.Cj && !a.Cf)   // a hidden layer's forward: one bf16 output
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, false, 0, kOutCi><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
-    else if (NFJ == 2 && BKB == 64 && a.Ci && a.Cj && !a.Cf)   // ... in both layouts
+    else if (a.Ci && a.Cj && !a.Cf)   // ... in both layouts
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false, false, 0, kOutCi | kOutCj><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
     else
         gemm_bf16_dlds<NFJ, BKB, NSTAGE, false><<<nblk, 512, 0, st>>>(a, tiles[0], tm);
@@ -1580,7 +1584,10 @@ int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, h
         p.tiles_seg0[1] = tiles[0];
         if (s0 + s1 <= 256) {
             p.nblk0 = (int)s0;
-            gemm_bf16_dlds_pair<1, 128, 3><<<s0 + s1, 512, 0, st>>>(p);
+            if (a0.Cf && !a0.Ci && !a0.Cj && a1.Cf && !a1.Ci && !a1.Cj)
+                gemm_bf16_dlds_pair<1, 128, 3, 3><<<s0 + s1, 512, 0, st>>>(p);
+            else
+                gemm_bf16_dlds_pair<1, 128, 3><<<s0 + s1, 512, 0, st>>>(p);
             return hipGetLastError() == hipSuccess ? TJ_OK : TJ_ERR_DEVICE;
         }
     }
