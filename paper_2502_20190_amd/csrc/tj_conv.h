@@ -279,10 +279,9 @@ __global__ __launch_bounds__(256) void dgrad_weights(const DgradWeightJobs jobs)
 
 // Sums the partial gradient slices of every layer into the flat gradient, all layers in one launch.
 // Job q: n_part slices of n elements each (slice z at part + z * zstride) -> dst[0, n); blocks
-// [block_begin[q], block_begin[q + 1]) work on it.  A block owns 128 consecutive elements (32 lanes
-// x 16 bytes); its 8 thread rows each add every 8th slice, four loads in flight at a time, then the
-// 8 sums are added in a fixed order: deterministic for a given n_part.  Slices start 16-byte aligned
-// and are padded to a multiple of 4 elements (zstride % 4 == 0).
+// [block_begin[q], block_begin[q + 1]) work on it, in one of the two forms below; both add in a fixed
+// order: deterministic for a given n_part.  Slices start 16-byte aligned and are padded to a multiple
+// of 4 elements (zstride % 4 == 0).
 struct ReduceJobs {
     int n_job;
     const float *part[TJ_MAX_LAYERS];
@@ -293,29 +292,66 @@ struct ReduceJobs {
     unsigned block_begin[TJ_MAX_LAYERS + 1];
 };
 
+// Elements one block reduces: 4 * kRedCols, or 1024 where a job has at most kReduceFew slices.
+constexpr int kReduceFew = 8;
+constexpr int kRedCols = 8, kRedGroups = 256 / kRedCols;
+inline unsigned reduce_blocks(size_t n, int n_part)
+{
+    const size_t per = n_part <= kReduceFew ? 1024 : 4 * kRedCols;
+    return (unsigned)((n + per - 1) / per);
+}
+
 __global__ __launch_bounds__(256) void reduce_parts(const ReduceJobs jobs)
 {
-    __shared__ float4 sh[8][32];
+    __shared__ float4 sh[kRedGroups][kRedCols];
     int q = 0;
     while (q + 1 < jobs.n_job && blockIdx.x >= jobs.block_begin[q + 1]) ++q;
     const float *__restrict__ part = jobs.part[q];
     const size_t zstride = jobs.zstride[q], n = jobs.n[q];
     const int n_part = jobs.n_part[q];
     float *__restrict__ dst = jobs.dst[q];
-    const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
-    const size_t e = ((size_t)(blockIdx.x - jobs.block_begin[q]) * 32 + col) * 4;
+    if (n_part <= kReduceFew) {
+        // few slices of a long vector (a linear layer's batch split): one float4 per thread, every slice's
+        // load in flight, added in slice order
+        const size_t e = ((size_t)(blockIdx.x - jobs.block_begin[q]) * 256 + threadIdx.x) * 4;
+        if (e >= n) return;
+        float4 p[kReduceFew];
+#pragma unroll
+        for (int u = 0; u < kReduceFew; ++u)
+            p[u] = u < n_part ? *(const float4 *)(part + (size_t)u * zstride + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < kReduceFew; ++u)
+            if (u < n_part) { sum.x += p[u].x; sum.y += p[u].y; sum.z += p[u].z; sum.w += p[u].w; }
+        const float out[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (e + k < n) dst[e + k] = out[k];
+        return;
+    }
+    // many slices of a short vector (a convolution's row split): a block owns kRedCols float4 columns (one
+    // 128-byte line per slice); its kRedGroups thread rows each add every kRedGroups-th slice, eight loads in
+    // flight, then the row sums are added in row order
+    const int col = threadIdx.x % kRedCols, grp = threadIdx.x / kRedCols;
+    const size_t e = ((size_t)(blockIdx.x - jobs.block_begin[q]) * kRedCols + col) * 4;
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
     if (e < n) {
         const float *src = part + e;
         int z = grp;
-        for (; z + 24 < n_part; z += 32) {
-            float4 p[4];
+        for (; z + 7 * kRedGroups < n_part; z += 8 * kRedGroups) {
+            float4 p[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) p[u] = *(const float4 *)(src + (size_t)(z + 8 * u) * zstride);
+            for (int u = 0; u < 8; ++u) p[u] = *(const float4 *)(src + (size_t)(z + kRedGroups * u) * zstride);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { sum.x += p[u].x; sum.y += p[u].y; sum.z += p[u].z; sum.w += p[u].w; }
+            for (int u = 0; u < 8; ++u) { sum.x += p[u].x; sum.y += p[u].y; sum.z += p[u].z; sum.w += p[u].w; }
         }
-        for (; z < n_part; z += 8) {
+        for (; z + kRedGroups < n_part; z += 2 * kRedGroups) {
+            const float4 p0 = *(const float4 *)(src + (size_t)z * zstride);
+            const float4 p1 = *(const float4 *)(src + (size_t)(z + kRedGroups) * zstride);
+            sum.x += p0.x; sum.y += p0.y; sum.z += p0.z; sum.w += p0.w;
+            sum.x += p1.x; sum.y += p1.y; sum.z += p1.z; sum.w += p1.w;
+        }
+        for (; z < n_part; z += kRedGroups) {
             const float4 p = *(const float4 *)(src + (size_t)z * zstride);
             sum.x += p.x; sum.y += p.y; sum.z += p.z; sum.w += p.w;
         }
@@ -324,7 +360,7 @@ __global__ __launch_bounds__(256) void reduce_parts(const ReduceJobs jobs)
     __syncthreads();
     if (grp != 0 || e >= n) return;
 #pragma unroll
-    for (int g = 1; g < 8; ++g) {
+    for (int g = 1; g < kRedGroups; ++g) {
         const float4 p = sh[g][col];
         sum.x += p.x; sum.y += p.y; sum.z += p.z; sum.w += p.w;
     }

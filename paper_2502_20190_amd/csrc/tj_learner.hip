@@ -1793,6 +1793,15 @@ template <typename T> struct ConvLearner : tj_learner {
 
     static dim3 grid1(size_t n) { return dim3((unsigned)((n + 255) / 256)); }
 
+    // A hidden linear layer's weight gradient straight from the row-major input rows and dZ (transposing LDS
+    // reads, as in the MLP learner): bf16, whole 32-row stages of the batch, widths that are whole 16-byte
+    // vectors and fill 256 x 128 tiles.  Such a layer needs neither the transposed input nor dZ^T.
+    bool lin_wgrad_trans(int l, int B) const
+    {
+        if (sizeof(T) != 2 || l < 1 || l >= L - 1 || lay[l].kind != TJ_LAYER_LINEAR) return false;
+        return B % 32 == 0 && B >= 1024 && lay[l].K % 8 == 0 && lay[l].O % 8 == 0 && lay[l].K >= 256 && lay[l].O >= 128;
+    }
+
     int transpose(const T *src, int lds, T *dst, int ldd, int R, int Cc, hipStream_t st)
     {
         if constexpr (sizeof(T) == 2) {
@@ -1921,7 +1930,7 @@ template <typename T> struct ConvLearner : tj_learner {
                     for (int net = 0; net < 2; ++net)
                         if ((rc = tj_gemm<T>(both[net], st)) != TJ_OK) return rc;
             } else {
-                if (l > 0 && lay[l - 1].kind == TJ_LAYER_CONV2D)   // transposed input of the s rows
+                if (l > 0 && lay[l - 1].kind == TJ_LAYER_CONV2D && !lin_wgrad_trans(l, B))   // transposed input of the s rows
                     if ((rc = transpose(act[l], y.ldK, y.XT, ldB, B, y.K, st)) != TJ_OK) return rc;
                 TjGemmArgs<T> gm;
                 memset(&gm, 0, sizeof(gm));
@@ -1946,7 +1955,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 }
                 gm.relu = 1;
                 gm.Ci = act[l + 1]; gm.ldci = lay[l + 1].ldK;
-                gm.Cj = lay[l + 1].XT; gm.ldcj = ldB; gm.cj_jmax = B;
+                if (!lin_wgrad_trans(l + 1, B)) { gm.Cj = lay[l + 1].XT; gm.ldcj = ldB; gm.cj_jmax = B; }
                 if ((rc = tj_gemm<T>(gm, st)) != TJ_OK) return rc;
             }
         }
@@ -1965,7 +1974,8 @@ template <typename T> struct ConvLearner : tj_learner {
             h.dX = nullptr; h.lddx = 0; h.dXT = nullptr; h.lddxt = 0; h.Kin = y.K;
             head_dx_done = head_fused<T>(A) && L >= 2 && lay[L - 2].kind == TJ_LAYER_LINEAR;
             if (head_dx_done) {   // the fused kernel also writes the head's input gradient
-                h.dX = lay[L - 2].dZ; h.lddx = y.ldK; h.dXT = lay[L - 2].dZT; h.lddxt = ldB;
+                h.dX = lay[L - 2].dZ; h.lddx = y.ldK;
+                if (!lin_wgrad_trans(L - 2, B)) { h.dXT = lay[L - 2].dZT; h.lddxt = ldB; }
             }
             if ((rc = run_head_td<T>(this, h, mb, d.gamma, d.huber_delta, st)) != TJ_OK) return rc;
         }
@@ -1979,7 +1989,7 @@ template <typename T> struct ConvLearner : tj_learner {
         auto add_reduce_job = [&](const float *part, size_t zstride, int n_part, float *dst, size_t n) {
             const int q = jobs.n_job++;
             jobs.part[q] = part; jobs.zstride[q] = zstride; jobs.n_part[q] = n_part; jobs.dst[q] = dst; jobs.n[q] = n;
-            jobs.block_begin[q + 1] = jobs.block_begin[q] + (unsigned)((n + 127) / 128);
+            jobs.block_begin[q + 1] = jobs.block_begin[q] + tjconv::reduce_blocks(n, n_part);
         };
         for (int l = L - 1; l >= 0; --l) {
             NLayer &y = lay[l];
@@ -2007,10 +2017,17 @@ template <typename T> struct ConvLearner : tj_learner {
                 TjGemmArgs<T> &gm = gw;
                 memset(&gm, 0, sizeof(gm));
                 gm.n_seg = 1;
-                gm.seg[0] = {0, y.O, conv ? y.patchesT : y.XT, nullptr, 0};
-                gm.Q = y.dZT;
-                gm.ldp = ldm;   // pitches follow the largest batch, so pad columns are never written
-                gm.ldq = ldm;
+                if (lin_wgrad_trans(l, B)) {   // row-major operands, contraction over their rows
+                    gm.seg[0] = {0, y.O, act[l], nullptr, 0};
+                    gm.Q = y.dZ;
+                    gm.ldp = y.ldK; gm.ldq = y.ldO;
+                    gm.trans = 1;
+                } else {
+                    gm.seg[0] = {0, y.O, conv ? y.patchesT : y.XT, nullptr, 0};
+                    gm.Q = y.dZT;
+                    gm.ldp = ldm;   // pitches follow the largest batch, so pad columns are never written
+                    gm.ldq = ldm;
+                }
                 gm.I = y.K; gm.K = Kc;
                 int ns = y.n_split;
                 const int ke = 128 / (int)sizeof(T);
@@ -2035,7 +2052,9 @@ template <typename T> struct ConvLearner : tj_learner {
                 gm.I = y.K; gm.K = y.ldO; gm.k_chunk = gm.K; gm.n_split = 1;
                 gm.mask = act[l]; gm.ldmask = y.ldK;
                 gm.Ci = below.dZ; gm.ldci = y.ldK;
-                if (below.kind == TJ_LAYER_LINEAR) { gm.Cj = below.dZT; gm.ldcj = ldB; gm.cj_jmax = B; }
+                if (below.kind == TJ_LAYER_LINEAR && !lin_wgrad_trans(l - 1, B)) {
+                    gm.Cj = below.dZT; gm.ldcj = ldB; gm.cj_jmax = B;
+                }
                 if constexpr (sizeof(T) == 2) {
                     if (gw_pending) {
                         if ((rc = tj_gemm_pair(gw, gm, st)) != TJ_OK) return rc;
