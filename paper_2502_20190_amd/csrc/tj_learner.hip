@@ -500,6 +500,30 @@ template <typename T> struct EmitTable {
     T *dst[TJ_MAX_LAYERS];
 };
 
+// Convolution weights whose input-gradient matrix the optimizer refreshes as it updates them:
+// Wd[(py, px, c)][(a, b, o)] = W[o][kh][kw][c] with kh = py + (A-1-a) s, kw = px + (A-1-b) s (the layout
+// tjconv::dgrad_weights builds; entries with kh or kw beyond the kernel are zero and never written here).
+struct DgradEmit {
+    int n;
+    size_t begin[TJ_MAX_LAYERS], end[TJ_MAX_LAYERS];   // flat parameter range of the layer's weights
+    tj_bf16 *wd[TJ_MAX_LAYERS];
+    int O[TJ_MAX_LAYERS], C[TJ_MAX_LAYERS], k[TJ_MAX_LAYERS], s[TJ_MAX_LAYERS], A[TJ_MAX_LAYERS];
+};
+
+__device__ __forceinline__ void emit_dgrad(const DgradEmit &dg, size_t e, float th)
+{
+    for (int q = 0; q < dg.n; ++q) {
+        if (e < dg.begin[q] || e >= dg.end[q]) continue;
+        const int O = dg.O[q], C = dg.C[q], k = dg.k[q], s = dg.s[q], A = dg.A[q];
+        const int idx = (int)(e - dg.begin[q]), kkc = k * k * C;
+        const int o = idx / kkc, r = idx - o * kkc;
+        const int kh = r / (k * C), kw = (r / C) % k, c = r % C;
+        const int py = kh % s, a = A - 1 - kh / s, px = kw % s, b = A - 1 - kw / s;
+        const size_t j = (size_t)(py * s + px) * C + c, col = (size_t)(a * A + b) * O + o;
+        dg.wd[q][j * ((size_t)A * A * O) + col] = tj_f32_to_bf16(th);
+    }
+}
+
 template <typename T> __device__ __forceinline__ void emit4(T *dst, const float (&x)[4]);
 template <> __device__ __forceinline__ void emit4<float>(float *dst, const float (&x)[4])
 {
@@ -532,7 +556,7 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
                                                    float *__restrict__ v, float *__restrict__ gpart,
                                                    int S, size_t gstride, size_t P, float lr, float b1,
                                                    float b2, float eps, float c1, float c2,
-                                                   const EmitTable<T> tab, const LossFinal lf)
+                                                   const EmitTable<T> tab, const LossFinal lf, const DgradEmit dg)
 {
     if (blockIdx.x == 0 && threadIdx.x < 64) {
         float s = 0.f;
@@ -585,6 +609,10 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
                         tab.dst[k][i + e - tab.begin[k]] = TjElem<T>::from_f32(ta[e]);
             }
         }
+        if (dg.n > 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) emit_dgrad(dg, i + e, ta[e]);
+        }
     } else {
         for (size_t e = i; e < P; ++e) {
             float g = gpart[e];
@@ -598,6 +626,7 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
             theta[e] = th;
             for (int k = 0; k < tab.n; ++k)
                 if (e >= tab.begin[k] && e < tab.end[k]) tab.dst[k][e - tab.begin[k]] = TjElem<T>::from_f32(th);
+            emit_dgrad(dg, e, th);
         }
     }
 }
@@ -1290,8 +1319,10 @@ template <typename T> struct MlpLearner : tj_learner {
             tab.dst[tab.n++] = Wc_on[l];
         }
         const LossFinal lf = {loss_part, n_loss_part, B, (uint32_t)t, d_stats, stats_internal};
+        DgradEmit no_dgrad;
+        no_dgrad.n = 0;
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S, Ppad, P, d.lr,
-                                                                      d.beta1, d.beta2, d.eps, c1, c2, tab, lf);
+                                                                      d.beta1, d.beta2, d.eps, c1, c2, tab, lf, no_dgrad);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
         if ((rc = recast(true, st, true)) != TJ_OK) return rc;   // transposed copies (and padded blocks)
@@ -1765,12 +1796,12 @@ template <typename T> struct ConvLearner : tj_learner {
             j.src = (online ? theta_on : theta_tg) + y.w_off;
             j.dst = online ? y.Wc_on : y.Wc_tg;
             if (after_adam && adam_emits(l)) j.dst = nullptr;
-            j.dstT = (online && l > 0) ? y.WcT_on : nullptr;   // the first layer has no input gradient
+            j.dstT = (online && keeps_wct(l)) ? y.WcT_on : nullptr;
             j.R = y.O; j.C = y.K; j.ldd = y.ldK; j.lddT = y.ldO;
             if (j.dst || j.dstT) jobs.job[n++] = j;
         }
         if constexpr (sizeof(T) == 2) {
-            if (online) {
+            if (online && !after_adam) {   // after an update the optimizer kernel has refreshed them
                 tjconv::DgradWeightJobs dj;
                 dj.n_job = 0;
                 dj.block_begin[0] = 0;
@@ -1800,6 +1831,25 @@ template <typename T> struct ConvLearner : tj_learner {
     {
         if (sizeof(T) != 2 || l < 1 || l >= L - 1 || lay[l].kind != TJ_LAYER_LINEAR) return false;
         return B % 32 == 0 && B >= 1024 && lay[l].K % 8 == 0 && lay[l].O % 8 == 0 && lay[l].K >= 256 && lay[l].O >= 128;
+    }
+
+    // A linear layer's input gradient with the row-major weight copy as its first operand (transposing LDS
+    // reads): bf16, a contraction over whole 32-row stages of the weight matrix, batches large enough for the
+    // 256 x 128 tiles that form takes.  Decided by the largest batch, so that the set of weight copies is fixed.
+    bool lin_dgrad_trans(int l) const
+    {
+        if (sizeof(T) != 2 || l < 1 || lay[l].kind != TJ_LAYER_LINEAR || Bmax < 1024) return false;
+        return lay[l].K % 8 == 0 && lay[l].O % 32 == 0;
+    }
+    // Layer l keeps a transposed weight copy: its input gradient exists and is a contraction over that copy (a
+    // convolution's is one only on the explicit patch path; the head's is not where the TD kernel writes it).
+    bool keeps_wct(int l) const
+    {
+        if (l == 0) return false;
+        const NLayer &y = lay[l];
+        if (y.kind == TJ_LAYER_CONV2D) return !y.dgrad_gather;
+        if (l == L - 1 && head_fused<T>(A) && L >= 2 && lay[L - 2].kind == TJ_LAYER_LINEAR) return false;
+        return !lin_dgrad_trans(l);
     }
 
     int transpose(const T *src, int lds, T *dst, int ldd, int R, int Cc, hipStream_t st)
@@ -2046,10 +2096,18 @@ template <typename T> struct ConvLearner : tj_learner {
                 TjGemmArgs<T> gm;
                 memset(&gm, 0, sizeof(gm));
                 gm.n_seg = 1;
-                gm.seg[0] = {0, B, y.WcT_on, nullptr, 0};
                 gm.Q = y.dZ;
-                gm.ldp = y.ldO; gm.ldq = y.ldO;
-                gm.I = y.K; gm.K = y.ldO; gm.k_chunk = gm.K; gm.n_split = 1;
+                gm.ldq = y.ldO;
+                gm.I = y.K;
+                if (lin_dgrad_trans(l)) {   // the weights as stored, [o][k]: the contraction runs over their rows
+                    gm.seg[0] = {0, B, y.Wc_on, nullptr, 0};
+                    gm.ldp = y.ldK; gm.K = y.O;
+                    gm.trans = 2;
+                } else {
+                    gm.seg[0] = {0, B, y.WcT_on, nullptr, 0};
+                    gm.ldp = y.ldO; gm.K = y.ldO;
+                }
+                gm.k_chunk = gm.K; gm.n_split = 1;
                 gm.mask = act[l]; gm.ldmask = y.ldK;
                 gm.Ci = below.dZ; gm.ldci = y.ldK;
                 if (below.kind == TJ_LAYER_LINEAR && !lin_wgrad_trans(l - 1, B)) {
@@ -2132,8 +2190,20 @@ template <typename T> struct ConvLearner : tj_learner {
             tab.dst[tab.n++] = lay[l].Wc_on;
         }
         const LossFinal lf = {loss_part, td_blocks<T>(B, A), B, (uint32_t)t, d_stats, stats_internal};
+        DgradEmit dg;   // the convolutions' input-gradient weights follow their master weights in the same kernel
+        dg.n = 0;
+        if constexpr (sizeof(T) == 2) {
+            for (int l = 0; l < L; ++l) {
+                const NLayer &y = lay[l];
+                if (!y.dgrad_gather) continue;
+                const int q = dg.n++;
+                dg.begin[q] = y.w_off; dg.end[q] = y.w_off + (size_t)y.O * y.K;
+                dg.wd[q] = y.Wd;
+                dg.O[q] = y.O; dg.C[q] = y.g.C; dg.k[q] = y.g.k; dg.s[q] = y.g.s; dg.A[q] = y.A;
+            }
+        }
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
-                                                                      d.beta2, d.eps, c1, c2, tab, lf);
+                                                                      d.beta2, d.eps, c1, c2, tab, lf, dg);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
         if ((rc = recast(true, st, true)) != TJ_OK) return rc;
@@ -2249,7 +2319,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 const NLayer &y = lay[l];
                 float *dst = tmp.data() + y.w_off;   // the kernels' order [O][k]
                 int rc;
-                if (tr && l > 0) {                   // the first layer keeps no transposed copy
+                if (tr && keeps_wct(l)) {
                     if ((rc = fetch_as_float<T>(y.WcT_on, (size_t)y.K * y.ldO, w, st)) != TJ_OK) return rc;
                     for (int o = 0; o < y.O; ++o)
                         for (int k = 0; k < y.K; ++k) dst[(size_t)o * y.K + k] = w[(size_t)k * y.ldO + o];

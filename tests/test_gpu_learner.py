@@ -417,6 +417,23 @@ def test_gathered_conv_operands_with_ragged_batches(tj, orc):
         _step_both(tj, orc, g, o, wl, _batch(wl, 360 + step, b), TOL["bf16"], sync=step > 0)
 
 
+def test_two_free_running_bf16_conv_steps(tj, orc):
+    """Two consecutive bf16 steps of a conv net on the patch-matrix-free path without reloading any
+    state: the second step's passes read what the first step's optimizer kernel emitted, among it the
+    rearranged weights of the convolutions' input-gradient contraction (no state call rebuilds
+    them in between).  A large learning rate makes a stale copy visible in the first layer's gradient."""
+    from paper_2502_20190_amd.synth import CONV
+
+    wl = _conv_workload("bf16", batch=21, in_chw=(4, 36, 36),
+                        layers=((CONV, 32, 8, 4), (CONV, 64, 4, 2), (LIN, 24, 0, 0), (LIN, 6, 0, 0)), n_actions=6)
+    wl = replace(wl, lr=1e-2, target_interval=100)
+    g, o = _pair(tj, orc, wl, seed=15)
+    for step in range(2):
+        worst, _ = _step_both(tj, orc, g, o, wl, _batch(wl, 380 + step), TOL["bf16"], check_state=(step == 0))
+        _check_compute_copies(tj, g, wl)
+    print("second free-running bf16 conv step:", worst)
+
+
 @pytest.mark.parametrize("hw,batch", [(36, 300), (100, 140)])
 def test_first_conv_kernel_loops_over_images(tj, orc, hw, batch):
     """More images (2 x batch) than the fused first-convolution kernel has blocks (one per CU), so
