@@ -25,8 +25,8 @@ sys.path.insert(0, ROOT)
 # same counters read for a streaming kernel of known size in the same runs (adam_update: FETCH_SIZE
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the kernel sources it was taken with.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 697.5e6, "gemm_source_sha256_16": "bfc56bdca1c31233"},
-                "c5": {"bytes_per_step": 1555.2e6, "gemm_source_sha256_16": "bfc56bdca1c31233"}}
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 697.6e6, "gemm_source_sha256_16": "bfc56bdca1c31233"},
+                "c5": {"bytes_per_step": 1556.8e6, "gemm_source_sha256_16": "bfc56bdca1c31233"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
