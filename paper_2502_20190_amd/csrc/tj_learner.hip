@@ -498,7 +498,19 @@ template <typename T> struct EmitTable {
     int n;
     size_t begin[TJ_MAX_LAYERS], end[TJ_MAX_LAYERS];
     T *dst[TJ_MAX_LAYERS];
+    // optional transposed copy of a small layer ([C][ldT], element (o, k) of the [O][C] block at k * ldT + o)
+    T *dstT[TJ_MAX_LAYERS];
+    int C[TJ_MAX_LAYERS], ldT[TJ_MAX_LAYERS];
 };
+
+template <typename T>
+__device__ __forceinline__ void emit_transposed(const EmitTable<T> &tab, int k, size_t e, float th)
+{
+    if (!tab.dstT[k] || e < tab.begin[k] || e >= tab.end[k]) return;
+    const size_t idx = e - tab.begin[k];
+    const int o = (int)(idx / (size_t)tab.C[k]), kk = (int)(idx % (size_t)tab.C[k]);
+    tab.dstT[k][(size_t)kk * tab.ldT[k] + o] = TjElem<T>::from_f32(th);
+}
 
 // Convolution weights whose input-gradient matrix the optimizer refreshes as it updates them:
 // Wd[(py, px, c)][(a, b, o)] = W[o][kh][kw][c] with kh = py + (A-1-a) s, kw = px + (A-1-b) s (the layout
@@ -545,6 +557,11 @@ struct LossFinal {
     int n_part, B;
     uint32_t t_next;
     tj_step_stats *out, *internal;   // out: caller's (may be null)
+    // on-policy update: per-block sums of the three terms (four floats per block) instead, finalised the same way
+    const float *ppo_part = nullptr;
+    int ppo_n_part = 0;
+    float c_v = 0.f, c_e = 0.f;
+    tj_ppo_stats *ppo_out = nullptr, *ppo_internal = nullptr;
 };
 
 // Adam on the flat fp32 master state (bias-corrected, eps outside the square root); the gradient
@@ -558,7 +575,26 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
                                                    float b2, float eps, float c1, float c2,
                                                    const EmitTable<T> tab, const LossFinal lf, const DgradEmit dg)
 {
-    if (blockIdx.x == 0 && threadIdx.x < 64) {
+    if (blockIdx.x == 0 && threadIdx.x < 64 && lf.ppo_part) {
+        // means of the three terms and the objective, from the per-block sums (fixed order)
+        float s[3] = {0.f, 0.f, 0.f};
+        for (int b = threadIdx.x; b < lf.ppo_n_part; b += 64)
+            for (int q = 0; q < 3; ++q) s[q] += lf.ppo_part[(size_t)b * 4 + q];
+#pragma unroll
+        for (int q = 0; q < 3; ++q)
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) s[q] += __shfl_down(s[q], off, 64);
+        if (threadIdx.x == 0) {
+            tj_ppo_stats o;
+            o.loss_pi = s[0] / (float)lf.B;
+            o.loss_v = s[1] / (float)lf.B;
+            o.entropy = s[2] / (float)lf.B;
+            o.loss = o.loss_pi + lf.c_v * o.loss_v - lf.c_e * o.entropy;
+            o.step = lf.t_next;
+            *lf.ppo_internal = o;
+            if (lf.ppo_out) *lf.ppo_out = o;
+        }
+    } else if (blockIdx.x == 0 && threadIdx.x < 64) {
         float s = 0.f;
         for (int b = threadIdx.x; b < lf.n_part; b += 64) s += lf.part[b];
 #pragma unroll
@@ -608,6 +644,8 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
                     if (i + e >= tab.begin[k] && i + e < tab.end[k])
                         tab.dst[k][i + e - tab.begin[k]] = TjElem<T>::from_f32(ta[e]);
             }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) emit_transposed<T>(tab, k, i + e, ta[e]);
         }
         if (dg.n > 0) {
 #pragma unroll
@@ -624,8 +662,10 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
             v[e] = vv;
             const float th = theta[e] - lr * (mm / c1) / (sqrtf(vv / c2) + eps);
             theta[e] = th;
-            for (int k = 0; k < tab.n; ++k)
+            for (int k = 0; k < tab.n; ++k) {
                 if (e >= tab.begin[k] && e < tab.end[k]) tab.dst[k][e - tab.begin[k]] = TjElem<T>::from_f32(th);
+                emit_transposed<T>(tab, k, e, th);
+            }
             emit_dgrad(dg, e, th);
         }
     }
@@ -800,30 +840,6 @@ __global__ __launch_bounds__(kPpoRows * kPpoLanes) void ppo_head(const PpoHeadAr
     for (int e = threadIdx.x; e < (a.A + 1) * kPpoRows; e += kPpoRows * kPpoLanes) {
         const int k = e / kPpoRows, rr = e % kPpoRows;
         if (rr < n_rows) a.dZT[(size_t)k * a.lddzt + row0 + rr] = tile[rr * pitch + k];
-    }
-}
-
-// Means of the three terms and the objective, from the per-block sums (fixed order).
-__global__ __launch_bounds__(64) void ppo_stats_final(const float *__restrict__ part, int n_part, int B, float c_v,
-                                                      float c_e, uint32_t t_next, tj_ppo_stats *out,
-                                                      tj_ppo_stats *internal)
-{
-    float s[3] = {0.f, 0.f, 0.f};
-    for (int b = threadIdx.x; b < n_part; b += 64)
-        for (int q = 0; q < 3; ++q) s[q] += part[(size_t)b * 4 + q];
-#pragma unroll
-    for (int q = 0; q < 3; ++q)
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) s[q] += __shfl_down(s[q], off, 64);
-    if (threadIdx.x == 0) {
-        tj_ppo_stats o;
-        o.loss_pi = s[0] / (float)B;
-        o.loss_v = s[1] / (float)B;
-        o.entropy = s[2] / (float)B;
-        o.loss = o.loss_pi + c_v * o.loss_v - c_e * o.entropy;
-        o.step = t_next;
-        *internal = o;
-        if (out) *out = o;
     }
 }
 
@@ -1110,9 +1126,23 @@ template <typename T> struct MlpLearner : tj_learner {
 
     virtual void plan_more(TjArena &) {}   // further pieces of a derived learner
 
+    // statistics of an on-policy update that the optimizer kernel finalises (part == nullptr: none)
+    struct PpoFinal {
+        const float *part = nullptr;
+        int n_part = 0;
+        float c_v = 0.f, c_e = 0.f;
+        tj_ppo_stats *out = nullptr, *internal = nullptr;
+    } ppo_fin;
+
     // fp32 master -> compute-type copies (and transposes for the online net)
     // Adam writes the straight copy of every weight block whose rows need no padding
     bool adam_emits(int l) const { return lay[l].ld_in == lay[l].in; }
+    // ... and the transposed copy of a small block with it (scattered element stores: only worth it where the
+    // copy kernel's launch costs more than they do)
+    bool adam_emits_t(int l) const
+    {
+        return adam_emits(l) && keeps_wct(l) && (size_t)lay[l].in * lay[l].out <= ((size_t)1 << 18);
+    }
 
     // Weight gradient of layer l (1-based) straight from the row-major X_{l-1} and dZ_l (transposing LDS
     // reads) instead of their transposed copies: bf16, whole 32-row stages of the batch, widths that are
@@ -1150,7 +1180,7 @@ template <typename T> struct MlpLearner : tj_learner {
             j.src = (online ? theta_on : theta_tg) + lay[l].w_off;
             j.dst = online ? Wc_on[l] : Wc_tg[l];
             if (after_adam && adam_emits(l)) j.dst = nullptr;
-            j.dstT = online && keeps_wct(l) ? WcT_on[l] : nullptr;
+            j.dstT = online && keeps_wct(l) && !(after_adam && adam_emits_t(l)) ? WcT_on[l] : nullptr;
             j.R = lay[l].out; j.C = lay[l].in;
             j.ldd = lay[l].ld_in; j.lddT = lay[l].ld_out;
             if (j.dst || j.dstT) jobs.job[n++] = j;
@@ -1316,9 +1346,16 @@ template <typename T> struct MlpLearner : tj_learner {
             if (!adam_emits(l)) continue;
             tab.begin[tab.n] = lay[l].w_off;
             tab.end[tab.n] = lay[l].w_off + (size_t)lay[l].in * lay[l].out;
+            tab.dstT[tab.n] = adam_emits_t(l) ? WcT_on[l] : nullptr;
+            tab.C[tab.n] = lay[l].in; tab.ldT[tab.n] = lay[l].ld_out;
             tab.dst[tab.n++] = Wc_on[l];
         }
-        const LossFinal lf = {loss_part, n_loss_part, B, (uint32_t)t, d_stats, stats_internal};
+        LossFinal lf = {loss_part, n_loss_part, B, (uint32_t)t, d_stats, stats_internal};
+        if (ppo_fin.part) {   // set by the on-policy learner for this call
+            lf.ppo_part = ppo_fin.part; lf.ppo_n_part = ppo_fin.n_part;
+            lf.c_v = ppo_fin.c_v; lf.c_e = ppo_fin.c_e;
+            lf.ppo_out = ppo_fin.out; lf.ppo_internal = ppo_fin.internal;
+        }
         DgradEmit no_dgrad;
         no_dgrad.n = 0;
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S, Ppad, P, d.lr,
@@ -1528,11 +1565,14 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
         const int nblk = (B + kPpoRows - 1) / kPpoRows;
         ppo_head<T><<<nblk, kPpoRows * kPpoLanes, 0, st>>>(a);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
-        ppo_stats_final<<<1, 64, 0, st>>>(ppo_part, nblk, B, pd.c_v, pd.c_e, (uint32_t)(this->t + 1), d_stats,
-                                          ppo_stats);
-        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = this->mark(2, st)) != TJ_OK) return rc;
-        return this->backward_update(B, 0, nullptr, st);
+        // the optimizer kernel's first wave turns the per-block sums into the step's statistics
+        this->ppo_fin.part = ppo_part; this->ppo_fin.n_part = nblk;
+        this->ppo_fin.c_v = pd.c_v; this->ppo_fin.c_e = pd.c_e;
+        this->ppo_fin.out = d_stats; this->ppo_fin.internal = ppo_stats;
+        rc = this->backward_update(B, 0, nullptr, st);
+        this->ppo_fin.part = nullptr;
+        return rc;
     }
 
     int ppo_evaluate(uint32_t n_, const float *d_obs, float *d_logits, float *d_value, hipStream_t st) override
@@ -2187,6 +2227,7 @@ template <typename T> struct ConvLearner : tj_learner {
             if (!adam_emits(l)) continue;
             tab.begin[tab.n] = lay[l].w_off;
             tab.end[tab.n] = lay[l].w_off + (size_t)lay[l].O * lay[l].K;
+            tab.dstT[tab.n] = nullptr; tab.C[tab.n] = 0; tab.ldT[tab.n] = 0;
             tab.dst[tab.n++] = lay[l].Wc_on;
         }
         const LossFinal lf = {loss_part, td_blocks<T>(B, A), B, (uint32_t)t, d_stats, stats_internal};
