@@ -449,10 +449,11 @@ int tj_balance_plan(const tj_balance_in *in, tj_balance_out *out);
  *   head-layer + TD kernel where that is used, else after the head GEMM),
  *   [2] after the TD / Huber kernel, [3] after the weight- and input-
  *   gradient GEMMs, [4] after the Adam kernel, which for MLPs also sums the
- *   slices of the split weight gradients (the transposed weight copies for the
- *   next step follow it) (n must be 5); every tj_ppo_step records [0] after the input
- *   cast, [1] after the forward GEMMs including the head, [2] after the
- *   objective kernels, [3] and [4] as above,
+ *   slices of the split weight gradients (where a layer still keeps a weight
+ *   copy that kernel does not write, a copy kernel follows it) (n must be 5);
+ *   every tj_ppo_step records [0] after the input cast, [1] after the forward
+ *   GEMMs including the head, [2] after the objective kernel, [3] and [4] as
+ *   above (the Adam kernel also finalises the step's statistics),
  * on the call's stream.  The caller reads them after synchronising. */
 int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n);
 int tj_frame_buffer_set_phase_events(tj_frame_buffer *buf, void *const *hip_events, uint32_t n);
