@@ -434,6 +434,20 @@ def test_two_free_running_bf16_conv_steps(tj, orc):
     print("second free-running bf16 conv step:", worst)
 
 
+def test_conv_net_linear_layers_on_row_major_operands(tj, orc):
+    """A conv net whose hidden linear layer (576 -> 128) takes the transposing-read contractions:
+    its weight gradient at the full batch of 1024 (whole 32-row stages), its input gradient at any
+    batch of a learner created for 1024 rows; a ragged batch of 40 afterwards keeps the input
+    gradient on that path and returns the weight gradient to the transposed operands."""
+    from paper_2502_20190_amd.synth import CONV
+
+    wl = _conv_workload("bf16", batch=1024, in_chw=(4, 36, 36),
+                        layers=((CONV, 32, 8, 4), (CONV, 64, 4, 2), (LIN, 128, 0, 0), (LIN, 6, 0, 0)), n_actions=6)
+    g, o = _pair(tj, orc, wl, seed=16)
+    for step, b in enumerate((1024, 40, 1024)):
+        _step_both(tj, orc, g, o, wl, _batch(wl, 390 + step, b), TOL["bf16"], sync=step > 0)
+
+
 @pytest.mark.parametrize("hw,batch", [(36, 300), (100, 140)])
 def test_first_conv_kernel_loops_over_images(tj, orc, hw, batch):
     """More images (2 x batch) than the fused first-convolution kernel has blocks (one per CU), so
