@@ -23,10 +23,11 @@ sys.path.insert(0, ROOT)
 # HBM traffic of the contraction launches of one step (c3, c5), from two rocprofv3 --pmc runs of
 # this script each (FETCH_SIZE, WRITE_SIZE; see profiles/c3_gemm_counters.md), scaled by what the
 # same counters read for a streaming kernel of known size in the same runs (adam_update: FETCH_SIZE
-# reads half the bytes, WRITE_SIZE all of them).  Valid for the kernel sources it was taken with.
-GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 697.6e6, "gemm_source_sha256_16": "bfc56bdca1c31233"},
-                "c5": {"bytes_per_step": 1556.8e6, "gemm_source_sha256_16": "bfc56bdca1c31233"}}
+# reads half the bytes, WRITE_SIZE all of them).  Valid for the sources it was taken with: the contraction
+# kernels and the learner that decides which of them a step launches.
+GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip", "tj_conv.h", "tj_learner.hip")
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 697.6e6, "gemm_source_sha256_16": "9fc973e48852bbca"},
+                "c5": {"bytes_per_step": 1556.5e6, "gemm_source_sha256_16": "9fc973e48852bbca"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
