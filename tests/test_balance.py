@@ -57,7 +57,7 @@ def test_library_routine_equals_the_oracle(orc):
 
 
 @pytest.mark.gpu
-def test_library_routine_equals_the_oracle_on_the_gpu_box(orc):
+def test_library_routine_equals_the_oracle_in_the_gpu_run(orc):
     """The same comparison in the GPU run (host arithmetic of the library, as loaded there)."""
     _library_routine_equals_the_oracle(orc)
 
