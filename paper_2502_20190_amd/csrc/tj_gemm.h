@@ -172,3 +172,20 @@ struct TjConvFirstArgs {
 };
 bool tj_conv_first_fits(int C, int H, int W, int k, int s, int O);
 int tj_conv_first(const TjConvFirstArgs &a, hipStream_t st);
+
+// Weight and bias gradient of that first convolution, also straight from the u8 stacks of the s
+// images (no channels-last copy of them is needed then) and the channels-last output gradient
+// dZ [B*OH*OW][32].  Block z of n_part (1 <= n_part <= B) sums the images z, z + n_part, ...:
+//   part[z*zstride + o*K + k] = sum dZ[m][o] * patch[m][k],   part[z*zstride + 32*K + o] = sum dZ[m][o],
+// patch values bf16(x * scale) as in the forward pass, k ordered (kh, kw, c).  Needs the forward
+// kernel's geometry and OH, OW multiples of 4.
+struct TjConvFirstWgradArgs {
+    const uint8_t *obs;
+    const tj_bf16 *dZ;
+    int B, H, W, k, s, OH, OW;
+    float scale;
+    float *part; size_t zstride;
+    int n_part;
+};
+bool tj_conv_first_wgrad_fits(int C, int H, int W, int k, int s, int O);
+int tj_conv_first_wgrad(const TjConvFirstWgradArgs &a, hipStream_t st);

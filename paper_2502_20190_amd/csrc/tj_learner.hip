@@ -16,6 +16,7 @@
 #include "tj_conv.h"
 #include <math.h>
 #include <string.h>
+#include <algorithm>
 #include <vector>
 
 namespace {
@@ -1653,6 +1654,8 @@ template <typename T> struct ConvLearner : tj_learner {
     int last_batch = -1;
     bool shape_ok = true;
     bool first_fused = false;   // layer 0 runs straight from the u8 frames (tj_conv_first)
+    bool first_wgrad_u8 = false;   // ... and so does its weight gradient: no channels-last copy of the s images
+    int n_cu = 0;                  // compute units of the device (asked once)
 
     size_t plan(void *base)
     {
@@ -1734,6 +1737,8 @@ template <typename T> struct ConvLearner : tj_learner {
         first_fused = sizeof(T) == 2 && d.obs_dtype == TJ_OBS_U8 && lay[0].kind == TJ_LAYER_CONV2D &&
                       lay[0].implicit && lay[0].ldK == lay[0].K &&
                       tj_conv_first_fits(lay[0].g.C, lay[0].g.H, lay[0].g.W, lay[0].g.k, lay[0].g.s, lay[0].O);
+        first_wgrad_u8 = first_fused && tj_conv_first_wgrad_fits(lay[0].g.C, lay[0].g.H, lay[0].g.W, lay[0].g.k,
+                                                                 lay[0].g.s, lay[0].O);
         P = off;
         Ppad = tj_align_up(P, 64);
         A = lay[L - 1].O;
@@ -1928,7 +1933,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 fa.B = B; fa.H = g.H; fa.W = g.W; fa.k = g.k; fa.s = g.s; fa.OH = g.OH; fa.OW = g.OW;
                 fa.W_on = lay[0].Wc_on; fa.W_tg = lay[0].Wc_tg;
                 fa.b_on = theta_on + lay[0].b_off; fa.b_tg = theta_tg + lay[0].b_off;
-                fa.act0 = act[0]; fa.out = act[1];
+                fa.act0 = first_wgrad_u8 ? nullptr : act[0]; fa.out = act[1];
                 fa.scale = 1.0f / 255.0f;
                 if ((rc = mark(0, st)) != TJ_OK) return rc;
                 if ((rc = tj_conv_first(fa, st)) != TJ_OK) return rc;
@@ -2089,7 +2094,26 @@ template <typename T> struct ConvLearner : tj_learner {
             const int ldm = conv ? round_up((int)((size_t)Bmax * y.OHW), VE) : ldB;
             bool wgrad_done = false;
             if constexpr (sizeof(T) == 2) {
-                if (conv && y.implicit) {   // straight from dZ and the layer input
+                if (l == 0 && first_done && first_wgrad_u8) {   // from the u8 stacks, one slice per block
+                    if (n_cu == 0) {
+                        int dev = 0, v = 0;
+                        n_cu = 256;
+                        if (hipGetDevice(&dev) == hipSuccess &&
+                            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+                            n_cu = v;
+                    }
+                    const tjconv::ConvGeom &g = y.g;
+                    TjConvFirstWgradArgs wa;
+                    wa.obs = (const uint8_t *)mb->obs; wa.dZ = y.dZ;
+                    wa.B = B; wa.H = g.H; wa.W = g.W; wa.k = g.k; wa.s = g.s; wa.OH = g.OH; wa.OW = g.OW;
+                    wa.scale = 1.0f / 255.0f;
+                    wa.part = y.part; wa.zstride = y.part_stride;
+                    wa.n_part = std::min(B, std::min(n_cu, y.n_split));
+                    if ((rc = tj_conv_first_wgrad(wa, st)) != TJ_OK) return rc;
+                    add_reduce_job(y.part, y.part_stride, wa.n_part, grad + y.w_off, (size_t)y.O * y.K + y.O);
+                    wgrad_done = true;
+                }
+                if (!wgrad_done && conv && y.implicit) {   // straight from dZ and the layer input
                     TjConvWgradArgs wa;
                     wa.dZ = y.dZ; wa.O = y.O; wa.act = act[l]; wa.g = y.gth;
                     wa.M = (int)Ms; wa.K = y.K;
