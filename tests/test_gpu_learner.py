@@ -453,7 +453,9 @@ def test_first_conv_kernel_loops_over_images(tj, orc, hw, batch):
     """More images (2 x batch) than the fused first-convolution kernel has blocks (one per CU), so
     every block walks several images: register prefetch of the next frame stack, hand-over between
     the image buffers.  36 x 36 frames fit two image buffers in LDS, 100 x 100 frames only one (the
-    variant with two barriers per image)."""
+    variant with two barriers per image).  The first layer's weight gradient takes both of its forms:
+    from the u8 stacks for 36 x 36 (8 x 8 outputs; blocks with two images and with one), from the
+    channels-last copy for 100 x 100 (image and gradient rows do not fit the LDS together)."""
     from paper_2502_20190_amd.synth import CONV
 
     wl = _conv_workload("bf16", batch=batch, in_chw=(4, hw, hw),
