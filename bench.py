@@ -2,9 +2,15 @@
 """Learner-throughput benchmark on one MI355X.
 
 A step = one pass of the whole hot path on one synthetic minibatch:
-tj_sample (staleness mask, prefix sum, uniform select, row gather from the
+tj_sample (staleness mask, prefix sum, uniform select, gather from the
 device-resident ring) followed by tj_learner_step (three forward passes,
 double-DQN TD target, Huber loss, backward, Adam, periodic target update).
+By default the gather of the observation rows is folded into the update: the
+sampler gathers the scalar fields and hands over indices, and the learner's
+first kernels read the sampled rows where they lie in the ring (the indirect
+minibatch of the C ABI); --copy-minibatch makes the sampler write dense copies
+that the learner then reads.  The stand-alone gather kernel is timed after the
+loop in either case, for its own roofline figure.
 The ring is filled on the device before the timed region starts.
 
 Prints ONE JSON line: transitions consumed per second, the roofline figure of
@@ -285,6 +291,9 @@ def main():
     ap.add_argument("--actor-rows", type=int, default=0,
                     help="after the learner loop, also time epsilon-greedy policy inference (tj_actor_act) "
                          "on this many observations per call (at most twice the batch)")
+    ap.add_argument("--copy-minibatch", action="store_true",
+                    help="tj_sample writes dense copies of the sampled observation rows and the learner reads "
+                         "those, instead of the learner reading the rows out of the ring through the indices")
     ap.add_argument("--overlap", action="store_true",
                     help="run the sample of step i+1 on a second stream while step i learns (double-buffered "
                          "minibatches) instead of one stream, strictly one after the other; measured: no "
@@ -349,7 +358,9 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
     # Buffer loop and learner loop run asynchronously (Section 3.1): the sampler fills minibatch
     # i % 2 on its own stream while the learner consumes the other one.  Two events per minibatch
     # order the hand-over in both directions; every step still samples and learns once.
-    mbs = [tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype) for _ in range(2 if overlap else 1)]
+    indirect = not (args.copy_minibatch or args.frame_ring)
+    mbs = [tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype, ring=buf if indirect else None)
+           for _ in range(2 if overlap else 1)]
     s_sample = torch.cuda.Stream() if overlap else None
     s_learn = torch.cuda.Stream() if overlap else None
     filled = [torch.cuda.Event() for _ in mbs]
@@ -375,6 +386,8 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
         else:
             rc = buf.sample(mbs[k], wl.current_version, wl.max_staleness, i)
             rc = rc or lrn.step(mbs[k])
+        if indirect and fresh is not None:      # the next insert may overwrite rows this update reads
+            buf.reads_done(stream=s_learn)
         n_issued[0] += 1
         if rc != tj.TJ_OK:
             raise tj.TjError(rc, "bench step")
@@ -408,8 +421,23 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
     assert st == tj.TJ_OK and t == warmup + K and np.isfinite(loss)
 
     ms = lambda evs, a, b: sum(e.elapsed_ms(a, b) for e in evs) / len(evs)
+    gather_ms = ms(bev, 1, 2)
+    if indirect:
+        # no gather kernel ran in the loop: time the stand-alone one (dense destination) on its own
+        dense = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype)
+        gev = [tj.HipEvents(3) for _ in range(12)]
+        for j in range(len(gev) + 3):
+            if j >= 3:
+                set_buf_events(buf.h, gev[j - 3].ev, 3)
+            rc = buf.sample(dense, wl.current_version, wl.max_staleness, 10_000 + j)
+            assert rc == tj.TJ_OK
+        torch.cuda.synchronize()
+        set_buf_events(buf.h, None, 0)
+        gather_ms = ms(gev, 1, 2)
+        del dense
     ph = {
-        "mask_scan_select_ms": ms(bev, 0, 1), "gather_ms": ms(bev, 1, 2),
+        "mask_scan_select_ms": ms(bev, 0, 1),
+        ("gather_ms_standalone" if indirect else "gather_ms"): gather_ms,
         "forward_gemm_ms": ms(lev, 0, 1),
         ("head_td_ms" if wl.precision == "bf16" and wl.layers[-1][1] <= 32 else "td_huber_ms"): ms(lev, 1, 2), "backward_gemm_ms": ms(lev, 2, 3),
         "adam_ms": ms(lev, 3, 4),
@@ -491,7 +519,9 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
         "vs_baseline": None, "dtype": wl.precision, "data": "synthetic",
         "config": {"workload": wl.name + ("+frame-ring" if args.frame_ring else ""), "ring_slots": wl.capacity, "obs_elems": wl.obs_elems,
                    "batch": wl.batch, "max_staleness": wl.max_staleness, "n_eligible": int(info.last_n_eligible),
-                   "layers": [l[1] for l in wl.layers], "params": P},
+                   "layers": [l[1] for l in wl.layers], "params": P,
+                   "minibatch": ("indirect: the learner reads the sampled ring rows through the indices" if indirect
+                                 else "dense copy written by the sampler")},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": gemm_traffic(wl.name.split("-")[0], n_gemm_launch),
                      "traffic_source": "rocprofv3 counters in profiles/ (null when the kernel sources have changed since)",
@@ -499,8 +529,10 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
                      "flops_per_launch": flops / n_gemm_launch, "avg_launch_ms": gemm_ms / n_gemm_launch},
         "phases_ms": ph, "phase_events_on_steps": len(sampled),
         "sample_learn_overlap": overlap,
-        "gather": {"bound": "hbm", "achieved": gather_bytes / (ph["gather_ms"] * 1e-3) / 1e9,
-                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": gather_bytes},
+        "gather": {"bound": "hbm", "achieved": gather_bytes / (gather_ms * 1e-3) / 1e9,
+                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": gather_bytes,
+                   "timed": ("stand-alone after the loop (dense destination); inside the loop the rows are read "
+                             "by the learner's first kernels" if indirect else "inside the loop")},
         "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9,
                  "peak": PEAK_HBM_GBS, "unit": "GB/s", "bytes": adam_bytes, "kernel_traffic_bytes": adam_kernel_traffic},
         "loss": loss,

@@ -62,9 +62,19 @@ typedef struct {
     uint32_t obs_dtype; /* TJ_OBS_F32 or TJ_OBS_U8                              */
 } tj_buffer_desc;
 
-/* A dense minibatch in caller-owned device memory (structure of arrays):
+/* A minibatch in caller-owned device memory (structure of arrays):
  * obs, next_obs [batch][obs_elems] in the ring's dtype; action i32, reward f32,
- * done u8, idx u32 [batch] (idx = the sampled ring slots). */
+ * done u8, idx u32 [batch] (idx = the sampled ring slots).
+ *
+ * Indirect form (row_index != NULL, read by tj_learner_step only): obs and
+ * next_obs are tables of n_rows rows of obs_elems elements, and row j of the
+ * minibatch is row min(row_index[j], n_rows - 1) of each; action, reward and
+ * done stay dense.  With obs / next_obs the ring's own arrays
+ * (tj_buffer_field_ptr 0 and 1), n_rows the ring's capacity and row_index the
+ * idx a tj_sample call produced, the learner's first kernels read the sampled
+ * transitions where they lie and no copy of their observations is made: the
+ * "load" of the learner loop (Section 3.1) happens inside the update.
+ * row_index == NULL: the dense form, n_rows is ignored. */
 typedef struct {
     void *obs;
     void *next_obs;
@@ -73,6 +83,8 @@ typedef struct {
     uint8_t *done;
     uint32_t *idx;
     uint32_t batch;
+    const uint32_t *row_index;
+    uint64_t n_rows;
 } tj_minibatch;
 
 typedef struct {
@@ -132,7 +144,10 @@ int tj_buffer_insert_concurrent(tj_buffer *buf, uint32_t n, const void *d_obs, c
  * list of eligible slots and K = |E|, draw j (0 <= j < batch) takes
  * E[floor(SplitMix64(seed, j) * K / 2^64)] (uniform, with replacement), and
  * minibatch row j is a copy of that ring row.  out->batch must equal `batch`
- * and every pointer in *out is a device pointer of that many rows.  The mask is
+ * and every pointer in *out is a device pointer of that many rows; out->obs
+ * and out->next_obs may both be NULL, then only idx, action, reward and done
+ * are produced (for the indirect minibatch form above).  out->row_index and
+ * out->n_rows are not read.  The mask is
  * recomputed from the version tags on every call.  Slots under an unfinished
  * tj_buffer_insert_concurrent are not eligible.  K == 0: idx is filled with
  * 0xFFFFFFFF, the other minibatch fields are left untouched and the sticky
@@ -160,6 +175,17 @@ int tj_sample(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t m
 #define TJ_SAMPLE_NOALLOC_MAX_CAPACITY 4194304ull
 int tj_sample_noalloc(tj_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
                       uint64_t seed, const tj_minibatch *out, void *hip_stream);
+
+/* For callers that hand the ring's own arrays to tj_learner_step (indirect
+ * minibatch) while tj_buffer_insert_concurrent is in use: declares that
+ * everything enqueued on `hip_stream` so far has finished reading the ring once
+ * the stream gets here.  Later concurrent inserts wait for that point, as they
+ * wait for the end of a tj_sample, before they overwrite slots.  Call it after
+ * the tj_learner_step that consumed the indices, on the same stream, and issue
+ * no tj_buffer_insert_concurrent between that tj_sample and this call: such an
+ * insert would wait for the sample only and could overwrite rows the update is
+ * still reading. */
+int tj_buffer_reads_done(tj_buffer *buf, void *hip_stream);
 
 /* Synchronises `hip_stream`, then reports ring state, the last K and the sticky
  * status (which it clears).  Returns the sticky status. */
@@ -282,7 +308,11 @@ int tj_learner_destroy(tj_learner *lrn);
  * gradients of L flow through Q_on(s) only; then Adam (bias-corrected, eps added
  * outside the square root) with t = 1, 2, ...; then, if t is a multiple of
  * target_interval, the target parameters become a copy of the online ones.
- * `mb` holds device pointers (idx is not read); mb->batch <= max_batch.
+ * `mb` holds device pointers (idx is not read); mb->batch <= max_batch.  Both
+ * forms of the minibatch are accepted; with the indirect form the tables must
+ * stay unchanged until the step's kernels have run (a network whose first
+ * layer is a convolution reads them again in its backward pass), and
+ * n_rows == 0 is TJ_ERR_INVALID_ARG.
  * Actions are expected in [0, A); the kernels cannot report a bad one, so an
  * action outside that range is read as the nearest valid one (0 or A - 1).
  * d_stats (device pointer, may be NULL) receives loss and t. */

@@ -26,7 +26,7 @@ TJ_MAX_LAYERS = 8
  TJ_STATE_ASTAR, TJ_STATE_WEIGHTS_COMPUTE, TJ_STATE_WEIGHTS_COMPUTE_T, TJ_STATE_WEIGHTS_COMPUTE_TARGET) = range(10)
 
 EXPORTS = [
-    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_sample_noalloc", "tj_actor_act", "tj_balance_plan", "tj_frame_buffer_arena_bytes", "tj_frame_buffer_create",
+    "tj_buffer_arena_bytes", "tj_buffer_create", "tj_buffer_destroy", "tj_buffer_insert", "tj_buffer_insert_concurrent", "tj_sample", "tj_sample_noalloc", "tj_buffer_reads_done", "tj_actor_act", "tj_balance_plan", "tj_frame_buffer_arena_bytes", "tj_frame_buffer_create",
     "tj_frame_buffer_destroy", "tj_frame_buffer_insert", "tj_frame_sample", "tj_frame_buffer_status",
     "tj_frame_buffer_field_ptr", "tj_frame_buffer_set_phase_events",
     "tj_buffer_status", "tj_buffer_field_ptr", "tj_learner_num_params", "tj_learner_arena_bytes",
@@ -43,7 +43,8 @@ class tj_buffer_desc(C.Structure):
 
 class tj_minibatch(C.Structure):
     _fields_ = [("obs", C.c_void_p), ("next_obs", C.c_void_p), ("action", C.c_void_p),
-                ("reward", C.c_void_p), ("done", C.c_void_p), ("idx", C.c_void_p), ("batch", C.c_uint32)]
+                ("reward", C.c_void_p), ("done", C.c_void_p), ("idx", C.c_void_p), ("batch", C.c_uint32),
+                ("row_index", C.c_void_p), ("n_rows", C.c_uint64)]
 
 
 class tj_buffer_info(C.Structure):
@@ -133,6 +134,8 @@ def lib():
         L.tj_sample_noalloc.argtypes = [vp, u32, i64, i64, u64, C.POINTER(tj_minibatch), vp]
         L.tj_buffer_status.restype = i32
         L.tj_buffer_status.argtypes = [vp, C.POINTER(tj_buffer_info), vp]
+        L.tj_buffer_reads_done.restype = i32
+        L.tj_buffer_reads_done.argtypes = [vp, vp]
         L.tj_buffer_field_ptr.restype = vp
         L.tj_buffer_field_ptr.argtypes = [vp, i32]
         L.tj_learner_num_params.restype = sz
@@ -209,21 +212,36 @@ def _require_gpu():
 
 
 class Minibatch:
-    """Caller-owned device tensors for one dense minibatch."""
+    """Caller-owned device tensors for one minibatch.
 
-    def __init__(self, batch: int, obs_elems: int, obs_dtype: str, device="cuda:0"):
+    Dense (default): obs / next_obs hold copies of the sampled rows.  With `ring` (a Buffer) the
+    minibatch is indirect: no observation tensors exist; `c` is what tj_sample fills (indices and
+    scalar fields) and `c_step` what tj_learner_step reads (the ring's own arrays + the indices)."""
+
+    def __init__(self, batch: int, obs_elems: int, obs_dtype: str, device="cuda:0", ring=None):
         import torch
 
         tdt = torch.float32 if obs_dtype == "f32" else torch.uint8
         self.batch = batch
-        self.obs = torch.empty((batch, obs_elems), dtype=tdt, device=device)
-        self.next_obs = torch.empty((batch, obs_elems), dtype=tdt, device=device)
+        self.ring = ring
         self.action = torch.empty(batch, dtype=torch.int32, device=device)
         self.reward = torch.empty(batch, dtype=torch.float32, device=device)
         self.done = torch.empty(batch, dtype=torch.uint8, device=device)
         self.idx = torch.empty(batch, dtype=torch.int32, device=device)   # bits are uint32
-        self.c = tj_minibatch(self.obs.data_ptr(), self.next_obs.data_ptr(), self.action.data_ptr(),
-                              self.reward.data_ptr(), self.done.data_ptr(), self.idx.data_ptr(), batch)
+        if ring is None:
+            self.obs = torch.empty((batch, obs_elems), dtype=tdt, device=device)
+            self.next_obs = torch.empty((batch, obs_elems), dtype=tdt, device=device)
+            self.c = tj_minibatch(self.obs.data_ptr(), self.next_obs.data_ptr(), self.action.data_ptr(),
+                                  self.reward.data_ptr(), self.done.data_ptr(), self.idx.data_ptr(), batch, None, 0)
+            self.c_step = self.c
+        else:
+            assert ring.obs_elems == obs_elems and ring.obs_dtype == obs_dtype
+            self.obs = self.next_obs = None
+            self.c = tj_minibatch(None, None, self.action.data_ptr(), self.reward.data_ptr(),
+                                  self.done.data_ptr(), self.idx.data_ptr(), batch, None, 0)
+            self.c_step = tj_minibatch(lib().tj_buffer_field_ptr(ring.h, 0), lib().tj_buffer_field_ptr(ring.h, 1),
+                                       self.action.data_ptr(), self.reward.data_ptr(), self.done.data_ptr(),
+                                       self.idx.data_ptr(), batch, self.idx.data_ptr(), ring.capacity)
 
     def load(self, obs, next_obs, action, reward, done) -> None:
         """Fill from host arrays (tests feed the learner without a ring)."""
@@ -236,7 +254,8 @@ class Minibatch:
         self.done.copy_(torch.from_numpy(np.ascontiguousarray(done, np.uint8)))
 
     def host(self):
-        out = {k: getattr(self, k).cpu().numpy() for k in ("obs", "next_obs", "action", "reward", "done")}
+        keys = ("action", "reward", "done") if self.ring is not None else ("obs", "next_obs", "action", "reward", "done")
+        out = {k: getattr(self, k).cpu().numpy() for k in keys}
         out["idx"] = self.idx.cpu().numpy().view(np.uint32)
         return out
 
@@ -381,6 +400,10 @@ class Buffer:
         st = lib().tj_buffer_status(self.h, C.byref(info), _stream_ptr(stream))
         return st, info
 
+    def reads_done(self, stream=None) -> None:
+        """After a Learner.step on an indirect minibatch, where concurrent inserts are in use."""
+        _check(lib().tj_buffer_reads_done(self.h, _stream_ptr(stream)), "tj_buffer_reads_done")
+
     def field(self, name: str):
         """A torch view of one ring field (tests only)."""
         import torch
@@ -447,7 +470,7 @@ class Learner:
 
     def step(self, mb: Minibatch, stream=None) -> int:
         self.last_batch = mb.batch
-        return lib().tj_learner_step(self.h, C.byref(mb.c), self.stats.data_ptr(), _stream_ptr(stream))
+        return lib().tj_learner_step(self.h, C.byref(mb.c_step), self.stats.data_ptr(), _stream_ptr(stream))
 
     def act(self, obs, epsilon: float, seed: int, want_q: bool = False, stream=None):
         """Epsilon-greedy actions for a device tensor of observations [n, obs elements]:

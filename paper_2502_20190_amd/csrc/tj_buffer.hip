@@ -753,8 +753,9 @@ static int sample_into(tj_buffer *buf, uint32_t batch, int64_t current_version, 
                        uint32_t *tile_count, uint32_t *tile_off, bool may_create_event)
 {
     if (!buf || !out || batch == 0 || out->batch != batch) return TJ_ERR_INVALID_ARG;
-    if (!out->obs || !out->next_obs || !out->action || !out->reward || !out->done || !out->idx)
-        return TJ_ERR_INVALID_ARG;
+    if (!out->action || !out->reward || !out->done || !out->idx) return TJ_ERR_INVALID_ARG;
+    // observations: both destinations, or neither (indices and scalar fields only)
+    if ((out->obs == nullptr) != (out->next_obs == nullptr)) return TJ_ERR_INVALID_ARG;
     if (batch > (1u << 20)) return TJ_ERR_SHAPE;
     // later concurrent inserts wait for the end of this sample: the event must exist
     if (buf->concurrent_used && !buf->sample_done) {
@@ -788,8 +789,10 @@ static int sample_into(tj_buffer *buf, uint32_t batch, int64_t current_version, 
     }
     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[1], st));
-    int rc = copy_rows(buf->ring.obs, out->obs, buf->ring.next_obs, out->next_obs, buf->row_bytes, batch,
-                       out->idx, 0, 0, buf->desc.capacity, st);
+    int rc = TJ_OK;
+    if (out->obs)
+        rc = copy_rows(buf->ring.obs, out->obs, buf->ring.next_obs, out->next_obs, buf->row_bytes, batch, out->idx, 0,
+                       0, buf->desc.capacity, st);
     if (rc == TJ_OK && buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[2], st));
     buf->last_sample_stream = st;
     buf->sampled = true;
@@ -852,6 +855,18 @@ int tj_sample_noalloc(tj_buffer *buf, uint32_t batch, int64_t current_version, i
     uint32_t *tile_off = tile_count + kNoAllocTiles;
     return sample_into(buf, batch, current_version, max_staleness, seed, out, (hipStream_t)hip_stream, mask,
                        tile_count, tile_off, false);
+}
+
+int tj_buffer_reads_done(tj_buffer *buf, void *hip_stream)
+{
+    if (!buf) return TJ_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the same marker a sample leaves at its end, moved behind the work that read the ring after it
+    if (!buf->sample_done) TJ_HIP_TRY(hipEventCreateWithFlags(&buf->sample_done, hipEventDisableTiming));
+    TJ_HIP_TRY(hipEventRecord(buf->sample_done, st));
+    buf->last_sample_stream = st;
+    buf->sampled = true;
+    return TJ_OK;
 }
 
 int tj_buffer_set_phase_events(tj_buffer *buf, void *const *hip_events, uint32_t n)
@@ -974,8 +989,9 @@ int tj_frame_sample(tj_frame_buffer *buf, uint32_t batch, int64_t current_versio
                     uint64_t seed, const tj_minibatch *out, void *hip_stream)
 {
     if (!buf || !out || batch == 0 || out->batch != batch) return TJ_ERR_INVALID_ARG;
-    if (!out->obs || !out->next_obs || !out->action || !out->reward || !out->done || !out->idx)
-        return TJ_ERR_INVALID_ARG;
+    if (!out->action || !out->reward || !out->done || !out->idx) return TJ_ERR_INVALID_ARG;
+    // observations: both destinations, or neither (indices and scalar fields only)
+    if ((out->obs == nullptr) != (out->next_obs == nullptr)) return TJ_ERR_INVALID_ARG;
     if (batch > (1u << 20)) return TJ_ERR_SHAPE;
     hipStream_t st = (hipStream_t)hip_stream;
     const uint32_t count = (uint32_t)buf->count, cap = (uint32_t)buf->desc.capacity;

@@ -17,13 +17,15 @@ struct ConvGeom {
 // Observation planes (NCHW, u8 scaled by 1/255 or fp32) -> channels-last T [n][H][W][C].
 template <typename T, typename S>
 __global__ __launch_bounds__(256) void to_nhwc(const S *__restrict__ src, T *__restrict__ dst, int n, int C,
-                                               int H, int W, float scale)
+                                               int H, int W, float scale, const uint32_t *__restrict__ rows,
+                                               uint32_t n_rows)
 {
     const size_t total = (size_t)n * H * W;
     const size_t p = (size_t)blockIdx.x * 256 + threadIdx.x;   // (img, y, x)
     if (p >= total) return;
     const size_t img = p / ((size_t)H * W), yx = p % ((size_t)H * W);
-    const S *sp = src + img * C * H * W + yx;
+    const size_t simg = rows ? (size_t)min(rows[img], n_rows - 1u) : img;   // source image, picked by index
+    const S *sp = src + simg * C * H * W + yx;
     T *dp = dst + p * C;
     for (int c = 0; c < C; ++c) dp[c] = TjElem<T>::from_f32((float)sp[(size_t)c * H * W] * scale);
 }
@@ -31,13 +33,15 @@ __global__ __launch_bounds__(256) void to_nhwc(const S *__restrict__ src, T *__r
 // u8 planes with C = 4 -> channels-last bf16, eight pixels per thread: one 8-byte load per plane,
 // four 16-byte stores.  H*W must be a multiple of 8.
 __global__ __launch_bounds__(256) void to_nhwc_u8c4(const uint8_t *__restrict__ src, tj_bf16 *__restrict__ dst,
-                                                    size_t n_img, int HW, float scale)
+                                                    size_t n_img, int HW, float scale,
+                                                    const uint32_t *__restrict__ rows, uint32_t n_rows)
 {
     const size_t groups = n_img * (size_t)(HW / 8);
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= groups) return;
     const size_t img = t / (HW / 8), p0 = (t % (HW / 8)) * 8;
-    const uint8_t *sp = src + img * 4 * (size_t)HW + p0;
+    const size_t simg = rows ? (size_t)min(rows[img], n_rows - 1u) : img;
+    const uint8_t *sp = src + simg * 4 * (size_t)HW + p0;
     uint64_t pl[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) pl[c] = *(const uint64_t *)(sp + (size_t)c * HW);

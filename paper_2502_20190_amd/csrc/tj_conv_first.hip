@@ -113,9 +113,20 @@ __global__ __launch_bounds__(kThreads) void conv_first_u8c4(const TjConvFirstArg
     const int n_task = HW / 4;                        // 4 consecutive pixels, all four planes
     const int n_round = (n_task + kThreads - 1) / kThreads;
     PlaneRegs px;
-    auto fetch = [&](int g) {                         // image g: s images first, then s'
-        const uint8_t *src = (g < a.B ? a.obs + (size_t)g * 4 * HW : a.next_obs + (size_t)(g - a.B) * 4 * HW);
+    const int n_img = 2 * a.B;
+    const int stride = (int)gridDim.x;
+    // Image g (s images first, then s') is row row_of(g) of its table: the batch position itself, or
+    // the caller's index for it.  Fetches go through the block's images in order, so the row of the
+    // next fetch is looked up right after the current one was issued, off the critical path.
+    auto row_of = [&](int g) -> uint32_t {
+        const uint32_t b = (uint32_t)(g < a.B ? g : g - a.B);
+        return a.rows ? min(a.rows[b], a.n_rows - 1u) : b;
+    };
+    uint32_t row_next = (int)blockIdx.x < n_img ? row_of((int)blockIdx.x) : 0u;
+    auto fetch = [&](int g) {
+        const uint8_t *src = (g < a.B ? a.obs : a.next_obs) + (size_t)row_next * 4 * HW;
         fetch_planes(px, src, HW, n_task, n_round, tid);
+        if (g + stride < n_img) row_next = row_of(g + stride);
     };
     auto convert = [&](int g, uint8_t *img) {         // ... and the channels-last copy of an s image
         tj_bf16 *keep = g < a.B && a.act0 ? a.act0 + (size_t)g * HW * 4 : nullptr;
@@ -124,7 +135,6 @@ __global__ __launch_bounds__(kThreads) void conv_first_u8c4(const TjConvFirstArg
 
     const int OHW = a.OH * a.OW;
     const int n_tile = (OHW + 31) / 32;
-    const int n_img = 2 * a.B;
     // patches x weights of image g in `img`.  Tile = 32 patches; lane l32 owns patch 32*tile + l32.
     auto patches = [&](int g, const uint8_t *img) {
         const int n_net = g < a.B ? 1 : 2;
@@ -174,7 +184,6 @@ __global__ __launch_bounds__(kThreads) void conv_first_u8c4(const TjConvFirstArg
         }
     };
 
-    const int stride = (int)gridDim.x;
     int g = blockIdx.x;
     if (g >= n_img) return;
     fetch(g);
@@ -298,7 +307,11 @@ __global__ __launch_bounds__(kThreads) void conv_first_wgrad_u8c4(const TjConvFi
     const int stride = (int)gridDim.x;
     int g = blockIdx.x;
     if (g >= a.B) return;                // the host launches at most B blocks
-    fetch_planes(px, a.obs + (size_t)g * 4 * HW, HW, n_task, n_round, tid);
+    // table row of an s image, as in the forward kernel; the next fetch's row is looked up one image ahead
+    auto row_of = [&](int b) -> uint32_t { return a.rows ? min(a.rows[b], a.n_rows - 1u) : (uint32_t)b; };
+    uint32_t row_next = row_of(g);
+    fetch_planes(px, a.obs + (size_t)row_next * 4 * HW, HW, n_task, n_round, tid);
+    if (g + stride < a.B) row_next = row_of(g + stride);
     dma_dz(g, dzb);
     int cur = 0;
     for (; g < a.B; g += stride) {
@@ -307,7 +320,8 @@ __global__ __launch_bounds__(kThreads) void conv_first_wgrad_u8c4(const TjConvFi
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of dZ(g) has landed
         __syncthreads();                 // image and dZ rows complete
         if (g + stride < a.B) {          // in flight during the MFMAs below
-            fetch_planes(px, a.obs + (size_t)(g + stride) * 4 * HW, HW, n_task, n_round, tid);
+            fetch_planes(px, a.obs + (size_t)row_next * 4 * HW, HW, n_task, n_round, tid);
+            if (g + 2 * stride < a.B) row_next = row_of(g + 2 * stride);
             dma_dz(g + stride, dzb + (cur ^ 1) * dz_bytes);
         }
         const uint8_t *dz = dzb + cur * dz_bytes + a_lane, *pim = img + b_lane;
@@ -389,6 +403,7 @@ int tj_conv_first(const TjConvFirstArgs &a, hipStream_t st)
     if (a.B < 1 || !tj_conv_first_fits(4, a.H, a.W, a.k, a.s, 32)) return TJ_ERR_SHAPE;
     if (a.OH != (a.H - a.k) / a.s + 1 || a.OW != (a.W - a.k) / a.s + 1) return TJ_ERR_SHAPE;
     if ((((uintptr_t)a.obs | (uintptr_t)a.next_obs) & 3) != 0) return TJ_ERR_INVALID_ARG;
+    if (a.rows && a.n_rows == 0) return TJ_ERR_INVALID_ARG;
     const bool two = tj_conv_first_lds_bytes(a.H, a.W, a.k, 2) <= kLdsLimit;
     const size_t lds = tj_conv_first_lds_bytes(a.H, a.W, a.k, two ? 2 : 1);
     static bool attr_set = false;
@@ -443,6 +458,7 @@ int tj_conv_first_wgrad(const TjConvFirstWgradArgs &a, hipStream_t st)
     if (a.OH != (a.H - a.k) / a.s + 1 || a.OW != (a.W - a.k) / a.s + 1) return TJ_ERR_SHAPE;
     if (a.zstride < (size_t)32 * 4 * a.k * a.k + 32) return TJ_ERR_SHAPE;
     if ((((uintptr_t)a.obs) & 3) != 0 || (((uintptr_t)a.dZ) & 15) != 0) return TJ_ERR_INVALID_ARG;
+    if (a.rows && a.n_rows == 0) return TJ_ERR_INVALID_ARG;
     const size_t lds = conv_first_wgrad_lds_bytes(a.H, a.W, a.k, a.OH * a.OW);
     static bool attr_set = false;
     if (!attr_set) {

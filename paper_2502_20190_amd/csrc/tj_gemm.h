@@ -169,6 +169,8 @@ struct TjConvFirstArgs {
     const float *b_on, *b_tg;
     tj_bf16 *act0, *out;
     float scale;
+    const uint32_t *rows;   // optional: image b of s / s' is row min(rows[b], n_rows - 1) of obs / next_obs
+    uint32_t n_rows;
 };
 bool tj_conv_first_fits(int C, int H, int W, int k, int s, int O);
 int tj_conv_first(const TjConvFirstArgs &a, hipStream_t st);
@@ -186,6 +188,8 @@ struct TjConvFirstWgradArgs {
     float scale;
     float *part; size_t zstride;
     int n_part;
+    const uint32_t *rows;   // optional, as in TjConvFirstArgs
+    uint32_t n_rows;
 };
 bool tj_conv_first_wgrad_fits(int C, int H, int W, int k, int s, int O);
 int tj_conv_first_wgrad(const TjConvFirstWgradArgs &a, hipStream_t st);

@@ -30,6 +30,8 @@ template <typename T> struct CastJob {
     T *dst;             // [R][ldd]   (may be null)
     T *dstT;            // [C][lddT]  (may be null)
     int R, C, ldd, lddT;
+    const uint32_t *rows = nullptr;   // optional: source row r is row min(rows[r], n_rows - 1) of src
+    uint32_t n_rows = 0;
 };
 template <typename T> struct CastJobs {
     CastJob<T> job[TJ_MAX_LAYERS];
@@ -70,7 +72,8 @@ __global__ __launch_bounds__(256) void cast_transpose(const CastJobs<T> jobs)
         const int r = r0 + tr + 16 * i, c = c0 + tc;
         float x[4] = {0.f, 0.f, 0.f, 0.f};
         if (r < jb.R && c < jb.C) {
-            const float *sp = jb.src + (size_t)r * jb.C + c;
+            const size_t rs = jb.rows ? (size_t)min(jb.rows[r], jb.n_rows - 1u) : (size_t)r;
+            const float *sp = jb.src + rs * jb.C + c;
             if (vec) {
                 const float4 v = *(const float4 *)sp;
                 x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
@@ -1194,6 +1197,7 @@ template <typename T> struct MlpLearner : tj_learner {
         const int B = (int)mb->batch;
         if (B < 1 || B > Bmax) return TJ_ERR_SHAPE;
         if (!mb->obs || !mb->next_obs || !mb->action || !mb->reward || !mb->done) return TJ_ERR_INVALID_ARG;
+        if (mb->row_index && (mb->n_rows == 0 || mb->n_rows > 0xFFFFFFFFull)) return TJ_ERR_INVALID_ARG;
         int rc;
         if (last_batch != B) {
             // pad columns beyond the batch must read as zero in the batch contraction
@@ -1208,6 +1212,10 @@ template <typename T> struct MlpLearner : tj_learner {
             jobs.job[0] = {(const float *)mb->obs, X[0], XT[0], B, lay[0].in, lay[0].ld_in, ldB};
             jobs.job[1] = {(const float *)mb->next_obs, X[0] + (size_t)B * lay[0].ld_in, nullptr, B,
                            lay[0].in, lay[0].ld_in, ldB};
+            if (mb->row_index) {   // rows of the caller's tables (the ring itself), picked by index
+                jobs.job[0].rows = jobs.job[1].rows = mb->row_index;
+                jobs.job[0].n_rows = jobs.job[1].n_rows = (uint32_t)mb->n_rows;
+            }
             if ((rc = launch_cast<T>(jobs, 2, st)) != TJ_OK) return rc;
         }
         if ((rc = mark(0, st)) != TJ_OK) return rc;
@@ -1917,6 +1925,7 @@ template <typename T> struct ConvLearner : tj_learner {
         const int B = (int)mb->batch;
         if (B < 1 || B > Bmax) return TJ_ERR_SHAPE;
         if (!mb->obs || !mb->next_obs || !mb->action || !mb->reward || !mb->done) return TJ_ERR_INVALID_ARG;
+        if (mb->row_index && (mb->n_rows == 0 || mb->n_rows > 0xFFFFFFFFull)) return TJ_ERR_INVALID_ARG;
         int rc;
         if (last_batch != B) {
             if (last_batch > B && (rc = launch_zero(act_begin, act_bytes, st)) != TJ_OK) return rc;
@@ -1935,6 +1944,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 fa.b_on = theta_on + lay[0].b_off; fa.b_tg = theta_tg + lay[0].b_off;
                 fa.act0 = first_wgrad_u8 ? nullptr : act[0]; fa.out = act[1];
                 fa.scale = 1.0f / 255.0f;
+                fa.rows = mb->row_index; fa.n_rows = (uint32_t)mb->n_rows;
                 if ((rc = mark(0, st)) != TJ_OK) return rc;
                 if ((rc = tj_conv_first(fa, st)) != TJ_OK) return rc;
                 first_done = true;
@@ -1943,6 +1953,8 @@ template <typename T> struct ConvLearner : tj_learner {
         if (!first_done) {   // observations -> channels-last compute type, images s | s'
             const tjconv::ConvGeom &g = lay[0].g;
             const size_t px = (size_t)B * g.H * g.W, img = (size_t)g.H * g.W * g.C;
+            const uint32_t *rows = mb->row_index;
+            const uint32_t n_rows = (uint32_t)mb->n_rows;
             bool fast = false;
             if constexpr (sizeof(T) == 2) {
                 fast = d.obs_dtype == TJ_OBS_U8 && g.C == 4 && (g.H * g.W) % 8 == 0 &&
@@ -1950,24 +1962,25 @@ template <typename T> struct ConvLearner : tj_learner {
                 if (fast) {
                     const size_t groups = (size_t)B * (g.H * g.W / 8);
                     tjconv::to_nhwc_u8c4<<<grid1(groups), 256, 0, st>>>((const uint8_t *)mb->obs, act[0], (size_t)B,
-                                                                        g.H * g.W, 1.0f / 255.0f);
+                                                                        g.H * g.W, 1.0f / 255.0f, rows, n_rows);
                     tjconv::to_nhwc_u8c4<<<grid1(groups), 256, 0, st>>>((const uint8_t *)mb->next_obs,
                                                                         act[0] + (size_t)B * img, (size_t)B,
-                                                                        g.H * g.W, 1.0f / 255.0f);
+                                                                        g.H * g.W, 1.0f / 255.0f, rows, n_rows);
                 }
             }
             if (fast) {
             } else if (d.obs_dtype == TJ_OBS_U8) {
                 tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->obs, act[0], B, g.C, g.H,
-                                                                       g.W, 1.0f / 255.0f);
+                                                                       g.W, 1.0f / 255.0f, rows, n_rows);
                 tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->next_obs,
                                                                        act[0] + (size_t)B * img, B, g.C, g.H, g.W,
-                                                                       1.0f / 255.0f);
+                                                                       1.0f / 255.0f, rows, n_rows);
             } else {
                 tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)mb->obs, act[0], B, g.C, g.H, g.W,
-                                                                     1.0f);
+                                                                     1.0f, rows, n_rows);
                 tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)mb->next_obs,
-                                                                     act[0] + (size_t)B * img, B, g.C, g.H, g.W, 1.0f);
+                                                                     act[0] + (size_t)B * img, B, g.C, g.H, g.W, 1.0f,
+                                                                     rows, n_rows);
             }
             if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
             if ((rc = mark(0, st)) != TJ_OK) return rc;
@@ -2107,6 +2120,7 @@ template <typename T> struct ConvLearner : tj_learner {
                     wa.obs = (const uint8_t *)mb->obs; wa.dZ = y.dZ;
                     wa.B = B; wa.H = g.H; wa.W = g.W; wa.k = g.k; wa.s = g.s; wa.OH = g.OH; wa.OW = g.OW;
                     wa.scale = 1.0f / 255.0f;
+                    wa.rows = mb->row_index; wa.n_rows = (uint32_t)mb->n_rows;
                     wa.part = y.part; wa.zstride = y.part_stride;
                     wa.n_part = std::min(B, std::min(n_cu, y.n_split));
                     if ((rc = tj_conv_first_wgrad(wa, st)) != TJ_OK) return rc;
@@ -2295,15 +2309,15 @@ template <typename T> struct ConvLearner : tj_learner {
                 fast = d.obs_dtype == TJ_OBS_U8 && g.C == 4 && (g.H * g.W) % 8 == 0 && ((uintptr_t)d_obs & 7) == 0;
                 if (fast)
                     tjconv::to_nhwc_u8c4<<<grid1((size_t)n * (g.H * g.W / 8)), 256, 0, st>>>(
-                        (const uint8_t *)d_obs, act[0], (size_t)n, g.H * g.W, 1.0f / 255.0f);
+                        (const uint8_t *)d_obs, act[0], (size_t)n, g.H * g.W, 1.0f / 255.0f, nullptr, 0u);
             }
             if (!fast) {
                 if (d.obs_dtype == TJ_OBS_U8)
                     tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)d_obs, act[0], n, g.C, g.H,
-                                                                           g.W, 1.0f / 255.0f);
+                                                                           g.W, 1.0f / 255.0f, nullptr, 0u);
                 else
                     tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)d_obs, act[0], n, g.C, g.H, g.W,
-                                                                         1.0f);
+                                                                         1.0f, nullptr, 0u);
             }
             if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         }

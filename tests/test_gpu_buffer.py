@@ -313,12 +313,12 @@ def test_insert_stream_races_sampling_stream(tj, orc):
         dev = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in rows.items()}
         _sync()                                     # the upload is done; from here on no host sync
         if it % 3 == 0:
-            keep = _busy(side, 1.0)
+            keep = _busy(side, 3.0)
         gbuf.insert_concurrent(dev["obs"], dev["next_obs"], dev["action"], dev["reward"], dev["done"],
                                dev["version"], side)
-        assert obuf.insert(**rows) == 0             # the oracle's ring: state after the insert
         mb = mbs[it % 2]
-        assert gbuf.sample(mb, cur, max_st, 100 + it) == tj.TJ_OK
+        assert gbuf.sample(mb, cur, max_st, 100 + it) == tj.TJ_OK   # issued with no host work in between
+        assert obuf.insert(**rows) == 0             # the oracle's ring: state after the insert
         st, info = gbuf.status()                    # synchronises the sampling stream only
         ex_begin, ex_len = int(info.last_excluded_begin), int(info.last_excluded_len)
         arcs_seen += ex_len > 0
