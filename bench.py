@@ -286,8 +286,9 @@ def main():
                     help="also push this many new transitions per step into the ring on a second stream "
                          "(tj_buffer_insert_concurrent) while the learner loops")
     ap.add_argument("--frame-ring", action="store_true",
-                    help="pixel workloads: keep the replay ring as one frame per slot (tj_frame_buffer) and "
-                         "rebuild the observation stacks in the gather")
+                    help="pixel workloads: keep the replay ring as one frame per slot (tj_frame_buffer); the "
+                         "learner reads the frames of each stack through their slots (with --copy-minibatch the "
+                         "gather rebuilds dense stacks)")
     ap.add_argument("--actor-rows", type=int, default=0,
                     help="after the learner loop, also time epsilon-greedy policy inference (tj_actor_act) "
                          "on this many observations per call (at most twice the batch)")
@@ -358,7 +359,7 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
     # Buffer loop and learner loop run asynchronously (Section 3.1): the sampler fills minibatch
     # i % 2 on its own stream while the learner consumes the other one.  Two events per minibatch
     # order the hand-over in both directions; every step still samples and learns once.
-    indirect = not (args.copy_minibatch or args.frame_ring)
+    indirect = not args.copy_minibatch
     mbs = [tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype, ring=buf if indirect else None)
            for _ in range(2 if overlap else 1)]
     s_sample = torch.cuda.Stream() if overlap else None

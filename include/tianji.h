@@ -74,7 +74,16 @@ typedef struct {
  * idx a tj_sample call produced, the learner's first kernels read the sampled
  * transitions where they lie and no copy of their observations is made: the
  * "load" of the learner loop (Section 3.1) happens inside the update.
- * row_index == NULL: the dense form, n_rows is ignored. */
+ *
+ * Indirect by planes (plane_index != NULL; pixel networks only): obs and
+ * next_obs both point at one table of n_rows planes of H*W elements (the
+ * frame ring's frames, tj_frame_buffer_field_ptr 0), and with C the network's
+ * input channels, channel c of s_j is plane
+ * min(plane_index[2*C*j + c], n_rows - 1) and channel c of s'_j plane
+ * min(plane_index[2*C*j + C + c], n_rows - 1).  tj_frame_sample fills
+ * plane_index when it is given no observation destinations.
+ * row_index == plane_index == NULL: the dense form, n_rows is ignored; giving
+ * both is an error. */
 typedef struct {
     void *obs;
     void *next_obs;
@@ -83,8 +92,9 @@ typedef struct {
     uint8_t *done;
     uint32_t *idx;
     uint32_t batch;
-    const uint32_t *row_index;
+    uint32_t *row_index;
     uint64_t n_rows;
+    uint32_t *plane_index;
 } tj_minibatch;
 
 typedef struct {
@@ -228,6 +238,11 @@ int tj_frame_buffer_destroy(tj_frame_buffer *buf);
 int tj_frame_buffer_insert(tj_frame_buffer *buf, uint32_t n, const uint8_t *d_frame, const int32_t *d_action,
                            const float *d_reward, const uint8_t *d_done, const int32_t *d_version,
                            void *hip_stream);
+/* As tj_sample.  With out->obs == out->next_obs == NULL no stack is rebuilt:
+ * out->plane_index (device, u32 [batch][2 * stack], required then) receives the
+ * slot of every frame of s (positions 0 .. k-1) and of s' (k .. 2k-1) of each
+ * drawn transition, all ones where nothing was eligible, for the minibatch
+ * form that is indirect by planes. */
 int tj_frame_sample(tj_frame_buffer *buf, uint32_t batch, int64_t current_version, int64_t max_staleness,
                     uint64_t seed, const tj_minibatch *out, void *hip_stream);
 int tj_frame_buffer_status(tj_frame_buffer *buf, tj_buffer_info *h_out, void *hip_stream);
@@ -309,7 +324,8 @@ int tj_learner_destroy(tj_learner *lrn);
  * outside the square root) with t = 1, 2, ...; then, if t is a multiple of
  * target_interval, the target parameters become a copy of the online ones.
  * `mb` holds device pointers (idx is not read); mb->batch <= max_batch.  Both
- * forms of the minibatch are accepted; with the indirect form the tables must
+ * forms of the minibatch are accepted (the form by planes by networks whose
+ * first layer is a convolution); with an indirect form the tables must
  * stay unchanged until the step's kernels have run (a network whose first
  * layer is a convolution reads them again in its backward pass), and
  * n_rows == 0 is TJ_ERR_INVALID_ARG.

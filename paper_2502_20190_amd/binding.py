@@ -44,7 +44,7 @@ class tj_buffer_desc(C.Structure):
 class tj_minibatch(C.Structure):
     _fields_ = [("obs", C.c_void_p), ("next_obs", C.c_void_p), ("action", C.c_void_p),
                 ("reward", C.c_void_p), ("done", C.c_void_p), ("idx", C.c_void_p), ("batch", C.c_uint32),
-                ("row_index", C.c_void_p), ("n_rows", C.c_uint64)]
+                ("row_index", C.c_void_p), ("n_rows", C.c_uint64), ("plane_index", C.c_void_p)]
 
 
 class tj_buffer_info(C.Structure):
@@ -214,9 +214,10 @@ def _require_gpu():
 class Minibatch:
     """Caller-owned device tensors for one minibatch.
 
-    Dense (default): obs / next_obs hold copies of the sampled rows.  With `ring` (a Buffer) the
-    minibatch is indirect: no observation tensors exist; `c` is what tj_sample fills (indices and
-    scalar fields) and `c_step` what tj_learner_step reads (the ring's own arrays + the indices)."""
+    Dense (default): obs / next_obs hold copies of the sampled rows.  With `ring` (a Buffer or a
+    FrameBuffer) the minibatch is indirect: no observation tensors exist; `c` is what the sampler
+    fills (indices and scalar fields; for a FrameBuffer also the slot of every frame of the two
+    stacks) and `c_step` what tj_learner_step reads (the ring's own arrays + those indices)."""
 
     def __init__(self, batch: int, obs_elems: int, obs_dtype: str, device="cuda:0", ring=None):
         import torch
@@ -234,6 +235,16 @@ class Minibatch:
             self.c = tj_minibatch(self.obs.data_ptr(), self.next_obs.data_ptr(), self.action.data_ptr(),
                                   self.reward.data_ptr(), self.done.data_ptr(), self.idx.data_ptr(), batch, None, 0)
             self.c_step = self.c
+        elif hasattr(ring, "stack"):     # frame ring: indirect by planes
+            assert ring.obs_elems == obs_elems and obs_dtype == "u8"
+            self.obs = self.next_obs = None
+            self.planes = torch.empty((batch, 2 * ring.stack), dtype=torch.int32, device=device)
+            frames = lib().tj_frame_buffer_field_ptr(ring.h, 0)
+            self.c = tj_minibatch(None, None, self.action.data_ptr(), self.reward.data_ptr(),
+                                  self.done.data_ptr(), self.idx.data_ptr(), batch, None, 0, self.planes.data_ptr())
+            self.c_step = tj_minibatch(frames, frames, self.action.data_ptr(), self.reward.data_ptr(),
+                                       self.done.data_ptr(), self.idx.data_ptr(), batch, None, ring.capacity,
+                                       self.planes.data_ptr())
         else:
             assert ring.obs_elems == obs_elems and ring.obs_dtype == obs_dtype
             self.obs = self.next_obs = None
@@ -257,6 +268,8 @@ class Minibatch:
         keys = ("action", "reward", "done") if self.ring is not None else ("obs", "next_obs", "action", "reward", "done")
         out = {k: getattr(self, k).cpu().numpy() for k in keys}
         out["idx"] = self.idx.cpu().numpy().view(np.uint32)
+        if getattr(self, "planes", None) is not None:
+            out["planes"] = self.planes.cpu().numpy().view(np.uint32)
         return out
 
 

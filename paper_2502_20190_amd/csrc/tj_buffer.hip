@@ -572,6 +572,25 @@ __global__ __launch_bounds__(256) void gather_stacks(const V *__restrict__ frame
     }
 }
 
+// The same addressing without the copy: out[r][q] = the slot whose frame is plane q of minibatch row r
+// (all ones where the draw found nothing).
+__global__ __launch_bounds__(256) void stack_plane_slots(const uint8_t *__restrict__ age, const uint32_t *__restrict__ idx,
+                                                         uint32_t *__restrict__ out, uint32_t batch, uint32_t k,
+                                                         uint32_t cap)
+{
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= batch * 2 * k) return;
+    const uint32_t r = i / (2 * k), q = i % (2 * k);
+    uint32_t t = idx[r];
+    if (t == kInvalid) { out[i] = kInvalid; return; }
+    const uint32_t p = q < k ? q : q - k;
+    if (q >= k) t = t + 1 == cap ? 0 : t + 1;
+    uint32_t back = k - 1 - p;
+    const uint32_t a = age[t];
+    if (back > a) back = a;
+    out[i] = t >= back ? t - back : t + cap - back;
+}
+
 template <typename V>
 int launch_gather_stacks(const void *frame, const uint8_t *age, const uint32_t *idx, void *obs, void *next_obs,
                          uint32_t frame_bytes, uint32_t k, uint32_t cap, uint32_t batch, hipStream_t st)
@@ -1015,6 +1034,13 @@ int tj_frame_sample(tj_frame_buffer *buf, uint32_t batch, int64_t current_versio
     if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
     if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[1], st));
     const uint32_t fb = buf->desc.frame_elems, k = buf->desc.stack;
+    if (!out->obs) {   // no stacks: the slots of their frames instead
+        if (!out->plane_index) return TJ_ERR_INVALID_ARG;
+        stack_plane_slots<<<(batch * 2 * k + 255) / 256, 256, 0, st>>>(buf->l.age, out->idx, out->plane_index, batch, k, cap);
+        if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
+        if (buf->timed) TJ_HIP_TRY(hipEventRecord(buf->ev[2], st));
+        return TJ_OK;
+    }
     auto aligned = [&](size_t a) {
         return fb % a == 0 && ((uintptr_t)buf->l.frame | (uintptr_t)out->obs | (uintptr_t)out->next_obs) % a == 0;
     };

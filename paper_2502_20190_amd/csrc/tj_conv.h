@@ -18,15 +18,22 @@ struct ConvGeom {
 template <typename T, typename S>
 __global__ __launch_bounds__(256) void to_nhwc(const S *__restrict__ src, T *__restrict__ dst, int n, int C,
                                                int H, int W, float scale, const uint32_t *__restrict__ rows,
-                                               uint32_t n_rows)
+                                               uint32_t n_rows, const uint32_t *__restrict__ planes)
 {
     const size_t total = (size_t)n * H * W;
     const size_t p = (size_t)blockIdx.x * 256 + threadIdx.x;   // (img, y, x)
     if (p >= total) return;
     const size_t img = p / ((size_t)H * W), yx = p % ((size_t)H * W);
+    T *dp = dst + p * C;
+    if (planes) {   // every channel is a plane of its own in the source table: planes[img * 2C + c]
+        for (int c = 0; c < C; ++c) {
+            const size_t pl = (size_t)min(planes[img * 2 * C + c], n_rows - 1u);
+            dp[c] = TjElem<T>::from_f32((float)src[pl * H * W + yx] * scale);
+        }
+        return;
+    }
     const size_t simg = rows ? (size_t)min(rows[img], n_rows - 1u) : img;   // source image, picked by index
     const S *sp = src + simg * C * H * W + yx;
-    T *dp = dst + p * C;
     for (int c = 0; c < C; ++c) dp[c] = TjElem<T>::from_f32((float)sp[(size_t)c * H * W] * scale);
 }
 
@@ -34,17 +41,24 @@ __global__ __launch_bounds__(256) void to_nhwc(const S *__restrict__ src, T *__r
 // four 16-byte stores.  H*W must be a multiple of 8.
 __global__ __launch_bounds__(256) void to_nhwc_u8c4(const uint8_t *__restrict__ src, tj_bf16 *__restrict__ dst,
                                                     size_t n_img, int HW, float scale,
-                                                    const uint32_t *__restrict__ rows, uint32_t n_rows)
+                                                    const uint32_t *__restrict__ rows, uint32_t n_rows,
+                                                    const uint32_t *__restrict__ planes)
 {
     const size_t groups = n_img * (size_t)(HW / 8);
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= groups) return;
     const size_t img = t / (HW / 8), p0 = (t % (HW / 8)) * 8;
-    const size_t simg = rows ? (size_t)min(rows[img], n_rows - 1u) : img;
-    const uint8_t *sp = src + simg * 4 * (size_t)HW + p0;
     uint64_t pl[4];
+    if (planes) {   // planes[img * 8 + c] = the source table's plane that holds channel c
 #pragma unroll
-    for (int c = 0; c < 4; ++c) pl[c] = *(const uint64_t *)(sp + (size_t)c * HW);
+        for (int c = 0; c < 4; ++c)
+            pl[c] = *(const uint64_t *)(src + (size_t)min(planes[img * 8 + c], n_rows - 1u) * HW + p0);
+    } else {
+        const size_t simg = rows ? (size_t)min(rows[img], n_rows - 1u) : img;
+        const uint8_t *sp = src + simg * 4 * (size_t)HW + p0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) pl[c] = *(const uint64_t *)(sp + (size_t)c * HW);
+    }
     uint4 *dp = (uint4 *)(dst + (img * HW + p0) * 4);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {   // pixels 2q, 2q+1

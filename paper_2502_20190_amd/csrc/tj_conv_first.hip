@@ -43,7 +43,30 @@ struct PlaneRegs {
     uint32_t px[kMaxRounds][4];
 };
 
-__device__ __forceinline__ void fetch_planes(PlaneRegs &p, const uint8_t *src, const int HW, const int n_task,
+// Byte offsets of an image's four planes inside its source table: the planes of batch position b, of the
+// table row an index names for it, or four planes named one by one (a frame ring's frames).  Indices
+// are clamped to the table.
+struct PlaneOff {
+    size_t o[4];
+};
+
+__device__ __forceinline__ PlaneOff plane_offsets(const uint32_t *rows, const uint32_t *planes, const uint32_t n_rows,
+                                                  const int b, const bool next, const int HW)
+{
+    PlaneOff p;
+    if (planes) {
+        const uint32_t *q = planes + (size_t)b * 8 + (next ? 4 : 0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) p.o[c] = (size_t)min(q[c], n_rows - 1u) * HW;
+    } else {
+        const uint32_t r = rows ? min(rows[b], n_rows - 1u) : (uint32_t)b;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) p.o[c] = ((size_t)r * 4 + c) * HW;
+    }
+    return p;
+}
+
+__device__ __forceinline__ void fetch_planes(PlaneRegs &p, const uint8_t *src, const PlaneOff &off, const int n_task,
                                              const int n_round, const int tid)
 {
 #pragma unroll
@@ -51,7 +74,7 @@ __device__ __forceinline__ void fetch_planes(PlaneRegs &p, const uint8_t *src, c
         const int t = tid + r * kThreads;
         if (r < n_round && t < n_task) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) p.px[r][c] = *(const uint32_t *)(src + (size_t)c * HW + 4 * t);
+            for (int c = 0; c < 4; ++c) p.px[r][c] = *(const uint32_t *)(src + off.o[c] + 4 * t);
         }
     }
 }
@@ -115,18 +138,16 @@ __global__ __launch_bounds__(kThreads) void conv_first_u8c4(const TjConvFirstArg
     PlaneRegs px;
     const int n_img = 2 * a.B;
     const int stride = (int)gridDim.x;
-    // Image g (s images first, then s') is row row_of(g) of its table: the batch position itself, or
-    // the caller's index for it.  Fetches go through the block's images in order, so the row of the
+    // Image g (s images first, then s') lies in its table at the batch position itself or where the
+    // caller's indices put it.  Fetches go through the block's images in order, so the place of the
     // next fetch is looked up right after the current one was issued, off the critical path.
-    auto row_of = [&](int g) -> uint32_t {
-        const uint32_t b = (uint32_t)(g < a.B ? g : g - a.B);
-        return a.rows ? min(a.rows[b], a.n_rows - 1u) : b;
+    auto where = [&](int g) -> PlaneOff {
+        return plane_offsets(a.rows, a.planes, a.n_rows, g < a.B ? g : g - a.B, g >= a.B, HW);
     };
-    uint32_t row_next = (int)blockIdx.x < n_img ? row_of((int)blockIdx.x) : 0u;
+    PlaneOff off_next = where((int)blockIdx.x < n_img ? (int)blockIdx.x : 0);
     auto fetch = [&](int g) {
-        const uint8_t *src = (g < a.B ? a.obs : a.next_obs) + (size_t)row_next * 4 * HW;
-        fetch_planes(px, src, HW, n_task, n_round, tid);
-        if (g + stride < n_img) row_next = row_of(g + stride);
+        fetch_planes(px, g < a.B ? a.obs : a.next_obs, off_next, n_task, n_round, tid);
+        if (g + stride < n_img) off_next = where(g + stride);
     };
     auto convert = [&](int g, uint8_t *img) {         // ... and the channels-last copy of an s image
         tj_bf16 *keep = g < a.B && a.act0 ? a.act0 + (size_t)g * HW * 4 : nullptr;
@@ -307,11 +328,10 @@ __global__ __launch_bounds__(kThreads) void conv_first_wgrad_u8c4(const TjConvFi
     const int stride = (int)gridDim.x;
     int g = blockIdx.x;
     if (g >= a.B) return;                // the host launches at most B blocks
-    // table row of an s image, as in the forward kernel; the next fetch's row is looked up one image ahead
-    auto row_of = [&](int b) -> uint32_t { return a.rows ? min(a.rows[b], a.n_rows - 1u) : (uint32_t)b; };
-    uint32_t row_next = row_of(g);
-    fetch_planes(px, a.obs + (size_t)row_next * 4 * HW, HW, n_task, n_round, tid);
-    if (g + stride < a.B) row_next = row_of(g + stride);
+    // place of an s image in its table, as in the forward kernel; the next fetch's is looked up one image ahead
+    PlaneOff off_next = plane_offsets(a.rows, a.planes, a.n_rows, g, false, HW);
+    fetch_planes(px, a.obs, off_next, n_task, n_round, tid);
+    if (g + stride < a.B) off_next = plane_offsets(a.rows, a.planes, a.n_rows, g + stride, false, HW);
     dma_dz(g, dzb);
     int cur = 0;
     for (; g < a.B; g += stride) {
@@ -320,8 +340,8 @@ __global__ __launch_bounds__(kThreads) void conv_first_wgrad_u8c4(const TjConvFi
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of dZ(g) has landed
         __syncthreads();                 // image and dZ rows complete
         if (g + stride < a.B) {          // in flight during the MFMAs below
-            fetch_planes(px, a.obs + (size_t)row_next * 4 * HW, HW, n_task, n_round, tid);
-            if (g + 2 * stride < a.B) row_next = row_of(g + 2 * stride);
+            fetch_planes(px, a.obs, off_next, n_task, n_round, tid);
+            if (g + 2 * stride < a.B) off_next = plane_offsets(a.rows, a.planes, a.n_rows, g + 2 * stride, false, HW);
             dma_dz(g + stride, dzb + (cur ^ 1) * dz_bytes);
         }
         const uint8_t *dz = dzb + cur * dz_bytes + a_lane, *pim = img + b_lane;
@@ -403,7 +423,8 @@ int tj_conv_first(const TjConvFirstArgs &a, hipStream_t st)
     if (a.B < 1 || !tj_conv_first_fits(4, a.H, a.W, a.k, a.s, 32)) return TJ_ERR_SHAPE;
     if (a.OH != (a.H - a.k) / a.s + 1 || a.OW != (a.W - a.k) / a.s + 1) return TJ_ERR_SHAPE;
     if ((((uintptr_t)a.obs | (uintptr_t)a.next_obs) & 3) != 0) return TJ_ERR_INVALID_ARG;
-    if (a.rows && a.n_rows == 0) return TJ_ERR_INVALID_ARG;
+    if ((a.rows || a.planes) && a.n_rows == 0) return TJ_ERR_INVALID_ARG;
+    if (a.rows && a.planes) return TJ_ERR_INVALID_ARG;
     const bool two = tj_conv_first_lds_bytes(a.H, a.W, a.k, 2) <= kLdsLimit;
     const size_t lds = tj_conv_first_lds_bytes(a.H, a.W, a.k, two ? 2 : 1);
     static bool attr_set = false;
@@ -458,7 +479,8 @@ int tj_conv_first_wgrad(const TjConvFirstWgradArgs &a, hipStream_t st)
     if (a.OH != (a.H - a.k) / a.s + 1 || a.OW != (a.W - a.k) / a.s + 1) return TJ_ERR_SHAPE;
     if (a.zstride < (size_t)32 * 4 * a.k * a.k + 32) return TJ_ERR_SHAPE;
     if ((((uintptr_t)a.obs) & 3) != 0 || (((uintptr_t)a.dZ) & 15) != 0) return TJ_ERR_INVALID_ARG;
-    if (a.rows && a.n_rows == 0) return TJ_ERR_INVALID_ARG;
+    if ((a.rows || a.planes) && a.n_rows == 0) return TJ_ERR_INVALID_ARG;
+    if (a.rows && a.planes) return TJ_ERR_INVALID_ARG;
     const size_t lds = conv_first_wgrad_lds_bytes(a.H, a.W, a.k, a.OH * a.OW);
     static bool attr_set = false;
     if (!attr_set) {

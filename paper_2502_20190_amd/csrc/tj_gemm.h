@@ -171,6 +171,8 @@ struct TjConvFirstArgs {
     float scale;
     const uint32_t *rows;   // optional: image b of s / s' is row min(rows[b], n_rows - 1) of obs / next_obs
     uint32_t n_rows;
+    const uint32_t *planes; // optional (not with rows): obs = next_obs = a table of n_rows planes of H*W bytes;
+                            // channel c of s_b is plane min(planes[8b + c], n_rows - 1), of s'_b planes[8b + 4 + c]
 };
 bool tj_conv_first_fits(int C, int H, int W, int k, int s, int O);
 int tj_conv_first(const TjConvFirstArgs &a, hipStream_t st);
@@ -190,6 +192,7 @@ struct TjConvFirstWgradArgs {
     int n_part;
     const uint32_t *rows;   // optional, as in TjConvFirstArgs
     uint32_t n_rows;
+    const uint32_t *planes; // optional, as in TjConvFirstArgs (the s planes)
 };
 bool tj_conv_first_wgrad_fits(int C, int H, int W, int k, int s, int O);
 int tj_conv_first_wgrad(const TjConvFirstWgradArgs &a, hipStream_t st);

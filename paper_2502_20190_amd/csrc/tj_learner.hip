@@ -1198,6 +1198,7 @@ template <typename T> struct MlpLearner : tj_learner {
         if (B < 1 || B > Bmax) return TJ_ERR_SHAPE;
         if (!mb->obs || !mb->next_obs || !mb->action || !mb->reward || !mb->done) return TJ_ERR_INVALID_ARG;
         if (mb->row_index && (mb->n_rows == 0 || mb->n_rows > 0xFFFFFFFFull)) return TJ_ERR_INVALID_ARG;
+        if (mb->plane_index) return TJ_ERR_INVALID_ARG;   // planes are channels of an image: pixel networks only
         int rc;
         if (last_batch != B) {
             // pad columns beyond the batch must read as zero in the batch contraction
@@ -1925,7 +1926,9 @@ template <typename T> struct ConvLearner : tj_learner {
         const int B = (int)mb->batch;
         if (B < 1 || B > Bmax) return TJ_ERR_SHAPE;
         if (!mb->obs || !mb->next_obs || !mb->action || !mb->reward || !mb->done) return TJ_ERR_INVALID_ARG;
-        if (mb->row_index && (mb->n_rows == 0 || mb->n_rows > 0xFFFFFFFFull)) return TJ_ERR_INVALID_ARG;
+        if ((mb->row_index || mb->plane_index) && (mb->n_rows == 0 || mb->n_rows > 0xFFFFFFFFull))
+            return TJ_ERR_INVALID_ARG;
+        if (mb->row_index && mb->plane_index) return TJ_ERR_INVALID_ARG;
         int rc;
         if (last_batch != B) {
             if (last_batch > B && (rc = launch_zero(act_begin, act_bytes, st)) != TJ_OK) return rc;
@@ -1944,7 +1947,7 @@ template <typename T> struct ConvLearner : tj_learner {
                 fa.b_on = theta_on + lay[0].b_off; fa.b_tg = theta_tg + lay[0].b_off;
                 fa.act0 = first_wgrad_u8 ? nullptr : act[0]; fa.out = act[1];
                 fa.scale = 1.0f / 255.0f;
-                fa.rows = mb->row_index; fa.n_rows = (uint32_t)mb->n_rows;
+                fa.rows = mb->row_index; fa.n_rows = (uint32_t)mb->n_rows; fa.planes = mb->plane_index;
                 if ((rc = mark(0, st)) != TJ_OK) return rc;
                 if ((rc = tj_conv_first(fa, st)) != TJ_OK) return rc;
                 first_done = true;
@@ -1955,6 +1958,8 @@ template <typename T> struct ConvLearner : tj_learner {
             const size_t px = (size_t)B * g.H * g.W, img = (size_t)g.H * g.W * g.C;
             const uint32_t *rows = mb->row_index;
             const uint32_t n_rows = (uint32_t)mb->n_rows;
+            // by planes: channel c of s_j is plane_index[2C j + c], of s'_j plane_index[2C j + C + c]
+            const uint32_t *pl_s = mb->plane_index, *pl_n = mb->plane_index ? mb->plane_index + g.C : nullptr;
             bool fast = false;
             if constexpr (sizeof(T) == 2) {
                 fast = d.obs_dtype == TJ_OBS_U8 && g.C == 4 && (g.H * g.W) % 8 == 0 &&
@@ -1962,25 +1967,25 @@ template <typename T> struct ConvLearner : tj_learner {
                 if (fast) {
                     const size_t groups = (size_t)B * (g.H * g.W / 8);
                     tjconv::to_nhwc_u8c4<<<grid1(groups), 256, 0, st>>>((const uint8_t *)mb->obs, act[0], (size_t)B,
-                                                                        g.H * g.W, 1.0f / 255.0f, rows, n_rows);
+                                                                        g.H * g.W, 1.0f / 255.0f, rows, n_rows, pl_s);
                     tjconv::to_nhwc_u8c4<<<grid1(groups), 256, 0, st>>>((const uint8_t *)mb->next_obs,
                                                                         act[0] + (size_t)B * img, (size_t)B,
-                                                                        g.H * g.W, 1.0f / 255.0f, rows, n_rows);
+                                                                        g.H * g.W, 1.0f / 255.0f, rows, n_rows, pl_n);
                 }
             }
             if (fast) {
             } else if (d.obs_dtype == TJ_OBS_U8) {
                 tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->obs, act[0], B, g.C, g.H,
-                                                                       g.W, 1.0f / 255.0f, rows, n_rows);
+                                                                       g.W, 1.0f / 255.0f, rows, n_rows, pl_s);
                 tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)mb->next_obs,
                                                                        act[0] + (size_t)B * img, B, g.C, g.H, g.W,
-                                                                       1.0f / 255.0f, rows, n_rows);
+                                                                       1.0f / 255.0f, rows, n_rows, pl_n);
             } else {
                 tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)mb->obs, act[0], B, g.C, g.H, g.W,
-                                                                     1.0f, rows, n_rows);
+                                                                     1.0f, rows, n_rows, pl_s);
                 tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)mb->next_obs,
                                                                      act[0] + (size_t)B * img, B, g.C, g.H, g.W, 1.0f,
-                                                                     rows, n_rows);
+                                                                     rows, n_rows, pl_n);
             }
             if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
             if ((rc = mark(0, st)) != TJ_OK) return rc;
@@ -2120,7 +2125,7 @@ template <typename T> struct ConvLearner : tj_learner {
                     wa.obs = (const uint8_t *)mb->obs; wa.dZ = y.dZ;
                     wa.B = B; wa.H = g.H; wa.W = g.W; wa.k = g.k; wa.s = g.s; wa.OH = g.OH; wa.OW = g.OW;
                     wa.scale = 1.0f / 255.0f;
-                    wa.rows = mb->row_index; wa.n_rows = (uint32_t)mb->n_rows;
+                    wa.rows = mb->row_index; wa.n_rows = (uint32_t)mb->n_rows; wa.planes = mb->plane_index;
                     wa.part = y.part; wa.zstride = y.part_stride;
                     wa.n_part = std::min(B, std::min(n_cu, y.n_split));
                     if ((rc = tj_conv_first_wgrad(wa, st)) != TJ_OK) return rc;
@@ -2309,15 +2314,15 @@ template <typename T> struct ConvLearner : tj_learner {
                 fast = d.obs_dtype == TJ_OBS_U8 && g.C == 4 && (g.H * g.W) % 8 == 0 && ((uintptr_t)d_obs & 7) == 0;
                 if (fast)
                     tjconv::to_nhwc_u8c4<<<grid1((size_t)n * (g.H * g.W / 8)), 256, 0, st>>>(
-                        (const uint8_t *)d_obs, act[0], (size_t)n, g.H * g.W, 1.0f / 255.0f, nullptr, 0u);
+                        (const uint8_t *)d_obs, act[0], (size_t)n, g.H * g.W, 1.0f / 255.0f, nullptr, 0u, nullptr);
             }
             if (!fast) {
                 if (d.obs_dtype == TJ_OBS_U8)
                     tjconv::to_nhwc<T, uint8_t><<<grid1(px), 256, 0, st>>>((const uint8_t *)d_obs, act[0], n, g.C, g.H,
-                                                                           g.W, 1.0f / 255.0f, nullptr, 0u);
+                                                                           g.W, 1.0f / 255.0f, nullptr, 0u, nullptr);
                 else
                     tjconv::to_nhwc<T, float><<<grid1(px), 256, 0, st>>>((const float *)d_obs, act[0], n, g.C, g.H, g.W,
-                                                                         1.0f, nullptr, 0u);
+                                                                         1.0f, nullptr, 0u, nullptr);
             }
             if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         }

@@ -189,3 +189,110 @@ def test_insert_after_reads_done_waits_for_the_update(tj):
     torch.cuda.synchronize()
     assert np.array_equal(lrn.get_state(tj.TJ_STATE_PARAMS), ref[0])
     assert torch.equal(buf.field("obs"), dev["obs"])         # and the insert did run
+
+
+# ---------------------------------------------------------------- frame ring: indirect by planes
+
+def _frame_stream(rng, n, frame_elems, done_p, t0=0):
+    frames = rng.integers(0, 256, (n, frame_elems)).astype(np.uint8)
+    done = (rng.random(n) < done_p).astype(np.uint8)
+    return (frames, rng.integers(0, 18, n).astype(np.int32), rng.uniform(-1, 1, n).astype(np.float32), done,
+            ((t0 + np.arange(n)) // 50).astype(np.int32))
+
+
+def _fill_frame_rings(tj, orc, rng, frame_elems, cap, total, k):
+    """The same ragged, wrapping inserts into the library's ring, the oracle's ring and a plain
+    host mirror of the frame slots."""
+    g = tj.FrameBuffer(cap, frame_elems, k)
+    o = orc.FrameBuffer(cap, frame_elems, k) if orc is not None else None
+    mirror = np.zeros((cap, frame_elems), np.uint8)
+    pos = 0
+    while pos < total:
+        n = int(min(total - pos, rng.integers(1, min(900, cap) + 1)))
+        rows = _frame_stream(rng, n, frame_elems, 0.02, pos)
+        assert g.insert_host(*rows) == tj.TJ_OK
+        if o is not None:
+            assert o.insert(*rows) == 0
+        mirror[(pos + np.arange(n)) % cap] = rows[0]
+        pos += n
+    return g, o, mirror
+
+
+@pytest.mark.parametrize("frame_elems,cap,total,k", [(7056, 1500, 5300, 4), (100, 4096, 9000, 4), (37, 700, 2500, 3)])
+def test_frame_plane_slots_against_the_oracle(tj, orc, frame_elems, cap, total, k):
+    """A frame sample without stack destinations: the frames its plane slots name, read from a host
+    mirror of the ring, are the oracle's rebuilt stacks (so every slot, with its look-back clamped
+    at episode starts and wrapped around the ring, is the right one)."""
+    rng = np.random.default_rng(frame_elems + cap + 1)
+    g, o, mirror = _fill_frame_rings(tj, orc, rng, frame_elems, cap, total, k)
+    cur = (total - 1) // 50
+    for seed, max_st, batch in ((1, 3, 64), (2, 0, 17), (3, 1000, 256)):
+        mb = tj.Minibatch(batch, frame_elems * k, "u8", ring=g)
+        assert g.sample(mb, cur, max_st, seed) == tj.TJ_OK
+        st, info = g.status()
+        ost, oidx, oK = o.sample(batch, cur, max_st, seed)
+        assert st == ost == 0 and info.last_n_eligible == oK
+        got = mb.host()
+        np.testing.assert_array_equal(got["idx"], oidx)
+        want = o.gather(oidx)
+        for f in ("action", "reward", "done"):
+            np.testing.assert_array_equal(got[f], want[f], err_msg=f)
+        planes = got["planes"]
+        assert planes.shape == (batch, 2 * k) and planes.max() < cap
+        np.testing.assert_array_equal(mirror[planes[:, :k]].reshape(batch, -1), want["obs"])
+        np.testing.assert_array_equal(mirror[planes[:, k:]].reshape(batch, -1), want["next_obs"])
+
+
+_FRAME_CASES = {
+    # the u8 first-layer kernels (forward and weight gradient) reading single frames
+    "fused-84": dict(hw=(84, 84), k=4, cap=700, total=1900, batch=96, precision="bf16",
+                     layers=((CONV, 32, 8, 4), (CONV, 64, 4, 2), (LIN, 24, 0, 0), (LIN, 18, 0, 0))),
+    # the channels-last layout kernels: four u8 planes at a time, and the general one (three planes, fp32 net)
+    "plain-u8c4": dict(hw=(20, 20), k=4, cap=600, total=1500, batch=40, precision="bf16",
+                       layers=((CONV, 16, 4, 2), (CONV, 16, 3, 1), (LIN, 24, 0, 0), (LIN, 18, 0, 0))),
+    "plain-fp32": dict(hw=(18, 18), k=3, cap=600, total=1500, batch=40, precision="fp32",
+                       layers=((CONV, 8, 4, 2), (CONV, 16, 3, 1), (LIN, 32, 0, 0), (LIN, 18, 0, 0))),
+}
+
+
+@pytest.mark.parametrize("case", sorted(_FRAME_CASES))
+def test_update_from_frame_planes_equals_update_from_stacks(tj, case):
+    import torch
+
+    c = _FRAME_CASES[case]
+    (H, W), k = c["hw"], c["k"]
+    wl = replace(synth.small_variant(synth.WORKLOADS["c4"], c["cap"], c["batch"]), obs_shape=(k, H, W),
+                 layers=c["layers"], precision=c["precision"], n_actions=18)
+    theta = synth.xavier_init(wl.layers, wl.in_chw, 3)
+    target = synth.xavier_init(wl.layers, wl.in_chw, 4)
+    cur = (c["total"] - 1) // 50
+    out = []
+    for indirect in (False, True):
+        g, _, _ = _fill_frame_rings(tj, None, np.random.default_rng(5), H * W, c["cap"], c["total"], k)
+        lrn = tj.learner_for_workload(wl, theta, target)
+        mb = tj.Minibatch(wl.batch, wl.obs_elems, "u8", ring=g if indirect else None)
+        losses = []
+        for i in range(3):
+            assert g.sample(mb, cur, 5, 900 + i) == tj.TJ_OK
+            assert lrn.step(mb) == tj.TJ_OK
+            losses.append(lrn.read_stats()[0])
+        torch.cuda.synchronize()
+        assert g.status()[0] == tj.TJ_OK
+        out.append(([lrn.get_state(w) for w in (tj.TJ_STATE_PARAMS, tj.TJ_STATE_ADAM_M, tj.TJ_STATE_ADAM_V)], losses))
+    for a, b in zip(out[0][0], out[1][0]):
+        assert np.array_equal(a, b)
+    assert out[0][1] == out[1][1]
+    assert not np.array_equal(out[0][0][0], theta)
+
+
+def test_frame_planes_argument_checks(tj):
+    g, _, _ = _fill_frame_rings(tj, None, np.random.default_rng(6), 64, 64, 40, 4)
+    mb = tj.Minibatch(8, 256, "u8", ring=g)
+    mb.c.plane_index = None                                  # no stacks and nowhere to put the slots
+    assert g.sample(mb, 0, 10, 1) == tj.TJ_ERR_INVALID_ARG
+    wl = _workload("mlp-fp32")                               # planes are image channels: not for an MLP
+    theta = synth.xavier_init(wl.layers, wl.in_chw, 3)
+    lrn = tj.learner_for_workload(wl, theta, theta)
+    m2 = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype, ring=tj.Buffer(wl.capacity, wl.obs_elems, wl.obs_dtype))
+    m2.c_step.plane_index = m2.idx.data_ptr()
+    assert lrn.step(m2) == tj.TJ_ERR_INVALID_ARG
