@@ -312,7 +312,7 @@ struct ReduceJobs {
 
 // Elements one block reduces: 4 * kRedCols, or 1024 where a job has at most kReduceFew slices.
 constexpr int kReduceFew = 8;
-constexpr int kRedCols = 8, kRedGroups = 256 / kRedCols;
+constexpr int kRedCols = 16, kRedGroups = 256 / kRedCols;
 inline unsigned reduce_blocks(size_t n, int n_part)
 {
     const size_t per = n_part <= kReduceFew ? 1024 : 4 * kRedCols;
@@ -347,8 +347,8 @@ __global__ __launch_bounds__(256) void reduce_parts(const ReduceJobs jobs)
             if (e + k < n) dst[e + k] = out[k];
         return;
     }
-    // many slices of a short vector (a convolution's row split): a block owns kRedCols float4 columns (one
-    // 128-byte line per slice); its kRedGroups thread rows each add every kRedGroups-th slice, eight loads in
+    // many slices of a short vector (a convolution's row split): a block owns kRedCols float4 columns (256
+    // bytes per slice); its kRedGroups thread rows each add every kRedGroups-th slice, eight loads in
     // flight, then the row sums are added in row order
     const int col = threadIdx.x % kRedCols, grp = threadIdx.x / kRedCols;
     const size_t e = ((size_t)(blockIdx.x - jobs.block_begin[q]) * kRedCols + col) * 4;

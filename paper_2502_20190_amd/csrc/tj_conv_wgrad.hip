@@ -11,11 +11,14 @@
 // values taken from four consecutive LDS rows, i.e. lane i, element j = row j, column i of a
 // 4 x 16 block whose rows the group's lanes 4j .. 4j+3 point at (8 bytes each).
 //
-// Block: all O (32 or 64) output channels x 256 patch columns, 8 waves of 32 columns; the patch
-// rows are split over blockIdx (deterministic partial sums, reduced by the caller).  Stages of 32
-// patch rows go global -> LDS directly (global_load_lds_dwordx4) through a ring of 3 buffers with
-// explicit vmcnt accounting, as in the GEMM kernels.  LDS rows are XOR-swizzled on the global
-// side so that the 8 rows one transposing read touches fall into distinct bank groups.
+// Block: all O (32 or 64) output channels x 128 patch columns, 8 waves = 4 column waves of 32 columns x 2
+// row groups; the patch rows are split over blockIdx (deterministic partial sums, reduced by the
+// caller).  Stages of 64 patch rows go global -> LDS directly (global_load_lds_dwordx4) through a ring
+// of 3 buffers with explicit vmcnt accounting, as in the GEMM kernels; row group g contracts rows
+// 32 g .. 32 g + 31 of every stage, and the two groups' accumulators are added through LDS at the end
+// (group 0 + group 1).  Two row groups per block instead of twice as many row slices: the same number
+// of blocks and resident waves writes half as many partial results.  LDS rows are XOR-swizzled on the
+// global side so that the rows one transposing read touches fall into distinct bank groups.
 #include "tj_gemm.h"
 
 namespace {
@@ -27,9 +30,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
 typedef __attribute__((address_space(3))) uint8_t *lds_u8_ptr;
 
-constexpr int kBM = 32;          // patch rows per stage
+constexpr int kBM = 64;          // patch rows per stage (32 per row group)
 constexpr int kNST = 3;          // ring depth
-constexpr int kBJ = 256;         // patch columns per block
+constexpr int kBJ = 128;         // patch columns per block
 constexpr int kLPS = 3;          // direct loads per stage per wave: 2 of the patch tile, 1 of dZ
 
 __device__ __forceinline__ bf16x8 read_tr8(const uint8_t *p0, const uint8_t *p1)
@@ -53,11 +56,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void conv_wgrad_bf16(const TjConvWgradArgs a, const int njb)
 {
     constexpr int O = 32 * NFI;
-    constexpr int SZB = kBM * kBJ * 2;   // 16 KiB: 32 rows of 512 bytes
-    constexpr int SZA = kBM * O * 2;     // 2 or 4 KiB
+    constexpr int SZB = kBM * kBJ * 2;   // 16 KiB: 64 rows of 256 bytes
+    constexpr int SZA = kBM * O * 2;     // 4 or 8 KiB
     constexpr int NA = SZA / 1024;       // dZ load instructions per stage
     __shared__ __align__(1024) uint8_t sB[kNST * SZB];
     __shared__ __align__(1024) uint8_t sA[kNST * SZA];
+    static_assert(kNST * SZB >= (4 * NFI * 16 + NFI) * 64 * 4, "the ring doubles as the row groups' reduction scratch");
 
     // id % 8 is the XCD a block lands on: the column blocks of one row slice share an XCD (and
     // with it the L2 that holds the slice's image rows)
@@ -72,16 +76,17 @@ void conv_wgrad_bf16(const TjConvWgradArgs a, const int njb)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cw = wave & 3, rg = wave >> 2;   // column wave, row group
 
     // ---- loader roles
-    // patch tile: instruction c = wave + 8 t covers rows 2c, 2c+1 (512 bytes each); this lane
-    // fetches the 16-byte vector stored at position (lane & 31) of row 2c + (lane >> 5)
-    const int bsw = ((2 * wave + (lane >> 5)) & 3) << 2;        // swizzle of the lane's rows (same for t = 0, 1)
-    int kkB = j0 + 8 * ((lane & 31) ^ bsw);
+    // patch tile: instruction c = wave + 8 t covers rows 4c .. 4c+3 (256 bytes each); this lane
+    // fetches the 16-byte vector stored at position (lane & 15) of row 4c + (lane >> 4)
+    const int bsw = (lane >> 4) << 2;                           // swizzle of the lane's row: (row & 3) << 2
+    int kkB = j0 + 8 * ((lane & 15) ^ bsw);
     if (kkB >= a.K) kkB = 0;                                    // columns past the patch: loaded, never stored
     const int koffB = tj_gather_koff(a.g, kkB);
-    const int browB[2] = {2 * wave + (lane >> 5), 2 * (wave + 8) + (lane >> 5)};
-    // dZ tile: instruction ia = wave % NA
+    const int browB[2] = {4 * wave + (lane >> 4), 4 * (wave + 8) + (lane >> 4)};
+    // dZ tile: instruction ia = wave % NA (with 32 channels the upper four waves repeat the lower four's loads)
     const int ia = wave % NA;
     int arow, acol;
     if (NFI == 2) {   // 128-byte rows, 8 per instruction
@@ -110,8 +115,8 @@ void conv_wgrad_bf16(const TjConvWgradArgs a, const int njb)
     // ---- consumer roles: lane (n = lane % 32, h = lane / 32) of a wave feeds column n of the MFMA
     // operand with contraction values 8h .. 8h+7 of each 16-row step, as two transposing reads
     const int i16 = lane & 15, g2 = (lane >> 4) & 1, h = lane >> 5;
-    const int rowl = 8 * h + (i16 >> 2);
-    const int b_off = rowl * 512 + (((4 * wave + 2 * g2 + ((i16 & 3) >> 1)) ^ (((i16 >> 2) & 3) << 2)) << 4) + (i16 & 1) * 8;
+    const int rowl = 32 * rg + 8 * h + (i16 >> 2);
+    const int b_off = rowl * 256 + (((4 * cw + 2 * g2 + ((i16 & 3) >> 1)) ^ (((i16 >> 2) & 3) << 2)) << 4) + (i16 & 1) * 8;
     int a_off[NFI];
 #pragma unroll
     for (int fi = 0; fi < NFI; ++fi) {
@@ -126,7 +131,7 @@ void conv_wgrad_bf16(const TjConvWgradArgs a, const int njb)
     for (int fi = 0; fi < NFI; ++fi)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[fi][r] = 0.f;
-    const bool do_bias = jb == 0 && wave == 0;
+    const bool do_bias = jb == 0 && cw == 0;
     float bs[NFI];
 #pragma unroll
     for (int fi = 0; fi < NFI; ++fi) bs[fi] = 0.f;
@@ -146,8 +151,8 @@ void conv_wgrad_bf16(const TjConvWgradArgs a, const int njb)
         const uint8_t *pB = sB + (s % kNST) * SZB + b_off;
         const uint8_t *pA = sA + (s % kNST) * SZA;
 #pragma unroll
-        for (int ks = 0; ks < kBM / 16; ++ks) {
-            const bf16x8 bq = read_tr8(pB + (16 * ks) * 512, pB + (16 * ks + 4) * 512);
+        for (int ks = 0; ks < 2; ++ks) {   // the row group's 32 rows, 16 per step
+            const bf16x8 bq = read_tr8(pB + (16 * ks) * 256, pB + (16 * ks + 4) * 256);
 #pragma unroll
             for (int fi = 0; fi < NFI; ++fi) {
                 const int rb = O * 2;
@@ -158,9 +163,29 @@ void conv_wgrad_bf16(const TjConvWgradArgs a, const int njb)
         }
     }
 
-    // ---- partial results: acc[fi][r] = dW(o = 32 fi + 8 (r/4) + 4 h + r%4, k = j0 + 32 wave + lane%32)
+    // ---- the two row groups' sums: group 1 hands its accumulators over through the (now idle) ring
+    float *red = (float *)sB;   // [cw][fi][r][lane], then the bias sums [fi][lane]
+    __syncthreads();            // every wave has left the last stage
+    if (rg == 1) {
+#pragma unroll
+        for (int fi = 0; fi < NFI; ++fi) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) red[((cw * NFI + fi) * 16 + r) * 64 + lane] = acc[fi][r];
+            if (do_bias) red[(4 * NFI * 16 + fi) * 64 + lane] = bs[fi];
+        }
+    }
+    __syncthreads();
+    if (rg == 1) return;
+#pragma unroll
+    for (int fi = 0; fi < NFI; ++fi) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[fi][r] += red[((cw * NFI + fi) * 16 + r) * 64 + lane];
+        if (do_bias) bs[fi] += red[(4 * NFI * 16 + fi) * 64 + lane];
+    }
+
+    // ---- partial results: acc[fi][r] = dW(o = 32 fi + 8 (r/4) + 4 h + r%4, k = j0 + 32 cw + lane%32)
     float *out = a.part + (size_t)z * a.zstride;
-    const int kk = j0 + 32 * wave + (lane & 31);
+    const int kk = j0 + 32 * cw + (lane & 31);
     if (kk < a.K) {
 #pragma unroll
         for (int fi = 0; fi < NFI; ++fi)

@@ -148,12 +148,12 @@ int tj_gemm_pair_f32(const TjGemmArgs<float> &a0, const TjGemmArgs<float> &a1, h
 // channels-last layer input (bf16, 32 or 64 output channels), split over the patch rows:
 //   part[z][o*K + k] = sum over slice z of dZ[m][o] * patch[m][k],  part[z][O*K + o] = sum dZ[m][o].
 struct TjConvWgradArgs {
-    const tj_bf16 *dZ; int O;   // [M rounded up to 32][O]; rows past M must be zero
+    const tj_bf16 *dZ; int O;   // [M rounded up to 64][O]; rows past M must be zero
     const tj_bf16 *act;         // layer input [img][H][W][C]
     TjGather g;                 // patch geometry of this layer
     int M, K;                   // patches, patch length
     float *part; size_t zstride;
-    int n_split, m_chunk;       // patch rows per slice, a multiple of 32; n_split * m_chunk >= M
+    int n_split, m_chunk;       // patch rows per slice, a multiple of 64; n_split * m_chunk >= M
 };
 int tj_conv_wgrad(const TjConvWgradArgs &a, hipStream_t st);
 

@@ -1734,8 +1734,8 @@ template <typename T> struct ConvLearner : tj_learner {
                 if (ns > (size_t)Bmax / 256) ns = (size_t)Bmax / 256;
                 y.n_split = (int)(ns < 1 ? 1 : (ns > 8 ? 8 : ns));
             }
-            if (y.implicit) {   // about 512 blocks, each with at least four 32-row stages
-                const size_t njb = ((size_t)y.K + 255) / 256, stages = (Ms + 31) / 32;
+            if (y.implicit) {   // about 512 blocks (128 patch columns each), each with at least four 64-row stages
+                const size_t njb = ((size_t)y.K + 127) / 128, stages = (Ms + 63) / 64;
                 ns = 512 / njb;
                 if (ns > stages / 4) ns = stages / 4;
                 y.n_split = (int)(ns < 1 ? 1 : ns);
@@ -1776,9 +1776,9 @@ template <typename T> struct ConvLearner : tj_learner {
                 const size_t n_img = l == 0 ? 2 * B : 3 * B;
                 act[l] = (T *)a.take(n_img * y.g.H * y.g.W * y.g.C * sizeof(T));
                 y.XT = nullptr;
-                if (y.implicit) {   // no patch matrices; dZ rows padded (zero) to whole 32-row stages
+                if (y.implicit) {   // no patch matrices; dZ rows padded (zero) to whole 64-row stages
                     y.patches = y.patchesT = y.dZT = nullptr;
-                    y.dZ = (T *)a.take((B * y.OHW + 32) * y.O * sizeof(T));
+                    y.dZ = (T *)a.take((B * y.OHW + 64) * y.O * sizeof(T));
                 } else {
                     y.patches = (T *)a.take(n_img * y.OHW * y.ldK * sizeof(T));
                     y.patchesT = (T *)a.take((size_t)y.K * round_up((int)(B * y.OHW), VE) * sizeof(T));
@@ -2138,7 +2138,7 @@ template <typename T> struct ConvLearner : tj_learner {
                     wa.M = (int)Ms; wa.K = y.K;
                     wa.part = y.part; wa.zstride = y.part_stride;
                     wa.n_split = y.n_split;
-                    wa.m_chunk = round_up((int)((Ms + y.n_split - 1) / y.n_split), 32);
+                    wa.m_chunk = round_up((int)((Ms + y.n_split - 1) / y.n_split), 64);
                     if ((rc = tj_conv_wgrad(wa, st)) != TJ_OK) return rc;
                     add_reduce_job(y.part, y.part_stride, y.n_split, grad + y.w_off, (size_t)y.O * y.K + y.O);
                     wgrad_done = true;
