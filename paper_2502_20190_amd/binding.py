@@ -258,6 +258,9 @@ class Minibatch:
         """Fill from host arrays (tests feed the learner without a ring)."""
         import torch
 
+        if self.ring is not None:
+            raise ValueError("an indirect minibatch has no observation tensors to load")
+
         self.obs.copy_(torch.from_numpy(np.ascontiguousarray(obs)).reshape(self.obs.shape))
         self.next_obs.copy_(torch.from_numpy(np.ascontiguousarray(next_obs)).reshape(self.obs.shape))
         self.action.copy_(torch.from_numpy(np.ascontiguousarray(action, np.int32)))

@@ -234,6 +234,24 @@ def test_full_size_device_filled_ring(tj, orc, name):
         pi = torch.from_numpy(oidx.astype(np.int64)).cuda()
         for f in FIELDS:
             assert torch.equal(getattr(mb, f), gbuf.field(f)[pi]), f
+    # The update at this size and in the launch configuration bench.py times: a learner that reads the
+    # sampled rows out of the full ring through the indices (byte offsets far beyond 4 GiB) ends bit for
+    # bit where a learner fed the dense minibatch checked above ends.
+    theta = synth.xavier_init(wl.layers, wl.in_chw, 1)
+    target = synth.xavier_init(wl.layers, wl.in_chw, 2)
+    seed = 77 + sweeps[-1]
+    mbi = tj.Minibatch(wl.batch, wl.obs_elems, wl.obs_dtype, ring=gbuf)
+    assert gbuf.sample(mbi, wl.current_version, sweeps[-1], seed) == tj.TJ_OK
+    assert torch.equal(mbi.idx, mb.idx)
+    states = []
+    for m in (mb, mbi):
+        lrn = tj.learner_for_workload(wl, theta, target)
+        assert lrn.step(m) == tj.TJ_OK
+        _sync()
+        states.append((lrn.get_state(tj.TJ_STATE_PARAMS), lrn.get_state(tj.TJ_STATE_ADAM_V), lrn.read_stats()))
+        del lrn
+    assert np.array_equal(states[0][0], states[1][0]) and np.array_equal(states[0][1], states[1][1])
+    assert states[0][2] == states[1][2] and not np.array_equal(states[0][0], theta)
 
 
 # ---------------------------------------------------------------- inserts concurrent with sampling
