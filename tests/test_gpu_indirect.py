@@ -39,6 +39,8 @@ def _mlp(*outs):
 
 _CASES = {
     "mlp-fp32": dict(base="c2", capacity=20_000, batch=200, layers=_mlp(64, 64, 18)),
+    # rows of 7 floats: no 16-byte vector fits a row
+    "mlp-fp32-odd": dict(base="c1", capacity=3_000, batch=50, obs_shape=(7,), layers=_mlp(16, 16, 2)),
     "mlp-bf16": dict(base="c3", capacity=30_000, batch=1024, layers=_mlp(256, 256, 32)),
     "mlp-bf16-ragged": dict(base="c3", capacity=9_000, batch=333, layers=_mlp(128, 64, 32)),
     # 84 x 84 u8 stacks, the first-layer kernels that read the frames themselves (forward and weight gradient)
