@@ -32,8 +32,8 @@ sys.path.insert(0, ROOT)
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the sources it was taken with: the contraction
 # kernels and the learner that decides which of them a step launches.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip", "tj_conv.h", "tj_learner.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 697.1e6, "gemm_source_sha256_16": "7e23a50fdc5da59e"},
-                "c5": {"bytes_per_step": 1354.2e6, "gemm_source_sha256_16": "7e23a50fdc5da59e"}}
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 697.4e6, "gemm_source_sha256_16": "3367172a1d67362e"},
+                "c5": {"bytes_per_step": 1354.2e6, "gemm_source_sha256_16": "3367172a1d67362e"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
@@ -43,7 +43,8 @@ def gemm_flops_per_step(wl, synth, head_in_td_phase):
     passes (2*B*W each), weight gradients (2*B*W) and input gradients for every
     layer but the first (2*B*W_l).  Where the head layer's forward runs fused
     with the TD kernel (bf16, at most 32 actions) its flops are left out, since
-    its time falls into the TD phase, not the GEMM phases."""
+    its time falls into the TD phase, not the GEMM phases; so are those of the
+    head's input gradient where that kernel writes it (the layer below is linear)."""
     shapes = synth.layer_shapes(wl.layers, wl.in_chw)
     per_sample = []
     for kind, ws, fin, fout, out_chw in shapes:
@@ -53,6 +54,8 @@ def gemm_flops_per_step(wl, synth, head_in_td_phase):
         per_sample.append(2 * w * (out_chw[1] * out_chw[2] if kind == synth.CONV else 1))
     fwd = sum(per_sample[:-1] if head_in_td_phase else per_sample)
     bwd = sum(per_sample) + sum(per_sample[1:])
+    if head_in_td_phase and len(shapes) >= 2 and shapes[-2][0] != synth.CONV:
+        bwd -= per_sample[-1]      # the TD kernel also writes the head's input gradient
     return wl.batch * (3 * fwd + bwd)
 
 
@@ -219,9 +222,18 @@ def bench_ppo(args):
           "backward_gemm_ms": ms(lev, 2, 3), "adam_ms": ms(lev, 3, 4)}
     shapes = synth.layer_shapes(layers, (D, 1, 1))
     per_sample = [2 * int(np.prod(ws)) for _, ws, _, _, _ in shapes]
-    flops = B * (2 * sum(per_sample) + sum(per_sample[1:]))     # forward, weight and input gradients
     n_layers = len(layers)
-    n_launch = n_layers + (n_layers if precision == "bf16" else 2 * n_layers - 1)   # the on-policy head is a GEMM
+    # bf16 with at most 32 head outputs: the head's forward runs inside the objective kernel, so its
+    # flops are left out of the GEMM phases, as for the Q-learner's fused head
+    fused_head = precision == "bf16" and A + 1 <= 32 and n_layers >= 2
+    # ... and the head's input gradient too where the layer below takes it row-major (the library's conditions)
+    fused_dx = (fused_head and n_layers >= 3 and hidden[-1] % 32 == 0 and hidden[-1] <= 1024 and hidden[-2] % 8 == 0
+                and B % 32 == 0)
+    fwd = sum(per_sample[:-1] if fused_head else per_sample)
+    bwd = sum(per_sample) + sum(per_sample[1:]) - (per_sample[-1] if fused_dx else 0)
+    flops = B * (fwd + bwd)     # forward, weight and input gradients
+    n_launch = ((n_layers - (1 if fused_head else 0)) + (n_layers if precision == "bf16" else 2 * n_layers - 1)
+                - (1 if fused_dx else 0))
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
     achieved = flops / (gemm_ms * 1e-3) / 1e12
     P = synth.num_params(layers, (D, 1, 1))

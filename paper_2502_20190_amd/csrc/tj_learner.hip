@@ -752,16 +752,23 @@ template <typename T> struct PpoHeadArgs {
 constexpr int kPpoRows = 32;    // samples per block of ppo_head
 constexpr int kPpoLanes = 8;    // lanes per sample: lane g owns head outputs g, g + 8, ...
 
+// The objective for the block's 32 samples; `z` = this thread's sample's head outputs (global memory
+// or LDS), read only where the sample exists.
+constexpr int kPpoTileElems = kPpoRows * (64 + 8);   // A + 1 <= 64 columns, plus one 16-byte vector per row (bf16: 8 elements)
+template <typename T> __device__ __forceinline__ int ppo_tile_cols(int A) { return (A + 1 + 16 / (int)sizeof(T) - 1) / (16 / (int)sizeof(T)) * (16 / (int)sizeof(T)); }
+
+// `tile` ([kPpoRows][cols + one vector], kPpoTileElems elements) receives the block's gradient rows, zero
+// in the pad columns (bf16: up to the next multiple of 16); `red` is scratch for the block sums.
 template <typename T>
-__global__ __launch_bounds__(kPpoRows * kPpoLanes) void ppo_head(const PpoHeadArgs<T> a)
+__device__ __forceinline__ void ppo_objective(const PpoHeadArgs<T> &a, const float *z, T *tile,
+                                              float (*red)[3])
 {
     constexpr int VEC = 16 / (int)sizeof(T);
-    constexpr int kMaxCols = 64 + VEC;               // A + 1 <= 64, rounded up to whole vectors, plus one
     constexpr int NI = 64 / kPpoLanes;               // head outputs per lane, at most
-    __shared__ __align__(16) T tile[kPpoRows * kMaxCols];
-    __shared__ float red[kPpoRows * kPpoLanes / 64][3];
-    const int cols = (a.A + 1 + VEC - 1) / VEC * VEC;  // row-major columns written per sample (<= lddz)
+    const int cols = ppo_tile_cols<T>(a.A);            // row-major columns written per sample (<= lddz)
     const int pitch = cols + VEC;                      // odd number of vectors: rows spread over the banks
+    // bf16: the fused head kernel contracts over the columns in steps of 16 (cols + 8 >= the next multiple of 16)
+    const int cols16 = sizeof(T) == 2 ? (cols + 15) / 16 * 16 : cols;
     const int row0 = blockIdx.x * kPpoRows;
     const int r = threadIdx.x / kPpoLanes, g = threadIdx.x % kPpoLanes;
     const int j = row0 + r;
@@ -772,7 +779,6 @@ __global__ __launch_bounds__(kPpoRows * kPpoLanes) void ppo_head(const PpoHeadAr
     };
     float l_pi = 0.f, l_v = 0.f, H = 0.f;
     if (j < a.B) {   // uniform over a sample's lanes
-        const float *z = a.Z + (size_t)j * a.ldz;
         float zv[NI];
         float mx = -INFINITY;
 #pragma unroll
@@ -813,7 +819,7 @@ __global__ __launch_bounds__(kPpoRows * kPpoLanes) void ppo_head(const PpoHeadAr
                 row[k] = TjElem<T>::from_f32(gr * inv_b);
             } else if (k == a.A) {
                 row[k] = TjElem<T>::from_f32(2.f * a.c_v * verr * inv_b);
-            } else if (k < cols) {
+            } else if (k < cols16) {
                 row[k] = TjElem<T>::from_f32(0.f);
             }
         }
@@ -844,6 +850,209 @@ __global__ __launch_bounds__(kPpoRows * kPpoLanes) void ppo_head(const PpoHeadAr
     for (int e = threadIdx.x; e < (a.A + 1) * kPpoRows; e += kPpoRows * kPpoLanes) {
         const int k = e / kPpoRows, rr = e % kPpoRows;
         if (rr < n_rows) a.dZT[(size_t)k * a.lddzt + row0 + rr] = tile[rr * pitch + k];
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kPpoRows * kPpoLanes) void ppo_head(const PpoHeadArgs<T> a)
+{
+    __shared__ __align__(16) T tile[kPpoTileElems];
+    __shared__ float red[kPpoRows * kPpoLanes / 64][3];
+    const size_t j = (size_t)blockIdx.x * kPpoRows + threadIdx.x / kPpoLanes;
+    ppo_objective<T>(a, a.Z + j * a.ldz, tile, red);
+}
+
+// The head layer's forward and the objective in one kernel (bf16, at most 32 head outputs): the
+// contraction of the Q-learner's fused head kernel for one tile of 32 samples (4 waves split it, each
+// streaming its own operand pieces through a wave-private swizzled LDS slab), then the objective on
+// the head outputs where they lie in LDS.  The outputs are also written to Z (fp32), as the head GEMM
+// would have left them.
+constexpr int kPpoFusedMaxK = 1024;   // widest head input whose input gradient the fused kernel takes
+struct PpoFusedArgs {
+    PpoHeadArgs<tj_bf16> h;            // h.Z: destination of the head outputs
+    const tj_bf16 *X; int ldx;         // head input [B][ldx]
+    const tj_bf16 *W; int ldw;         // [A + 1][ldw]
+    const float *bias;
+    int K;
+    // optional: the head's input gradient dX[j][k] = relu'(X[j][k]) sum_o dZ[j][o] W[o][k], from the
+    // transposed weight copy WT [K][ldwt] (pad columns zero, ldwt >= the head outputs rounded up to 16);
+    // needs K % 32 == 0
+    const tj_bf16 *WT; int ldwt;
+    tj_bf16 *dX; int lddx;
+};
+
+__global__ __launch_bounds__(kPpoRows * kPpoLanes) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void ppo_head_fused(const PpoFusedArgs a)
+{
+    // at most 32 head outputs: gradient rows of 32 columns plus one vector
+    __shared__ __align__(16) tj_bf16 tile[kPpoRows * 40];
+    __shared__ float red[kPpoRows * kPpoLanes / 64][3];
+    constexpr int NW = kPpoRows * kPpoLanes / 64;   // 4 waves
+    // 32 KiB of slabs, 35 KB per block in all: four blocks per CU, so that 32768 samples are one round.
+    // During the contraction: per wave 256 16-byte slots of X and 256 of W.  Afterwards: the waves' partial
+    // tiles [0, 18 K), the summed head outputs behind them, the sign bits of the head's input (one byte
+    // per 8 columns, the input gradient's ReLU mask) at 24 K; last, per wave 4 KiB of gradient rows at 0.
+    __shared__ headu32x4 stage[NW][2][256];
+    typedef float PartTile[kPpoRows][36];
+    typedef float OutTile[kPpoRows][33];
+    constexpr int kMaskAt = 24576, kMaskPitch = kPpoFusedMaxK / 8;
+    static_assert(sizeof(PartTile) * NW + sizeof(OutTile) <= kMaskAt, "partial and output tiles end before the mask bytes");
+    static_assert(kMaskAt + kPpoRows * kMaskPitch <= (int)sizeof(stage) && NW * 4096 <= kMaskAt, "mask bytes and row slabs fit");
+    PartTile *part = (PartTile *)&stage[0][0][0];
+    OutTile &zs = *(OutTile *)((uint8_t *)&stage[0][0][0] + sizeof(PartTile) * NW);
+    uint8_t *xmask = (uint8_t *)&stage[0][0][0] + kMaskAt;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int j0 = blockIdx.x * kPpoRows, n_out = a.h.A + 1;
+    const tj_bf16 *xbase = a.X + (size_t)j0 * a.ldx;
+    const headu32x4 zero = {0u, 0u, 0u, 0u};
+    const int lrow = lane >> 3, lpiece = lane & 7;   // loader role: row 8 t + lrow, 16-byte piece lpiece
+    const int n_trip = (a.K + 63) / 64;
+    const bool keep_mask = a.dX != nullptr;           // then K <= kPpoFusedMaxK: at most 4 trips per wave
+    uint32_t mreg[4] = {0u, 0u, 0u, 0u};              // sign bits of this lane's operand pieces: byte s of word (trip - w) / NW
+    headf32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    headu32x4 xr[2][4], wr[2][4];   // two trips of loads stay in flight per wave
+    // block-uniform bases + 32-bit byte offsets per lane (a tile's rows span well under 4 GiB)
+    const uint8_t *xb = (const uint8_t *)xbase, *wb = (const uint8_t *)a.W;
+    auto fetch = [&](int set, int trip) {
+        const int k = trip * 64 + lpiece * 8;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int row = 8 * t + lrow;
+            const uint32_t xo = (uint32_t)(row * a.ldx + k) * 2u, wo = (uint32_t)(row * a.ldw + k) * 2u;
+            xr[set][t] = (k < a.K && j0 + row < a.h.B) ? *(const headu32x4 *)(xb + xo) : zero;
+            wr[set][t] = (k < a.K && row < n_out) ? *(const headu32x4 *)(wb + wo) : zero;
+        }
+    };
+    auto consume = [&](int set, int trip) {
+        head_wave_sync();   // the last trip's operand reads precede these writes
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int row = 8 * t + lrow, slot = 8 * row + (lpiece ^ (row & 7));
+            stage[w][0][slot] = xr[set][t];
+            stage[w][1][slot] = wr[set][t];
+        }
+        head_wave_sync();
+        uint32_t word = 0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int slot = 8 * r + ((2 * s + h) ^ (r & 7));
+            const headu32x4 xv = stage[w][0][slot];   // columns 64 trip + 8 (2s + h) .. + 7 of sample r
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(headbf16x8, stage[w][1][slot]),
+                                                          __builtin_bit_cast(headbf16x8, xv), acc, 0, 0, 0);
+            if (keep_mask) {   // bit e of byte s: element e of this piece is positive
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    word |= ((int16_t)(xv[u] & 0xFFFFu) > 0 ? 1u : 0u) << (8 * s + 2 * u);
+                    word |= ((int16_t)(xv[u] >> 16) > 0 ? 1u : 0u) << (8 * s + 2 * u + 1);
+                }
+            }
+        }
+        if (keep_mask) {
+            const int i = (trip - w) / NW;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mreg[q] = i == q ? word : mreg[q];
+        }
+    };
+    fetch(0, w);
+    fetch(1, w + NW);
+    for (int trip = w; trip < n_trip; trip += 2 * NW) {
+        consume(0, trip);
+        fetch(0, trip + 2 * NW);
+        consume(1, trip + NW);
+        fetch(1, trip + 3 * NW);
+    }
+    __syncthreads();   // every wave is done with its slab before the partial tiles overwrite them
+    // acc[4*q + e] = partial output 8*q + 4*h + e of sample r
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        *(float4 *)&part[w][r][8 * q + 4 * h] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    if (keep_mask) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int trip = w + NW * i;
+            if (trip >= n_trip) continue;
+#pragma unroll
+            for (int sp = 0; sp < 4; ++sp) xmask[r * kMaskPitch + trip * 8 + 2 * sp + h] = (uint8_t)(mreg[i] >> (8 * sp));
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < kPpoRows * 32; e += kPpoRows * kPpoLanes) {
+        const int j = e >> 5, i = e & 31;
+        float z = part[0][j][i];
+#pragma unroll
+        for (int s = 1; s < NW; ++s) z += part[s][j][i];
+        if (i < n_out) z += a.bias[i];
+        zs[j][i] = z;
+        if (i < n_out && j0 + j < a.h.B) const_cast<float *>(a.h.Z)[(size_t)(j0 + j) * a.h.ldz + i] = z;
+    }
+    __syncthreads();
+    ppo_objective<tj_bf16>(a.h, &zs[threadIdx.x / kPpoLanes][0], tile, red);
+    if (!a.dX) return;   // block-uniform
+
+    // ---- input gradient of the head layer for the block's 32 samples.  Per 32 columns k one MFMA tile
+    // D(k, sample) = sum_o WT[k][o] dZ[sample][o] (one or two 16-wide steps over the head outputs); a
+    // wave takes pairs of such tiles, stages them as [sample][64 columns] in its slab (vector v of row r
+    // at v ^ (r & 7)) and writes rows of 128 bytes, masked with the sign bits kept from the contraction.
+    __syncthreads();     // the partial tiles and head outputs have been read: the slabs are free again
+    const int cols = ppo_tile_cols<tj_bf16>(a.h.A), pitch = cols + 8, nks = (cols + 15) / 16;
+    headu32x4 dz[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+        dz[ks] = ks < nks ? *(const headu32x4 *)(tile + r * pitch + 8 * h + 16 * ks) : zero;
+    uint8_t *slab = (uint8_t *)&stage[0][0][0] + w * 4096;
+    const int n_chunk = a.K / 32, n_group = (n_chunk + 1) / 2;
+    for (int gi = w; gi < n_group; gi += NW) {
+        const int c_begin = 2 * gi, c_n = min(2, n_chunk - c_begin);
+        // the group's weight pieces first, all loads in flight together (a tile past the end repeats the last one)
+        headu32x4 wv[2][2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int k0 = min(c_begin + c, n_chunk - 1) * 32;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                wv[c][ks] = ks < nks ? *(const headu32x4 *)((const uint8_t *)a.WT +
+                                                             (uint32_t)((k0 + r) * a.ldwt + 8 * h + 16 * ks) * 2u)
+                                     : zero;
+        }
+        head_wave_sync();   // the last group's rows have been read out of the slab
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            if (c >= c_n) break;
+            headf32x16 d = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                if (ks < nks)
+                    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(headbf16x8, wv[c][ks]),
+                                                                __builtin_bit_cast(headbf16x8, dz[ks]), d, 0, 0, 0);
+            }
+            // d[4q + e] = dX(sample r, column 32 (c_begin + c) + 8q + 4h + e), before the mask
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t lo = (uint32_t)tj_f32_to_bf16(d[4 * q]) | ((uint32_t)tj_f32_to_bf16(d[4 * q + 1]) << 16);
+                const uint32_t hi = (uint32_t)tj_f32_to_bf16(d[4 * q + 2]) | ((uint32_t)tj_f32_to_bf16(d[4 * q + 3]) << 16);
+                const int v = 4 * c + q;
+                *(uint2 *)(slab + r * 128 + ((v ^ (r & 7)) << 4) + 8 * h) = make_uint2(lo, hi);
+            }
+        }
+        head_wave_sync();
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int row = 8 * pass + (lane >> 3), v = lane & 7;
+            if (v < 4 * c_n && j0 + row < a.h.B) {
+                const int k = 32 * c_begin + 8 * v;
+                const headu32x4 g = *(const headu32x4 *)(slab + row * 128 + ((v ^ (row & 7)) << 4));
+                const uint32_t bits = xmask[row * kMaskPitch + (k >> 3)];
+                headu32x4 o;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t lo = (bits >> (2 * u)) & 1u ? (g[u] & 0xFFFFu) : 0u;
+                    const uint32_t hi = (bits >> (2 * u + 1)) & 1u ? (g[u] & 0xFFFF0000u) : 0u;
+                    o[u] = lo | hi;
+                }
+                *(headu32x4 *)((uint8_t *)(a.dX + (size_t)j0 * a.lddx) + (uint32_t)(row * a.lddx + k) * 2u) = o;
+            }
+        }
     }
 }
 
@@ -1168,9 +1377,11 @@ template <typename T> struct MlpLearner : tj_learner {
     }
     // Layer index l (0-based) keeps a transposed weight copy: its input gradient exists, is a contraction
     // (the head's is not where the TD kernel writes it) and does not read the straight copy.
+    virtual bool head_input_gradient_fused() const { return false; }   // a derived learner's head kernel reads WcT
     bool keeps_wct(int l) const
     {
         if (l == 0) return false;
+        if (l == L - 1 && head_input_gradient_fused()) return true;
         if (l == L - 1 && n_pass == 3 && head_fused<T>(A)) return false;
         return !dgrad_trans(l + 1);
     }
@@ -1504,6 +1715,16 @@ template <typename T> struct MlpLearner : tj_learner {
 // the whole batch.  One forward pass (no target network, no s'), so the activation buffers hold
 // max_batch rows; backward, slice reduction, Adam and the weight copies are the Q-learner's.
 template <typename T> struct PpoLearner : MlpLearner<T> {
+    // The objective kernel can also produce the head's input gradient (bf16, at most 32 head outputs, a head
+    // input of whole 32-column tiles without row padding, a transposed weight copy wide enough for its
+    // 16-wide contraction steps); the transposed copy of the head's weights is kept for it.
+    bool head_input_gradient_fused() const override
+    {
+        if (sizeof(T) != 2 || this->L < 3 || this->A > 32) return false;
+        const auto &lh = this->lay[this->L - 1];
+        const int cols16 = (round_up(this->A, 8) + 15) / 16 * 16;
+        return lh.in % 32 == 0 && lh.in <= kPpoFusedMaxK && lh.ld_in == lh.in && lh.ld_out >= cols16;
+    }
     using Base = MlpLearner<T>;
     tj_ppo_desc pd;
     float *ppo_part = nullptr;
@@ -1522,7 +1743,7 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
     }
 
     // forward of n rows of fp32 observations through the trunk and the head; head rows in Qout
-    int forward(int n, const float *d_obs, bool keep_transposes, hipStream_t st)
+    int forward(int n, const float *d_obs, bool keep_transposes, hipStream_t st, bool trunk_only = false)
     {
         int rc;
         const auto &lay = this->lay;
@@ -1531,7 +1752,7 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
                        this->ldB};
         if ((rc = launch_cast<T>(jobs, 1, st)) != TJ_OK) return rc;
         if (keep_transposes && (rc = this->mark(0, st)) != TJ_OK) return rc;
-        for (int l = 0; l < this->L; ++l) {
+        for (int l = 0; l < this->L - (trunk_only ? 1 : 0); ++l) {
             TjGemmArgs<T> g;
             memset(&g, 0, sizeof(g));
             g.n_seg = 1;
@@ -1563,7 +1784,11 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
             if (this->last_batch > B && (rc = launch_zero(this->act_begin, this->act_bytes, st)) != TJ_OK) return rc;
             this->last_batch = B;
         }
-        if ((rc = forward(B, pb->obs, true, st)) != TJ_OK) return rc;
+        // bf16 with at most 32 head outputs: the head layer's forward runs inside the objective kernel
+        const bool fused = sizeof(T) == 2 && this->A <= 32 && this->L >= 2;
+        // the same kernel writes the head's input gradient where the layer below takes it row-major
+        const bool fused_dx = fused && head_input_gradient_fused() && this->wgrad_trans(this->L - 1, B);
+        if ((rc = forward(B, pb->obs, true, st, fused)) != TJ_OK) return rc;
         if ((rc = this->mark(1, st)) != TJ_OK) return rc;
         const auto &lh = this->lay[this->L - 1];
         PpoHeadArgs<T> a;
@@ -1573,14 +1798,30 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
         a.dZ = this->dZ[this->L]; a.lddz = lh.ld_out; a.dZT = this->dZT[this->L]; a.lddzt = this->ldB;
         a.part = ppo_part;
         const int nblk = (B + kPpoRows - 1) / kPpoRows;
-        ppo_head<T><<<nblk, kPpoRows * kPpoLanes, 0, st>>>(a);
+        if constexpr (sizeof(T) == 2) {
+            if (fused) {
+                PpoFusedArgs f;
+                f.h = a;
+                f.X = this->X[this->L - 1]; f.ldx = lh.ld_in;
+                f.W = this->Wc_on[this->L - 1]; f.ldw = lh.ld_in;
+                f.bias = this->theta_on + lh.b_off;
+                f.K = lh.ld_in;
+                f.WT = nullptr; f.ldwt = 0; f.dX = nullptr; f.lddx = 0;
+                if (fused_dx) {   // ... and the head's input gradient, row-major only
+                    f.WT = this->WcT_on[this->L - 1]; f.ldwt = lh.ld_out;
+                    f.dX = this->dZ[this->L - 1]; f.lddx = lh.ld_in;
+                }
+                ppo_head_fused<<<nblk, kPpoRows * kPpoLanes, 0, st>>>(f);
+            }
+        }
+        if (!fused) ppo_head<T><<<nblk, kPpoRows * kPpoLanes, 0, st>>>(a);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = this->mark(2, st)) != TJ_OK) return rc;
         // the optimizer kernel's first wave turns the per-block sums into the step's statistics
         this->ppo_fin.part = ppo_part; this->ppo_fin.n_part = nblk;
         this->ppo_fin.c_v = pd.c_v; this->ppo_fin.c_e = pd.c_e;
         this->ppo_fin.out = d_stats; this->ppo_fin.internal = ppo_stats;
-        rc = this->backward_update(B, 0, nullptr, st);
+        rc = this->backward_update(B, 0, nullptr, st, fused_dx);
         this->ppo_fin.part = nullptr;
         return rc;
     }
@@ -1897,9 +2138,11 @@ template <typename T> struct ConvLearner : tj_learner {
     }
     // Layer l keeps a transposed weight copy: its input gradient exists and is a contraction over that copy (a
     // convolution's is one only on the explicit patch path; the head's is not where the TD kernel writes it).
+    virtual bool head_input_gradient_fused() const { return false; }   // a derived learner's head kernel reads WcT
     bool keeps_wct(int l) const
     {
         if (l == 0) return false;
+        if (l == L - 1 && head_input_gradient_fused()) return true;
         const NLayer &y = lay[l];
         if (y.kind == TJ_LAYER_CONV2D) return !y.dgrad_gather;
         if (l == L - 1 && head_fused<T>(A) && L >= 2 && lay[L - 2].kind == TJ_LAYER_LINEAR) return false;
