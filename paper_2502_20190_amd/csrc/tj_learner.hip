@@ -1359,12 +1359,14 @@ template <typename T> struct MlpLearner : tj_learner {
 
     // Weight gradient of layer l (1-based) straight from the row-major X_{l-1} and dZ_l (transposing LDS
     // reads) instead of their transposed copies: bf16, whole 32-row stages of the batch, widths that are
-    // whole 16-byte vectors.  The first and the last layer keep the transposed operands: their narrow
-    // sides fill too few of the 256 x 128 tiles that form takes.  Where it applies, the transposed copy
-    // of X_{l-1} and of dZ_l is not written at all.
+    // whole 16-byte vectors.  The first and the last layer too, although their narrow sides fill few of the
+    // 256 x 128 tiles that form takes (their pair is 96 blocks on the 256-1024-1024-1024-32 net): what
+    // counts is that no transposed copy of X_{l-1} and of dZ_l is written at all where it applies, which
+    // makes the forward pass of the last hidden layer and the input-gradient pass of the second layer
+    // one-layout launches like the others.
     bool wgrad_trans(int l, int B) const
     {
-        if (sizeof(T) != 2 || B % 32 != 0 || l < 2 || l > L - 1) return false;
+        if (sizeof(T) != 2 || B % 32 != 0 || l < 1 || l > L) return false;
         return lay[l - 1].in % 8 == 0 && lay[l - 1].out % 8 == 0;
     }
 
@@ -1421,7 +1423,7 @@ template <typename T> struct MlpLearner : tj_learner {
         // network input: [s ; s'] in compute type, and the transpose of s
         {
             CastJobs<T> jobs;
-            jobs.job[0] = {(const float *)mb->obs, X[0], XT[0], B, lay[0].in, lay[0].ld_in, ldB};
+            jobs.job[0] = {(const float *)mb->obs, X[0], wgrad_trans(1, B) ? nullptr : XT[0], B, lay[0].in, lay[0].ld_in, ldB};
             jobs.job[1] = {(const float *)mb->next_obs, X[0] + (size_t)B * lay[0].ld_in, nullptr, B,
                            lay[0].in, lay[0].ld_in, ldB};
             if (mb->row_index) {   // rows of the caller's tables (the ring itself), picked by index
@@ -1748,8 +1750,8 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
         int rc;
         const auto &lay = this->lay;
         CastJobs<T> jobs;
-        jobs.job[0] = {d_obs, this->X[0], keep_transposes ? this->XT[0] : nullptr, n, lay[0].in, lay[0].ld_in,
-                       this->ldB};
+        jobs.job[0] = {d_obs, this->X[0], keep_transposes && !this->wgrad_trans(1, n) ? this->XT[0] : nullptr, n,
+                       lay[0].in, lay[0].ld_in, this->ldB};
         if ((rc = launch_cast<T>(jobs, 1, st)) != TJ_OK) return rc;
         if (keep_transposes && (rc = this->mark(0, st)) != TJ_OK) return rc;
         for (int l = 0; l < this->L - (trunk_only ? 1 : 0); ++l) {
