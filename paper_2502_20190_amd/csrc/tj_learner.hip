@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kTdBlock) void td_huber(const float *__restrict__ Q
         for (int a = 0; a < A; ++a) {
             const T val = a == aj ? gz : z0;
             dZ[(size_t)j * lddz + a] = val;
-            dZT[(size_t)a * lddzt + j] = val;
+            if (dZT) dZT[(size_t)a * lddzt + j] = val;   // null where the head's weight gradient reads dZ row-major
         }
     }
     // wave reduction in a fixed order
@@ -260,7 +260,7 @@ struct HeadTdArgs {
     const int32_t *action; const float *reward; const uint8_t *done;
     float gamma, kappa;
     tj_bf16 *dZ; int lddz;                 // [B][lddz]
-    tj_bf16 *dZT; int lddzt;               // [A][lddzt]
+    tj_bf16 *dZT; int lddzt;               // [A][lddzt]; may be null (the head's weight gradient reads dZ row-major)
     int32_t *astar;
     float *loss_part;                      // one per block
     // optional: gradient wrt the head's input rows of s, dX[j][k] = relu'(X[j][k]) g_j W_on[a_j][k]
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(kHeadThreads) void head_td(const HeadTdArgs a)
             if (aj == 8 * vc + 2 * u || aj == 8 * vc + 2 * u + 1) o[u] = gz << (16 * (aj & 1));
         *(headu32x4 *)(a.dZ + (size_t)(j0 + j) * a.lddz + 8 * vc) = o;
     }
-    for (int e = threadIdx.x; e < a.A * (kHeadRows / 8); e += kHeadThreads) {
+    for (int e = threadIdx.x; a.dZT && e < a.A * (kHeadRows / 8); e += kHeadThreads) {
         const int arow = e >> 2, vc = e & 3;
         if (j0 + 8 * vc >= a.lddzt) continue;
         headu32x4 o = zero;
@@ -745,7 +745,7 @@ template <typename T> struct PpoHeadArgs {
     const float *Z; int ldz; int B, A;
     const int32_t *action; const float *old_logp, *adv, *ret;
     float clip, c_v, c_e;
-    T *dZ; int lddz; T *dZT; int lddzt;
+    T *dZ; int lddz; T *dZT; int lddzt;   // dZT may be null (the head's weight gradient reads dZ row-major)
     float *part;   // [blocks][4]: sum L_pi, sum L_v, sum H, unused
 };
 
@@ -847,7 +847,7 @@ __device__ __forceinline__ void ppo_objective(const PpoHeadArgs<T> &a, const flo
         *(uint4 *)(a.dZ + (size_t)(row0 + rr) * a.lddz + c * VEC) = *(const uint4 *)(tile + rr * pitch + c * VEC);
     }
     // transposed gradient: 32 consecutive samples of one head output per 32 lanes
-    for (int e = threadIdx.x; e < (a.A + 1) * kPpoRows; e += kPpoRows * kPpoLanes) {
+    for (int e = threadIdx.x; a.dZT && e < (a.A + 1) * kPpoRows; e += kPpoRows * kPpoLanes) {
         const int k = e / kPpoRows, rr = e % kPpoRows;
         if (rr < n_rows) a.dZT[(size_t)k * a.lddzt + row0 + rr] = tile[rr * pitch + k];
     }
@@ -1459,7 +1459,7 @@ template <typename T> struct MlpLearner : tj_learner {
             h.b_on = theta_on + lh.b_off; h.b_tg = theta_tg + lh.b_off;
             h.B = B; h.A = A; h.K = lh.ld_in;
             h.Q = Qout; h.ldq = ldA;
-            h.dZ = dZ[L]; h.lddz = lh.ld_out; h.dZT = dZT[L]; h.lddzt = ldB;
+            h.dZ = dZ[L]; h.lddz = lh.ld_out; h.dZT = wgrad_trans(L, B) ? nullptr : dZT[L]; h.lddzt = ldB;
             h.astar = astar; h.loss_part = loss_part;
             h.dX = nullptr; h.lddx = 0; h.dXT = nullptr; h.lddxt = 0; h.Kin = lh.in;
             if (head_fused<T>(A) && L >= 2) {   // the fused kernel also writes the head's input gradient
@@ -1797,7 +1797,8 @@ template <typename T> struct PpoLearner : MlpLearner<T> {
         a.Z = this->Qout; a.ldz = this->ldA; a.B = B; a.A = this->A - 1;
         a.action = pb->action; a.old_logp = pb->old_logp; a.adv = pb->adv; a.ret = pb->ret;
         a.clip = pd.clip; a.c_v = pd.c_v; a.c_e = pd.c_e;
-        a.dZ = this->dZ[this->L]; a.lddz = lh.ld_out; a.dZT = this->dZT[this->L]; a.lddzt = this->ldB;
+        a.dZ = this->dZ[this->L]; a.lddz = lh.ld_out; a.lddzt = this->ldB;
+        a.dZT = this->wgrad_trans(this->L, B) ? nullptr : this->dZT[this->L];
         a.part = ppo_part;
         const int nblk = (B + kPpoRows - 1) / kPpoRows;
         if constexpr (sizeof(T) == 2) {
