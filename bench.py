@@ -32,8 +32,8 @@ sys.path.insert(0, ROOT)
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the sources it was taken with: the contraction
 # kernels and the learner that decides which of them a step launches.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip", "tj_conv.h", "tj_learner.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 663.0e6, "gemm_source_sha256_16": "17fe24b8a9afab86"},
-                "c5": {"bytes_per_step": 1355.1e6, "gemm_source_sha256_16": "17fe24b8a9afab86"}}
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 663.0e6, "gemm_source_sha256_16": "e5c56b24947320a9"},
+                "c5": {"bytes_per_step": 1355.1e6, "gemm_source_sha256_16": "e5c56b24947320a9"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 

@@ -9,7 +9,8 @@
 //   gpart                         fp32 [S][Ppad] split-K partial gradients, summed into slice 0
 //   Wc_on[l]  T [out][ld(in)]     WcT_on[l] T [in][ld(out)]   Wc_tg[l]
 //   X[l]   T [3B][ld(d_l)]   rows: s | s' (online) | s' (target); X[0] has 2B rows
-//   XT[l]  T [d_l][ld(B)]    transposed copy of the s rows
+//   XT[l]  T [d_l][ld(B)]    transposed copy of the s rows (written only for weight gradients that
+//                            contract over transposed operands: ragged batches or widths)
 //   Qout   fp32 [3B][ld4(A)]
 //   dZ[l]  T [B][ld(d_l)]    dZT[l] T [d_l][ld(B)]
 #include "tj_gemm.h"
@@ -1420,7 +1421,8 @@ template <typename T> struct MlpLearner : tj_learner {
             last_batch = B;
         }
 
-        // network input: [s ; s'] in compute type, and the transpose of s
+        // network input: [s ; s'] in compute type (and the transpose of s where the first layer's weight
+        // gradient still contracts over transposed operands)
         {
             CastJobs<T> jobs;
             jobs.job[0] = {(const float *)mb->obs, X[0], wgrad_trans(1, B) ? nullptr : XT[0], B, lay[0].in, lay[0].ld_in, ldB};
@@ -1510,7 +1512,7 @@ template <typename T> struct MlpLearner : tj_learner {
                 g.qsum = gpart + lp.b_off; g.qsum_zstride = Ppad;
             }
             // the head's weight gradient waits for the first layer's (bf16, two layers or more): both are
-            // skinny split contractions that fill the chip only together
+            // narrow split contractions, neither of which fills the chip alone
             const bool defer_head = l == L && L >= 2 && sizeof(T) == 2;
             if (defer_head && head_dx_done) {
                 gw_head = gw;
