@@ -32,10 +32,27 @@ sys.path.insert(0, ROOT)
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the sources it was taken with: the contraction
 # kernels and the learner that decides which of them a step launches.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip", "tj_conv.h", "tj_learner.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 663.0e6, "gemm_source_sha256_16": "e5c56b24947320a9"},
-                "c5": {"bytes_per_step": 1355.1e6, "gemm_source_sha256_16": "e5c56b24947320a9"}}
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 738.6e6, "gemm_source_sha256_16": "8ce19a5ec9bc14a7"},
+                "c5": {"bytes_per_step": 1354.3e6, "gemm_source_sha256_16": "8ce19a5ec9bc14a7"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
+
+
+def adam_slice_traffic(dims, precision, B, P):
+    """Bytes the optimizer kernel of an MLP moves on top of the algorithmic ones: it adds the S
+    slices of the split weight-gradient contraction (S more gradient reads, one gradient write).
+    dims: (in, out) per layer.  On a bf16 network of three layers or more whose first and last
+    layers take the transposing-read contractions (the library's conditions), the slices of the
+    layers between them are summed by blocks that ride in the last weight-gradient launch, and
+    the optimizer kernel only has the first layer's and the head's slices left."""
+    S = max(1, min(8, B // (1024 if precision == "bf16" else 64)))
+    if S == 1:
+        return 0
+    ends = [dims[0], dims[-1]]
+    early = (precision == "bf16" and len(dims) >= 3 and B % 32 == 0 and all(i % 8 == 0 and o % 8 == 0 for i, o in ends)
+             and (dims[0][0] * dims[0][1] + dims[0][1]) % 4 == 0)
+    n = sum(i * o + o for i, o in ends) if early else P
+    return 4 * S * n
 
 
 def gemm_flops_per_step(wl, synth, head_in_td_phase):
@@ -237,8 +254,9 @@ def bench_ppo(args):
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
     achieved = flops / (gemm_ms * 1e-3) / 1e12
     P = synth.num_params(layers, (D, 1, 1))
-    S = max(1, min(8, B // (1024 if precision == "bf16" else 64)))
-    adam_bytes = (30 if precision == "bf16" else 28) * P               # algorithmic; the kernel also reads the S gradient slices
+    adam_bytes = (30 if precision == "bf16" else 28) * P               # algorithmic; the kernel also reads gradient slices
+    widths = [D] + [l[1] for l in layers]
+    adam_extra = adam_slice_traffic(list(zip(widths[:-1], widths[1:])), precision, B, P)
     gae_bytes = n_env * T * (4 + 4 + 1 + 4 + 4) + n_env * 4      # reward, value, done in; adv, ret out
     out = {
         "metric": "learner transitions consumed/sec at 1 MI355X",
@@ -256,7 +274,7 @@ def bench_ppo(args):
         "gae": {"bound": "hbm", "achieved": gae_bytes / (gae_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "bytes": gae_bytes, "frac": gae_bytes / (gae_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "adam": {"bound": "hbm", "achieved": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                 "unit": "GB/s", "bytes": adam_bytes, "kernel_traffic_bytes": adam_bytes + (4 * S * P if S > 1 else 0),
+                 "unit": "GB/s", "bytes": adam_bytes, "kernel_traffic_bytes": adam_bytes + adam_extra,
                  "frac": adam_bytes / (ph["adam_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "loss": stats[3],
     }
@@ -516,11 +534,10 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
     adam_bytes = (30 if wl.precision == "bf16" else 28) * P
     adam_kernel_traffic = adam_bytes
     if n_conv == 0:
-        # MLPs: the kernel also sums the S slices of the split weight-gradient contraction
-        # (S more gradient reads, one gradient write): traffic of the kernel, not of the algorithm
-        S = max(1, min(8, wl.batch // (1024 if wl.precision == "bf16" else 64)))
-        if S > 1:
-            adam_kernel_traffic += 4 * S * P
+        # MLPs: the kernel also sums slices of the split weight-gradient contraction: traffic of the
+        # kernel, not of the algorithm
+        widths = [wl.obs_elems] + [l[1] for l in wl.layers]
+        adam_kernel_traffic += adam_slice_traffic(list(zip(widths[:-1], widths[1:])), wl.precision, wl.batch, P)
     gather_bytes = 2 * wl.batch * wl.record_bytes
     if args.frame_ring:   # k + 1 distinct frames read, 2k planes written, plus the scalars
         k, fe = wl.obs_shape[0], wl.obs_shape[1] * wl.obs_shape[2]

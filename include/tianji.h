@@ -494,9 +494,12 @@ int tj_balance_plan(const tj_balance_in *in, tj_balance_out *out);
  *   [0] after the input cast, [1] after the forward GEMMs (before the fused
  *   head-layer + TD kernel where that is used, else after the head GEMM),
  *   [2] after the TD / Huber kernel, [3] after the weight- and input-
- *   gradient GEMMs, [4] after the Adam kernel, which for MLPs also sums the
- *   slices of the split weight gradients (where a layer still keeps a weight
- *   copy that kernel does not write, a copy kernel follows it) (n must be 5);
+ *   gradient GEMMs (on a bf16 MLP of three layers or more the last of those
+ *   launches also adds up the slices of the hidden layers' split weight
+ *   gradients), [4] after the Adam kernel, which for MLPs sums the
+ *   slices of the split weight gradients that are still apart (where a layer
+ *   still keeps a weight copy that kernel does not write, a copy kernel
+ *   follows it) (n must be 5);
  *   every tj_ppo_step records [0] after the input cast, [1] after the forward
  *   GEMMs including the head, [2] after the objective kernel, [3] and [4] as
  *   above (the Adam kernel also finalises the step's statistics),

@@ -139,6 +139,20 @@ template <typename T> int tj_gemm(const TjGemmArgs<T> &a, hipStream_t st);
 // Two independent bf16 GEMMs as one launch where both fit the direct-to-LDS kernel (they share
 // one ramp-up and tail); otherwise the same as two tj_gemm calls.
 int tj_gemm_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, hipStream_t st);
+// Sum of the S gradient slices of the flat parameters [begin, end) (multiples of 4): g[i] += g[s*stride + i]
+// for s = 1 .. S-1 in that order, the order in which the optimizer kernel adds slices.
+struct TjSliceSum {
+    float *g;
+    int S;
+    size_t stride, begin, end;
+};
+// tj_gemm_pair for two split weight gradients with transposed operands that fill only part of the chip
+// (a network's first layer and its head), with that sum as further blocks of the same launch: the
+// streaming work runs on the compute units the contractions leave idle.  The range must not overlap
+// what the two problems write.  *fused says whether the sum was launched; if not, the call was
+// tj_gemm_pair and the optimizer has to add those slices itself.
+int tj_gemm_pair_sum(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, const TjSliceSum &r,
+                     hipStream_t st, bool *fused);
 // bf16 with gathered operands: the same for two convolutions of equal shape class
 int tj_gemm_gather_pair(const TjGemmArgs<tj_bf16> &a0, const TjGemmArgs<tj_bf16> &a1, hipStream_t st);
 // fp32: the same for two small problems (falls back to two launches otherwise)

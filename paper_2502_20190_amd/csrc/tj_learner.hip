@@ -571,14 +571,16 @@ struct LossFinal {
 
 // Adam on the flat fp32 master state (bias-corrected, eps outside the square root); the gradient
 // is the sum of S slices (split batch contraction of the weight-gradient GEMMs), added in slice
-// order and written back to slice 0.  Also emits the compute-type copy of the weights: with one
-// slice 16 B read and 12 B + sizeof(T) written per parameter.
+// order and written back to slice 0.  For the parameters [sum_begin, sum_end) (multiples of 4) an
+// earlier launch has done that sum already and slice 0 is the gradient.  Also emits the compute-type
+// copy of the weights: with one slice 16 B read and 12 B + sizeof(T) written per parameter.
 template <typename T>
 __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, float *__restrict__ m,
                                                    float *__restrict__ v, float *__restrict__ gpart,
                                                    int S, size_t gstride, size_t P, float lr, float b1,
                                                    float b2, float eps, float c1, float c2,
-                                                   const EmitTable<T> tab, const LossFinal lf, const DgradEmit dg)
+                                                   const EmitTable<T> tab, const LossFinal lf, const DgradEmit dg,
+                                                   const size_t sum_begin, const size_t sum_end)
 {
     if (blockIdx.x == 0 && threadIdx.x < 64 && lf.ppo_part) {
         // means of the three terms and the objective, from the per-block sums (fixed order)
@@ -617,7 +619,7 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
     if (i + 4 <= P) {
         float4 g = ld4_stream(gpart + i);
         float4 mm = ld4_stream(m + i), vv = ld4_stream(v + i), th = ld4_stream(theta + i);
-        if (S > 1) {   // slices are added in slice order, eight loads in flight at a time
+        if (S > 1 && !(i >= sum_begin && i < sum_end)) {   // slices are added in slice order, eight loads in flight at a time
             float4 p[8];
             for (int s0 = 1; s0 < S; s0 += 8) {
 #pragma unroll
@@ -659,8 +661,10 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
     } else {
         for (size_t e = i; e < P; ++e) {
             float g = gpart[e];
-            for (int s = 1; s < S; ++s) g += gpart[(size_t)s * gstride + e];
-            if (S > 1) gpart[e] = g;
+            if (!(e >= sum_begin && e < sum_end)) {
+                for (int s = 1; s < S; ++s) g += gpart[(size_t)s * gstride + e];
+                if (S > 1) gpart[e] = g;
+            }
             const float mm = b1 * m[e] + (1.f - b1) * g;
             const float vv = b2 * v[e] + (1.f - b2) * g * g;
             m[e] = mm;
@@ -1487,6 +1491,7 @@ template <typename T> struct MlpLearner : tj_learner {
         // fills the chip); its input gradient runs alone unless the TD kernel has already written it.
         TjGemmArgs<T> gw_head;
         bool head_pending = false;
+        bool slices_summed = false;   // the hidden layers' gradient slices are summed before the optimizer launch
         for (int l = L; l >= 1; --l) {
             const LayerPlan &lp = lay[l - 1];
             TjGemmArgs<T> gw, gd;
@@ -1552,8 +1557,16 @@ template <typename T> struct MlpLearner : tj_learner {
                 continue;
             }
             if (head_pending) {   // l == 1
-                if constexpr (sizeof(T) == 2) rc = tj_gemm_pair(gw, gw_head, st);
-                else rc = TJ_ERR_SHAPE;   // the fused head kernel exists for bf16 only
+                if constexpr (sizeof(T) == 2) {
+                    // The first layer's and the head's weight gradients fill less than half of the chip, and the
+                    // slices of the layers between them (a contiguous range of the flat gradient) are complete
+                    // by now: their sum rides in this launch, and the optimizer reads one slice for them.
+                    const TjSliceSum r = {gpart, S, Ppad, lay[1].w_off, lay[L - 1].w_off};
+                    if (L >= 3 && S > 1) rc = tj_gemm_pair_sum(gw, gw_head, r, st, &slices_summed);
+                    else rc = tj_gemm_pair(gw, gw_head, st);
+                } else {
+                    rc = TJ_ERR_SHAPE;   // the fused head kernel exists for bf16 only
+                }
                 if (rc != TJ_OK) return rc;
                 head_pending = false;
                 continue;
@@ -1561,7 +1574,7 @@ template <typename T> struct MlpLearner : tj_learner {
             if ((rc = tj_gemm<T>(gw, st)) != TJ_OK) return rc;
         }
 
-        if ((rc = mark(3, st)) != TJ_OK) return rc;   // the S slices of the gradient are summed by the Adam kernel
+        if ((rc = mark(3, st)) != TJ_OK) return rc;   // the gradient slices not summed yet are summed by the Adam kernel
         t += 1;
         const float c1 = (float)(1.0 - pow((double)d.beta1, (double)t));
         const float c2 = (float)(1.0 - pow((double)d.beta2, (double)t));
@@ -1583,8 +1596,10 @@ template <typename T> struct MlpLearner : tj_learner {
         }
         DgradEmit no_dgrad;
         no_dgrad.n = 0;
+        const size_t sum_begin = slices_summed ? lay[1].w_off : 0, sum_end = slices_summed ? lay[L - 1].w_off : 0;
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S, Ppad, P, d.lr,
-                                                                      d.beta1, d.beta2, d.eps, c1, c2, tab, lf, no_dgrad);
+                                                                      d.beta1, d.beta2, d.eps, c1, c2, tab, lf, no_dgrad,
+                                                                      sum_begin, sum_end);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
         if ((rc = recast(true, st, true)) != TJ_OK) return rc;   // transposed copies (and padded blocks)
@@ -2535,7 +2550,7 @@ template <typename T> struct ConvLearner : tj_learner {
             }
         }
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
-                                                                      d.beta2, d.eps, c1, c2, tab, lf, dg);
+                                                                      d.beta2, d.eps, c1, c2, tab, lf, dg, 0, 0);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
         if ((rc = recast(true, st, true)) != TJ_OK) return rc;
