@@ -267,7 +267,7 @@ def bench_ppo(args):
                    "layers": [l[1] for l in layers], "params": P},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[precision], "unit": "TFLOP/s",
                      "frac": achieved / PEAK_TFLOPS[precision], "traffic": None,
-                     "kernel": "gemm_bf16_dlds + gemm_bf16_dlds_pair" if precision == "bf16" else "gemm_pq<float>",
+                     "kernel": "gemm_bf16_dlds + gemm_bf16_dlds_pair + gemm_bf16_dlds_pair_sum (its blocks that add gradient slices included)" if precision == "bf16" else "gemm_pq<float>",
                      "launches_per_step": n_launch, "flops_per_launch": flops / n_launch,
                      "avg_launch_ms": gemm_ms / n_launch},
         "phases_ms": ph, "phase_events_on_steps": len(sampled),
@@ -523,7 +523,7 @@ def bench_replay(args, cfg, steps, warmup, with_cpu_baseline):
     if wl.precision != "bf16":
         gemm_kernel_name = "gemm_pq<float>"
     elif n_conv == 0:
-        gemm_kernel_name = "gemm_bf16_dlds + gemm_bf16_dlds_pair"
+        gemm_kernel_name = "gemm_bf16_dlds + gemm_bf16_dlds_pair + gemm_bf16_dlds_pair_sum (its blocks that add gradient slices included)"
     else:
         gemm_kernel_name = "gemm_bf16_dlds (gathered operands) + conv_first_u8c4 + conv_wgrad_bf16"
     gemm_ms = ph["forward_gemm_ms"] + ph["backward_gemm_ms"]
