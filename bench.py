@@ -32,8 +32,8 @@ sys.path.insert(0, ROOT)
 # reads half the bytes, WRITE_SIZE all of them).  Valid for the sources it was taken with: the contraction
 # kernels and the learner that decides which of them a step launches.
 GEMM_SOURCES = ("tj_gemm.h", "tj_gemm.hip", "tj_conv_first.hip", "tj_conv_wgrad.hip", "tj_conv.h", "tj_learner.hip")
-GEMM_TRAFFIC = {"c3": {"bytes_per_step": 738.6e6, "gemm_source_sha256_16": "8ce19a5ec9bc14a7"},
-                "c5": {"bytes_per_step": 1354.3e6, "gemm_source_sha256_16": "8ce19a5ec9bc14a7"}}
+GEMM_TRAFFIC = {"c3": {"bytes_per_step": 738.6e6, "gemm_source_sha256_16": "db2a35045902baea"},
+                "c5": {"bytes_per_step": 1354.0e6, "gemm_source_sha256_16": "db2a35045902baea"}}
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
 
@@ -46,13 +46,18 @@ def adam_slice_traffic(dims, precision, B, P):
     layers between them are summed by blocks that ride in the last weight-gradient launch, and
     the optimizer kernel only has the first layer's and the head's slices left."""
     S = max(1, min(8, B // (1024 if precision == "bf16" else 64)))
-    if S == 1:
-        return 0
     ends = [dims[0], dims[-1]]
-    early = (precision == "bf16" and len(dims) >= 3 and B % 32 == 0 and all(i % 8 == 0 and o % 8 == 0 for i, o in ends)
-             and (dims[0][0] * dims[0][1] + dims[0][1]) % 4 == 0)
-    n = sum(i * o + o for i, o in ends) if early else P
-    return 4 * S * n
+    n_ends = sum(i * o + o for i, o in ends)
+    S_ends = S      # the first layer's and the head's gradients take more slices on a large batch
+    if precision == "bf16" and len(dims) >= 3 and (dims[0][0] * dims[0][1] + dims[0][1]) % 4 == 0 and (P - dims[-1][0] * dims[-1][1] - dims[-1][1]) % 4 == 0:
+        tiles = sum(((i + 255) // 256) * ((o + 127) // 128) for i, o in ends)
+        S_ends = max(S, min(B // 1024, 256 // tiles))
+    early = (precision == "bf16" and len(dims) >= 3 and S > 1 and B % 32 == 0
+             and all(i % 8 == 0 and o % 8 == 0 for i, o in ends) and S_ends >= 1)
+    extra = 4 * S_ends * n_ends if S_ends > 1 else 0
+    if not early and S > 1:
+        extra += 4 * S * (P - n_ends)
+    return extra
 
 
 def gemm_flops_per_step(wl, synth, head_in_td_phase):

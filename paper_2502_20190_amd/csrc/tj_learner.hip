@@ -6,7 +6,7 @@
 // Device layout inside the caller's arena (T = fp32 or bf16 compute type, every
 // 2-D buffer has its row pitch padded to a 16-byte multiple, pads stay zero):
 //   theta_on, theta_tg, m, v      fp32 [P]      master state, flat order
-//   gpart                         fp32 [S][Ppad] split-K partial gradients, summed into slice 0
+//   gpart                         fp32 [S_ends][Ppad] split-K partial gradients, summed into slice 0 (S slices for the hidden layers)
 //   Wc_on[l]  T [out][ld(in)]     WcT_on[l] T [in][ld(out)]   Wc_tg[l]
 //   X[l]   T [3B][ld(d_l)]   rows: s | s' (online) | s' (target); X[0] has 2B rows
 //   XT[l]  T [d_l][ld(B)]    transposed copy of the s rows (written only for weight gradients that
@@ -571,16 +571,17 @@ struct LossFinal {
 
 // Adam on the flat fp32 master state (bias-corrected, eps outside the square root); the gradient
 // is the sum of S slices (split batch contraction of the weight-gradient GEMMs), added in slice
-// order and written back to slice 0.  For the parameters [sum_begin, sum_end) (multiples of 4) an
-// earlier launch has done that sum already and slice 0 is the gradient.  Also emits the compute-type
-// copy of the weights: with one slice 16 B read and 12 B + sizeof(T) written per parameter.
+// order and written back to slice 0.  The parameters [mid_begin, mid_end) (multiples of 4; a
+// network's hidden layers) have S_mid slices instead: 1 where an earlier launch has done that sum
+// already and slice 0 is the gradient.  Also emits the compute-type copy of the weights: with one
+// slice 16 B read and 12 B + sizeof(T) written per parameter.
 template <typename T>
 __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, float *__restrict__ m,
                                                    float *__restrict__ v, float *__restrict__ gpart,
                                                    int S, size_t gstride, size_t P, float lr, float b1,
                                                    float b2, float eps, float c1, float c2,
                                                    const EmitTable<T> tab, const LossFinal lf, const DgradEmit dg,
-                                                   const size_t sum_begin, const size_t sum_end)
+                                                   const size_t mid_begin, const size_t mid_end, const int S_mid)
 {
     if (blockIdx.x == 0 && threadIdx.x < 64 && lf.ppo_part) {
         // means of the three terms and the objective, from the per-block sums (fixed order)
@@ -619,15 +620,16 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
     if (i + 4 <= P) {
         float4 g = ld4_stream(gpart + i);
         float4 mm = ld4_stream(m + i), vv = ld4_stream(v + i), th = ld4_stream(theta + i);
-        if (S > 1 && !(i >= sum_begin && i < sum_end)) {   // slices are added in slice order, eight loads in flight at a time
+        const int Sv = (i >= mid_begin && i < mid_end) ? S_mid : S;
+        if (Sv > 1) {   // slices are added in slice order, eight loads in flight at a time
             float4 p[8];
-            for (int s0 = 1; s0 < S; s0 += 8) {
+            for (int s0 = 1; s0 < Sv; s0 += 8) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
-                    if (s0 + u < S) p[u] = ld4_stream(gpart + (size_t)(s0 + u) * gstride + i);
+                    if (s0 + u < Sv) p[u] = ld4_stream(gpart + (size_t)(s0 + u) * gstride + i);
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
-                    if (s0 + u < S) { g.x += p[u].x; g.y += p[u].y; g.z += p[u].z; g.w += p[u].w; }
+                    if (s0 + u < Sv) { g.x += p[u].x; g.y += p[u].y; g.z += p[u].z; g.w += p[u].w; }
             }
             *(float4 *)(gpart + i) = g;   // slice 0 keeps the step's gradient
         }
@@ -661,10 +663,9 @@ __global__ __launch_bounds__(256) void adam_update(float *__restrict__ theta, fl
     } else {
         for (size_t e = i; e < P; ++e) {
             float g = gpart[e];
-            if (!(e >= sum_begin && e < sum_end)) {
-                for (int s = 1; s < S; ++s) g += gpart[(size_t)s * gstride + e];
-                if (S > 1) gpart[e] = g;
-            }
+            const int Se = (e >= mid_begin && e < mid_end) ? S_mid : S;
+            for (int s = 1; s < Se; ++s) g += gpart[(size_t)s * gstride + e];
+            if (Se > 1) gpart[e] = g;
             const float mm = b1 * m[e] + (1.f - b1) * g;
             const float vv = b2 * v[e] + (1.f - b2) * g * g;
             m[e] = mm;
@@ -1268,6 +1269,7 @@ template <typename T> struct MlpLearner : tj_learner {
     static constexpr int VE = TjElem<T>::kVec;
     tj_learner_desc d;
     int L = 0, A = 0, Bmax = 0, ldB = 0, ldA = 0, S = 1;
+    int S_ends = 1;   // slices of the first and the last layer's weight gradients (>= S)
     int n_pass = 3;                        // stacked forward passes: s, s' (online), s' (target); 1 = on-policy
     size_t P = 0, Ppad = 0;
     std::vector<LayerPlan> lay;
@@ -1316,7 +1318,17 @@ template <typename T> struct MlpLearner : tj_learner {
         theta_tg = (float *)a.take(P * 4);
         m = (float *)a.take(P * 4);
         v = (float *)a.take(P * 4);
-        gpart = (float *)a.take((size_t)S * Ppad * 4);
+        // The first layer's and the head's weight gradients share one launch of few 256 x 128 tiles; on a
+        // large batch more slices than S let that launch reach every CU (bf16 nets of three layers or more,
+        // where those two layers are apart in the flat gradient and their ranges start at whole vectors).
+        S_ends = S;
+        if (sizeof(T) == 2 && L >= 3 && lay[1].w_off % 4 == 0 && lay[L - 1].w_off % 4 == 0) {
+            const int tiles = ((lay[0].in + 255) / 256) * ((lay[0].out + 127) / 128) +
+                              ((lay[L - 1].in + 255) / 256) * ((lay[L - 1].out + 127) / 128);
+            const int want = Bmax / 1024, fit = 256 / tiles;
+            S_ends = std::max(S, std::min(want, fit));
+        }
+        gpart = (float *)a.take((size_t)S_ends * Ppad * 4);
         size_t wc0 = a.off;
         for (int l = 0; l < L; ++l) Wc_on[l] = (T *)a.take((size_t)lay[l].out * lay[l].ld_in * sizeof(T));
         wc_bytes = a.off - wc0;
@@ -1510,9 +1522,10 @@ template <typename T> struct MlpLearner : tj_learner {
                     g.ldp = ldB; g.ldq = ldB;
                 }
                 g.I = lp.in; g.K = Kb;
-                g.n_split = S;
+                const int Sl = (l == 1 || l == L) ? S_ends : S;
+                g.n_split = Sl;
                 const int ke = 128 / (int)sizeof(T);
-                g.k_chunk = round_up((Kb + S - 1) / S, ke);
+                g.k_chunk = round_up((Kb + Sl - 1) / Sl, ke);
                 g.Cf = gpart + lp.w_off; g.ldcf = lp.in; g.cf_zstride = Ppad;
                 g.qsum = gpart + lp.b_off; g.qsum_zstride = Ppad;
             }
@@ -1596,10 +1609,12 @@ template <typename T> struct MlpLearner : tj_learner {
         }
         DgradEmit no_dgrad;
         no_dgrad.n = 0;
-        const size_t sum_begin = slices_summed ? lay[1].w_off : 0, sum_end = slices_summed ? lay[L - 1].w_off : 0;
-        adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S, Ppad, P, d.lr,
+        // hidden layers: S slices, or one where the last launch has summed them; first and last layer: S_ends
+        const bool mid = L >= 3 && (slices_summed || S_ends != S);
+        const size_t mid_begin = mid ? lay[1].w_off : 0, mid_end = mid ? lay[L - 1].w_off : 0;
+        adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, gpart, S_ends, Ppad, P, d.lr,
                                                                       d.beta1, d.beta2, d.eps, c1, c2, tab, lf, no_dgrad,
-                                                                      sum_begin, sum_end);
+                                                                      mid_begin, mid_end, slices_summed ? 1 : S);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
         if ((rc = recast(true, st, true)) != TJ_OK) return rc;   // transposed copies (and padded blocks)
@@ -2550,7 +2565,7 @@ template <typename T> struct ConvLearner : tj_learner {
             }
         }
         adam_update<T><<<(unsigned)((P + 1023) / 1024), 256, 0, st>>>(theta_on, m, v, grad, 1, Ppad, P, d.lr, d.beta1,
-                                                                      d.beta2, d.eps, c1, c2, tab, lf, dg, 0, 0);
+                                                                      d.beta2, d.eps, c1, c2, tab, lf, dg, 0, 0, 1);
         if (hipGetLastError() != hipSuccess) return TJ_ERR_DEVICE;
         if ((rc = mark(4, st)) != TJ_OK) return rc;
         if ((rc = recast(true, st, true)) != TJ_OK) return rc;
