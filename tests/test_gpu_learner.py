@@ -312,6 +312,23 @@ def test_c3_full_size_step(tj, orc):
     print("c3 full-size worst relative errors:", worst)
 
 
+def test_large_batch_takes_more_slices_for_the_narrow_layers(tj, orc):
+    """A bf16 learner made for 12288 rows splits the weight gradients of its first layer and of its
+    head 12 ways over the batch and those of the hidden layer 8 ways; the hidden layer's slices are
+    added up by blocks of the last weight-gradient launch, the others by the optimizer kernel.  A
+    full batch, then two smaller ones on the same learner (most slices of the narrow layers then
+    cover no rows at all; the last one is not a multiple of 32, so the contractions take the
+    kernels without transposing reads and the optimizer adds every slice); each step starts from the
+    oracle's state."""
+    wl = replace(synth.WORKLOADS["c3"], obs_shape=(64,), n_actions=8, batch=12288,
+                 layers=((LIN, 256, 0, 0), (LIN, 256, 0, 0), (LIN, 8, 0, 0)))
+    g, o = _pair(tj, orc, wl, seed=33)
+    for step, n in enumerate((12288, 4096, 1000)):
+        worst, _ = _step_both(tj, orc, g, o, wl, _batch(wl, 700 + step, n), TOL["bf16"], sync=(step > 0))
+        _check_compute_copies(tj, g, wl)
+        print(f"batch {n} on a learner made for 12288:", worst)
+
+
 def test_two_free_running_bf16_steps(tj, orc):
     """Two consecutive bf16 steps without reloading any state: the second step's forward and
     backward passes read the weight copies the first step's optimizer kernel emitted.  A large
